@@ -1,0 +1,217 @@
+"""Plain fp64 oracle of the per-compression-event retention step.
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke entry and by the
+CPU-baseline leg of the benchmark; never by the product path.  It shares no
+code with the HIP library and does not import it.
+
+What is computed, and where the paper defines it (Sec. 4.1 "Method: A V-Space
+Diversity Penalty"):
+
+* V-signatures: each value row scaled by 1/(||row||_2 + eps)        (Eq. 1,
+  with one layer and one head per problem: every (sequence, layer, KV-head)
+  is its own selection problem).
+* cosine of two signatures = their dot product                      (text
+  after Eq. 1).
+* marginal gain  s_i - lambda * max(0, max_{j in S} cos(v_i, v_j))  (Eq. 2).
+* greedy fill: first pick argmax s, then argmax of the marginal gain over
+  the unselected tokens, k-1 times                                  (Eq. 3).
+* Algorithm 1: the same rule with the n x n cosine matrix computed once and
+  a running maximum m (initialised to zero, which is the max(0, .) floor);
+  lambda == 0 returns top-k(s) through an explicit branch; the result is the
+  sorted index set.
+* The cache after the event is the selected rows of K and V in ascending
+  token order (Sec. 1: a budget-bounded subset of cached tokens is kept;
+  Algorithm 1 returns sort(S)).
+
+The paper's base scorer is external to it.  The stand-in used by the synthetic
+workloads is the mean over G grouped queries of softmax_i(q_g . k_i / sqrt(d))
+(`score_softmax_mean`), or scores handed in directly.
+
+Readings taken where the paper is silent: ties in every argmax go to the
+lowest token index (this makes the greedy loop at lambda = 0 coincide with a
+stable top-k, as the text requires of the fast path); eps is added to the
+norm; all n tokens are candidates.
+
+Pins (tests/test_oracle_pins.py): a worked four-token case derived by hand,
+lambda = 0 against a stable sort, orthonormal / identical / antipodal value
+rows (closed forms), an exhaustive from-scratch evaluation of Eq. 2 on tiny
+inputs (`greedy_from_definition`, which keeps no running maximum and no cosine
+matrix), softmax rows summing to one and matching scipy, invariants (k unique
+indices, first pick = argmax s, non-increasing pick gains).  No function here
+is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+NEG_INF = -np.inf
+
+
+# --------------------------------------------------------------------------
+# exact widening of the device formats
+# --------------------------------------------------------------------------
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """uint16 bfloat16 bit patterns -> float64, exactly (bf16 is the top half
+    of an IEEE binary32)."""
+    b = np.ascontiguousarray(bits).astype(np.uint32) << np.uint32(16)
+    return b.view(np.float32).astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# base score stand-in
+# --------------------------------------------------------------------------
+def score_softmax_mean(K: np.ndarray, Q: np.ndarray) -> np.ndarray:
+    """s_i = (1/G) sum_g softmax_i(q_g . k_i / sqrt(d)).  K [n,d], Q [G,d]."""
+    K = np.asarray(K, dtype=np.float64)
+    Q = np.asarray(Q, dtype=np.float64)
+    n, d = K.shape
+    z = (Q @ K.T) / np.sqrt(float(d))              # [G, n]
+    z = z - z.max(axis=1, keepdims=True)
+    p = np.exp(z)
+    p = p / p.sum(axis=1, keepdims=True)
+    return p.mean(axis=0)
+
+
+# --------------------------------------------------------------------------
+# Eq. 1
+# --------------------------------------------------------------------------
+def signatures(V: np.ndarray, eps: float) -> np.ndarray:
+    """v_i = u_i / (||u_i||_2 + eps), one layer and one head (u_i = V_i)."""
+    V = np.asarray(V, dtype=np.float64)
+    norm = np.sqrt((V * V).sum(axis=1, keepdims=True))
+    return V / (norm + eps)
+
+
+def signatures_flat(V_all: np.ndarray, eps: float) -> np.ndarray:
+    """Eq. 1 as printed: u_i is the mean of V over all layers and heads.
+    V_all [L*H, n, d]."""
+    u = np.asarray(V_all, dtype=np.float64).mean(axis=0)
+    return signatures(u, eps)
+
+
+# --------------------------------------------------------------------------
+# top-k (lambda = 0 branch of Algorithm 1)
+# --------------------------------------------------------------------------
+def _argmax_lowest(a: np.ndarray) -> int:
+    """argmax with ties to the lowest index (numpy's argmax already returns
+    the first maximum; spelled out because the reading matters)."""
+    return int(np.flatnonzero(a == a.max())[0])
+
+
+def topk_order(s: np.ndarray, k: int) -> np.ndarray:
+    """The k largest scores in pick order (descending score, ties to the
+    lower index)."""
+    s = np.asarray(s, dtype=np.float64)
+    order = np.argsort(-s, kind="stable")
+    return order[:k].astype(np.int64)
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1
+# --------------------------------------------------------------------------
+def alpha_select(s, V, k: int, lam: float, eps: float = 1e-6):
+    """Algorithm 1, step by step, in fp64.
+
+    Returns a dict with
+      order   [k]  picks in the order they were made,
+      gain    [k]  marginal gain of each pick when it was made (gain[0] is
+                   max s),
+      second  [k]  the best marginal gain among the other unselected tokens
+                   at that step (-inf when none is left),
+      sorted  [k]  sort(S), the algorithm's return value.
+    """
+    s = np.asarray(s, dtype=np.float64)
+    n = s.shape[0]
+    if not (1 <= k <= n):
+        raise ValueError("need 1 <= k <= n")
+    if not (lam >= 0.0):
+        raise ValueError("need lambda >= 0")
+    if lam == 0.0:
+        order = topk_order(s, k)
+        gain = s[order].copy()
+        second = np.full(k, NEG_INF)
+        rest = np.sort(s)[::-1]
+        for t in range(k):
+            if t + 1 < n:
+                second[t] = rest[t + 1]
+        return dict(order=order, gain=gain, second=second,
+                    sorted=np.sort(order))
+    Vh = signatures(V, eps)
+    sims = Vh @ Vh.T                                # n x n cosine matrix
+    m = np.zeros(n)
+    selected = np.zeros(n, dtype=bool)
+    order = np.empty(k, dtype=np.int64)
+    gain = np.empty(k)
+    second = np.full(k, NEG_INF)
+
+    def take(a, t):
+        i = _argmax_lowest(a)
+        order[t] = i
+        gain[t] = a[i]
+        b = a.copy()
+        b[i] = NEG_INF
+        second[t] = b.max() if n > 1 else NEG_INF
+        selected[i] = True
+        np.maximum(m, sims[i, :], out=m)
+
+    take(s.copy(), 0)                               # i_1 = argmax s
+    for t in range(1, k):
+        a = s - lam * m
+        a[selected] = NEG_INF
+        take(a, t)
+    return dict(order=order, gain=gain, second=second, sorted=np.sort(order))
+
+
+# --------------------------------------------------------------------------
+# Eq. 2 / Eq. 3 written out with no running state (for tiny n)
+# --------------------------------------------------------------------------
+def marginal_gains(s, Vh, S, lam: float) -> np.ndarray:
+    """Eq. 2 for every token given the selected list S (signatures Vh already
+    unit-normalised); selected tokens get -inf.  Nothing incremental: the
+    inner maximum is recomputed over the whole of S."""
+    s = np.asarray(s, dtype=np.float64)
+    n = s.shape[0]
+    out = np.empty(n)
+    Sset = set(int(j) for j in S)
+    for i in range(n):
+        if i in Sset:
+            out[i] = NEG_INF
+            continue
+        red = 0.0
+        if len(S):
+            red = max(0.0, max(float(np.dot(Vh[i], Vh[j])) for j in S))
+        out[i] = s[i] - lam * red
+    return out
+
+
+def greedy_from_definition(s, V, k: int, lam: float, eps: float = 1e-6):
+    """Eq. 3 with Eq. 2 evaluated from scratch at every step."""
+    s = np.asarray(s, dtype=np.float64)
+    Vh = signatures(V, eps)
+    S = [_argmax_lowest(s)]
+    gains = [float(s[S[0]])]
+    for _ in range(1, k):
+        g = marginal_gains(s, Vh, S, lam)
+        i = _argmax_lowest(g)
+        S.append(i)
+        gains.append(float(g[i]))
+    return np.asarray(S, dtype=np.int64), np.asarray(gains)
+
+
+# --------------------------------------------------------------------------
+# cache update
+# --------------------------------------------------------------------------
+def compact(X: np.ndarray, idx_sorted: np.ndarray) -> np.ndarray:
+    """Rows of X at the ascending indices, bit for bit (X may be a raw
+    integer view of the device format)."""
+    return np.ascontiguousarray(np.asarray(X)[np.asarray(idx_sorted)])
+
+
+def retain(K, V, k: int, lam: float, eps: float = 1e-6, Q=None, s=None):
+    """Whole event for one head: score (unless given), select, and the
+    sorted index set.  K, V are float64 views of the cached rows."""
+    if s is None:
+        s = score_softmax_mean(K, Q)
+    sel = alpha_select(s, V, k, lam, eps)
+    sel["s"] = np.asarray(s, dtype=np.float64)
+    return sel

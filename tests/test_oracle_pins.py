@@ -1,0 +1,250 @@
+"""Pins of the fp64 oracle against what the paper and the mathematics fix
+(Sec. 4.1: Eq. 1-3, Algorithm 1).  CPU only."""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import alpha_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- hand cases
+def test_hand_case_five_tokens():
+    g = json.load(open(os.path.join(GOLD, "hand_case.json")))
+    r = O.alpha_select(g["s"], np.array(g["V"]), g["k"], g["lambda"], g["eps"])
+    assert r["order"].tolist() == g["order"]
+    np.testing.assert_allclose(r["gain"], g["gain"], rtol=0, atol=1e-12)
+    assert r["sorted"].tolist() == g["sorted"]
+
+
+def test_hand_case_four_tokens_two_lambdas():
+    g = json.load(open(os.path.join(GOLD, "hand_case.json")))["second_case"]
+    for c in g["cases"]:
+        r = O.alpha_select(g["s"], np.array(g["V"]), g["k"], c["lambda"], g["eps"])
+        assert r["order"].tolist() == c["order"]
+        np.testing.assert_allclose(r["gain"], c["gain"], atol=1e-12)
+
+
+# ------------------------------------------------- lambda = 0 is stable top-k
+@pytest.mark.parametrize("seed", range(5))
+def test_lambda_zero_is_stable_topk(seed):
+    rng = _rng(seed)
+    n, d, k = 97, 16, 31
+    s = rng.integers(0, 12, n).astype(np.float64)      # many exact ties
+    V = rng.normal(size=(n, d))
+    r = O.alpha_select(s, V, k, 0.0)
+    # independent statement of "k largest, ties to the lower index"
+    expect = sorted(range(n), key=lambda i: (-s[i], i))[:k]
+    assert r["order"].tolist() == expect
+    assert r["sorted"].tolist() == sorted(expect)
+
+
+def test_greedy_loop_at_tiny_lambda_matches_topk_when_gaps_are_large():
+    # with score gaps of 1 and lambda = 1e-9 the loop (not the fast path) must
+    # still give top-k: pins the loop's masking and the first pick
+    rng = _rng(3)
+    n, k = 40, 17
+    s = rng.permutation(n).astype(np.float64)
+    V = rng.normal(size=(n, 8))
+    r = O.alpha_select(s, V, k, 1e-9)
+    assert r["order"].tolist() == list(np.argsort(-s)[:k])
+
+
+# ------------------------------------------------------------- closed forms
+def test_orthonormal_rows_give_topk_for_any_lambda():
+    rng = _rng(1)
+    n = 24
+    Qm, _ = np.linalg.qr(rng.normal(size=(32, 32)))
+    V = Qm[:n] * rng.uniform(0.5, 3.0, size=(n, 1))     # orthogonal, any norm
+    s = rng.normal(size=n)
+    for lam in (0.25, 1.0, 5.0):
+        r = O.alpha_select(s, V, 9, lam, eps=0.0)
+        assert r["order"].tolist() == list(np.argsort(-s, kind="stable")[:9])
+        np.testing.assert_allclose(r["gain"], np.sort(s)[::-1][:9], atol=1e-12)
+
+
+def test_identical_rows_shift_every_later_gain_by_lambda():
+    rng = _rng(2)
+    n, k, lam = 30, 12, 0.7
+    V = np.tile(rng.normal(size=(1, 8)), (n, 1))
+    s = rng.normal(size=n)
+    r = O.alpha_select(s, V, k, lam, eps=0.0)
+    top = np.argsort(-s, kind="stable")[:k]
+    assert r["order"].tolist() == top.tolist()
+    np.testing.assert_allclose(r["gain"][0], s[top[0]], atol=1e-12)
+    np.testing.assert_allclose(r["gain"][1:], s[top[1:]] - lam, atol=1e-12)
+
+
+def test_antipodal_pairs_get_no_bonus():
+    # rows x and -x: cosine -1 is floored to zero, so with mutually orthogonal
+    # pairs the result is top-k
+    n = 16
+    V = np.zeros((n, 8))
+    for p in range(8):
+        V[2 * p, p] = 1.0
+        V[2 * p + 1, p] = -1.0
+    s = _rng(4).normal(size=n)
+    r = O.alpha_select(s, V, 7, 0.9, eps=0.0)
+    assert r["order"].tolist() == list(np.argsort(-s, kind="stable")[:7])
+
+
+def test_k_equals_one_and_k_equals_n():
+    rng = _rng(5)
+    s = rng.normal(size=13)
+    V = rng.normal(size=(13, 4))
+    assert O.alpha_select(s, V, 1, 0.5)["order"].tolist() == [int(np.argmax(s))]
+    assert O.alpha_select(s, V, 13, 0.5)["sorted"].tolist() == list(range(13))
+
+
+# ------------------------------------------------ Eq. 2 from scratch, tiny n
+@pytest.mark.parametrize("seed", range(12))
+def test_algorithm1_equals_definition_on_tiny_inputs(seed):
+    rng = _rng(100 + seed)
+    n = int(rng.integers(2, 13))
+    d = int(rng.integers(2, 6))
+    V = rng.normal(size=(n, d))
+    if seed % 3 == 0:                        # near-duplicate rows
+        V[n // 2:] = V[: n - n // 2] + 0.05 * rng.normal(size=(n - n // 2, d))
+    s = rng.normal(size=n) if seed % 2 else rng.uniform(0, 0.02, size=n)
+    for lam in (0.25, 0.5, 1.0, 1.5):
+        for k in range(1, n + 1):
+            a = O.alpha_select(s, V, k, lam)
+            order, gains = O.greedy_from_definition(s, V, k, lam)
+            assert a["order"].tolist() == order.tolist()
+            np.testing.assert_allclose(a["gain"], gains, atol=1e-13)
+
+
+def test_each_pick_is_the_exhaustive_argmax():
+    # for every prefix of the pick list, every unselected token's Eq. 2 value
+    # is <= the gain of the token that was picked (and ties go low)
+    rng = _rng(42)
+    n, k, lam, eps = 11, 8, 0.5, 1e-6
+    V = rng.normal(size=(n, 3))
+    s = rng.uniform(0, 0.5, size=n)
+    r = O.alpha_select(s, V, k, lam, eps)
+    Vh = O.signatures(V, eps)
+    for t in range(1, k):
+        S = r["order"][:t].tolist()
+        best, arg = -np.inf, None
+        for i in range(n):
+            if i in S:
+                continue
+            red = max([0.0] + [float(Vh[i] @ Vh[j]) for j in S])
+            g = s[i] - lam * red
+            if g > best:
+                best, arg = g, i
+        assert arg == r["order"][t]
+        assert abs(best - r["gain"][t]) < 1e-13
+
+
+# ----------------------------------------------------------------- invariants
+@pytest.mark.parametrize("seed", range(4))
+def test_invariants(seed):
+    rng = _rng(200 + seed)
+    n, d, k = 150, 32, 60
+    V = rng.normal(size=(n, d))
+    V[50:100] = V[:50] + 0.05 * rng.normal(size=(50, d))
+    s = rng.lognormal(size=n)
+    r = O.alpha_select(s, V, k, 0.5)
+    assert len(set(r["order"].tolist())) == k
+    assert r["order"].min() >= 0 and r["order"].max() < n
+    assert r["order"][0] == int(np.argmax(s))
+    assert np.all(np.diff(r["gain"]) <= 1e-15)            # non-increasing
+    assert np.all(r["second"] <= r["gain"] + 1e-15)
+    assert r["sorted"].tolist() == sorted(r["order"].tolist())
+
+
+def test_positive_row_scaling_leaves_picks_unchanged():
+    rng = _rng(7)
+    n, d, k = 80, 16, 30
+    V = rng.normal(size=(n, d))
+    s = rng.uniform(0, 0.02, size=n)
+    a = O.alpha_select(s, V, k, 0.5, eps=0.0)
+    scale = 2.0 ** rng.integers(-6, 7, size=(n, 1))
+    b = O.alpha_select(s, V * scale, k, 0.5, eps=0.0)
+    assert a["order"].tolist() == b["order"].tolist()
+
+
+def test_signatures_norm_and_eps_reading():
+    rng = _rng(8)
+    V = rng.normal(size=(9, 5))
+    V[3] = 0.0
+    eps = 1e-3
+    Vh = O.signatures(V, eps)
+    nv = np.linalg.norm(V, axis=1)
+    np.testing.assert_allclose(np.linalg.norm(Vh, axis=1), nv / (nv + eps), atol=1e-14)
+    assert np.all(Vh[3] == 0.0)             # zero row stays zero, never penalised
+    flat = O.signatures_flat(np.stack([V[:3], 3 * V[:3]]), 0.0)
+    np.testing.assert_allclose(flat, O.signatures(V[:3], 0.0), atol=1e-14)
+
+
+def test_cosine_matrix_properties():
+    rng = _rng(9)
+    Vh = O.signatures(rng.standard_t(3, size=(40, 16)), 0.0)
+    S = Vh @ Vh.T
+    np.testing.assert_allclose(S, S.T, atol=1e-15)
+    np.testing.assert_allclose(np.diag(S), 1.0, atol=1e-14)
+    assert np.abs(S).max() <= 1 + 1e-14
+
+
+# ----------------------------------------------------------------- base score
+def test_score_is_mean_of_softmax_rows():
+    rng = _rng(10)
+    n, d, G = 50, 16, 7
+    K = rng.normal(size=(n, d))
+    Q = rng.normal(size=(G, d))
+    s = O.score_softmax_mean(K, Q)
+    assert abs(s.sum() - 1.0) < 1e-14
+    ref = scipy.special.softmax(Q @ K.T / 4.0, axis=1).mean(axis=0)
+    np.testing.assert_allclose(s, ref, rtol=1e-13)
+    # one query: plain softmax; by hand for a two-token case
+    s2 = O.score_softmax_mean(np.array([[2.0, 0.0], [0.0, 0.0]]), np.array([[np.sqrt(2.0), 0.0]]))
+    np.testing.assert_allclose(s2, [np.e**2 / (np.e**2 + 1), 1 / (np.e**2 + 1)], rtol=1e-14)
+    # logits far beyond exp's range must not overflow (max-subtraction)
+    big = O.score_softmax_mean(np.array([[4000.0, 0.0], [0.0, 0.0]]), np.array([[4000.0, 0.0]]))
+    np.testing.assert_allclose(big, [1.0, 0.0], atol=1e-300)
+
+
+# ------------------------------------------------------------ format / compact
+def test_bf16_widening_is_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x0000, 0x4049, 0x7F7F, 0x0080], dtype=np.uint16)
+    want = [1.0, -1.0, 0.0, 3.140625, 3.3895313892515355e38, 2.0 ** -126]
+    np.testing.assert_array_equal(O.bf16_bits_to_f64(bits), want)
+
+
+def test_compact_is_a_row_gather():
+    X = np.arange(40, dtype=np.uint16).reshape(10, 4)
+    idx = np.array([1, 4, 9])
+    out = O.compact(X, idx)
+    assert out.tolist() == [X[1].tolist(), X[4].tolist(), X[9].tolist()]
+    assert O.compact(out, np.arange(3)).tolist() == out.tolist()
+
+
+# ---------------------------------------- a planted mistake must break a pin
+def test_pins_catch_planted_mistakes(monkeypatch):
+    g = json.load(open(os.path.join(GOLD, "hand_case.json")))
+    V = np.array(g["V"])
+
+    def no_floor(s, V, k, lam, eps=1e-6):
+        s = np.asarray(s, float)
+        Vh = O.signatures(V, eps)
+        sims = Vh @ Vh.T
+        m = np.full(len(s), -np.inf)             # mistake: m not floored at 0
+        sel, order = np.zeros(len(s), bool), []
+        a = s.copy()
+        for _ in range(k):
+            i = int(np.argmax(a)); order.append(i); sel[i] = True
+            m = np.maximum(m, sims[i])
+            a = s - lam * m; a[sel] = -np.inf
+        return order
+
+    assert no_floor(g["s"], V, g["k"], g["lambda"], 0.0) != g["order"]
