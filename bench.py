@@ -1,0 +1,129 @@
+#!/usr/bin/env python3
+"""Benchmark of the retention step (score -> greedy selection -> compaction)
+on one MI355X.  Prints one JSON line.
+
+A step is one kvr_retain call over all heads of the workload, with K, V and
+Q (or s) already resident in HBM.  value = heads / second.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(w, data, b, lam, budget_s=12.0):
+    """The fp64 oracle, as it stands, on a bounded sample of the same heads."""
+    import numpy as np
+    from oracle import alpha_oracle as O
+    from paper_2605_14292_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    rng = np.random.default_rng(11)
+    heads = rng.permutation(w.heads)
+    done, t_used = 0, 0.0
+    for h in heads:
+        K64, V64 = W.to_f64(data["K"][h]), W.to_f64(data["V"][h])
+        Q64 = W.to_f64(data["Q"][h]) if "Q" in data else None
+        s64 = W.to_f64(data["s"][h]) if "s" in data else None
+        kb = data["K"][h].cpu().view(data["K"].dtype).numpy() if False else None
+        t0 = time.perf_counter()
+        r = O.retain(K64, V64, b, lam, 1e-6, Q=Q64, s=s64)
+        O.compact(K64, r["sorted"])
+        O.compact(V64, r["sorted"])
+        t_used += time.perf_counter() - t0
+        done += 1
+        if t_used >= budget_s or done >= 4096:
+            break
+    return {"value": done / t_used, "unit": "head-events/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {w.heads} heads of {w.name} (fp64 numpy oracle, {t_used:.1f} s, "
+                      "rate extrapolates linearly over heads)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--b", type=int, default=None)
+    ap.add_argument("--lam", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (heads shard with no exchange; "
+                 "see DESIGN.md); --gpus must be 1")
+
+    import torch
+    from paper_2605_14292_amd import binding as B
+    from paper_2605_14292_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    dev = "cuda:0"
+    w = W.WORKLOADS[args.workload]
+    b = w.b if args.b is None else args.b
+    lam = w.lam if args.lam is None else args.lam
+    data = W.generate(w, seed=args.seed, device=dev)
+    out = B.RetainBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, "Q" in data, want_trace=False)
+    Q, s = data.get("Q"), data.get("s")
+
+    def step():
+        B.kvr_retain(data["K"], data["V"], b, lam, 1e-6, Q=Q, s=s, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, z in ev:
+        a.record()
+        step()
+        z.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    dev_ms = sorted(a.elapsed_time(z) for a, z in ev)
+    dev_avg_ms = sum(dev_ms) / len(dev_ms)
+
+    bytes_step = w.algorithmic_bytes_per_head(b, lam) * w.heads
+    achieved = bytes_step / (dev_avg_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"{w.name}:b{b}:lam{lam}")
+    line = {
+        "metric": "retention events/sec (heads*events)",
+        "value": w.heads / (wall / args.steps),
+        "unit": "head-events/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.what}", "heads": w.heads, "n": w.n, "b": b,
+                   "d": w.d, "lambda": lam, "scores": w.scores, "G": w.G if w.scores == "computed" else 0},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "kvr_retain (whole step)", "device_ms_avg": dev_avg_ms,
+                     "device_ms_median": dev_ms[len(dev_ms) // 2],
+                     "algorithmic_bytes_per_step": bytes_step},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, data, b, lam)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,136 @@
+/*
+ * kvr -- per-compression-event KV retention step of the alpha selector on one
+ * MI355X (gfx950).  C ABI; every pointer below marked "device" is HIP device
+ * memory owned by the caller, everything else is a plain host value.
+ *
+ * One "head" is one independent selection problem: the n cached tokens of one
+ * (sequence, layer, KV-head), with that head's own K rows, V rows and base
+ * scores.  The library runs all `heads` problems of a call in one launch
+ * sequence on the caller's stream.
+ *
+ * The method (paper Sec. 4.1 "Method: A V-Space Diversity Penalty"):
+ *   - V-signature  v_i = V_i / (||V_i||_2 + eps)                    (Eq. 1,
+ *     one layer and one head per problem)
+ *   - marginal gain  s_i - lambda * max(0, max_{j in S} v_i . v_j)  (Eq. 2)
+ *   - greedy fill: first pick argmax s, then argmax of the marginal gain over
+ *     unselected tokens, b-1 times                                  (Eq. 3,
+ *     Algorithm 1; b is the paper's k)
+ *   - lambda == 0 returns top-b(s) through an explicit branch that never
+ *     touches V                                                     (Alg. 1)
+ *   - the cache keeps the selected rows in ascending token order    (Alg. 1
+ *     returns sort(S); Sec. 1)
+ * Every argmax breaks ties towards the lowest token index.
+ *
+ * Common rules
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and return without synchronising.
+ *   - Inputs are read-only; outputs must not alias inputs or each other.
+ *   - The library allocates no device memory and keeps no state between
+ *     calls.  `workspace` is reserved for future kernels: every entry point
+ *     accepts NULL / 0 as long as kvr_workspace_bytes() reports 0 for the
+ *     same arguments.
+ *   - Return value: KVR_OK or a negative kvr_status.  Argument errors are
+ *     detected on the host before anything is launched.  Non-finite scores or
+ *     rows give unspecified picks (but never out-of-range indices).
+ *   - Device pointers must be 16-byte aligned; d must be 128 (the head
+ *     dimension of every benchmark configuration); strides are in elements,
+ *     stride_tok >= d and a multiple of 8, stride_head >= n*stride_tok and a
+ *     multiple of 8.
+ */
+#ifndef KVR_H_
+#define KVR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVR_OK = 0,
+  KVR_ERR_ARG = -1,        /* NULL pointer, bad size, b<1, b>n, lambda<0/NaN, G<1, misaligned */
+  KVR_ERR_UNSUPPORTED = -2,/* d != 128, unknown dtype, n or G above the limits below */
+  KVR_ERR_WORKSPACE = -3,  /* workspace smaller than kvr_workspace_bytes() */
+  KVR_ERR_HIP = -4         /* a HIP launch or runtime call failed */
+} kvr_status;
+
+typedef enum { KVR_F32 = 0, KVR_BF16 = 1 } kvr_dtype;
+
+#define KVR_MAX_N 8192     /* candidates per head */
+#define KVR_MAX_G 64       /* grouped queries per KV head */
+
+/* Layout of a [heads, n, d] tensor of cached rows; d is contiguous. */
+typedef struct {
+  int32_t heads;           /* sequences * layers * kv_heads, flattened */
+  int32_t n;               /* candidate tokens per head, 1..KVR_MAX_N */
+  int32_t d;               /* head dimension (128) */
+  int32_t dtype;           /* kvr_dtype of K, V, Q and of the compacted rows */
+  int64_t stride_head;     /* elements between consecutive heads */
+  int64_t stride_tok;      /* elements between consecutive tokens */
+} kvr_layout;
+
+int kvr_version(void);
+const char* kvr_strerror(int status);
+
+/* Bytes of caller-provided device workspace the calls below need for these
+ * arguments (currently always 0).  Host-only; returns a kvr_status. */
+int kvr_workspace_bytes(const kvr_layout* lay, int b, int G, size_t* bytes_out);
+
+/*
+ * Base scores, the stand-in for the paper's external scorer (Sec. 4.1 takes s
+ * as given): s_i = (1/G) sum_g softmax_i(q_g . k_i / sqrt(d)), the softmax
+ * taken over the n tokens of the head, no mask.
+ *   K      device, [heads, n, d] per `lay`
+ *   Q      device, dense [heads, G, d], same dtype as K
+ *   s_out  device, dense float32 [heads, n]
+ */
+int kvr_score(const void* K, const void* Q, int G, const kvr_layout* lay,
+              float* s_out, void* stream);
+
+/*
+ * Algorithm 1 for every head: greedy selection of b tokens under the V-space
+ * redundancy penalty (Eq. 2-3); lambda == 0 is top-b of s and reads no V.
+ *   V           device, [heads, n, d] per `lay` (may be NULL iff lambda == 0)
+ *   s           device, dense float32 [heads, n]
+ *   idx_sorted  device, int32 [heads, b], ascending token indices (sort(S))
+ *   pick_order  device, int32 [heads, b] or NULL: picks in the order made
+ *   pick_gain   device, float32 [heads, b] or NULL: marginal gain of each pick
+ *               when it was made (pick_gain[0] = max s; with lambda == 0 the
+ *               t-th largest score)
+ */
+int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay,
+                      int b, float lambda, float eps,
+                      int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Cache update: K_out[h,t,:] = K[h, idx[h,t], :] and the same for V, copied
+ * bit for bit.  Either of K / V (with its output) may be NULL to skip it.
+ *   idx           device, int32 [heads, b], every entry in [0, n)
+ *   K_out, V_out  device, dense [heads, b, d], dtype of `lay`
+ * An index outside [0, n) is clamped into range rather than read out of
+ * bounds (the output row is then meaningless).
+ */
+int kvr_compact(const void* K, const void* V, const kvr_layout* lay,
+                const int32_t* idx, int b, void* K_out, void* V_out, void* stream);
+
+/*
+ * The whole event in one call: score (when Q is given) -> select -> compact.
+ * Exactly one of (Q, G >= 1) and s_in must be provided:
+ *   Q != NULL: scores are computed as in kvr_score; s_out (device, dense
+ *              float32 [heads, n], required) receives them.
+ *   Q == NULL: s_in (device, dense float32 [heads, n]) is used; G is ignored.
+ * Outputs as in kvr_select_greedy and kvr_compact; pick_order and pick_gain
+ * may be NULL.
+ */
+int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* s_in,
+               const kvr_layout* lay, int b, float lambda, float eps,
+               float* s_out, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+               void* K_out, void* V_out,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVR_H_ */

@@ -1,0 +1,187 @@
+"""ctypes binding of libkvr.so: argument marshalling only.
+
+Every function has the name and the meaning of the C entry point declared in
+include/kvr.h; tensors are torch device tensors used as plain device buffers.
+The library is required: importing this module without a built libkvr.so, or
+calling it without a GPU, raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvr.so")
+
+KVR_F32, KVR_BF16 = 0, 1
+KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
+           "kvr_select_greedy", "kvr_compact", "kvr_retain")
+
+
+class kvr_layout(ctypes.Structure):
+    _fields_ = [("heads", ctypes.c_int32), ("n", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("stride_head", ctypes.c_int64),
+                ("stride_tok", ctypes.c_int64)]
+
+
+class KvrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2605_14292_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lp = ctypes.POINTER(kvr_layout)
+    lib.kvr_version.restype = i32
+    lib.kvr_strerror.restype = ctypes.c_char_p
+    lib.kvr_strerror.argtypes = [i32]
+    lib.kvr_workspace_bytes.restype = i32
+    lib.kvr_workspace_bytes.argtypes = [lp, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.kvr_score.restype = i32
+    lib.kvr_score.argtypes = [vp, vp, i32, lp, vp, vp]
+    lib.kvr_select_greedy.restype = i32
+    lib.kvr_select_greedy.argtypes = [vp, vp, lp, i32, f32, f32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.kvr_compact.restype = i32
+    lib.kvr_compact.argtypes = [vp, vp, lp, vp, i32, vp, vp, vp]
+    lib.kvr_retain.restype = i32
+    lib.kvr_retain.argtypes = [vp, vp, vp, i32, vp, lp, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp,
+                               ctypes.c_size_t, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return _lib.kvr_strerror(int(status)).decode()
+
+
+def kvr_version() -> int:
+    return int(_lib.kvr_version())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def layout_of(x: torch.Tensor) -> kvr_layout:
+    """Layout of a [heads, n, d] device tensor (last dim contiguous)."""
+    if x.dim() != 3 or x.stride(2) != 1:
+        raise ValueError("expected a [heads, n, d] tensor with contiguous d")
+    if x.dtype == torch.bfloat16:
+        dt = KVR_BF16
+    elif x.dtype == torch.float32:
+        dt = KVR_F32
+    else:
+        raise ValueError("dtype must be bfloat16 or float32")
+    return kvr_layout(x.shape[0], x.shape[1], x.shape[2], dt, x.stride(0), x.stride(1))
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("kvr takes device tensors only (no CPU fallback exists)")
+
+
+def _check(rc: int, where: str):
+    if rc != KVR_OK:
+        raise KvrError(rc, where)
+
+
+def kvr_workspace_bytes(lay: kvr_layout, b: int, G: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(_lib.kvr_workspace_bytes(ctypes.byref(lay), b, G, ctypes.byref(out)), "kvr_workspace_bytes")
+    return int(out.value)
+
+
+def kvr_score(K, Q, s_out=None, stream=None):
+    _need_cuda(K, Q, s_out)
+    lay = layout_of(K)
+    G = Q.shape[1]
+    if s_out is None:
+        s_out = torch.empty((lay.heads, lay.n), dtype=torch.float32, device=K.device)
+    _check(_lib.kvr_score(_ptr(K), _ptr(Q), G, ctypes.byref(lay), _ptr(s_out), _stream(stream)),
+           "kvr_score")
+    return s_out
+
+
+def kvr_select_greedy(V, s, b, lam, eps=1e-6, idx_sorted=None, pick_order=None, pick_gain=None,
+                      want_trace=True, stream=None, lay=None):
+    _need_cuda(V, s, idx_sorted, pick_order, pick_gain)
+    if lay is None:
+        lay = layout_of(V)
+    dev = s.device
+    if idx_sorted is None:
+        idx_sorted = torch.empty((lay.heads, b), dtype=torch.int32, device=dev)
+    if want_trace:
+        if pick_order is None:
+            pick_order = torch.empty((lay.heads, b), dtype=torch.int32, device=dev)
+        if pick_gain is None:
+            pick_gain = torch.empty((lay.heads, b), dtype=torch.float32, device=dev)
+    _check(_lib.kvr_select_greedy(_ptr(V), _ptr(s), ctypes.byref(lay), b, lam, eps,
+                                  _ptr(idx_sorted), _ptr(pick_order), _ptr(pick_gain),
+                                  None, 0, _stream(stream)), "kvr_select_greedy")
+    return idx_sorted, pick_order, pick_gain
+
+
+def kvr_compact(K, V, idx, K_out=None, V_out=None, stream=None):
+    _need_cuda(K, V, idx, K_out, V_out)
+    ref = K if K is not None else V
+    lay = layout_of(ref)
+    b = idx.shape[1]
+    if K is not None and K_out is None:
+        K_out = torch.empty((lay.heads, b, lay.d), dtype=K.dtype, device=K.device)
+    if V is not None and V_out is None:
+        V_out = torch.empty((lay.heads, b, lay.d), dtype=V.dtype, device=V.device)
+    _check(_lib.kvr_compact(_ptr(K), _ptr(V), ctypes.byref(lay), _ptr(idx), b, _ptr(K_out),
+                            _ptr(V_out), _stream(stream)), "kvr_compact")
+    return K_out, V_out
+
+
+class RetainBuffers:
+    """Preallocated outputs of kvr_retain for one shape (so a timed loop
+    allocates nothing)."""
+
+    def __init__(self, heads, n, b, d, dtype, device, computed_scores, want_trace=True):
+        self.idx_sorted = torch.empty((heads, b), dtype=torch.int32, device=device)
+        self.pick_order = torch.empty((heads, b), dtype=torch.int32, device=device) if want_trace else None
+        self.pick_gain = torch.empty((heads, b), dtype=torch.float32, device=device) if want_trace else None
+        self.K_out = torch.empty((heads, b, d), dtype=dtype, device=device)
+        self.V_out = torch.empty((heads, b, d), dtype=dtype, device=device)
+        self.s_out = torch.empty((heads, n), dtype=torch.float32, device=device) if computed_scores else None
+
+
+def kvr_retain(K, V, b, lam, eps=1e-6, Q=None, s=None, out: RetainBuffers | None = None,
+               want_trace=True, stream=None):
+    _need_cuda(K, V, Q, s)
+    lay = layout_of(K)
+    if layout_of(V).stride_head != lay.stride_head or layout_of(V).stride_tok != lay.stride_tok:
+        raise ValueError("K and V must share one layout")
+    if out is None:
+        out = RetainBuffers(lay.heads, lay.n, b, lay.d, K.dtype, K.device, Q is not None, want_trace)
+    G = 0 if Q is None else Q.shape[1]
+    _check(_lib.kvr_retain(_ptr(K), _ptr(V), _ptr(Q), G, _ptr(s), ctypes.byref(lay), b, lam, eps,
+                           _ptr(out.s_out), _ptr(out.idx_sorted), _ptr(out.pick_order),
+                           _ptr(out.pick_gain), _ptr(out.K_out), _ptr(out.V_out), None, 0,
+                           _stream(stream)), "kvr_retain")
+    return out

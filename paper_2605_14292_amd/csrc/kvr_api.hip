@@ -1,0 +1,139 @@
+// C-ABI entry points: argument validation on the host, then kernel launches on
+// the caller's stream.  Nothing here allocates, synchronises or keeps state.
+#include "../../include/kvr.h"
+
+#include <cmath>
+
+#include "kvr_kernels.hpp"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_layout(const kvr_layout* lay) {
+  if (!lay) return KVR_ERR_ARG;
+  if (lay->heads < 1 || lay->n < 1) return KVR_ERR_ARG;
+  if (lay->dtype != KVR_F32 && lay->dtype != KVR_BF16) return KVR_ERR_UNSUPPORTED;
+  if (lay->d != 128) return KVR_ERR_UNSUPPORTED;
+  if (lay->n > KVR_MAX_N) return KVR_ERR_UNSUPPORTED;
+  if (lay->stride_tok < lay->d || (lay->stride_tok & 7)) return KVR_ERR_ARG;
+  if (lay->stride_head < static_cast<int64_t>(lay->n) * lay->stride_tok || (lay->stride_head & 7))
+    return KVR_ERR_ARG;
+  if (lay->heads > 65535 * 1024) return KVR_ERR_UNSUPPORTED;
+  return KVR_OK;
+}
+
+kvr::Layout to_dev(const kvr_layout* lay) {
+  kvr::Layout l;
+  l.heads = lay->heads; l.n = lay->n; l.d = lay->d; l.dtype = lay->dtype;
+  l.stride_head = lay->stride_head; l.stride_tok = lay->stride_tok;
+  return l;
+}
+
+int check_select(const kvr_layout* lay, int b, float lambda, float eps) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (b < 1 || b > lay->n) return KVR_ERR_ARG;
+  if (!(lambda >= 0.0f) || std::isinf(lambda)) return KVR_ERR_ARG;
+  if (!(eps >= 0.0f) || std::isinf(eps)) return KVR_ERR_ARG;
+  return KVR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvr_version(void) { return 1; }
+
+const char* kvr_strerror(int status) {
+  switch (status) {
+    case KVR_OK: return "ok";
+    case KVR_ERR_ARG: return "invalid argument";
+    case KVR_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case KVR_ERR_WORKSPACE: return "workspace too small";
+    case KVR_ERR_HIP: return "HIP launch failed";
+    default: return "unknown kvr status";
+  }
+}
+
+int kvr_workspace_bytes(const kvr_layout* lay, int b, int G, size_t* bytes_out) {
+  if (!bytes_out) return KVR_ERR_ARG;
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (b < 1 || b > lay->n || G < 0 || G > KVR_MAX_G) return KVR_ERR_ARG;
+  *bytes_out = 0;
+  return KVR_OK;
+}
+
+int kvr_score(const void* K, const void* Q, int G, const kvr_layout* lay, float* s_out,
+              void* stream) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (!K || !Q || !s_out) return KVR_ERR_ARG;
+  if (G < 1) return KVR_ERR_ARG;
+  if (G > KVR_MAX_G) return KVR_ERR_UNSUPPORTED;
+  if (!aligned16(K) || !aligned16(Q) || !aligned16(s_out)) return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_score(K, Q, G, to_dev(lay), s_out, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
+int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay, int b, float lambda,
+                      float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  const int rc = check_select(lay, b, lambda, eps);
+  if (rc) return rc;
+  if (!s || !idx_sorted) return KVR_ERR_ARG;
+  if (lambda != 0.0f && !V) return KVR_ERR_ARG;
+  if ((V && !aligned16(V)) || !aligned16(s)) return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_select_generic(V, s, to_dev(lay), b, lambda, eps, idx_sorted,
+                                                  pick_order, pick_gain,
+                                                  static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
+int kvr_compact(const void* K, const void* V, const kvr_layout* lay, const int32_t* idx, int b,
+                void* K_out, void* V_out, void* stream) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (b < 1 || b > lay->n || !idx) return KVR_ERR_ARG;
+  if ((K == nullptr) != (K_out == nullptr) || (V == nullptr) != (V_out == nullptr)) return KVR_ERR_ARG;
+  if (!K && !V) return KVR_ERR_ARG;
+  if ((K && (!aligned16(K) || !aligned16(K_out))) || (V && (!aligned16(V) || !aligned16(V_out))))
+    return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_compact(K, V, to_dev(lay), idx, b, K_out, V_out,
+                                           static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
+int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* s_in,
+               const kvr_layout* lay, int b, float lambda, float eps, float* s_out,
+               int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
+               void* V_out, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  const int rc = check_select(lay, b, lambda, eps);
+  if (rc) return rc;
+  if (!K || !V || !idx_sorted || !K_out || !V_out) return KVR_ERR_ARG;
+  if ((Q == nullptr) == (s_in == nullptr)) return KVR_ERR_ARG;
+  if (Q && (G < 1)) return KVR_ERR_ARG;
+  if (Q && G > KVR_MAX_G) return KVR_ERR_UNSUPPORTED;
+  if (Q && !s_out) return KVR_ERR_ARG;  // the computed scores need somewhere to live
+  if (!aligned16(K) || !aligned16(V) || !aligned16(K_out) || !aligned16(V_out) ||
+      (Q && !aligned16(Q)) || (s_in && !aligned16(s_in)) || (s_out && !aligned16(s_out)))
+    return KVR_ERR_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const kvr::Layout l = to_dev(lay);
+  const float* s = s_in;
+  if (Q) {
+    if (kvr::launch_score(K, Q, G, l, s_out, st) != hipSuccess) return KVR_ERR_HIP;
+    s = s_out;
+  }
+  if (kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) !=
+      hipSuccess)
+    return KVR_ERR_HIP;
+  if (kvr::launch_compact(K, V, l, idx_sorted, b, K_out, V_out, st) != hipSuccess)
+    return KVR_ERR_HIP;
+  return KVR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,193 @@
+// Base scores: s_i = (1/G) sum_g softmax_i(q_g . k_i / sqrt(d)).
+// (Stand-in for the external scorer of paper Sec. 4.1, which takes s as given.)
+//
+// One workgroup per head.  A group of 16 lanes owns one K row per step (16
+// bytes of bf16 or 32 bytes of fp32 per lane, so a wave reads four whole rows
+// with one coalesced request); the query slices a lane needs stay in
+// registers.  The logits of the head are kept in LDS when G*n floats fit, so K
+// is read from HBM exactly once; otherwise the logits are recomputed in a
+// second pass.
+#include "kvr_device.hpp"
+#include "kvr_kernels.hpp"
+
+namespace kvr {
+
+constexpr int kScoreThreads = 256;
+constexpr int kGT = 8;                       // queries handled per register tile
+constexpr int kZMaxFloats = 16384;           // logits kept in LDS (64 KB)
+
+template <int DT>
+__device__ __forceinline__ void row_logits(const char* Kh, long long stride_tok, int j, int c,
+                                           const float (&q)[kGT][8], int gcount, float scale,
+                                           float (&z)[kGT]) {
+  float k[8];
+  load8<DT>(Kh + (static_cast<long long>(j) * stride_tok + c * 8) * elem_bytes<DT>(), k);
+#pragma unroll
+  for (int g = 0; g < kGT; ++g) {
+    float acc = 0.f;
+    if (g < gcount) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc = fmaf(k[e], q[g][e], acc);
+      acc = group16_sum(acc) * scale;
+    }
+    z[g] = acc;
+  }
+}
+
+template <int DT, bool ZFITS>
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __restrict__ K,
+                                                              const void* __restrict__ Q, int G,
+                                                              Layout lay,
+                                                              float* __restrict__ s_out) {
+  extern __shared__ float smem[];
+  // smem: zbuf[G*n] (ZFITS) | acc[n] ; then red[2*kGT*4]
+  const int n = lay.n;
+  float* zbuf = smem;                                 // ZFITS: [G][n]
+  float* acc = smem + (ZFITS ? G * n : 0);            // [n] running mean
+  float* red = acc + n;                               // [4 waves][kGT] x2
+  const int h = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15;                            // 16-byte chunk of the row
+  const int rsub = tid >> 4;                          // row within a step (0..15)
+  const char* Kh = static_cast<const char*>(K) + h * lay.stride_head * elem_bytes<DT>();
+  const char* Qh = static_cast<const char*>(Q) +
+                   static_cast<long long>(h) * G * kD * elem_bytes<DT>();
+  const float scale = 0.08838834764831845f;           // 1/sqrt(128)
+  const float invG = 1.0f / static_cast<float>(G);
+
+  for (int j = tid; j < n; j += kScoreThreads) acc[j] = 0.f;
+
+  for (int g0 = 0; g0 < G; g0 += kGT) {
+    const int gcount = min(kGT, G - g0);
+    float q[kGT][8];
+#pragma unroll
+    for (int g = 0; g < kGT; ++g) {
+      if (g < gcount) {
+        load8<DT>(Qh + (static_cast<long long>(g0 + g) * kD + c * 8) * elem_bytes<DT>(), q[g]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[g][e] = 0.f;
+      }
+    }
+    // pass A: logits, running max per query
+    float zmax[kGT];
+#pragma unroll
+    for (int g = 0; g < kGT; ++g) zmax[g] = -INFINITY;
+    for (int j0 = 0; j0 < n; j0 += kScoreThreads / 16) {
+      const int j = j0 + rsub;
+      if (j < n) {
+        float z[kGT];
+        row_logits<DT>(Kh, lay.stride_tok, j, c, q, gcount, scale, z);
+#pragma unroll
+        for (int g = 0; g < kGT; ++g) {
+          zmax[g] = fmaxf(zmax[g], z[g]);
+          if (ZFITS && c == 0 && g < gcount) zbuf[(g0 + g) * n + j] = z[g];
+        }
+      }
+    }
+    // block max per query
+#pragma unroll
+    for (int g = 0; g < kGT; ++g) {
+      float v = zmax[g];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+      if (lane == 0) red[wave * kGT + g] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < kGT; ++g)
+      zmax[g] = fmaxf(fmaxf(red[g], red[kGT + g]), fmaxf(red[2 * kGT + g], red[3 * kGT + g]));
+    __syncthreads();
+    // pass B: sum of exp per query
+    float zsum[kGT];
+#pragma unroll
+    for (int g = 0; g < kGT; ++g) zsum[g] = 0.f;
+    if (ZFITS) {
+      for (int j = tid; j < n; j += kScoreThreads) {
+#pragma unroll
+        for (int g = 0; g < kGT; ++g)
+          if (g < gcount) {
+            const float e = __expf(zbuf[(g0 + g) * n + j] - zmax[g]);
+            zbuf[(g0 + g) * n + j] = e;
+            zsum[g] += e;
+          }
+      }
+    } else {
+      for (int j0 = 0; j0 < n; j0 += kScoreThreads / 16) {
+        const int j = j0 + rsub;
+        if (j < n) {
+          float z[kGT];
+          row_logits<DT>(Kh, lay.stride_tok, j, c, q, gcount, scale, z);
+          if (c == 0) {
+#pragma unroll
+            for (int g = 0; g < kGT; ++g)
+              if (g < gcount) zsum[g] += __expf(z[g] - zmax[g]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < kGT; ++g) {
+      float v = zsum[g];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+      if (lane == 0) red[wave * kGT + g] = v;
+    }
+    __syncthreads();
+    float rinv[kGT];
+#pragma unroll
+    for (int g = 0; g < kGT; ++g)
+      rinv[g] = 1.0f / (red[g] + red[kGT + g] + red[2 * kGT + g] + red[3 * kGT + g]);
+    __syncthreads();
+    // pass C: accumulate the mean of the softmax rows
+    if (ZFITS) {
+      for (int j = tid; j < n; j += kScoreThreads) {
+        float a = acc[j];
+#pragma unroll
+        for (int g = 0; g < kGT; ++g)
+          if (g < gcount) a = fmaf(zbuf[(g0 + g) * n + j], rinv[g] * invG, a);
+        acc[j] = a;
+      }
+    } else {
+      for (int j0 = 0; j0 < n; j0 += kScoreThreads / 16) {
+        const int j = j0 + rsub;
+        if (j < n) {
+          float z[kGT];
+          row_logits<DT>(Kh, lay.stride_tok, j, c, q, gcount, scale, z);
+          if (c == 0) {
+            float a = acc[j];
+#pragma unroll
+            for (int g = 0; g < kGT; ++g)
+              if (g < gcount) a = fmaf(__expf(z[g] - zmax[g]), rinv[g] * invG, a);
+            acc[j] = a;
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  float* so = s_out + static_cast<long long>(h) * n;
+  for (int j = tid; j < n; j += kScoreThreads) so[j] = acc[j];
+}
+
+hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay, float* s_out,
+                        hipStream_t st) {
+  const bool zfits = static_cast<long long>(G) * lay.n <= kZMaxFloats;
+  const size_t smem = (static_cast<size_t>(zfits ? G * lay.n : 0) + lay.n + 2 * kGT * 4) * 4;
+  dim3 grid(lay.heads), block(kScoreThreads);
+  auto go = [&](auto kern) -> hipError_t {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(smem));
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, block, smem, st, K, Q, G, lay, s_out);
+    return hipSuccess;
+  };
+  hipError_t e;
+  if (lay.dtype == DT_BF16) e = zfits ? go(&score_kernel<DT_BF16, true>) : go(&score_kernel<DT_BF16, false>);
+  else e = zfits ? go(&score_kernel<DT_F32, true>) : go(&score_kernel<DT_F32, false>);
+  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+}  // namespace kvr

@@ -1,0 +1,221 @@
+"""Parity of the HIP path (through the C-ABI) with the fp64 oracle on the five
+benchmark configurations and on edge cases.  Needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import alpha_oracle as O
+from paper_2605_14292_amd import workloads as W
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def B():
+    from paper_2605_14292_amd import binding
+    return binding
+
+
+def _bits(t):
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.int16).numpy() if t.dtype == torch.bfloat16 else t.view(torch.int32).numpy()
+
+
+def _check_heads(w, data, out, b, lam, eps, heads):
+    """Element-by-element comparison for the listed heads of a workload run."""
+    reports = []
+    for h in heads:
+        K64, V64 = W.to_f64(data["K"][h]), W.to_f64(data["V"][h])
+        if "Q" in data:
+            s64 = O.score_softmax_mean(K64, W.to_f64(data["Q"][h]))
+            P.check_scores(out.s_out[h].cpu().numpy(), s64)
+        else:
+            s64 = W.to_f64(data["s"][h])
+        order = out.pick_order[h].cpu().numpy()
+        gain = out.pick_gain[h].cpu().numpy()
+        idx = out.idx_sorted[h].cpu().numpy()
+        reports.append(P.check_head(s64, V64, b, lam, eps, order, gain, idx))
+        # compaction: bit-exact rows at the HIP path's own (validated) index set
+        np.testing.assert_array_equal(_bits(out.K_out[h]), O.compact(_bits(data["K"][h]), idx))
+        np.testing.assert_array_equal(_bits(out.V_out[h]), O.compact(_bits(data["V"][h]), idx))
+    return P.summarize(reports)
+
+
+def _run(w, data, b=None, lam=None, eps=1e-6):
+    b = w.b if b is None else b
+    lam = w.lam if lam is None else lam
+    out = B().kvr_retain(data["K"], data["V"], b, lam, eps, Q=data.get("Q"), s=data.get("s"))
+    torch.cuda.synchronize()
+    return out, b, lam
+
+
+@pytest.mark.parametrize("name,heads", [("c1", 1), ("c2", 112), ("c3", 192), ("c5", 24), ("c4", 6)])
+def test_config_small_slice_every_head(name, heads):
+    w = W.WORKLOADS[name]
+    data = W.generate(w, heads=heads, seed=0, device=DEV)
+    out, b, lam = _run(w, data)
+    rep = _check_heads(w, data, out, b, lam, 1e-6, range(heads))
+    print(f"\n[{name}] {rep}")
+    assert rep["heads"] == heads
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.25, 0.5, 1.0])
+@pytest.mark.parametrize("b", [128, 64])
+def test_c5_lambda_sweep(lam, b):
+    w = W.WORKLOADS["c5"]
+    data = W.generate(w, heads=16, seed=1, device=DEV)
+    out, b, lam = _run(w, data, b=b, lam=lam)
+    rep = _check_heads(w, data, out, b, lam, 1e-6, range(16))
+    print(f"\n[c5 lam={lam} b={b}] {rep}")
+    if lam == 0.0:
+        # exactly the stable top-b of the scores the HIP path itself produced
+        s = out.s_out.cpu().numpy()
+        for h in range(16):
+            want = np.sort(np.argsort(-s[h], kind="stable")[:b])
+            np.testing.assert_array_equal(out.idx_sorted[h].cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("name,sample", [("c3", 48), ("c5", 24), ("c4", 6), ("c2", 112)])
+def test_config_full_size_sampled_heads(name, sample):
+    """The launch configuration the benchmark times: all heads resident in HBM,
+    a fixed random sample of heads checked element by element."""
+    w = W.WORKLOADS[name]
+    data = W.generate(w, seed=0, device=DEV)
+    out, b, lam = _run(w, data)
+    rng = np.random.default_rng(7)
+    heads = sorted(rng.choice(w.heads, size=min(sample, w.heads), replace=False).tolist())
+    rep = _check_heads(w, data, out, b, lam, 1e-6, heads)
+    print(f"\n[{name} full, {w.heads} heads] {rep}")
+    # properties that hold at any size, on every head
+    idx = out.idx_sorted.cpu().numpy()
+    assert idx.min() >= 0 and idx.max() < w.n
+    assert np.all(np.diff(idx, axis=1) > 0)
+    po = np.sort(out.pick_order.cpu().numpy(), axis=1)
+    np.testing.assert_array_equal(po, idx)
+    g = out.pick_gain.cpu().numpy()
+    assert np.all(np.diff(g, axis=1) <= 0)
+
+
+def _mk(h, n, seed, dtype=torch.bfloat16, d=128):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    K = torch.randn((h, n, d), generator=g).to(dtype)
+    V = torch.randn((h, n, d), generator=g).to(dtype)
+    s = torch.rand((h, n), generator=g)
+    return K.to(DEV), V.to(DEV), s.to(DEV)
+
+
+@pytest.mark.parametrize("n,b", [(1, 1), (2, 2), (17, 5), (77, 77), (193, 64), (257, 1), (300, 299),
+                                 (1000, 33), (2049, 40)])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_ragged_sizes(n, b, dtype):
+    K, V, s = _mk(3, n, 1000 + n, dtype)
+    data = {"K": K, "V": V, "s": s}
+    out = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s)
+    torch.cuda.synchronize()
+    w = W.WORKLOADS["c3"]
+    rep = _check_heads(w, data, out, b, 0.5, 1e-6, range(3))
+    assert rep["heads"] == 3
+
+
+def test_exactly_representable_inputs_match_with_zero_near_ties():
+    # signed basis rows (norm 1, eps 0) with duplicates, dyadic scores and
+    # lambda: every quantity is exact in fp32, so the picks must be the
+    # oracle's, pick by pick
+    rng = np.random.default_rng(5)
+    h, n, b, lam = 4, 160, 70, 0.5
+    V = np.zeros((h, n, 128), dtype=np.float32)
+    for hh in range(h):
+        ax = rng.integers(0, 40, size=n)
+        sg = rng.choice([-1.0, 1.0], size=n)
+        V[hh, np.arange(n), ax] = sg
+    s = (rng.permutation(h * n).reshape(h, n) / 1024.0).astype(np.float32)
+    Vt = torch.tensor(V).to(torch.bfloat16).to(DEV)
+    Kt = torch.tensor(rng.normal(size=(h, n, 128)).astype(np.float32)).to(torch.bfloat16).to(DEV)
+    st = torch.tensor(s).to(DEV)
+    out = B().kvr_retain(Kt, Vt, b, lam, 0.0, s=st)
+    torch.cuda.synchronize()
+    for hh in range(h):
+        r = O.alpha_select(s[hh].astype(np.float64), V[hh].astype(np.float64), b, lam, 0.0)
+        np.testing.assert_array_equal(out.pick_order[hh].cpu().numpy(), r["order"])
+        np.testing.assert_array_equal(out.pick_gain[hh].cpu().numpy().astype(np.float64), r["gain"])
+        np.testing.assert_array_equal(out.idx_sorted[hh].cpu().numpy(), r["sorted"])
+
+
+def test_identical_value_rows_and_score_ties():
+    h, n, b = 2, 130, 50
+    K, V, s = _mk(h, n, 3)
+    V[:] = V[:, :1, :]
+    s = torch.floor(s * 8) / 8                    # many exact ties
+    out = B().kvr_retain(K, V, b, 0.75, 1e-6, s=s)
+    torch.cuda.synchronize()
+    data = {"K": K, "V": V, "s": s}
+    _check_heads(W.WORKLOADS["c3"], data, out, b, 0.75, 1e-6, range(h))
+    sn = s.cpu().numpy()
+    for hh in range(h):
+        want = np.argsort(-sn[hh], kind="stable")[:b]
+        np.testing.assert_array_equal(out.pick_order[hh].cpu().numpy(), want)
+
+
+def test_lambda_zero_reads_no_values_and_is_stable_topb():
+    h, n, b = 5, 500, 128
+    K, V, s = _mk(h, n, 4)
+    s = torch.floor(s * 64) / 64
+    lay = B().layout_of(V)
+    idx, order, gain = B().kvr_select_greedy(None, s, b, 0.0, lay=lay)
+    torch.cuda.synchronize()
+    sn = s.cpu().numpy()
+    for hh in range(h):
+        want = np.argsort(-sn[hh], kind="stable")[:b]
+        np.testing.assert_array_equal(order[hh].cpu().numpy(), want)
+        np.testing.assert_array_equal(idx[hh].cpu().numpy(), np.sort(want))
+        np.testing.assert_array_equal(gain[hh].cpu().numpy(), sn[hh][want])
+
+
+def test_strided_layout_and_separate_calls_equal_retain():
+    h, n, b, G = 6, 200, 48, 3
+    g = torch.Generator(device="cpu").manual_seed(9)
+    big = torch.randn((h, n + 5, 136), generator=g).to(torch.bfloat16).to(DEV)
+    bigv = torch.randn((h, n + 5, 136), generator=g).to(torch.bfloat16).to(DEV)
+    K, V = big[:, :n, :128], bigv[:, :n, :128]
+    Q = torch.randn((h, G, 128), generator=g).to(torch.bfloat16).to(DEV)
+    out = B().kvr_retain(K, V, b, 0.5, 1e-6, Q=Q)
+    s = B().kvr_score(K, Q)
+    idx, order, gain = B().kvr_select_greedy(V, s, b, 0.5, 1e-6)
+    Ko, Vo = B().kvr_compact(K, V, idx)
+    torch.cuda.synchronize()
+    assert torch.equal(s, out.s_out) and torch.equal(idx, out.idx_sorted)
+    assert torch.equal(order, out.pick_order) and torch.equal(gain, out.pick_gain)
+    assert torch.equal(Ko, out.K_out) and torch.equal(Vo, out.V_out)
+    data = {"K": K.contiguous(), "V": V.contiguous(), "Q": Q}
+    _check_heads(W.WORKLOADS["c2"], data, out, b, 0.5, 1e-6, range(h))
+
+
+def test_compact_alone_and_idempotence():
+    h, n, b = 3, 100, 20
+    K, V, _ = _mk(h, n, 11)
+    rng = np.random.default_rng(0)
+    idx = np.stack([np.sort(rng.choice(n, b, replace=False)) for _ in range(h)]).astype(np.int32)
+    it = torch.tensor(idx).to(DEV)
+    Ko, Vo = B().kvr_compact(K, V, it)
+    torch.cuda.synchronize()
+    for hh in range(h):
+        np.testing.assert_array_equal(_bits(Ko[hh]), O.compact(_bits(K[hh]), idx[hh]))
+        np.testing.assert_array_equal(_bits(Vo[hh]), O.compact(_bits(V[hh]), idx[hh]))
+    ident = torch.arange(b, dtype=torch.int32, device=DEV).repeat(h, 1)
+    K2, _ = B().kvr_compact(Ko, None, ident)
+    torch.cuda.synchronize()
+    assert torch.equal(K2, Ko)
+
+
+def test_runs_are_deterministic_and_stream_independent():
+    w = W.WORKLOADS["c2"]
+    data = W.generate(w, heads=32, seed=3, device=DEV)
+    a, _, _ = _run(w, data)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        b2 = B().kvr_retain(data["K"], data["V"], w.b, w.lam, 1e-6, Q=data["Q"], stream=st)
+    st.synchronize()
+    for f in ("idx_sorted", "pick_order", "pick_gain", "K_out", "V_out", "s_out"):
+        assert torch.equal(getattr(a, f), getattr(b2, f)), f
