@@ -19,13 +19,13 @@ __global__ __launch_bounds__(kSelThreads) void select_generic_kernel(
   extern __shared__ float smem[];
   const int n = lay.n;
   const int nwords = (n + 31) >> 5;
-  float* sc = smem;                         // [n] scores
+  unsigned long long* red = reinterpret_cast<unsigned long long*>(smem);   // [4] wave maxima
+  float* sc = smem + 8;                     // [n] scores
   float* m = sc + n;                        // [n] running max cosine (floored at 0)
   float* r = m + n;                         // [n] 1/(||V_j|| + eps)
   float* vi = r + n;                        // [128] current pick's row times r_i
   uint32_t* selw = reinterpret_cast<uint32_t*>(vi + kD);          // [nwords] selected bits
   uint32_t* woff = selw + nwords;                                  // [nwords] prefix counts
-  unsigned long long* red = reinterpret_cast<unsigned long long*>(woff + nwords + (nwords & 1));
 
   const int h = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -126,8 +126,7 @@ hipError_t launch_select_generic(const void* V, const float* s, const Layout& la
                                  float lambda, float eps, int32_t* idx_sorted,
                                  int32_t* pick_order, float* pick_gain, hipStream_t st) {
   const int nwords = (lay.n + 31) >> 5;
-  const size_t smem = (3 * static_cast<size_t>(lay.n) + kD) * 4 +
-                      (2 * static_cast<size_t>(nwords) + (nwords & 1)) * 4 + 4 * 8;
+  const size_t smem = (8 + 3 * static_cast<size_t>(lay.n) + kD + 2 * static_cast<size_t>(nwords)) * 4;
   dim3 grid(lay.heads), block(kSelThreads);
   hipError_t e;
   if (lay.dtype == DT_BF16) {
