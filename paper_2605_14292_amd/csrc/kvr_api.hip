@@ -86,9 +86,14 @@ int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay, int 
   if (!s || !idx_sorted) return KVR_ERR_ARG;
   if (lambda != 0.0f && !V) return KVR_ERR_ARG;
   if ((V && !aligned16(V)) || !aligned16(s)) return KVR_ERR_ARG;
-  const hipError_t e = kvr::launch_select_generic(V, s, to_dev(lay), b, lambda, eps, idx_sorted,
-                                                  pick_order, pick_gain,
-                                                  static_cast<hipStream_t>(stream));
+  const kvr::Layout l = to_dev(lay);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (kvr::dense_supported(l, b, 0, false))
+    e = kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
+                                 pick_order, pick_gain, nullptr, nullptr, st);
+  else
+    e = kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
   return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
 }
 
@@ -124,6 +129,11 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const kvr::Layout l = to_dev(lay);
   const float* s = s_in;
+  if (kvr::dense_supported(l, b, G, Q != nullptr)) {
+    const hipError_t e = kvr::launch_retain_dense(K, V, Q, G, s_in, l, b, lambda, eps, s_out, idx_sorted,
+                                                  pick_order, pick_gain, K_out, V_out, st);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+  }
   if (Q) {
     if (kvr::launch_score(K, Q, G, l, s_out, st) != hipSuccess) return KVR_ERR_HIP;
     s = s_out;

@@ -18,4 +18,12 @@ hipError_t launch_select_generic(const void* V, const float* s, const Layout& la
 hipError_t launch_compact(const void* K, const void* V, const Layout& lay, const int32_t* idx,
                           int b, void* K_out, void* V_out, hipStream_t st);
 
+// Fused path for bf16 heads with n <= 256 (any of K/Q/K_out/V_out may be null
+// to skip scoring or compaction).
+bool dense_supported(const Layout& lay, int b, int G, bool has_q);
+hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                               const Layout& lay, int b, float lambda, float eps, float* s_out,
+                               int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                               void* K_out, void* V_out, hipStream_t st);
+
 }  // namespace kvr
