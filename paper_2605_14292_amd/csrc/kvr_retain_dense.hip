@@ -53,14 +53,38 @@ __host__ __device__ constexpr int dense_smem_bytes(int NT) {
     v += __int_as_float(_o);                                                                   \
   }
 
+// Max over the wave, returned wave-uniform.  Each step is one v_max_f32 with a
+// DPP source (the compiler's own lowering of a DPP move plus fmaxf costs four
+// instructions a step, which is most of a pick's latency); lanes whose DPP
+// source is out of range keep their value.  s_nop 1 covers the two wait states
+// a DPP read needs after a VALU write of the same register.
 __device__ __forceinline__ float wave_max_uniform(float v) {
-  KVR_DPP_MAX(v, 0x111, 0xf)   // row_shr:1
-  KVR_DPP_MAX(v, 0x112, 0xf)   // row_shr:2
-  KVR_DPP_MAX(v, 0x114, 0xf)   // row_shr:4
-  KVR_DPP_MAX(v, 0x118, 0xf)   // row_shr:8
-  KVR_DPP_MAX(v, 0x142, 0xa)   // row_bcast:15 into rows 1 and 3
-  KVR_DPP_MAX(v, 0x143, 0xc)   // row_bcast:31 into rows 2 and 3
+  asm volatile(
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(v));
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// Orders LDS traffic between the lanes of one wave.  Lanes of a wave run in
+// lock-step and the LDS pipeline is in order, but the compiler reasons per
+// thread: without a fence it may forward a lane's own earlier store to a load
+// that another lane has overwritten in between.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// max(a, b) as the hardware does it (a NaN operand yields the other one), without
+// the canonicalising self-max the compiler adds around fmaxf on loaded values
+__device__ __forceinline__ float hw_max(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
 }
 // max / sum over each half of the wave (lanes 0-31 and 32-63); valid in lanes 31 and 63
 __device__ __forceinline__ float half_max_at_31(float v) {
@@ -210,7 +234,7 @@ __global__ __launch_bounds__(kDenseThreads) void retain_dense_kernel(DenseArgs a
       p += __shfl_xor(p, 32, kWave);                 // queries 0-3 live in lanes 0-31, 4-7 in 32-63
       const int j = I * 32 + (lane & 31);
       if (I < NT && hf == 0) {
-        s_l[j] = p;
+        s_l[j] = j < n ? p : -INFINITY;               // padding never competes
         if (j < n && a.s_out) a.s_out[static_cast<long long>(h) * n + j] = p;
       }
     }
@@ -276,59 +300,74 @@ __global__ __launch_bounds__(kDenseThreads) void retain_dense_kernel(DenseArgs a
 
   // ------------------------------------------------------------------ greedy
   if (wave == 0) {
+    // Token j lives in lane j%64, slot j/64.  A selected (or padding) token has
+    // its score replaced by -inf, so its gain is -inf and it never ties with a
+    // finite maximum; the exact selected set is rebuilt from the pick list.
     float sreg[NQ], mreg[NQ];
-    bool on[NQ];                                     // token still unselected (false for padding)
-    int tjb[NQ];
+    int jb4[NQ], tjb4[NQ];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
       const int j = lane + 64 * q;
-      sreg[q] = s_l[j];
+      sreg[q] = s_l[j];                                // -inf beyond n
       mreg[q] = 0.f;
-      on[q] = j < n;
-      tjb[q] = j * (j + 1) / 2;
+      jb4[q] = j * 4;
+      tjb4[q] = (j * (j + 1) / 2) * 4;
     }
     const float nlam = -a.lambda;
+    const char* trib = reinterpret_cast<const char*>(tri);
     for (int t = 0; t < b; ++t) {
       float av[NQ];
-      float best = -INFINITY;
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        av[q] = on[q] ? fmaf(nlam, mreg[q], sreg[q]) : -INFINITY;
-        best = fmaxf(best, av[q]);
-      }
+      for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
+      float best = av[0];
+#pragma unroll
+      for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
       const float amax = wave_max_uniform(best);
       int i = -1;
 #pragma unroll
       for (int q = NQ - 1; q >= 0; --q) {
-        const unsigned long long eq = __ballot(on[q] && av[q] == amax);
+        const unsigned long long eq = __ballot(av[q] == amax);
         if (eq) i = (__ffsll(static_cast<long long>(eq)) - 1) + 64 * q;
       }
-      if (i < 0) {                                   // only with non-finite gains: lowest unselected token
+      if (!(amax > -INFINITY)) {
+        // Non-finite input only: every remaining gain is -inf or NaN.  Take the
+        // lowest token that is not in the pick list yet (slow, never on finite data).
+        i = -1;
 #pragma unroll
         for (int q = NQ - 1; q >= 0; --q) {
-          const unsigned long long al = __ballot(on[q]);
+          const int j = lane + 64 * q;
+          bool free_tok = j < n;
+          wave_lds_sync();                             // order_l is written by lane 0
+          for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
+          const unsigned long long al = __ballot(free_tok);
           if (al) i = (__ffsll(static_cast<long long>(al)) - 1) + 64 * q;
         }
       }
 #pragma unroll
-      for (int q = 0; q < NQ; ++q)
-        if (lane + 64 * q == i) on[q] = false;
+      for (int q = 0; q < NQ; ++q) sreg[q] = (jb4[q] == i * 4) ? -INFINITY : sreg[q];
       if (lane == 0) { order_l[t] = i; gain_l[t] = amax; }
       if (t + 1 == b || !diverse) continue;
-      const int ti = i * (i + 1) / 2;
+      // row i of the packed triangle: element (i,j) sits at max(T(i)+j, T(j)+i)
+      const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
 #pragma unroll
       for (int q = 0; q < NQ; ++q) {
-        const int j = lane + 64 * q;
-        const int addr = j <= i ? ti + j : tjb[q] + i;
-        mreg[q] = fmaxf(mreg[q], tri[addr]);
+        const int a0 = ti4 + jb4[q], a1 = tjb4[q] + i4;
+        const float c = *reinterpret_cast<const float*>(trib + (a0 > a1 ? a0 : a1));
+        mreg[q] = hw_max(mreg[q], c);
       }
     }
-    // sort(S): ascending indices from the selected masks
+    // sort(S): flag the picked tokens, then ascending indices by prefix popcount
+    int32_t* flag = reinterpret_cast<int32_t*>(rinv);   // rinv is dead by now
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) flag[lane + 64 * q] = 0;
+    wave_lds_sync();                                   // order_l was written by lane 0
+    for (int u = lane; u < b; u += kWave) flag[order_l[u]] = 1;
+    wave_lds_sync();                                   // flags are set by other lanes
     int off = 0;
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
       const int j = lane + 64 * q;
-      const bool picked = j < n && !on[q];
+      const bool picked = flag[j] != 0;
       const unsigned long long sel = __ballot(picked);
       if (picked) {
         const int rank = __popcll(sel & ((1ull << lane) - 1ull));
@@ -351,7 +390,8 @@ __global__ __launch_bounds__(kDenseThreads) void retain_dense_kernel(DenseArgs a
     for (int t0 = 0; t0 < b; t0 += kDenseThreads / 16) {
       const int t = t0 + (tid >> 4);
       if (t < b) {
-        const long long src = head_off + (idx_l[t] * a.stride_tok + chunk * 8) * 2;
+        const int it = min(max(idx_l[t], 0), n - 1);   // never read outside the head, whatever the scores were
+        const long long src = head_off + (it * a.stride_tok + chunk * 8) * 2;
         const long long dst = ((ob + t) * kD + chunk * 8) * 2;
         uint4 kv, vv;
         if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
