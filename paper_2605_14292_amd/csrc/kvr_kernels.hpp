@@ -26,4 +26,11 @@ hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int 
                                int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                                void* K_out, void* V_out, hipStream_t st);
 
+// Speculative row-block path for bf16 heads with 256 < n <= 4096 (selection plus
+// optional compaction; scores come in through s).
+bool blocked_supported(const Layout& lay, int b);
+hipError_t launch_select_blocked(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                                 float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
+                                 float* pick_gain, void* K_out, void* V_out, hipStream_t st);
+
 }  // namespace kvr
