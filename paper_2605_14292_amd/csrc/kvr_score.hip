@@ -170,8 +170,133 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
   for (int j = tid; j < n; j += kScoreThreads) so[j] = acc[j];
 }
 
+// ---------------------------------------------------------------------------
+// bf16, G <= 8: the logits are a thin dense contraction ([G x d] x [d x n]), so
+// they go through the matrix cores.  K is streamed from HBM once, 128 tokens at a
+// time: coalesced 16-byte loads into registers (the next chunk is in flight while
+// the current one is multiplied), a padded LDS stage, MFMA fragments out of LDS.
+// The logits of the head wait in LDS for the softmax.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+constexpr int kStageTok = 128;
+constexpr int kStagePitch = 272;   // 256 + 16 bytes: consecutive rows land in different banks
+
+__global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* __restrict__ K,
+                                                                   const char* __restrict__ Q, int G,
+                                                                   Layout lay,
+                                                                   float* __restrict__ s_out) {
+  extern __shared__ __align__(16) char smem_raw[];
+  char* stage = smem_raw;                                                   // [128][272]
+  float* zbuf = reinterpret_cast<float*>(smem_raw + kStageTok * kStagePitch);  // [G][n]
+  const int n = lay.n;
+  float* red = zbuf + G * n;                                                // [64]
+  const int h = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const char* Kh = K + h * lay.stride_head * 2;
+  bf16x8 qf[8];
+  {
+    const int g = lane & 31;
+    const char* qp = Q + (static_cast<long long>(h) * G + g) * kD * 2 + hf * 16;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      uint4 w = make_uint4(0u, 0u, 0u, 0u);
+      if (g < G) w = *reinterpret_cast<const uint4*>(qp + ks * 32);
+      qf[ks] = *reinterpret_cast<bf16x8*>(&w);
+    }
+  }
+  const int chunk16 = tid & 15, r0 = tid >> 4;
+  const int nchunks = (n + kStageTok - 1) / kStageTok;
+  uint4 reg[8];
+  auto fetch = [&](int c) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int row = c * kStageTok + r0 + 16 * k;
+      reg[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (row < n) reg[k] = *reinterpret_cast<const uint4*>(Kh + (static_cast<long long>(row) * lay.stride_tok + chunk16 * 8) * 2);
+    }
+  };
+  fetch(0);
+  const float scale = 0.08838834764831845f;
+  for (int c = 0; c < nchunks; ++c) {
+    __syncthreads();                                   // the stage is free again
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      *reinterpret_cast<uint4*>(stage + (r0 + 16 * k) * kStagePitch + chunk16 * 16) = reg[k];
+    __syncthreads();
+    if (c + 1 < nchunks) fetch(c + 1);
+    f32x16 acc = {0};
+    const char* fp = stage + (wave * 32 + (lane & 31)) * kStagePitch + hf * 16;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], *reinterpret_cast<const bf16x8*>(fp + ks * 32), acc, 0, 0, 0);
+    const int j = c * kStageTok + wave * 32 + (lane & 31);
+    if (j < n) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (hf * 4 + r < G) zbuf[(hf * 4 + r) * n + j] = acc[r] * scale;
+    }
+  }
+  __syncthreads();
+  // softmax over the tokens for each query, then the mean over queries
+  float zmax[8], zsum[8];
+#pragma unroll
+  for (int g = 0; g < 8; ++g) { zmax[g] = -INFINITY; zsum[g] = 0.f; }
+  for (int j = tid; j < n; j += kScoreThreads)
+#pragma unroll
+    for (int g = 0; g < 8; ++g)
+      if (g < G) zmax[g] = fmaxf(zmax[g], zbuf[g * n + j]);
+#pragma unroll
+  for (int g = 0; g < 8; ++g) {
+    float v = zmax[g];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    if (lane == 0) red[wave * 8 + g] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < 8; ++g) zmax[g] = fmaxf(fmaxf(red[g], red[8 + g]), fmaxf(red[16 + g], red[24 + g]));
+  for (int j = tid; j < n; j += kScoreThreads)
+#pragma unroll
+    for (int g = 0; g < 8; ++g)
+      if (g < G) {
+        const float e = __expf(zbuf[g * n + j] - zmax[g]);
+        zbuf[g * n + j] = e;
+        zsum[g] += e;
+      }
+#pragma unroll
+  for (int g = 0; g < 8; ++g) {
+    float v = zsum[g];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    if (lane == 0) red[32 + wave * 8 + g] = v;
+  }
+  __syncthreads();
+  const float invG = 1.0f / static_cast<float>(G);
+  float wgt[8];
+#pragma unroll
+  for (int g = 0; g < 8; ++g) wgt[g] = invG / (red[32 + g] + red[40 + g] + red[48 + g] + red[56 + g]);
+  float* so = s_out + static_cast<long long>(h) * n;
+  for (int j = tid; j < n; j += kScoreThreads) {
+    float p = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g)
+      if (g < G) p = fmaf(zbuf[g * n + j], wgt[g], p);
+    so[j] = p;
+  }
+}
+
 hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay, float* s_out,
                         hipStream_t st) {
+  if (lay.dtype == DT_BF16 && G <= 8 && static_cast<long long>(G) * lay.n <= 24576) {
+    const int smem_m = kStageTok * kStagePitch + (G * lay.n + 64) * 4;
+    const hipError_t em = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem_m);
+    if (em != hipSuccess) return em;
+    hipLaunchKernelGGL(score_mfma_kernel, dim3(lay.heads), dim3(kScoreThreads), smem_m, st,
+                       static_cast<const char*>(K), static_cast<const char*>(Q), G, lay, s_out);
+    return hipGetLastError();
+  }
   const bool zfits = static_cast<long long>(G) * lay.n <= kZMaxFloats;
   const size_t smem = (static_cast<size_t>(zfits ? G * lay.n : 0) + lay.n + 2 * kGT * 4) * 4;
   dim3 grid(lay.heads), block(kScoreThreads);
