@@ -4,24 +4,29 @@
 // Algorithm 1 reads only the b rows of its n x n cosine matrix that belong to
 // picked tokens, one row per pick.  A single row is a matrix-vector product and
 // would leave the matrix cores idle, so rows are produced sixteen at a time,
-// speculatively: whenever the next pick has no row yet, the sixteen currently
-// best candidates (the top few of every wave's token range) get their rows
+// speculatively: whenever the next pick has no row yet, sixteen currently
+// strong candidates (the best few of every wave's token range) get their rows
 // against all n tokens in one pass of bf16 MFMA (16x16x32, fp32 accumulate) over
-// V.  Gains only ever decrease, so the following picks mostly come from those
-// sixteen; on the benchmark inputs about eight picks are served per pass, i.e. V
-// is streamed ~b/8 times instead of b times.  Nothing is approximated: every
-// pick is still the exact argmax of Eq. 2 over all unselected tokens, and a pick
-// outside the speculated set simply starts a new pass.
+// V.  Gains only ever decrease (m only grows), so the following picks mostly
+// come from those sixteen: V is streamed roughly b/8 times instead of b times.
+//
+// Nothing is approximated.  Between passes the sixteen candidates race among
+// themselves with exact gains (all candidate-to-candidate cosines are in the
+// pass), against the best gain any other token had when the others were last
+// brought up to date.  That value can only have dropped since, so a candidate
+// that beats it (gain, then lower index) is the exact argmax of Eq. 2 over all
+// unselected tokens.  When no candidate beats it, the rows picked since are
+// applied to every token's m, the bound is recomputed, and if an outside token
+// still wins a new pass starts with that token among the nominees.
 //
 // Layout: one workgroup per head, W = n/256 (rounded up to a power of two)
 // wave64s.  Token j = 256*w + 64*k + lane belongs to wave w, lane `lane`, slot k
 // (k < 4); its score, running maximum m and inverse norm stay in that lane's
-// registers for the whole event.  The MFMA result tile has candidates along
-// rows and tokens along columns; a small per-wave LDS scratch turns it into
-// "my four tokens x sixteen candidates" per lane, after which serving a pick
-// is lane-local.  Each pick is a DPP max-reduction inside every wave, one
-// 8-byte slot per wave in LDS, one barrier, and a second DPP reduction over the
-// wave results (ties go to the lowest token index at both levels).
+// registers for the whole event.  V is streamed through a wave-private padded
+// LDS stage (coalesced 16-byte global loads, next chunk in flight while the
+// current one is multiplied).  The MFMA result tile has candidates along rows
+// and tokens along columns; the same LDS area turns it into "my four tokens x
+// sixteen candidates" per lane, after which serving a pick is lane-local.
 #include "kvr_device.hpp"
 #include "kvr_kernels.hpp"
 
@@ -33,6 +38,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kBlkRows = 16;        // speculated rows per pass
 constexpr int kBlkMaxB = 1024;      // pick lists kept in LDS
 constexpr int kScrPitch = 20;       // floats per token column in the transpose scratch (bank spread)
+constexpr int kStgPitch = 272;      // bytes per staged row (256 + 16)
 
 __device__ __forceinline__ float blk_wave_max(float v) {
   asm volatile(
@@ -46,6 +52,17 @@ __device__ __forceinline__ float blk_wave_max(float v) {
       : "+v"(v));
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
+// max over lanes 0..15 only (the sixteen candidates), wave-uniform result
+__device__ __forceinline__ float blk_row0_max(float v) {
+  asm volatile(
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+}
 __device__ __forceinline__ float blk_hw_max(float a, float b) {
   float r;
   asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
@@ -55,6 +72,10 @@ __device__ __forceinline__ void blk_wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// (gain, index) order of every argmax: larger gain first, then the lower index
+__device__ __forceinline__ bool key_beats(float ga, int ia, float gb, int ib) {
+  return ga > gb || (ga == gb && ia < ib);
 }
 
 struct BlockedArgs {
@@ -66,11 +87,14 @@ struct BlockedArgs {
   float lambda, eps;
 };
 
-__host__ __device__ constexpr int blocked_smem_bytes(int W) {
-  // slots[2][16]{gain,idx} | cand[16] | candr[16] | wcount[16] | order[kBlkMaxB] | gain[kBlkMaxB] |
-  // idxs[kBlkMaxB] | rn[256*W] (inverse norms, later pick flags) | scratch[W][16*kScrPitch]
-  return (64 + 16 + 16 + 16 + 3 * kBlkMaxB + 256 * W + W * 16 * kScrPitch) * 4;
-}
+template <int W> struct BlkCfg {
+  static constexpr int kChunkTok = W <= 4 ? 32 : 16;                // tokens staged per step and wave
+  static constexpr int kStageBytes = kChunkTok * kStgPitch + 16 * kScrPitch * 4;   // row stage + transpose scratch
+  // floats: slots[2][16]{gain,idx}=64 | cand 16 | candr 16 | cs 16 | cm 16 | wcount 16 | cc 256 |
+  //         order kBlkMaxB | gain kBlkMaxB | idxs kBlkMaxB | rn 256*W ; then the per-wave stages
+  static constexpr int kFixedFloats = 64 + 16 * 5 + 256 + 3 * kBlkMaxB + 256 * W;
+  static constexpr int kSmemBytes = kFixedFloats * 4 + W * kStageBytes;
+};
 
 #define KVR_CASE(C)                                                      \
   case C:                                                                \
@@ -78,79 +102,58 @@ __host__ __device__ constexpr int blocked_smem_bytes(int W) {
     break;
 
 template <int W>
-__global__ __launch_bounds__(64 * W) void select_blocked_kernel(BlockedArgs a) {
+__global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kernel(BlockedArgs a) {
+  using Cfg = BlkCfg<W>;
   constexpr int NT = 64 * W;                       // threads
-  constexpr int RW = kBlkRows / W;                 // candidates contributed per wave and pass
+  constexpr int RW = kBlkRows / W;                 // nominees per wave and pass
+  constexpr int CH = Cfg::kChunkTok;
+  constexpr int LPC = CH / 4;                      // 16-byte global loads per lane and chunk
   extern __shared__ __align__(16) float smem[];
-  float* slot_gain = smem;                         // [2][16]
-  int32_t* slot_idx = reinterpret_cast<int32_t*>(smem + 32);   // [2][16]
-  int32_t* cand_l = reinterpret_cast<int32_t*>(smem + 64);     // [16] token of each speculated row, -1 = none
-  float* candr = smem + 80;                        // [16] its inverse norm
-  int32_t* wcount = reinterpret_cast<int32_t*>(smem + 96);     // [16]
-  int32_t* order_l = reinterpret_cast<int32_t*>(smem + 112);
-  float* gain_l = smem + 112 + kBlkMaxB;
-  int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 112 + 2 * kBlkMaxB);
-  float* rn = smem + 112 + 3 * kBlkMaxB;           // [256*W]
+  float* slot_gain = smem;                                         // [2][16]
+  int32_t* slot_idx = reinterpret_cast<int32_t*>(smem + 32);       // [2][16]
+  int32_t* cand_l = reinterpret_cast<int32_t*>(smem + 64);         // [16] token of each speculated row, -1 = none
+  float* candr = smem + 80;                                        // [16] its inverse norm
+  float* cs_l = smem + 96;                                         // [16] its score
+  float* cm_l = smem + 112;                                        // [16] its m when the pass was built
+  int32_t* wcount = reinterpret_cast<int32_t*>(smem + 128);        // [16]
+  float* cc = smem + 144;                                          // [16][16] cosine(candidate x, candidate c)
+  int32_t* order_l = reinterpret_cast<int32_t*>(smem + 400);
+  float* gain_l = smem + 400 + kBlkMaxB;
+  int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 400 + 2 * kBlkMaxB);
+  float* rn = smem + 400 + 3 * kBlkMaxB;                           // [256*W] inverse norms, later pick flags
   int32_t* flag = reinterpret_cast<int32_t*>(rn);
-  float* scratch_all = rn + 256 * W;
+  char* stage_all = reinterpret_cast<char*>(rn + 256 * W);
 
   const int h = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = a.n, b = a.b;
-  const long long head_off = h * a.stride_head * 2;           // bytes
+  const long long head_off = h * a.stride_head * 2;               // bytes
   const char* Vh = a.V + head_off;
   const bool diverse = a.lambda != 0.0f;
   const int base = w * 256;
-  float* scratch = scratch_all + w * 16 * kScrPitch;
+  char* stage = stage_all + w * Cfg::kStageBytes;
+  float* scratch = reinterpret_cast<float*>(stage + Cfg::kChunkTok * kStgPitch);
 
   // ---- per-token state in registers
   float s[4], m[4], r[4];
-  int tok[4];
+  int tok[4], cslot[4];          // cslot: row of the current pass that belongs to this token, or -1
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     tok[k] = base + 64 * k + lane;
     s[k] = tok[k] < n ? a.s_in[static_cast<long long>(h) * n + tok[k]] : -INFINITY;
     m[k] = 0.f;
     r[k] = 0.f;
+    cslot[k] = -1;
   }
-  if (diverse && b > 1) {
-    // inverse norms (Eq. 1): 16 lanes per row, coalesced; this is the one full read of V from HBM
-    const int c16 = tid & 15;
-    for (int j0 = 0; j0 < n; j0 += NT / 16) {
-      const int j = j0 + (tid >> 4);
-      if (j < n) {
-        float x[8];
-        load8<DT_BF16>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2, x);
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
-        ss = group16_sum(ss);
-        if (c16 == 0) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 4; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
-  }
-
-  float vals[4][kBlkRows];       // cos numerators: my token k against speculated row c
-#pragma unroll
-  for (int k = 0; k < 4; ++k)
-#pragma unroll
-    for (int c = 0; c < kBlkRows; ++c) vals[k][c] = 0.f;
-  int cm = -2;                   // lanes 0..15: token of speculated row `lane`
-  float crv = 0.f;               // lanes 0..15: its inverse norm
   const float nlam = -a.lambda;
   int par = 0;
   int t = 0;
   bool starved = false;          // no finite gain left (non-finite input only)
 
-  for (; t < b; ++t) {
-    // ---- wave-local argmax of the marginal gain
-    float av[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) av[k] = fmaf(nlam, m[k], s[k]);
+  // Workgroup-wide argmax of up to four per-lane values with token ids tok[k]:
+  // DPP inside the wave, one LDS slot per wave, one barrier, DPP over the slots.
+  auto wg_argmax = [&](const float (&av)[4], float& gbest, int& ibest) {
     const float best = blk_hw_max(blk_hw_max(av[0], av[1]), blk_hw_max(av[2], av[3]));
     const float amax_w = blk_wave_max(best);
     int i_w = -1;
@@ -161,48 +164,172 @@ __global__ __launch_bounds__(64 * W) void select_blocked_kernel(BlockedArgs a) {
     }
     if (lane == 0) { slot_gain[par * 16 + w] = amax_w; slot_idx[par * 16 + w] = i_w; }
     __syncthreads();
-    // ---- across waves: larger gain, then lower wave (= lower token range)
     const float g = lane < W ? slot_gain[par * 16 + lane] : -INFINITY;
     const int ii = lane < W ? slot_idx[par * 16 + lane] : -1;
     par ^= 1;
-    const float gmax = blk_wave_max(g);
-    if (!(gmax > -INFINITY)) { starved = true; break; }
-    const unsigned long long eqw = __ballot(lane < W && g == gmax);
-    const int win = __ffsll(static_cast<long long>(eqw)) - 1;
-    const int i = __builtin_amdgcn_readlane(ii, win);
-    if (tid == 0) { order_l[t] = i; gain_l[t] = gmax; }
-    if (t + 1 == b) { ++t; break; }
-    if (!diverse) {
+    gbest = blk_wave_max(g);
+    const unsigned long long eqw = __ballot(lane < W && g == gbest);   // lowest wave = lowest token range
+    ibest = eqw ? __builtin_amdgcn_readlane(ii, __ffsll(static_cast<long long>(eqw)) - 1) : -1;
+  };
+
+  if (!diverse || b == 1) {
+    // lambda = 0 (or a single pick): plain top-b of the scores, V is never read
+    for (; t < b; ++t) {
+      float gmax; int i;
+      wg_argmax(s, gmax, i);
+      if (!(gmax > -INFINITY)) { starved = true; break; }
+      if (tid == 0) { order_l[t] = i; gain_l[t] = gmax; }
 #pragma unroll
       for (int k = 0; k < 4; ++k) s[k] = tok[k] == i ? -INFINITY : s[k];
-      continue;
     }
-    // ---- is the row of pick i among the speculated ones?
-    unsigned long long hit = __ballot(cm == i);
-    if (!hit) {
-      // ---- new pass: every wave nominates its RW best unselected tokens (i is one of them)
-      float ts[4] = {av[0], av[1], av[2], av[3]};
+  } else {
+    // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the one full read of V from HBM
+    {
+      const int c16 = tid & 15;
+      for (int j0 = 0; j0 < n; j0 += NT / 16) {
+        const int j = j0 + (tid >> 4);
+        if (j < n) {
+          float x[8];
+          load8<DT_BF16>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2, x);
+          float ss = 0.f;
 #pragma unroll
-      for (int q = 0; q < RW; ++q) {
-        const float bq = blk_hw_max(blk_hw_max(ts[0], ts[1]), blk_hw_max(ts[2], ts[3]));
-        const float mx = blk_wave_max(bq);
-        int cj = -1, ck = 0, cl = 0;
-#pragma unroll
-        for (int k = 3; k >= 0; --k) {
-          const unsigned long long eq = __ballot(ts[k] == mx);
-          if (eq) { cl = __ffsll(static_cast<long long>(eq)) - 1; ck = k; cj = base + 64 * k + cl; }
+          for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+          ss = group16_sum(ss);
+          if (c16 == 0) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
         }
-        const float rsel = ck == 0 ? r[0] : ck == 1 ? r[1] : ck == 2 ? r[2] : r[3];
-        const float rc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(rsel), cl));
-        const bool ok = mx > -INFINITY;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) ts[k] = (k == ck && lane == cl) ? -INFINITY : ts[k];
-        if (lane == 0) { cand_l[w * RW + q] = ok ? cj : -1; candr[w * RW + q] = ok ? rc : 0.f; }
       }
       __syncthreads();
-      cm = lane < kBlkRows ? cand_l[lane] : -2;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
+    }
+
+    float vals[4][kBlkRows];       // dot products: my token k against speculated row c
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int c = 0; c < kBlkRows; ++c) vals[k][c] = 0.f;
+    // candidate state, replicated in lanes 0..15 of every wave (lane = row of the pass)
+    int ctok = -1;                 // token of the row, -1 = empty
+    float crv = 0.f;               // its inverse norm
+    float gs = -INFINITY;          // its score; -inf once picked
+    float gm = 0.f;                // its running maximum
+    unsigned long long pend = 0;   // rows picked since the other tokens were last updated, 4 bits each
+    int np = 0;
+    float gout = -INFINITY;        // best gain outside the candidates, as of the last update
+    int jout = -1;
+    bool out_valid = false;
+#ifdef KVR_STATS
+    int st_blocks = 0, st_syncs = 0;
+#endif
+
+    while (t < b) {
+      if (!out_valid) {
+        // ---- bring every token up to date with the rows picked since the last update
+        for (int q = 0; q < np; ++q) {
+          const int c = static_cast<int>((pend >> (4 * q)) & 15ull);
+          const float rc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(crv), c));
+          float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+          switch (c) {
+            KVR_CASE(0) KVR_CASE(1) KVR_CASE(2) KVR_CASE(3) KVR_CASE(4) KVR_CASE(5) KVR_CASE(6) KVR_CASE(7)
+            KVR_CASE(8) KVR_CASE(9) KVR_CASE(10) KVR_CASE(11) KVR_CASE(12) KVR_CASE(13) KVR_CASE(14) KVR_CASE(15)
+            default: break;
+          }
+          m[0] = blk_hw_max(m[0], v0 * rc * r[0]);
+          m[1] = blk_hw_max(m[1], v1 * rc * r[1]);
+          m[2] = blk_hw_max(m[2], v2 * rc * r[2]);
+          m[3] = blk_hw_max(m[3], v3 * rc * r[3]);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) s[k] = cslot[k] == c ? -INFINITY : s[k];   // the picked token itself
+        }
+        np = 0; pend = 0;
+        // ---- best gain among the tokens that are not candidates
+        float av[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) av[k] = cslot[k] >= 0 ? -INFINITY : fmaf(nlam, m[k], s[k]);
+        wg_argmax(av, gout, jout);
+        out_valid = true;
+#ifdef KVR_STATS
+        ++st_syncs;
+#endif
+      }
+      // ---- race: the best live candidate against the best outside token
+      const float gcand = lane < kBlkRows ? fmaf(nlam, gm, gs) : -INFINITY;
+      const float gc = blk_row0_max(gcand);
+      int uc = -1, tc = 0x7fffffff;
+      if (gc > -INFINITY) {
+        const unsigned long long eq = __ballot(lane < kBlkRows && gcand == gc);
+        uc = __ffsll(static_cast<long long>(eq)) - 1;
+        tc = __builtin_amdgcn_readlane(ctok, uc);
+        if (eq & (eq - 1)) {                           // equal gains: the lowest token id wins
+          for (unsigned long long rest = eq & (eq - 1); rest; rest &= rest - 1) {
+            const int u2 = __ffsll(static_cast<long long>(rest)) - 1;
+            const int t2 = __builtin_amdgcn_readlane(ctok, u2);
+            if (t2 < tc) { tc = t2; uc = u2; }
+          }
+        }
+      }
+      if (uc >= 0 && key_beats(gc, tc, gout, jout < 0 ? 0x7fffffff : jout)) {
+        // the candidate is the exact argmax over all unselected tokens
+        if (tid == 0) { order_l[t] = tc; gain_l[t] = gc; }
+        ++t;
+        pend |= static_cast<unsigned long long>(uc) << (4 * np);
+        ++np;
+        if (lane == uc) gs = -INFINITY;
+        if (lane < kBlkRows) gm = blk_hw_max(gm, cc[uc * 16 + lane]);
+        continue;
+      }
+      if (np > 0) { out_valid = false; continue; }     // the outside bound is stale: refresh it first
+      if (jout < 0 || !(gout > -INFINITY)) { starved = true; break; }   // nothing finite left anywhere
+      if (t + 1 == b) {                                // last pick needs no row
+        if (tid == 0) { order_l[t] = jout; gain_l[t] = gout; }
+        ++t;
+        break;
+      }
+      // ---- new pass.  Every token's m is up to date here.  Each wave nominates its RW best
+      // unselected tokens (the winning outside token is the best of its wave) and reports the
+      // best of the rest, which becomes the new outside bound.
+      {
+        float ts[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { ts[k] = fmaf(nlam, m[k], s[k]); cslot[k] = -1; }
+#pragma unroll
+        for (int q = 0; q < RW; ++q) {
+          const float bq = blk_hw_max(blk_hw_max(ts[0], ts[1]), blk_hw_max(ts[2], ts[3]));
+          const float mx = blk_wave_max(bq);
+          int cj = -1, ck = 0, cl = 0;
+#pragma unroll
+          for (int k = 3; k >= 0; --k) {
+            const unsigned long long eq = __ballot(ts[k] == mx);
+            if (eq) { cl = __ffsll(static_cast<long long>(eq)) - 1; ck = k; cj = base + 64 * k + cl; }
+          }
+          const bool ok = mx > -INFINITY && cj >= 0;
+          const float rsel = ck == 0 ? r[0] : ck == 1 ? r[1] : ck == 2 ? r[2] : r[3];
+          const float ssel = ck == 0 ? s[0] : ck == 1 ? s[1] : ck == 2 ? s[2] : s[3];
+          const float msel = ck == 0 ? m[0] : ck == 1 ? m[1] : ck == 2 ? m[2] : m[3];
+          const float rc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(rsel), cl));
+          const float sc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ssel), cl));
+          const float mc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(msel), cl));
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const bool mine = ok && k == ck && lane == cl;
+            ts[k] = mine ? -INFINITY : ts[k];
+            cslot[k] = mine ? w * RW + q : cslot[k];
+          }
+          if (lane == 0) {
+            const int slot = w * RW + q;
+            cand_l[slot] = ok ? cj : -1;
+            candr[slot] = ok ? rc : 0.f;
+            cs_l[slot] = ok ? sc : -INFINITY;
+            cm_l[slot] = ok ? mc : 0.f;
+          }
+        }
+        wg_argmax(ts, gout, jout);                     // barrier inside: the nominee tables are complete
+      }
+      ctok = lane < kBlkRows ? cand_l[lane] : -1;
       crv = lane < kBlkRows ? candr[lane] : 0.f;
-      // A operand: the sixteen candidate rows (lane: row lane%16, k-group lane/16)
+      gs = lane < kBlkRows ? cs_l[lane] : -INFINITY;
+      gm = lane < kBlkRows ? cm_l[lane] : 0.f;
+      // ---- A operand: the sixteen nominated rows (lane: row lane%16, k-group lane/16)
       const int kg = lane >> 4;
       const int ci = cand_l[lane & 15];
       bf16x8 af[4];
@@ -212,55 +339,81 @@ __global__ __launch_bounds__(64 * W) void select_blocked_kernel(BlockedArgs a) {
         if (ci >= 0) x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(ci) * a.stride_tok + ks * 32 + kg * 8) * 2);
         af[ks] = *reinterpret_cast<bf16x8*>(&x);
       }
-      // stream this wave's 256 tokens through the matrix cores, 16 at a time
-      f32x4 acc[16];
+      // ---- stream this wave's 256 tokens: coalesced loads -> padded LDS stage -> MFMA fragments.
+      // 64 tokens (one slot k of every lane) at a time: their four 16x16 result tiles have token
+      // column lane%16 and candidates 4*(lane/16)+0..3 in each lane; the wave's scratch turns them
+      // into "token against all sixteen candidates" in the lane that owns the token (lane group
+      // sub%4 owns sub-block sub of the 64).
+      uint4 pre[LPC];
+      auto fetch = [&](int ch) {
+        // The row index is made opaque so that the unrolled pass does not keep sixty-four
+        // precomputed 64-bit addresses alive across the whole selection loop.
+        int row0 = base + (lane >> 4);
+        asm volatile("" : "+v"(row0));
 #pragma unroll
-      for (int sub = 0; sub < 16; ++sub) {
-        const int tb = base + sub * 16 + (lane & 15);
-        acc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
-        uint4 x[4];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          x[ks] = make_uint4(0u, 0u, 0u, 0u);
-          if (tb < n) x[ks] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(tb) * a.stride_tok + ks * 32 + kg * 8) * 2);
+        for (int q = 0; q < LPC; ++q) {
+          const int row = row0 + ch * CH + 4 * q;
+          pre[q] = make_uint4(0u, 0u, 0u, 0u);
+          if (row < n) pre[q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
         }
+      };
+      fetch(0);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-          acc[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks], *reinterpret_cast<bf16x8*>(&x[ks]), acc[sub], 0, 0, 0);
-      }
-      // A result tile has token column lane%16 and candidates 4*(lane/16)+0..3 in each lane.
-      // Turn it into "token sub*16+col against all sixteen candidates" in the lane that owns
-      // that token (lane group sub%4, slot sub/4) through the wave's LDS scratch.
+      for (int k = 0; k < 4; ++k) {
+        f32x4 acc[4];
 #pragma unroll
-      for (int sub = 0; sub < 16; ++sub) {
-        *reinterpret_cast<f32x4*>(scratch + (lane & 15) * kScrPitch + 4 * kg) = acc[sub];
-        blk_wave_sync();
-        if (kg == (sub & 3)) {
+        for (int sub = 0; sub < 4; ++sub) acc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int c4 = 0; c4 < 4; ++c4) {
-            const f32x4 vv = *reinterpret_cast<const f32x4*>(scratch + (lane & 15) * kScrPitch + 4 * c4);
-            vals[sub >> 2][4 * c4 + 0] = vv[0]; vals[sub >> 2][4 * c4 + 1] = vv[1];
-            vals[sub >> 2][4 * c4 + 2] = vv[2]; vals[sub >> 2][4 * c4 + 3] = vv[3];
+        for (int c2 = 0; c2 < 64 / CH; ++c2) {
+          const int ch = k * (64 / CH) + c2;
+          blk_wave_sync();                             // fragments of the previous chunk have been read
+#pragma unroll
+          for (int q = 0; q < LPC; ++q)
+            *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kStgPitch + (lane & 15) * 16) = pre[q];
+          blk_wave_sync();
+          if (ch + 1 < 256 / CH) fetch(ch + 1);
+#pragma unroll
+          for (int s2 = 0; s2 < CH / 16; ++s2) {
+            const char* fp = stage + (s2 * 16 + (lane & 15)) * kStgPitch + kg * 16;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+              acc[c2 * (CH / 16) + s2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  af[ks], *reinterpret_cast<const bf16x8*>(fp + ks * 64), acc[c2 * (CH / 16) + s2], 0, 0, 0);
           }
         }
-        blk_wave_sync();
-      }
-      hit = __ballot(cm == i);
-    }
-    const int c = __ffsll(static_cast<long long>(hit)) - 1;      // 0..15 (i is always nominated)
-    const float rc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(crv), c & 15));
-    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
-    switch (c) {
-      KVR_CASE(0) KVR_CASE(1) KVR_CASE(2) KVR_CASE(3) KVR_CASE(4) KVR_CASE(5) KVR_CASE(6) KVR_CASE(7)
-      KVR_CASE(8) KVR_CASE(9) KVR_CASE(10) KVR_CASE(11) KVR_CASE(12) KVR_CASE(13) KVR_CASE(14) KVR_CASE(15)
-      default: break;
-    }
-    m[0] = blk_hw_max(m[0], v0 * rc * r[0]);
-    m[1] = blk_hw_max(m[1], v1 * rc * r[1]);
-    m[2] = blk_hw_max(m[2], v2 * rc * r[2]);
-    m[3] = blk_hw_max(m[3], v3 * rc * r[3]);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) s[k] = tok[k] == i ? -INFINITY : s[k];
+        for (int sub = 0; sub < 4; ++sub) {
+          blk_wave_sync();
+          *reinterpret_cast<f32x4*>(scratch + (lane & 15) * kScrPitch + 4 * kg) = acc[sub];
+          blk_wave_sync();
+          if (kg == sub) {
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+              const f32x4 vv = *reinterpret_cast<const f32x4*>(scratch + (lane & 15) * kScrPitch + 4 * c4);
+              vals[k][4 * c4 + 0] = vv[0]; vals[k][4 * c4 + 1] = vv[1];
+              vals[k][4 * c4 + 2] = vv[2]; vals[k][4 * c4 + 3] = vv[3];
+            }
+          }
+        }
+      }
+      // ---- candidate-to-candidate cosines, written by the lanes that own the candidate tokens
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (cslot[k] >= 0) {
+#pragma unroll
+          for (int x = 0; x < kBlkRows; ++x) cc[x * 16 + cslot[k]] = vals[k][x] * candr[x] * r[k];
+        }
+      }
+      __syncthreads();
+      // gout / jout from the nomination are exact for the new outside set
+#ifdef KVR_STATS
+      ++st_blocks;
+#endif
+    }
+#ifdef KVR_STATS
+    __syncthreads();
+    if (tid == 0 && b >= 4) { gain_l[b - 1] = st_blocks; gain_l[b - 2] = st_syncs; }
+#endif
   }
 
   // ---- sort(S): flag the picked tokens, ascending indices by prefix counts
@@ -275,7 +428,7 @@ __global__ __launch_bounds__(64 * W) void select_blocked_kernel(BlockedArgs a) {
     if (tid == 0) {
       int j = 0;
       for (int u = t; u < b; ++u) {
-        while (j < n && flag[j]) ++j;
+        while (j < n - 1 && flag[j]) ++j;
         order_l[u] = j; gain_l[u] = -INFINITY; flag[j] = 1;
       }
     }
@@ -341,19 +494,18 @@ hipError_t launch_select_blocked(const void* K, const void* V, const float* s, c
   a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
   a.n = lay.n; a.b = b; a.lambda = lambda; a.eps = eps;
   dim3 grid(lay.heads);
-  auto go = [&](auto kern, int W) -> hipError_t {
-    const int smem = blocked_smem_bytes(W);
+  auto go = [&](auto kern, int threads, int smem) -> hipError_t {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, dim3(64 * W), smem, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(threads), smem, st, a);
     return hipGetLastError();
   };
   const int waves = (lay.n + 255) / 256;
-  if (waves <= 2) return go(&select_blocked_kernel<2>, 2);
-  if (waves <= 4) return go(&select_blocked_kernel<4>, 4);
-  if (waves <= 8) return go(&select_blocked_kernel<8>, 8);
-  return go(&select_blocked_kernel<16>, 16);
+  if (waves <= 2) return go(&select_blocked_kernel<2>, 128, BlkCfg<2>::kSmemBytes);
+  if (waves <= 4) return go(&select_blocked_kernel<4>, 256, BlkCfg<4>::kSmemBytes);
+  if (waves <= 8) return go(&select_blocked_kernel<8>, 512, BlkCfg<8>::kSmemBytes);
+  return go(&select_blocked_kernel<16>, 1024, BlkCfg<16>::kSmemBytes);
 }
 
 }  // namespace kvr
