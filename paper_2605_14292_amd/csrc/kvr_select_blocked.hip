@@ -87,23 +87,24 @@ struct BlockedArgs {
   float lambda, eps;
 };
 
-template <int W> struct BlkCfg {
+template <int W, int S> struct BlkCfg {
   static constexpr int kChunkTok = W <= 4 ? 32 : 16;                // tokens staged per step and wave
   static constexpr int kStageBytes = kChunkTok * kStgPitch + 16 * kScrPitch * 4;   // row stage + transpose scratch
   // floats: slots[2][16]{gain,idx}=64 | cand 16 | candr 16 | cs 16 | cm 16 | wcount 16 | cc 256 |
   //         order kBlkMaxB | gain kBlkMaxB | idxs kBlkMaxB | rn 256*W ; then the per-wave stages
-  static constexpr int kFixedFloats = 64 + 16 * 5 + 256 + 3 * kBlkMaxB + 256 * W;
+  static constexpr int kFixedFloats = 64 + 16 * 5 + 256 + 3 * kBlkMaxB + 64 * S * W;
   static constexpr int kSmemBytes = kFixedFloats * 4 + W * kStageBytes;
 };
 
-#define KVR_CASE(C)                                                      \
-  case C:                                                                \
-    v0 = vals[0][C]; v1 = vals[1][C]; v2 = vals[2][C]; v3 = vals[3][C];  \
+#define KVR_CASE(C)                                  \
+  case C:                                            \
+    _Pragma("unroll") for (int k = 0; k < S; ++k) v[k] = vals[k][C]; \
     break;
 
-template <int W>
+template <int W, int S>
 __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kernel(BlockedArgs a) {
-  using Cfg = BlkCfg<W>;
+  using Cfg = BlkCfg<W, S>;
+  constexpr int TPW = 64 * S;                      // tokens per wave
   constexpr int NT = 64 * W;                       // threads
   constexpr int RW = kBlkRows / W;                 // nominees per wave and pass
   constexpr int CH = Cfg::kChunkTok;
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
   int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 400 + 2 * kBlkMaxB);
   float* rn = smem + 400 + 3 * kBlkMaxB;                           // [256*W] inverse norms, later pick flags
   int32_t* flag = reinterpret_cast<int32_t*>(rn);
-  char* stage_all = reinterpret_cast<char*>(rn + 256 * W);
+  char* stage_all = reinterpret_cast<char*>(rn + TPW * W);
 
   const int h = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -131,15 +132,15 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
   const long long head_off = h * a.stride_head * 2;               // bytes
   const char* Vh = a.V + head_off;
   const bool diverse = a.lambda != 0.0f;
-  const int base = w * 256;
+  const int base = w * TPW;
   char* stage = stage_all + w * Cfg::kStageBytes;
   float* scratch = reinterpret_cast<float*>(stage + Cfg::kChunkTok * kStgPitch);
 
   // ---- per-token state in registers
-  float s[4], m[4], r[4];
-  int tok[4], cslot[4];          // cslot: row of the current pass that belongs to this token, or -1
+  float s[S], m[S], r[S];
+  int tok[S], cslot[S];          // cslot: row of the current pass that belongs to this token, or -1
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
+  for (int k = 0; k < S; ++k) {
     tok[k] = base + 64 * k + lane;
     s[k] = tok[k] < n ? a.s_in[static_cast<long long>(h) * n + tok[k]] : -INFINITY;
     m[k] = 0.f;
@@ -153,12 +154,14 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
 
   // Workgroup-wide argmax of up to four per-lane values with token ids tok[k]:
   // DPP inside the wave, one LDS slot per wave, one barrier, DPP over the slots.
-  auto wg_argmax = [&](const float (&av)[4], float& gbest, int& ibest) {
-    const float best = blk_hw_max(blk_hw_max(av[0], av[1]), blk_hw_max(av[2], av[3]));
+  auto wg_argmax = [&](const float (&av)[S], float& gbest, int& ibest) {
+    float best = av[0];
+#pragma unroll
+    for (int k = 1; k < S; ++k) best = blk_hw_max(best, av[k]);
     const float amax_w = blk_wave_max(best);
     int i_w = -1;
 #pragma unroll
-    for (int k = 3; k >= 0; --k) {
+    for (int k = S - 1; k >= 0; --k) {
       const unsigned long long eq = __ballot(av[k] == amax_w);
       if (eq) i_w = base + 64 * k + (__ffsll(static_cast<long long>(eq)) - 1);
     }
@@ -180,7 +183,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
       if (!(gmax > -INFINITY)) { starved = true; break; }
       if (tid == 0) { order_l[t] = i; gain_l[t] = gmax; }
 #pragma unroll
-      for (int k = 0; k < 4; ++k) s[k] = tok[k] == i ? -INFINITY : s[k];
+      for (int k = 0; k < S; ++k) s[k] = tok[k] == i ? -INFINITY : s[k];
     }
   } else {
     // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the one full read of V from HBM
@@ -200,14 +203,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
       }
       __syncthreads();
 #pragma unroll
-      for (int k = 0; k < 4; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
+      for (int k = 0; k < S; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
     }
 
-    float vals[4][kBlkRows];       // dot products: my token k against speculated row c
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-#pragma unroll
-      for (int c = 0; c < kBlkRows; ++c) vals[k][c] = 0.f;
+    float vals[S][kBlkRows];       // dot products: my token k against speculated row c (set by every pass)
     // candidate state, replicated in lanes 0..15 of every wave (lane = row of the pass)
     int ctok = -1;                 // token of the row, -1 = empty
     float crv = 0.f;               // its inverse norm
@@ -228,24 +227,25 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
         for (int q = 0; q < np; ++q) {
           const int c = static_cast<int>((pend >> (4 * q)) & 15ull);
           const float rc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(crv), c));
-          float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+          float v[S];
           switch (c) {
             KVR_CASE(0) KVR_CASE(1) KVR_CASE(2) KVR_CASE(3) KVR_CASE(4) KVR_CASE(5) KVR_CASE(6) KVR_CASE(7)
             KVR_CASE(8) KVR_CASE(9) KVR_CASE(10) KVR_CASE(11) KVR_CASE(12) KVR_CASE(13) KVR_CASE(14) KVR_CASE(15)
-            default: break;
-          }
-          m[0] = blk_hw_max(m[0], v0 * rc * r[0]);
-          m[1] = blk_hw_max(m[1], v1 * rc * r[1]);
-          m[2] = blk_hw_max(m[2], v2 * rc * r[2]);
-          m[3] = blk_hw_max(m[3], v3 * rc * r[3]);
+            default:
 #pragma unroll
-          for (int k = 0; k < 4; ++k) s[k] = cslot[k] == c ? -INFINITY : s[k];   // the picked token itself
+              for (int k = 0; k < S; ++k) v[k] = 0.f;
+              break;
+          }
+#pragma unroll
+          for (int k = 0; k < S; ++k) m[k] = blk_hw_max(m[k], v[k] * rc * r[k]);
+#pragma unroll
+          for (int k = 0; k < S; ++k) s[k] = cslot[k] == c ? -INFINITY : s[k];   // the picked token itself
         }
         np = 0; pend = 0;
         // ---- best gain among the tokens that are not candidates
-        float av[4];
+        float av[S];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) av[k] = cslot[k] >= 0 ? -INFINITY : fmaf(nlam, m[k], s[k]);
+        for (int k = 0; k < S; ++k) av[k] = cslot[k] >= 0 ? -INFINITY : fmaf(nlam, m[k], s[k]);
         wg_argmax(av, gout, jout);
         out_valid = true;
 #ifdef KVR_STATS
@@ -289,28 +289,32 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
       // unselected tokens (the winning outside token is the best of its wave) and reports the
       // best of the rest, which becomes the new outside bound.
       {
-        float ts[4];
+        float ts[S];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { ts[k] = fmaf(nlam, m[k], s[k]); cslot[k] = -1; }
+        for (int k = 0; k < S; ++k) { ts[k] = fmaf(nlam, m[k], s[k]); cslot[k] = -1; }
 #pragma unroll
         for (int q = 0; q < RW; ++q) {
-          const float bq = blk_hw_max(blk_hw_max(ts[0], ts[1]), blk_hw_max(ts[2], ts[3]));
+          float bq = ts[0];
+#pragma unroll
+          for (int k = 1; k < S; ++k) bq = blk_hw_max(bq, ts[k]);
           const float mx = blk_wave_max(bq);
           int cj = -1, ck = 0, cl = 0;
 #pragma unroll
-          for (int k = 3; k >= 0; --k) {
+          for (int k = S - 1; k >= 0; --k) {
             const unsigned long long eq = __ballot(ts[k] == mx);
             if (eq) { cl = __ffsll(static_cast<long long>(eq)) - 1; ck = k; cj = base + 64 * k + cl; }
           }
           const bool ok = mx > -INFINITY && cj >= 0;
-          const float rsel = ck == 0 ? r[0] : ck == 1 ? r[1] : ck == 2 ? r[2] : r[3];
-          const float ssel = ck == 0 ? s[0] : ck == 1 ? s[1] : ck == 2 ? s[2] : s[3];
-          const float msel = ck == 0 ? m[0] : ck == 1 ? m[1] : ck == 2 ? m[2] : m[3];
+          float rsel = r[0], ssel = s[0], msel = m[0];
+#pragma unroll
+          for (int k = 1; k < S; ++k) {
+            rsel = ck == k ? r[k] : rsel; ssel = ck == k ? s[k] : ssel; msel = ck == k ? m[k] : msel;
+          }
           const float rc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(rsel), cl));
           const float sc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ssel), cl));
           const float mc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(msel), cl));
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
+          for (int k = 0; k < S; ++k) {
             const bool mine = ok && k == ck && lane == cl;
             ts[k] = mine ? -INFINITY : ts[k];
             cslot[k] = mine ? w * RW + q : cslot[k];
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
       };
       fetch(0);
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < S; ++k) {
         f32x4 acc[4];
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub) acc[sub] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -371,7 +375,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
           for (int q = 0; q < LPC; ++q)
             *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kStgPitch + (lane & 15) * 16) = pre[q];
           blk_wave_sync();
-          if (ch + 1 < 256 / CH) fetch(ch + 1);
+          if (ch + 1 < TPW / CH) fetch(ch + 1);
 #pragma unroll
           for (int s2 = 0; s2 < CH / 16; ++s2) {
             const char* fp = stage + (s2 * 16 + (lane & 15)) * kStgPitch + kg * 16;
@@ -398,7 +402,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
       }
       // ---- candidate-to-candidate cosines, written by the lanes that own the candidate tokens
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < S; ++k) {
         if (cslot[k] >= 0) {
 #pragma unroll
           for (int x = 0; x < kBlkRows; ++x) cc[x * 16 + cslot[k]] = vals[k][x] * candr[x] * r[k];
@@ -419,7 +423,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
   // ---- sort(S): flag the picked tokens, ascending indices by prefix counts
   __syncthreads();
 #pragma unroll
-  for (int k = 0; k < 4; ++k) flag[base + 64 * k + lane] = 0;
+  for (int k = 0; k < S; ++k) flag[base + 64 * k + lane] = 0;
   __syncthreads();
   for (int u = tid; u < t; u += NT) flag[order_l[u]] = 1;
   __syncthreads();
@@ -435,10 +439,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
     __syncthreads();
   }
   {
-    unsigned long long sel[4];
+    unsigned long long sel[S];
     int cnt = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < S; ++k) {
       sel[k] = __ballot(tok[k] < n && flag[tok[k]] != 0);
       cnt += __popcll(sel[k]);
     }
@@ -447,7 +451,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_blocked_kerne
     int off = 0;
     for (int u = 0; u < w; ++u) off += wcount[u];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < S; ++k) {
       if ((sel[k] >> lane) & 1ull) {
         const int rank = off + __popcll(sel[k] & ((1ull << lane) - 1ull));
         if (rank < b) idxs_l[rank] = tok[k];
@@ -501,11 +505,10 @@ hipError_t launch_select_blocked(const void* K, const void* V, const float* s, c
     hipLaunchKernelGGL(kern, grid, dim3(threads), smem, st, a);
     return hipGetLastError();
   };
-  const int waves = (lay.n + 255) / 256;
-  if (waves <= 2) return go(&select_blocked_kernel<2>, 128, BlkCfg<2>::kSmemBytes);
-  if (waves <= 4) return go(&select_blocked_kernel<4>, 256, BlkCfg<4>::kSmemBytes);
-  if (waves <= 8) return go(&select_blocked_kernel<8>, 512, BlkCfg<8>::kSmemBytes);
-  return go(&select_blocked_kernel<16>, 1024, BlkCfg<16>::kSmemBytes);
+  if (lay.n <= 512) return go(&select_blocked_kernel<2, 4>, 128, BlkCfg<2, 4>::kSmemBytes);
+  if (lay.n <= 1024) return go(&select_blocked_kernel<4, 4>, 256, BlkCfg<4, 4>::kSmemBytes);
+  if (lay.n <= 2048) return go(&select_blocked_kernel<8, 4>, 512, BlkCfg<8, 4>::kSmemBytes);
+  return go(&select_blocked_kernel<8, 8>, 512, BlkCfg<8, 8>::kSmemBytes);
 }
 
 }  // namespace kvr
