@@ -103,17 +103,16 @@ struct DenseArgs {
   float* s_out; int32_t* idx_sorted; int32_t* pick_order; float* pick_gain;
   char* K_out; char* V_out;
   long long stride_head, stride_tok;   // elements
-  int n, b, G;
+  int n, b, G, heads;
   float lambda, eps;
 };
 
-// Stage one head's [n,128] bf16 rows into LDS (row pitch kRowPitch), zero rows
-// beyond n, so MFMA fragments of padded blocks are zero.
+// One head's [n,128] bf16 rows: coalesced 16-byte loads into registers (rows beyond n read
+// as zero, so MFMA fragments of padded blocks are zero), then into the padded LDS stage.
 template <int NT>
-__device__ __forceinline__ void stage_rows(const char* __restrict__ src, long long stride_tok, int n,
-                                           char* stage, int tid) {
-  constexpr int kIters = NT * 32 * 16 / kDenseThreads;   // 16-byte chunks per thread
-  uint4 reg[kIters];
+__device__ __forceinline__ void load_rows(const char* __restrict__ src, long long stride_tok, int n,
+                                          int tid, uint4 (&reg)[NT * 32 * 16 / kDenseThreads]) {
+  constexpr int kIters = NT * 32 * 16 / kDenseThreads;
   const int chunk = tid & 15, r0 = tid >> 4;
 #pragma unroll
   for (int k = 0; k < kIters; ++k) {
@@ -121,11 +120,15 @@ __device__ __forceinline__ void stage_rows(const char* __restrict__ src, long lo
     reg[k] = make_uint4(0u, 0u, 0u, 0u);
     if (row < n) reg[k] = *reinterpret_cast<const uint4*>(src + (row * stride_tok + chunk * 8) * 2);
   }
+}
+template <int NT>
+__device__ __forceinline__ void store_rows(char* stage, int tid,
+                                           const uint4 (&reg)[NT * 32 * 16 / kDenseThreads]) {
+  constexpr int kIters = NT * 32 * 16 / kDenseThreads;
+  const int chunk = tid & 15, r0 = tid >> 4;
 #pragma unroll
-  for (int k = 0; k < kIters; ++k) {
-    const int row = r0 + 16 * k;
-    *reinterpret_cast<uint4*>(stage + row * kRowPitch + chunk * 16) = reg[k];
-  }
+  for (int k = 0; k < kIters; ++k)
+    *reinterpret_cast<uint4*>(stage + (r0 + 16 * k) * kRowPitch + chunk * 16) = reg[k];
 }
 
 __device__ __forceinline__ bf16x8 frag_at(const char* stage, int block, int ks, int lane) {
@@ -133,12 +136,16 @@ __device__ __forceinline__ bf16x8 frag_at(const char* stage, int block, int ks, 
   return *reinterpret_cast<const bf16x8*>(stage + row * kRowPitch + ks * 32 + hf * 16);
 }
 
+// Workgroups are persistent: each walks over heads blockIdx.x, blockIdx.x + gridDim.x, ...
+// While one wave runs the pick chain of a head, the rows (and scores) of the workgroup's next
+// head are already on their way from HBM into registers.
 template <int NT>
-__global__ __launch_bounds__(kDenseThreads) void retain_dense_kernel(DenseArgs a) {
+__global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense_kernel(DenseArgs a) {
   constexpr int N32 = NT * 32;
   constexpr int NQ = NT / 2;                         // tokens per lane in the greedy wave
   constexpr int NTILES = NT * (NT + 1) / 2;
-  constexpr int MAXT = (NTILES + 3) / 4;             // Gram tiles per wave
+  constexpr int MAXT = NT + 1;                       // Gram tiles per working wave
+  constexpr int kIters = NT * 32 * 16 / kDenseThreads;
   extern __shared__ __align__(16) char smem[];
   char* stage = smem;                                // staged rows (phase 1) ...
   float* tri = reinterpret_cast<float*>(smem);       // ... later the packed cosine triangle
@@ -149,257 +156,389 @@ __global__ __launch_bounds__(kDenseThreads) void retain_dense_kernel(DenseArgs a
   int32_t* order_l = idx_l + kMaxB;
   float* gain_l = reinterpret_cast<float*>(order_l + kMaxB);
 
-  const int h = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tid0 = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
   const int n = a.n, b = a.b;
-  const long long head_off = h * a.stride_head * 2;  // bytes
   const bool diverse = a.lambda != 0.0f;
+  const bool need_v = diverse && b > 1;
 
-  // ------------------------------------------------------------------ scores
-  if (a.Q) {
-    stage_rows<NT>(a.K + head_off, a.stride_tok, n, stage, tid);
-    bf16x8 qf[8];
-    {
-      const int g = lane & 31;
-      const char* qp = a.Q + (static_cast<long long>(h) * a.G + g) * kD * 2 + hf * 16;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        uint4 w = make_uint4(0u, 0u, 0u, 0u);
-        if (g < a.G) w = *reinterpret_cast<const uint4*>(qp + ks * 32);
-        qf[ks] = *reinterpret_cast<bf16x8*>(&w);
+  uint4 vpre[kIters];                                // rows of V of the head about to be processed
+  float spre = -INFINITY;                            // its score for token `tid` (scores given)
+  auto prefetch = [&](int hh, int tid) {
+    if (need_v) load_rows<NT>(a.V + hh * a.stride_head * 2, a.stride_tok, n, tid, vpre);
+    if (!a.Q && tid < N32) spre = tid < n ? a.s_in[static_cast<long long>(hh) * n + tid] : -INFINITY;
+  };
+  if (static_cast<int>(blockIdx.x) < a.heads) prefetch(blockIdx.x, tid0);
+
+#ifdef KVR_STATS
+  long long st_acc[4] = {0, 0, 0, 0};
+  long long st_x[2] = {0, 0};
+#endif
+  for (int h = blockIdx.x; h < a.heads; h += gridDim.x) {
+    const long long head_off = h * a.stride_head * 2;  // bytes
+    // The thread index is made opaque once per head: otherwise every per-lane LDS address of
+    // the body is loop-invariant, gets hoisted out of the head loop and lives in registers.
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, hf = lane >> 5;
+#ifdef KVR_STATS
+    const long long st0 = __builtin_readcyclecounter();
+    long long st_a = st0, st_b = st0;
+#endif
+    // ---------------------------------------------------------------- scores
+    if (a.Q) {
+      {
+        uint4 kreg[kIters];
+        load_rows<NT>(a.K + head_off, a.stride_tok, n, tid, kreg);
+        store_rows<NT>(stage, tid, kreg);
       }
-    }
-    __syncthreads();
-    constexpr int BPW = (NT + 3) / 4;                // token blocks per wave
-    float z[BPW][4];
-    const float scale = 0.08838834764831845f;        // 1/sqrt(128)
-    float zmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      bf16x8 qf[8];
+      {
+        const int g = lane & 31;
+        const char* qp = a.Q + (static_cast<long long>(h) * a.G + g) * kD * 2 + hf * 16;
 #pragma unroll
-    for (int k = 0; k < BPW; ++k) {
-      const int I = wave + 4 * k;
-      f32x16 acc = {0};
-      if (I < NT) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], frag_at(stage, I, ks, lane), acc, 0, 0, 0);
+        for (int ks = 0; ks < 8; ++ks) {
+          uint4 w = make_uint4(0u, 0u, 0u, 0u);
+          if (g < a.G) w = *reinterpret_cast<const uint4*>(qp + ks * 32);
+          qf[ks] = *reinterpret_cast<bf16x8*>(&w);
+        }
       }
-      const bool live = I < NT && (I * 32 + (lane & 31)) < n;
+      __syncthreads();
+      constexpr int BPW = (NT + 3) / 4;              // token blocks per wave
+      float z[BPW][4];
+      const float scale = 0.08838834764831845f;      // 1/sqrt(128)
+      float zmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+      for (int k = 0; k < BPW; ++k) {
+        const int I = wave + 4 * k;
+        f32x16 acc = {0};
+        if (I < NT) {
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], frag_at(stage, I, ks, lane), acc, 0, 0, 0);
+        }
+        const bool live = I < NT && (I * 32 + (lane & 31)) < n;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          z[k][r] = live ? acc[r] * scale : -INFINITY; // rows g = hf*4 + r of the 32x32 tile
+          zmax[r] = fmaxf(zmax[r], z[k][r]);
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        z[k][r] = live ? acc[r] * scale : -INFINITY;   // rows g = hf*4 + r of the 32x32 tile
-        zmax[r] = fmaxf(zmax[r], z[k][r]);
+        const float v = half_max_at_31(zmax[r]);
+        if ((lane & 31) == 31) red[wave * 8 + hf * 4 + r] = v;
       }
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float v = half_max_at_31(zmax[r]);
-      if ((lane & 31) == 31) red[wave * 8 + hf * 4 + r] = v;
-    }
-    __syncthreads();
-    float zsum[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int g = hf * 4 + r;
-      zmax[r] = fmaxf(fmaxf(red[g], red[8 + g]), fmaxf(red[16 + g], red[24 + g]));
-      zsum[r] = 0.f;
-    }
-#pragma unroll
-    for (int k = 0; k < BPW; ++k)
+      __syncthreads();
+      float zsum[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        z[k][r] = __expf(z[k][r] - zmax[r]);         // exp(-inf) = 0 for padded tokens
-        zsum[r] += z[k][r];
+        const int g = hf * 4 + r;
+        zmax[r] = fmaxf(fmaxf(red[g], red[8 + g]), fmaxf(red[16 + g], red[24 + g]));
+        zsum[r] = 0.f;
       }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float v = half_sum_at_31(zsum[r]);
-      if ((lane & 31) == 31) red[32 + wave * 8 + hf * 4 + r] = v;
-    }
-    __syncthreads();
-    const float invG = 1.0f / static_cast<float>(a.G);
-    float w[4];
+      for (int k = 0; k < BPW; ++k)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int g = hf * 4 + r;
-      const float tot = red[32 + g] + red[40 + g] + red[48 + g] + red[56 + g];
-      w[r] = g < a.G ? invG / tot : 0.f;
-    }
+        for (int r = 0; r < 4; ++r) {
+          z[k][r] = __expf(z[k][r] - zmax[r]);       // exp(-inf) = 0 for padded tokens
+          zsum[r] += z[k][r];
+        }
 #pragma unroll
-    for (int k = 0; k < BPW; ++k) {
-      const int I = wave + 4 * k;
-      float p = 0.f;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) p = fmaf(z[k][r], w[r], p);
-      p += __shfl_xor(p, 32, kWave);                 // queries 0-3 live in lanes 0-31, 4-7 in 32-63
-      const int j = I * 32 + (lane & 31);
-      if (I < NT && hf == 0) {
-        s_l[j] = j < n ? p : -INFINITY;               // padding never competes
-        if (j < n && a.s_out) a.s_out[static_cast<long long>(h) * n + j] = p;
+      for (int r = 0; r < 4; ++r) {
+        const float v = half_sum_at_31(zsum[r]);
+        if ((lane & 31) == 31) red[32 + wave * 8 + hf * 4 + r] = v;
       }
+      __syncthreads();
+      const float invG = 1.0f / static_cast<float>(a.G);
+      float w[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int g = hf * 4 + r;
+        const float tot = red[32 + g] + red[40 + g] + red[48 + g] + red[56 + g];
+        w[r] = g < a.G ? invG / tot : 0.f;
+      }
+#pragma unroll
+      for (int k = 0; k < BPW; ++k) {
+        const int I = wave + 4 * k;
+        float p = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) p = fmaf(z[k][r], w[r], p);
+        p += __shfl_xor(p, 32, kWave);               // queries 0-3 live in lanes 0-31, 4-7 in 32-63
+        const int j = I * 32 + (lane & 31);
+        if (I < NT && hf == 0) {
+          s_l[j] = j < n ? p : -INFINITY;             // padding never competes
+          if (j < n && a.s_out) a.s_out[static_cast<long long>(h) * n + j] = p;
+        }
+      }
+      __syncthreads();                                // K fragments are dead; s_l is complete
+    } else {
+      if (tid < N32) s_l[tid] = spre;
     }
-    __syncthreads();                                  // K fragments are dead; s_l is complete
-  } else {
-    for (int j = tid; j < N32; j += kDenseThreads)
-      s_l[j] = j < n ? a.s_in[static_cast<long long>(h) * n + j] : -INFINITY;
-  }
 
-  // -------------------------------------------------- Gram -> packed cosines
-  if (diverse && b > 1) {
-    stage_rows<NT>(a.V + head_off, a.stride_tok, n, stage, tid);
-    __syncthreads();
-    f32x16 acc[MAXT];
+    // ------------------------------------------------ Gram -> packed cosines
+    if (need_v) {
+      store_rows<NT>(stage, tid, vpre);
+      __syncthreads();
+#ifdef KVR_STATS
+      st_a = __builtin_readcyclecounter();
+#endif
+      // Tile rows are paired so that every working wave owns NT+1 tiles: wave w takes row
+      // NT-1-w (tiles J = 0..NT-1-w) and row w (tiles J = 0..w).  The row block's fragments stay
+      // in registers while the column blocks stream out of LDS.
+      f32x16 acc[MAXT];
+      const bool working = wave < NT / 2;
+      const int n1 = NT - wave;                       // tiles of the first row
+      if (working) {
+        bf16x8 af[8];
 #pragma unroll
-    for (int sl = 0; sl < MAXT; ++sl) {
-      const int t = wave * MAXT + sl;
-      acc[sl] = f32x16{0};
-      if (t < NTILES) {
-        int I = 0;
-        while ((I + 1) * (I + 2) / 2 <= t) ++I;
-        const int J = t - I * (I + 1) / 2;
+        for (int ks = 0; ks < 8; ++ks) af[ks] = frag_at(stage, NT - 1 - wave, ks, lane);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-          acc[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_at(stage, I, ks, lane),
-                                                            frag_at(stage, J, ks, lane), acc[sl], 0, 0, 0);
-        if (I == J) {                                 // squared norms sit on the diagonal
+        for (int sl = 0; sl < MAXT; ++sl) {
+          if (sl == n1) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int il = (r >> 2) * 8 + hf * 4 + (r & 3);
-            if (il == (lane & 31)) rinv[I * 32 + il] = acc[sl][r];
+            for (int ks = 0; ks < 8; ++ks) af[ks] = frag_at(stage, wave, ks, lane);
+          }
+          const int I = sl < n1 ? NT - 1 - wave : wave;
+          const int J = sl < n1 ? sl : sl - n1;
+          acc[sl] = f32x16{0};
+          __builtin_amdgcn_sched_barrier(0);          // keep one tile's fragment loads in flight, not all of them
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks)
+            acc[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks], frag_at(stage, J, ks, lane), acc[sl], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (I == J) {                               // squared norms sit on the diagonal
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int il = (r >> 2) * 8 + hf * 4 + (r & 3);
+              if (il == (lane & 31)) rinv[I * 32 + il] = acc[sl][r];
+            }
+          }
+        }
+      }
+      __syncthreads();                                // staged rows are dead from here on
+#ifdef KVR_STATS
+      st_b = __builtin_readcyclecounter();
+#endif
+      for (int j = tid; j < N32; j += kDenseThreads) rinv[j] = 1.0f / (sqrtf(rinv[j]) + a.eps);
+      __syncthreads();
+      if (working) {
+#pragma unroll
+        for (int sl = 0; sl < MAXT; ++sl) {
+          const int I = sl < n1 ? NT - 1 - wave : wave;
+          const int J = sl < n1 ? sl : sl - n1;
+          const int j = J * 32 + (lane & 31);
+          const float rc = rinv[j];
+          int i = I * 32 + hf * 4;                    // first of this lane's rows in the tile
+          int off = i * (i + 1) / 2 + j;              // T(i) + j; T(i+1) = T(i) + i + 1
+          if (I != J) {
+#pragma unroll
+            for (int R = 0; R < 4; ++R) {
+              const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
+              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+              int o = off;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                tri[o] = acc[sl][R * 4 + q] * rrow[q] * rc;
+                o += i + q + 1;
+              }
+              off += 8 * i + 36;                      // T(i+8) - T(i)
+              i += 8;
+            }
+          } else {
+            // Diagonal tile: only j <= i is stored, and (i,i) holds +inf: reading the row of a
+            // pick drives the pick's own m to +inf and its gain to -inf, which is how a
+            // selected token leaves the race.
+#pragma unroll
+            for (int R = 0; R < 4; ++R) {
+              const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
+              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+              int o = off;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const float c = j == i + q ? INFINITY : acc[sl][R * 4 + q] * rrow[q] * rc;
+                if (j <= i + q) tri[o] = c;
+                o += i + q + 1;
+              }
+              off += 8 * i + 36;
+              i += 8;
+            }
           }
         }
       }
     }
-    __syncthreads();                                  // staged rows are dead from here on
-    for (int j = tid; j < N32; j += kDenseThreads) rinv[j] = 1.0f / (sqrtf(rinv[j]) + a.eps);
     __syncthreads();
-#pragma unroll
-    for (int sl = 0; sl < MAXT; ++sl) {
-      const int t = wave * MAXT + sl;
-      if (t < NTILES) {
-        int I = 0;
-        while ((I + 1) * (I + 2) / 2 <= t) ++I;
-        const int J = t - I * (I + 1) / 2;
-        const int j = J * 32 + (lane & 31);
-        const float rc = rinv[j];
-#pragma unroll
-        for (int R = 0; R < 4; ++R) {
-          const int i0 = I * 32 + R * 8 + hf * 4;
-          const float4 rr = *reinterpret_cast<const float4*>(rinv + i0);
-          const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int i = i0 + q;
-            if (I != J || j <= i) tri[i * (i + 1) / 2 + j] = acc[sl][R * 4 + q] * rrow[q] * rc;
-          }
-        }
-      }
-    }
-  }
-  __syncthreads();
+#ifdef KVR_STATS
+    const long long st1 = __builtin_readcyclecounter();
+#endif
+    // the next head of this workgroup starts its trip from HBM now
+    if (h + static_cast<int>(gridDim.x) < a.heads) prefetch(h + gridDim.x, tid);
 
-  // ------------------------------------------------------------------ greedy
-  if (wave == 0) {
-    // Token j lives in lane j%64, slot j/64.  A selected (or padding) token has
-    // its score replaced by -inf, so its gain is -inf and it never ties with a
-    // finite maximum; the exact selected set is rebuilt from the pick list.
-    float sreg[NQ], mreg[NQ];
-    int jb4[NQ], tjb4[NQ];
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int j = lane + 64 * q;
-      sreg[q] = s_l[j];                                // -inf beyond n
-      mreg[q] = 0.f;
-      jb4[q] = j * 4;
-      tjb4[q] = (j * (j + 1) / 2) * 4;
-    }
-    const float nlam = -a.lambda;
-    const char* trib = reinterpret_cast<const char*>(tri);
-    for (int t = 0; t < b; ++t) {
-      float av[NQ];
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
-      float best = av[0];
-#pragma unroll
-      for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
-      const float amax = wave_max_uniform(best);
-      int i = -1;
-#pragma unroll
-      for (int q = NQ - 1; q >= 0; --q) {
-        const unsigned long long eq = __ballot(av[q] == amax);
-        if (eq) i = (__ffsll(static_cast<long long>(eq)) - 1) + 64 * q;
-      }
-      if (!(amax > -INFINITY)) {
-        // Non-finite input only: every remaining gain is -inf or NaN.  Take the
-        // lowest token that is not in the pick list yet (slow, never on finite data).
-        i = -1;
-#pragma unroll
-        for (int q = NQ - 1; q >= 0; --q) {
-          const int j = lane + 64 * q;
-          bool free_tok = j < n;
-          wave_lds_sync();                             // order_l is written by lane 0
-          for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
-          const unsigned long long al = __ballot(free_tok);
-          if (al) i = (__ffsll(static_cast<long long>(al)) - 1) + 64 * q;
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) sreg[q] = (jb4[q] == i * 4) ? -INFINITY : sreg[q];
-      if (lane == 0) { order_l[t] = i; gain_l[t] = amax; }
-      if (t + 1 == b || !diverse) continue;
-      // row i of the packed triangle: element (i,j) sits at max(T(i)+j, T(j)+i)
-      const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
+    // ---------------------------------------------------------------- greedy
+    if (wave == 0) {
+      // Token j lives in lane j%64, slot j/64.  Picks are collected one per lane and flushed to
+      // LDS every 64 picks.
+      float sreg[NQ], mreg[NQ];
+      int jb4[NQ], tjb4[NQ];
 #pragma unroll
       for (int q = 0; q < NQ; ++q) {
-        const int a0 = ti4 + jb4[q], a1 = tjb4[q] + i4;
-        const float c = *reinterpret_cast<const float*>(trib + (a0 > a1 ? a0 : a1));
-        mreg[q] = hw_max(mreg[q], c);
+        const int j = lane + 64 * q;
+        sreg[q] = s_l[j];                              // -inf beyond n
+        mreg[q] = 0.f;
+        jb4[q] = j * 4;
+        tjb4[q] = (j * (j + 1) / 2) * 4;
+      }
+      const float nlam = -a.lambda;
+      typedef __attribute__((address_space(3))) const float* lds_fp;
+      // LDS byte address of the triangle, folded into the per-lane offsets once
+      const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
+          (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
+      int ja[NQ], tja[NQ];
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) { ja[q] = jb4[q] + tri0; tja[q] = tjb4[q] + tri0; }
+      int rec_i = 0;
+      float rec_g = 0.f;
+      int t = 0;
+      bool finite = true;
+      // One pick: gains, DPP max, lowest tied index.  Returns the token, or -1 when no finite
+      // gain is left (non-finite input only).
+      auto pick = [&](float& amax) -> int {
+        float av[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
+        float best = av[0];
+#pragma unroll
+        for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
+        amax = wave_max_uniform(best);
+        int i = -1;
+#pragma unroll
+        for (int q = NQ - 1; q >= 0; --q) {
+          const unsigned long long eq = __ballot(av[q] == amax);
+          if (eq) i = (__ffsll(static_cast<long long>(eq)) - 1) + 64 * q;
+        }
+        return amax > -INFINITY ? i : -1;
+      };
+      auto record = [&](int i, float g) {
+        if (lane == (t & 63)) { rec_i = i; rec_g = g; }
+        if ((t & 63) == 63) { order_l[t - 63 + lane] = rec_i; gain_l[t - 63 + lane] = rec_g; }
+      };
+      if (diverse) {
+        // all picks but the last read the row of the pick; its diagonal entry (+inf) retires it
+        for (; t + 1 < b; ++t) {
+          float amax;
+          const int i = pick(amax);
+          if (i < 0) { finite = false; break; }
+          record(i, amax);
+          const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
+          float c[NQ];                                 // all slots' reads in flight before the first use
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) {
+            const int a0 = ti4 + ja[q], a1 = tja[q] + i4;     // element (i,j) sits at max(T(i)+j, T(j)+i)
+            c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a0 > a1 ? a0 : a1)));
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
+        }
+      } else {
+        for (; t + 1 < b; ++t) {
+          float amax;
+          const int i = pick(amax);
+          if (i < 0) { finite = false; break; }
+          record(i, amax);
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) sreg[q] = (jb4[q] == i * 4) ? -INFINITY : sreg[q];
+        }
+      }
+      if (finite) {
+        float amax;
+        const int i = pick(amax);
+        if (i < 0) finite = false;
+        else { record(i, amax); ++t; }
+      }
+      if (t & 63) {                                    // picks still held in registers
+        if (lane < (t & 63)) { order_l[(t & ~63) + lane] = rec_i; gain_l[(t & ~63) + lane] = rec_g; }
+      }
+      if (!finite) {
+        // Non-finite input only: fill up with the lowest tokens that are not in the pick list.
+        wave_lds_sync();
+        for (; t < b; ++t) {
+          int i = -1;
+#pragma unroll
+          for (int q = NQ - 1; q >= 0; --q) {
+            const int j = lane + 64 * q;
+            bool free_tok = j < n;
+            for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
+            const unsigned long long al = __ballot(free_tok);
+            if (al) i = (__ffsll(static_cast<long long>(al)) - 1) + 64 * q;
+          }
+          if (lane == 0) { order_l[t] = i; gain_l[t] = -INFINITY; }
+          wave_lds_sync();
+        }
+      }
+      // sort(S): flag the picked tokens, then ascending indices by prefix popcount
+      int32_t* flag = reinterpret_cast<int32_t*>(rinv);   // rinv is dead by now
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) flag[lane + 64 * q] = 0;
+      wave_lds_sync();                                   // order_l was written by other lanes
+      for (int u = lane; u < b; u += kWave) flag[order_l[u]] = 1;
+      wave_lds_sync();                                   // flags are set by other lanes
+      int off = 0;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const int j = lane + 64 * q;
+        const bool picked = flag[j] != 0;
+        const unsigned long long sel = __ballot(picked);
+        if (picked) {
+          const int rank = __popcll(sel & ((1ull << lane) - 1ull));
+          idx_l[off + rank] = j;
+        }
+        off += __popcll(sel);
       }
     }
-    // sort(S): flag the picked tokens, then ascending indices by prefix popcount
-    int32_t* flag = reinterpret_cast<int32_t*>(rinv);   // rinv is dead by now
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) flag[lane + 64 * q] = 0;
-    wave_lds_sync();                                   // order_l was written by lane 0
-    for (int u = lane; u < b; u += kWave) flag[order_l[u]] = 1;
-    wave_lds_sync();                                   // flags are set by other lanes
-    int off = 0;
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int j = lane + 64 * q;
-      const bool picked = flag[j] != 0;
-      const unsigned long long sel = __ballot(picked);
-      if (picked) {
-        const int rank = __popcll(sel & ((1ull << lane) - 1ull));
-        idx_l[off + rank] = j;
-      }
-      off += __popcll(sel);
-    }
-  }
-  __syncthreads();
+    __syncthreads();
 
-  // --------------------------------------------------- outputs and compaction
-  const long long ob = static_cast<long long>(h) * b;
-  for (int t = tid; t < b; t += kDenseThreads) {
-    a.idx_sorted[ob + t] = idx_l[t];
-    if (a.pick_order) a.pick_order[ob + t] = order_l[t];
-    if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
-  }
-  if (a.K_out || a.V_out) {
-    const int chunk = tid & 15;
-    for (int t0 = 0; t0 < b; t0 += kDenseThreads / 16) {
-      const int t = t0 + (tid >> 4);
-      if (t < b) {
-        const int it = min(max(idx_l[t], 0), n - 1);   // never read outside the head, whatever the scores were
-        const long long src = head_off + (it * a.stride_tok + chunk * 8) * 2;
-        const long long dst = ((ob + t) * kD + chunk * 8) * 2;
-        uint4 kv, vv;
-        if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
-        if (a.V_out) vv = *reinterpret_cast<const uint4*>(a.V + src);
-        if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kv;
-        if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vv;
+#ifdef KVR_STATS
+    const long long st2 = __builtin_readcyclecounter();
+#endif
+    // ------------------------------------------------- outputs and compaction
+    const long long ob = static_cast<long long>(h) * b;
+    for (int t = tid; t < b; t += kDenseThreads) {
+      a.idx_sorted[ob + t] = idx_l[t];
+      if (a.pick_order) a.pick_order[ob + t] = order_l[t];
+      if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
+    }
+    if (a.K_out || a.V_out) {
+      const int chunk = tid & 15;
+      for (int t0 = 0; t0 < b; t0 += kDenseThreads / 16) {
+        const int t = t0 + (tid >> 4);
+        if (t < b) {
+          const int it = min(max(idx_l[t], 0), n - 1);   // never read outside the head, whatever the scores were
+          const long long src = head_off + (it * a.stride_tok + chunk * 8) * 2;
+          const long long dst = ((ob + t) * kD + chunk * 8) * 2;
+          uint4 kv, vv;
+          if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
+          if (a.V_out) vv = *reinterpret_cast<const uint4*>(a.V + src);
+          if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kv;
+          if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vv;
+        }
       }
     }
+    __syncthreads();                                   // idx_l / s_l are reused by the next head
+#ifdef KVR_STATS
+    {
+      const long long st3 = __builtin_readcyclecounter();
+      st_acc[0] += st1 - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2; st_acc[3] += 1;
+      st_x[0] += st_a - st0; st_x[1] += st_b - st_a;
+      if (tid == 0 && a.pick_gain && b >= 4) {
+        a.pick_gain[ob + b - 1] = static_cast<float>(st_acc[0]) / st_acc[3];
+        a.pick_gain[ob + b - 2] = static_cast<float>(st_acc[1]) / st_acc[3];
+        a.pick_gain[ob + b - 3] = static_cast<float>(st_acc[2]) / st_acc[3];
+        a.pick_gain[ob + b - 4] = static_cast<float>(st_x[0]) / st_acc[3];
+        a.pick_gain[ob + b - 5] = static_cast<float>(st_x[1]) / st_acc[3];
+      }
+    }
+#endif
   }
 }
 
@@ -417,12 +556,24 @@ hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int 
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);
   a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
-  a.n = lay.n; a.b = b; a.G = G; a.lambda = lambda; a.eps = eps;
-  dim3 grid(lay.heads), block(kDenseThreads);
+  a.n = lay.n; a.b = b; a.G = G; a.heads = lay.heads; a.lambda = lambda; a.eps = eps;
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+  }
+  dim3 block(kDenseThreads);
   auto go = [&](auto kern, int smem) -> hipError_t {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
+    // persistent workgroups: as many as fit the chip at once (LDS-limited), never more than heads
+    int per_cu = 160 * 1024 / smem;
+    per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+    const int blocks = lay.heads < cus * per_cu ? lay.heads : cus * per_cu;
+    dim3 grid(blocks);
     hipLaunchKernelGGL(kern, grid, block, smem, st, a);
     return hipGetLastError();
   };
