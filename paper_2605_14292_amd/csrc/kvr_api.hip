@@ -92,6 +92,9 @@ int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay, int 
   if (kvr::dense_supported(l, b, 0, false))
     e = kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
                                  pick_order, pick_gain, nullptr, nullptr, st);
+  else if (kvr::pool_supported(l, b))
+    e = kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
+                                nullptr, nullptr, st);
   else if (kvr::blocked_supported(l, b))
     e = kvr::launch_select_blocked(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                    nullptr, nullptr, st);
@@ -140,6 +143,11 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
   if (Q) {
     if (kvr::launch_score(K, Q, G, l, s_out, st) != hipSuccess) return KVR_ERR_HIP;
     s = s_out;
+  }
+  if (kvr::pool_supported(l, b)) {
+    const hipError_t e = kvr::launch_select_pool(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
+                                                 pick_gain, K_out, V_out, st);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (kvr::blocked_supported(l, b)) {
     const hipError_t e = kvr::launch_select_blocked(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,

@@ -33,4 +33,11 @@ hipError_t launch_select_blocked(const void* K, const void* V, const float* s, c
                                  float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
                                  float* pick_gain, void* K_out, void* V_out, hipStream_t st);
 
+// Pool-based exact greedy for bf16 heads with 256 < n <= 4096 and b <= 256 (selection plus
+// optional compaction; scores come in through s).
+bool pool_supported(const Layout& lay, int b);
+hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                              float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st);
+
 }  // namespace kvr

@@ -1,0 +1,514 @@
+// Greedy selection (paper Sec. 4.1, Algorithm 1) for heads with 256 < n <= 4096
+// bf16 tokens and b <= 256, followed by the compaction of the kept rows.
+//
+// Exact greedy on a pool.  Streaming all of V for every pick (one cosine row per
+// pick) is what Algorithm 1 asks for literally; it is also what makes large n
+// memory-bound many times over.  Gains only ever decrease (m only grows), so the
+// selection is organised in epochs:
+//   1. every token's m is up to date; the P = 128 currently best unselected
+//      tokens form the pool (each wave contributes its best P/W, found by a
+//      bitwise threshold search on the gains), and the best gain outside the
+//      pool is recorded as the bound;
+//   2. the pool's rows are gathered into LDS and their P x P cosine triangle is
+//      computed on bf16 MFMA (32x32x16, fp32 accumulate), exactly as in the
+//      small-n kernel;
+//   3. one wave runs Algorithm 1 inside the pool (DPP argmax, one LDS row read
+//      per pick) for as long as the pool's best (gain, lower index) beats the
+//      bound -- the bound can only have dropped since, so such a pick is the
+//      exact argmax of Eq. 2 over all unselected tokens;
+//   4. one pass over V applies the rows picked in the epoch (<= 32, as one or two
+//      16-row MFMA operands, 16x16x32) to every token outside the pool.
+// On the benchmark inputs an epoch serves ~20 picks, so V is streamed ~b/20
+// times.  Nothing is approximated.
+//
+// Layout: one workgroup per head, W wave64s, token j = 64*S*w + 64*k + lane in
+// wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
+// lane's registers for the whole event.
+#include "kvr_device.hpp"
+#include "kvr_kernels.hpp"
+
+namespace kvr {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kPool = 128;          // pool size
+constexpr int kPoolMaxB = 256;      // pick lists kept in LDS
+constexpr int kPoolMaxPend = 32;    // picks per epoch (two 16-row MFMA operands)
+constexpr int kPoolPitch = 272;     // bytes per staged row (256 + 16)
+constexpr int kPoolChunk = 16;      // tokens staged per step and wave in the pass over V
+
+__device__ __forceinline__ float pool_wave_max(float v) {
+  asm volatile(
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float pool_hw_max(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ void pool_wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+struct PoolArgs {
+  const char* K; const char* V; const float* s_in;
+  int32_t* idx_sorted; int32_t* pick_order; float* pick_gain;
+  char* K_out; char* V_out;
+  long long stride_head, stride_tok;   // elements
+  int n, b;
+  float lambda, eps;
+};
+
+template <int W, int S> struct PoolCfg {
+  static constexpr int kWaveStage = kPoolChunk * kPoolPitch + 1024;   // row stage + 256-float scratch per wave
+  static constexpr int kTriBytes = kPool * (kPool + 1) / 2 * 4;
+  static constexpr int kUnion = (W * kWaveStage > kTriBytes ? W * kWaveStage : kTriBytes);
+  // floats: slots 64 | shared 16 | wcount 16 | pool_tok,r,s,m,picked 5*128 | pend 32 | pend_r 32 |
+  //         order,gain,idxs 3*kPoolMaxB | rn 64*S*W ; then pool rows ; then the union area
+  static constexpr int kFixedFloats = 64 + 16 + 16 + 5 * kPool + 64 + 3 * kPoolMaxB + 64 * S * W;
+  static constexpr int kSmemBytes = kFixedFloats * 4 + kPool * kPoolPitch + kUnion;
+};
+
+template <int W, int S>
+__global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(PoolArgs a) {
+  using Cfg = PoolCfg<W, S>;
+  constexpr int TPW = 64 * S;
+  constexpr int NT = 64 * W;
+  constexpr int Q = kPool / W;                     // pool members contributed per wave
+  constexpr int CH = kPoolChunk;
+  constexpr int LPC = CH / 4;
+  extern __shared__ __align__(16) float smem[];
+  float* slot_gain = smem;                                       // [2][16]
+  int32_t* slot_idx = reinterpret_cast<int32_t*>(smem + 32);     // [2][16]
+  int32_t* shared_i = reinterpret_cast<int32_t*>(smem + 64);     // [16] np, t, stop reason
+  int32_t* wcount = reinterpret_cast<int32_t*>(smem + 80);       // [16]
+  int32_t* pool_tok = reinterpret_cast<int32_t*>(smem + 96);     // [P] token of the member, -1 = none
+  float* pool_r = smem + 96 + kPool;
+  float* pool_s = smem + 96 + 2 * kPool;
+  float* pool_m = smem + 96 + 3 * kPool;
+  int32_t* pool_picked = reinterpret_cast<int32_t*>(smem + 96 + 4 * kPool);
+  int32_t* pend_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool);        // [32] pool slots picked this epoch
+  float* pend_r = smem + 96 + 5 * kPool + 32;                                  // [32] their inverse norms
+  int32_t* order_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64);
+  float* gain_l = smem + 96 + 5 * kPool + 64 + kPoolMaxB;
+  int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64 + 2 * kPoolMaxB);
+  float* rn = smem + Cfg::kFixedFloats - TPW * W;                // [n padded] inverse norms, later pick flags
+  int32_t* flag = reinterpret_cast<int32_t*>(rn);
+  char* prow = reinterpret_cast<char*>(smem + Cfg::kFixedFloats);   // [P][272 B] pool rows
+  char* uni = prow + kPool * kPoolPitch;
+  float* tri = reinterpret_cast<float*>(uni);                    // packed P x P cosine triangle (race) ...
+  // ... or the per-wave row stages of the pass over V
+
+  const int h = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = a.n, b = a.b;
+  const long long head_off = h * a.stride_head * 2;             // bytes
+  const char* Vh = a.V + head_off;
+  const bool diverse = a.lambda != 0.0f;
+  const int base = w * TPW;
+  char* stage = uni + w * Cfg::kWaveStage;
+  float* scratch = reinterpret_cast<float*>(stage + CH * kPoolPitch);
+
+  float s[S], m[S], r[S];
+  int tok[S], pslot[S];          // pslot: pool slot of this token in the current epoch, or -1
+#pragma unroll
+  for (int k = 0; k < S; ++k) {
+    tok[k] = base + 64 * k + lane;
+    s[k] = tok[k] < n ? a.s_in[static_cast<long long>(h) * n + tok[k]] : -INFINITY;
+    m[k] = 0.f;
+    r[k] = 0.f;
+    pslot[k] = -1;
+  }
+  const float nlam = -a.lambda;
+  int par = 0;
+  int t = 0;
+  bool starved = false;
+
+  auto wg_argmax = [&](const float (&av)[S], float& gbest, int& ibest) {
+    float best = av[0];
+#pragma unroll
+    for (int k = 1; k < S; ++k) best = pool_hw_max(best, av[k]);
+    const float amax_w = pool_wave_max(best);
+    int i_w = -1;
+#pragma unroll
+    for (int k = S - 1; k >= 0; --k) {
+      const unsigned long long eq = __ballot(av[k] == amax_w);
+      if (eq) i_w = base + 64 * k + (__ffsll(static_cast<long long>(eq)) - 1);
+    }
+    if (lane == 0) { slot_gain[par * 16 + w] = amax_w; slot_idx[par * 16 + w] = i_w; }
+    __syncthreads();
+    const float g = lane < W ? slot_gain[par * 16 + lane] : -INFINITY;
+    const int ii = lane < W ? slot_idx[par * 16 + lane] : -1;
+    par ^= 1;
+    gbest = pool_wave_max(g);
+    const unsigned long long eqw = __ballot(lane < W && g == gbest);
+    ibest = eqw ? __builtin_amdgcn_readlane(ii, __ffsll(static_cast<long long>(eqw)) - 1) : -1;
+  };
+
+  if (!diverse || b == 1) {
+    for (; t < b; ++t) {
+      float gmax; int i;
+      wg_argmax(s, gmax, i);
+      if (!(gmax > -INFINITY)) { starved = true; break; }
+      if (tid == 0) { order_l[t] = i; gain_l[t] = gmax; }
+#pragma unroll
+      for (int k = 0; k < S; ++k) s[k] = tok[k] == i ? -INFINITY : s[k];
+    }
+  } else {
+    // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the first read of V from HBM
+    {
+      const int c16 = tid & 15;
+      for (int j0 = 0; j0 < n; j0 += NT / 16) {
+        const int j = j0 + (tid >> 4);
+        if (j < n) {
+          float x[8];
+          load8<DT_BF16>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2, x);
+          float ss = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+          ss = group16_sum(ss);
+          if (c16 == 0) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < S; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
+    }
+
+    while (t < b) {
+      // ================= 1. pool = the best Q unselected tokens of every wave =================
+      float g[S];
+      uint32_t key[S];
+#pragma unroll
+      for (int k = 0; k < S; ++k) { g[k] = fmaf(nlam, m[k], s[k]); key[k] = ordered_key(g[k]); }
+      uint32_t tau = 0;                              // largest key value with at least Q keys >= it
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = tau | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < S; ++k) c += __popcll(__ballot(key[k] >= cand));
+        if (c >= Q) tau = cand;
+      }
+      int taken = 0;                                 // members with key > tau come first, ties in token order
+#pragma unroll
+      for (int k = 0; k < S; ++k) taken += __popcll(__ballot(key[k] > tau));
+      int need_eq = Q - taken;                       // how many of the key == tau tokens join
+      int rank_base = 0;
+      float go[S];                                   // gains of the tokens left outside
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        const bool above = key[k] > tau, equal = key[k] == tau;
+        const unsigned long long eqm = __ballot(equal);
+        const int eq_before = __popcll(eqm & ((1ull << lane) - 1ull));
+        const bool in = above || (equal && eq_before < need_eq);
+        const unsigned long long inm = __ballot(in);
+        const int slot = w * Q + rank_base + __popcll(inm & ((1ull << lane) - 1ull));
+        pslot[k] = in ? slot : -1;
+        if (in) {
+          pool_tok[slot] = tok[k] < n ? tok[k] : -1;
+          pool_r[slot] = r[k];
+          pool_s[slot] = s[k];
+          pool_m[slot] = m[k];
+          pool_picked[slot] = 0;
+        }
+        go[k] = in ? -INFINITY : g[k];
+        rank_base += __popcll(inm);
+        const int eq_in = __popcll(eqm);
+        need_eq -= eq_in < need_eq ? eq_in : need_eq;
+      }
+      float gout; int jout;
+      wg_argmax(go, gout, jout);                     // barrier inside: the pool tables are complete
+      // ================= 2. pool rows -> LDS, cosine triangle on MFMA =================
+      for (int p0 = 0; p0 < kPool; p0 += NT / 16) {
+        const int p = p0 + (tid >> 4);
+        const int tk = pool_tok[p];
+        uint4 x = make_uint4(0u, 0u, 0u, 0u);
+        if (tk >= 0) x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(tk) * a.stride_tok + (tid & 15) * 8) * 2);
+        *reinterpret_cast<uint4*>(prow + p * kPoolPitch + (tid & 15) * 16) = x;
+      }
+      __syncthreads();
+      {
+        const int hf = lane >> 5;
+        for (int tile = w; tile < 10; tile += W) {   // lower-triangular 32x32 tiles of the 128 x 128 matrix
+          int I = 0;
+          while ((I + 1) * (I + 2) / 2 <= tile) ++I;
+          const int J = tile - I * (I + 1) / 2;
+          f32x16 acc = {0};
+          const char* pa = prow + (I * 32 + (lane & 31)) * kPoolPitch + hf * 16;
+          const char* pb = prow + (J * 32 + (lane & 31)) * kPoolPitch + hf * 16;
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pa + ks * 32),
+                                                          *reinterpret_cast<const bf16x8*>(pb + ks * 32), acc, 0, 0, 0);
+          const int j = J * 32 + (lane & 31);
+          const float rc = pool_r[j];
+          int i = I * 32 + hf * 4;
+          int off = i * (i + 1) / 2 + j;
+#pragma unroll
+          for (int R = 0; R < 4; ++R) {
+            const float4 rr = *reinterpret_cast<const float4*>(pool_r + i);
+            const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+            int o = off;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              // the diagonal holds +inf: the row of a pick retires the pick itself
+              const float c = (I == J && j == i + q) ? INFINITY : acc[R * 4 + q] * rrow[q] * rc;
+              if (I != J || j <= i + q) tri[o] = c;
+              o += i + q + 1;
+            }
+            off += 8 * i + 36;
+            i += 8;
+          }
+        }
+      }
+      __syncthreads();
+      // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
+      if (w == 0) {
+        float sreg[2], mreg[2];
+        int treg[2], ja[2], tja[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int p = lane + 64 * q;
+          sreg[q] = pool_s[p]; mreg[q] = pool_m[p]; treg[q] = pool_tok[p];
+          ja[q] = p * 4; tja[q] = (p * (p + 1) / 2) * 4;
+        }
+        const int jb = jout < 0 ? 0x7fffffff : jout;
+        int np = 0, stop = 0;                        // stop: 1 = bound wins, 2 = nothing finite left
+        const char* trib = reinterpret_cast<const char*>(tri);
+        while (t < b && np < kPoolMaxPend) {
+          const float a0 = fmaf(nlam, mreg[0], sreg[0]), a1 = fmaf(nlam, mreg[1], sreg[1]);
+          const float amax = pool_wave_max(pool_hw_max(a0, a1));
+          if (!(amax > -INFINITY)) { stop = jout < 0 ? 2 : 1; break; }
+          const unsigned long long e0 = __ballot(a0 == amax), e1 = __ballot(a1 == amax);
+          const int il = e0 ? __ffsll(static_cast<long long>(e0)) - 1 : __ffsll(static_cast<long long>(e1)) - 1;
+          const int i = e0 ? il : il + 64;           // pool slots are in token order, lowest slot = lowest token
+          const int ti = __builtin_amdgcn_readlane(e0 ? treg[0] : treg[1], il);
+          if (!(amax > gout || (amax == gout && ti < jb))) { stop = 1; break; }
+          if (lane == 0) {
+            order_l[t] = ti; gain_l[t] = amax; pend_l[np] = i; pend_r[np] = pool_r[i]; pool_picked[i] = 1;
+          }
+          ++t; ++np;
+          if (t == b) break;
+          const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
+          float c[2];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int x0 = ti4 + ja[q], x1 = tja[q] + i4;
+            c[q] = *reinterpret_cast<const float*>(trib + (x0 > x1 ? x0 : x1));
+          }
+          mreg[0] = pool_hw_max(mreg[0], c[0]);
+          mreg[1] = pool_hw_max(mreg[1], c[1]);
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) pool_m[lane + 64 * q] = mreg[q];   // the pool's m is authoritative
+        if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
+      }
+      __syncthreads();
+      const int np = shared_i[0];
+      t = shared_i[1];
+      const int stop = shared_i[2];
+      // pool members: m from the race, picked members leave
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        if (pslot[k] >= 0) {
+          m[k] = pool_m[pslot[k]];
+          if (pool_picked[pslot[k]]) s[k] = -INFINITY;
+        }
+      }
+      if (t >= b) break;
+      if (stop == 2 || (np == 0 && !(gout > -INFINITY))) { starved = true; break; }
+      if (np == 0 && t + 1 == b) {                   // the outside token wins the last pick: no row needed
+        if (tid == 0) { order_l[t] = jout; gain_l[t] = gout; }
+#pragma unroll
+        for (int k = 0; k < S; ++k) s[k] = tok[k] == jout ? -INFINITY : s[k];
+        ++t;
+        break;
+      }
+      if (np == 0) { starved = true; break; }        // cannot happen on finite input: the best token is in the pool
+      __syncthreads();                               // everyone is done with the triangle (the stages alias it)
+      // ================= 4. one pass over V: the epoch's picks against every outside token =================
+      if (np > 0) {
+        const int kg = lane >> 4;
+        const int tiles = (np + 15) >> 4;            // 1 or 2 A operands of 16 picked rows
+        bf16x8 af[2][4];
+        float pr[2][4];
+#pragma unroll
+        for (int at = 0; at < 2; ++at) {
+          const int pi = at * 16 + (lane & 15);
+          const int ps = pi < np ? pend_l[pi] : -1;
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            uint4 x = make_uint4(0u, 0u, 0u, 0u);
+            if (ps >= 0) x = *reinterpret_cast<const uint4*>(prow + ps * kPoolPitch + ks * 64 + kg * 16);
+            af[at][ks] = *reinterpret_cast<bf16x8*>(&x);
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int ri = at * 16 + 4 * kg + i;     // result row i of this lane belongs to pick ri
+            pr[at][i] = ri < np ? pend_r[ri] : 0.f;
+          }
+        }
+        uint4 pre[LPC];
+        auto fetch = [&](int ch) {
+          int row0 = base + (lane >> 4);
+          asm volatile("" : "+v"(row0));             // keep the unrolled pass from hoarding addresses
+#pragma unroll
+          for (int q = 0; q < LPC; ++q) {
+            const int row = row0 + ch * CH + 4 * q;
+            pre[q] = make_uint4(0u, 0u, 0u, 0u);
+            if (row < n) pre[q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
+          }
+        };
+        fetch(0);
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+          float part[4];                             // per 16-token sub-block: max over my four picked rows
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub) {
+            const int ch = k * 4 + sub;
+            pool_wave_sync();
+#pragma unroll
+            for (int q = 0; q < LPC; ++q)
+              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) = pre[q];
+            pool_wave_sync();
+            if (ch + 1 < TPW / CH) fetch(ch + 1);
+            const char* fp = stage + (lane & 15) * kPoolPitch + kg * 16;
+            bf16x8 bfr[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bfr[ks] = *reinterpret_cast<const bf16x8*>(fp + ks * 64);
+            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[0][ks], bfr[ks], acc0, 0, 0, 0);
+            float pm = pool_hw_max(pool_hw_max(acc0[0] * pr[0][0], acc0[1] * pr[0][1]),
+                                   pool_hw_max(acc0[2] * pr[0][2], acc0[3] * pr[0][3]));
+            if (tiles > 1) {
+              f32x4 acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+              for (int ks = 0; ks < 4; ++ks) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][ks], bfr[ks], acc1, 0, 0, 0);
+              const float pm1 = pool_hw_max(pool_hw_max(acc1[0] * pr[1][0], acc1[1] * pr[1][1]),
+                                            pool_hw_max(acc1[2] * pr[1][2], acc1[3] * pr[1][3]));
+              pm = pool_hw_max(pm, pm1);
+            }
+            part[sub] = pm;
+          }
+          // lane (col, kg) holds partial maxima of token col of sub-block 0..3; the owner of token
+          // (sub, col) is lane (col, kg = sub).  Exchange through the wave's scratch: [sub][kg][col].
+          pool_wave_sync();
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub) scratch[sub * 64 + kg * 16 + (lane & 15)] = part[sub];
+          pool_wave_sync();
+          const float* sp = scratch + kg * 64 + (lane & 15);
+          const float mx = pool_hw_max(pool_hw_max(sp[0], sp[16]), pool_hw_max(sp[32], sp[48]));
+          if (pslot[k] < 0) m[k] = pool_hw_max(m[k], mx * r[k]);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < S; ++k) pslot[k] = -1;
+      __syncthreads();                               // stages are dead: the next epoch reuses the area
+    }
+  }
+
+  // ---- sort(S): flag the picked tokens, ascending indices by prefix counts
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < S; ++k) flag[base + 64 * k + lane] = 0;
+  __syncthreads();
+  for (int u = tid; u < t; u += NT) flag[order_l[u]] = 1;
+  __syncthreads();
+  if (starved) {
+    if (tid == 0) {                                  // non-finite input only: lowest unpicked tokens fill up
+      int j = 0;
+      for (int u = t; u < b; ++u) {
+        while (j < n - 1 && flag[j]) ++j;
+        order_l[u] = j; gain_l[u] = -INFINITY; flag[j] = 1;
+      }
+    }
+    __syncthreads();
+  }
+  {
+    unsigned long long sel[S];
+    int cnt = 0;
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+      sel[k] = __ballot(tok[k] < n && flag[tok[k]] != 0);
+      cnt += __popcll(sel[k]);
+    }
+    if (lane == 0) wcount[w] = cnt;
+    __syncthreads();
+    int off = 0;
+    for (int u = 0; u < w; ++u) off += wcount[u];
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+      if ((sel[k] >> lane) & 1ull) {
+        const int rank = off + __popcll(sel[k] & ((1ull << lane) - 1ull));
+        if (rank < b) idxs_l[rank] = tok[k];
+      }
+      off += __popcll(sel[k]);
+    }
+  }
+  __syncthreads();
+  const long long ob = static_cast<long long>(h) * b;
+  for (int u = tid; u < b; u += NT) {
+    a.idx_sorted[ob + u] = idxs_l[u];
+    if (a.pick_order) a.pick_order[ob + u] = order_l[u];
+    if (a.pick_gain) a.pick_gain[ob + u] = gain_l[u];
+  }
+  if (a.K_out || a.V_out) {
+    const int chunk = tid & 15;
+    for (int t0 = 0; t0 < b; t0 += NT / 16) {
+      const int u = t0 + (tid >> 4);
+      if (u < b) {
+        const int it = min(max(idxs_l[u], 0), n - 1);
+        const long long src = head_off + (static_cast<long long>(it) * a.stride_tok + chunk * 8) * 2;
+        const long long dst = ((ob + u) * kD + chunk * 8) * 2;
+        uint4 kv, vv;
+        if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
+        if (a.V_out) vv = *reinterpret_cast<const uint4*>(a.V + src);
+        if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kv;
+        if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vv;
+      }
+    }
+  }
+}
+
+bool pool_supported(const Layout& lay, int b) {
+  return lay.dtype == DT_BF16 && lay.n > 256 && lay.n <= 4096 && b <= kPoolMaxB;
+}
+
+hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                              float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st) {
+  PoolArgs a;
+  a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s_in = s;
+  a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
+  a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);
+  a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
+  a.n = lay.n; a.b = b; a.lambda = lambda; a.eps = eps;
+  dim3 grid(lay.heads);
+  auto go = [&](auto kern, int threads, int smem) -> hipError_t {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, dim3(threads), smem, st, a);
+    return hipGetLastError();
+  };
+  if (lay.n <= 512) return go(&select_pool_kernel<2, 4>, 128, PoolCfg<2, 4>::kSmemBytes);
+  if (lay.n <= 1024) return go(&select_pool_kernel<4, 4>, 256, PoolCfg<4, 4>::kSmemBytes);
+  if (lay.n <= 2048) return go(&select_pool_kernel<8, 4>, 512, PoolCfg<8, 4>::kSmemBytes);
+  return go(&select_pool_kernel<8, 8>, 512, PoolCfg<8, 8>::kSmemBytes);
+}
+
+}  // namespace kvr
