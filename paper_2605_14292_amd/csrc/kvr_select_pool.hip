@@ -188,7 +188,13 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       for (int k = 0; k < S; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
     }
 
+#ifdef KVR_STATS
+    long long st[6] = {0, 0, 0, 0, 0, 0};
+#endif
     while (t < b) {
+#ifdef KVR_STATS
+      const long long c0 = __builtin_readcyclecounter();
+#endif
       // ================= 1. pool = the best Q unselected tokens of every wave =================
       float g[S];
       uint32_t key[S];
@@ -231,6 +237,9 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       }
       float gout; int jout;
       wg_argmax(go, gout, jout);                     // barrier inside: the pool tables are complete
+#ifdef KVR_STATS
+      const long long c1 = __builtin_readcyclecounter();
+#endif
       // ================= 2. pool rows -> LDS, cosine triangle on MFMA =================
       for (int p0 = 0; p0 < kPool; p0 += NT / 16) {
         const int p = p0 + (tid >> 4);
@@ -256,25 +265,44 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           const int j = J * 32 + (lane & 31);
           const float rc = pool_r[j];
           int i = I * 32 + hf * 4;
-          int off = i * (i + 1) / 2 + j;
+          int off = i * (i + 1) / 2 + j;               // T(i) + j; T(i+1) = T(i) + i + 1
+          if (I != J) {
 #pragma unroll
-          for (int R = 0; R < 4; ++R) {
-            const float4 rr = *reinterpret_cast<const float4*>(pool_r + i);
-            const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-            int o = off;
+            for (int R = 0; R < 4; ++R) {
+              const float4 rr = *reinterpret_cast<const float4*>(pool_r + i);
+              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+              int o = off;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              // the diagonal holds +inf: the row of a pick retires the pick itself
-              const float c = (I == J && j == i + q) ? INFINITY : acc[R * 4 + q] * rrow[q] * rc;
-              if (I != J || j <= i + q) tri[o] = c;
-              o += i + q + 1;
+              for (int q = 0; q < 4; ++q) {
+                tri[o] = acc[R * 4 + q] * rrow[q] * rc;
+                o += i + q + 1;
+              }
+              off += 8 * i + 36;
+              i += 8;
             }
-            off += 8 * i + 36;
-            i += 8;
+          } else {
+#pragma unroll
+            for (int R = 0; R < 4; ++R) {
+              const float4 rr = *reinterpret_cast<const float4*>(pool_r + i);
+              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+              int o = off;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                // the diagonal holds +inf: the row of a pick retires the pick itself
+                const float c = j == i + q ? INFINITY : acc[R * 4 + q] * rrow[q] * rc;
+                if (j <= i + q) tri[o] = c;
+                o += i + q + 1;
+              }
+              off += 8 * i + 36;
+              i += 8;
+            }
           }
         }
       }
       __syncthreads();
+#ifdef KVR_STATS
+      const long long c2 = __builtin_readcyclecounter();
+#endif
       // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
       if (w == 0) {
         float sreg[2], mreg[2];
@@ -317,6 +345,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
       }
       __syncthreads();
+#ifdef KVR_STATS
+      const long long c3 = __builtin_readcyclecounter();
+      st[0] += c1 - c0; st[1] += c2 - c1; st[2] += c3 - c2; st[4] += 1;
+#endif
       const int np = shared_i[0];
       t = shared_i[1];
       const int stop = shared_i[2];
@@ -361,30 +393,36 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
             pr[at][i] = ri < np ? pend_r[ri] : 0.f;
           }
         }
-        uint4 pre[LPC];
-        auto fetch = [&](int ch) {
+        uint4 pre[4][LPC];                           // the next 64 tokens of this wave, in flight
+        auto fetch = [&](int kk) {
           int row0 = base + (lane >> 4);
           asm volatile("" : "+v"(row0));             // keep the unrolled pass from hoarding addresses
 #pragma unroll
-          for (int q = 0; q < LPC; ++q) {
-            const int row = row0 + ch * CH + 4 * q;
-            pre[q] = make_uint4(0u, 0u, 0u, 0u);
-            if (row < n) pre[q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
-          }
+          for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+            for (int q = 0; q < LPC; ++q) {
+              const int row = row0 + (kk * 4 + sub) * CH + 4 * q;
+              pre[sub][q] = make_uint4(0u, 0u, 0u, 0u);
+              if (row < n) pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
+            }
         };
         fetch(0);
 #pragma unroll
         for (int k = 0; k < S; ++k) {
+          uint4 cur[4][LPC];
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+            for (int q = 0; q < LPC; ++q) cur[sub][q] = pre[sub][q];
+          if (k + 1 < S) fetch(k + 1);
           float part[4];                             // per 16-token sub-block: max over my four picked rows
 #pragma unroll
           for (int sub = 0; sub < 4; ++sub) {
-            const int ch = k * 4 + sub;
             pool_wave_sync();
 #pragma unroll
             for (int q = 0; q < LPC; ++q)
-              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) = pre[q];
+              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) = cur[sub][q];
             pool_wave_sync();
-            if (ch + 1 < TPW / CH) fetch(ch + 1);
             const char* fp = stage + (lane & 15) * kPoolPitch + kg * 16;
             bf16x8 bfr[4];
 #pragma unroll
@@ -418,7 +456,16 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #pragma unroll
       for (int k = 0; k < S; ++k) pslot[k] = -1;
       __syncthreads();                               // stages are dead: the next epoch reuses the area
+#ifdef KVR_STATS
+      st[3] += __builtin_readcyclecounter() - c3;
+#endif
     }
+#ifdef KVR_STATS
+    __syncthreads();
+    if (tid == 0 && b >= 8) {
+      for (int q = 0; q < 5; ++q) gain_l[b - 1 - q] = static_cast<float>(st[q]);
+    }
+#endif
   }
 
   // ---- sort(S): flag the picked tokens, ascending indices by prefix counts
