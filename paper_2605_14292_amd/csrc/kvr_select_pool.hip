@@ -158,15 +158,86 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     ibest = eqw ? __builtin_amdgcn_readlane(ii, __ffsll(static_cast<long long>(eqw)) - 1) : -1;
   };
 
-  if (!diverse || b == 1) {
-    for (; t < b; ++t) {
-      float gmax; int i;
-      wg_argmax(s, gmax, i);
-      if (!(gmax > -INFINITY)) { starved = true; break; }
-      if (tid == 0) { order_l[t] = i; gain_l[t] = gmax; }
+  if (b == 1) {
+    float gmax; int i;
+    wg_argmax(s, gmax, i);
+    if (!(gmax > -INFINITY)) starved = true;
+    else { if (tid == 0) { order_l[0] = i; gain_l[0] = gmax; } t = 1; }
+  } else if (!diverse) {
+    // lambda = 0: plain top-b of the scores (ties to the lower index); V is never read.  The b-th
+    // largest score key is found bit by bit (one workgroup-wide count per bit), the selected
+    // tokens are ranked among themselves, which gives the pick order.
+    int32_t* cnt_l = reinterpret_cast<int32_t*>(slot_gain);     // [2][16] per-wave counts
+    uint32_t* sel_key = reinterpret_cast<uint32_t*>(rn);        // [b]
+    int32_t* sel_tok = reinterpret_cast<int32_t*>(rn) + kPoolMaxB;
+    uint32_t key[S];
 #pragma unroll
-      for (int k = 0; k < S; ++k) s[k] = tok[k] == i ? -INFINITY : s[k];
+    for (int k = 0; k < S; ++k) key[k] = tok[k] < n ? ordered_key(s[k] + 0.0f) : 0u;   // -0 counts as +0
+    auto wg_count = [&](int c_w) -> int {
+      if (lane == 0) cnt_l[par * 16 + w] = c_w;
+      __syncthreads();
+      int c = 0;
+#pragma unroll
+      for (int u = 0; u < W; ++u) c += cnt_l[par * 16 + u];
+      par ^= 1;
+      return c;
+    };
+    uint32_t tau = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = tau | (1u << bit);
+      int c_w = 0;
+#pragma unroll
+      for (int k = 0; k < S; ++k) c_w += __popcll(__ballot(key[k] >= cand));
+      if (wg_count(c_w) >= b) tau = cand;
     }
+    int above_w = 0, equal_w = 0;
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+      above_w += __popcll(__ballot(key[k] > tau));
+      equal_w += __popcll(__ballot(key[k] == tau));
+    }
+    // per-wave prefixes: selected-before (for the ascending index list) and equal-before (ties in token order)
+    if (lane == 0) { cnt_l[par * 16 + w] = above_w; wcount[w] = equal_w; }
+    __syncthreads();
+    int above_all = 0, above_before = 0, equal_before = 0;
+#pragma unroll
+    for (int u = 0; u < W; ++u) {
+      above_all += cnt_l[par * 16 + u];
+      if (u < w) { above_before += cnt_l[par * 16 + u]; equal_before += wcount[u]; }
+    }
+    par ^= 1;
+    const int need_eq = b - above_all;                 // >= 1 by construction of tau
+    int eq_taken_before = equal_before < need_eq ? equal_before : need_eq;
+    int pos = above_before + eq_taken_before;          // selected tokens before this wave, in token order
+    int eq_seen = equal_before;
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+      const bool above = key[k] > tau, equal = key[k] == tau;
+      const unsigned long long eqm = __ballot(equal);
+      const int my_eq = eq_seen + __popcll(eqm & ((1ull << lane) - 1ull));
+      const bool in = above || (equal && my_eq < need_eq);
+      const unsigned long long inm = __ballot(in);
+      if (in) {
+        const int p = pos + __popcll(inm & ((1ull << lane) - 1ull));
+        sel_key[p] = key[k];
+        sel_tok[p] = tok[k];
+      }
+      pos += __popcll(inm);
+      eq_seen += __popcll(eqm);
+    }
+    __syncthreads();
+    // rank of each selected token in (score descending, index ascending) order
+    for (int e = tid; e < b; e += NT) {
+      const uint32_t ke = sel_key[e];
+      int rank = 0;
+      for (int f = 0; f < b; ++f) {
+        const uint32_t kf = sel_key[f];
+        rank += (kf > ke || (kf == ke && f < e)) ? 1 : 0;      // the list is in token order: f < e <=> lower index
+      }
+      order_l[rank] = sel_tok[e];
+      gain_l[rank] = key_to_float(ke);
+    }
+    t = b;
   } else {
     // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the first read of V from HBM
     {
