@@ -89,7 +89,13 @@ int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay, int 
   const kvr::Layout l = to_dev(lay);
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (kvr::dense_supported(l, b, 0, false))
+  if (kvr::pruned_supported(l, b, lambda, false)) {
+    e = kvr::launch_retain_pruned(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
+                                  nullptr, nullptr, st);
+    if (e == hipSuccess)
+      e = kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
+                                   pick_order, pick_gain, nullptr, nullptr, st, true);
+  } else if (kvr::dense_supported(l, b, 0, false))
     e = kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
                                  pick_order, pick_gain, nullptr, nullptr, st);
   else if (kvr::pool_supported(l, b))
@@ -135,6 +141,14 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const kvr::Layout l = to_dev(lay);
   const float* s = s_in;
+  if (kvr::pruned_supported(l, b, lambda, Q != nullptr)) {
+    hipError_t e = kvr::launch_retain_pruned(K, V, s_in, l, b, lambda, eps, idx_sorted, pick_order,
+                                             pick_gain, K_out, V_out, st);
+    if (e == hipSuccess)
+      e = kvr::launch_retain_dense(K, V, nullptr, 0, s_in, l, b, lambda, eps, s_out, idx_sorted,
+                                   pick_order, pick_gain, K_out, V_out, st, true);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+  }
   if (kvr::dense_supported(l, b, G, Q != nullptr)) {
     const hipError_t e = kvr::launch_retain_dense(K, V, Q, G, s_in, l, b, lambda, eps, s_out, idx_sorted,
                                                   pick_order, pick_gain, K_out, V_out, st);

@@ -1,0 +1,106 @@
+// Pieces shared by the fused kernels for short heads (n <= 256 bf16 tokens): wave-level
+// reductions, the padded LDS row stage and its MFMA fragment reads.
+#pragma once
+#include "kvr_device.hpp"
+
+namespace kvr {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kDenseThreads = 256;
+constexpr int kRowPitch = 272;   // bytes per staged row: 256 + 16 so that 8 consecutive rows hit distinct banks
+
+__host__ __device__ constexpr int dense_tri_floats(int NT) { return (NT * 32) * (NT * 32 + 1) / 2; }
+__host__ __device__ constexpr int dense_region_a(int NT) {
+  const int tri = dense_tri_floats(NT) * 4, stage = NT * 32 * kRowPitch;
+  return ((tri > stage ? tri : stage) + 15) & ~15;
+}
+
+#define KVR_DPP_MAX(v, ctrl, rmask)                                                        \
+  {                                                                                        \
+    const int _o = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), ctrl, \
+                                               rmask, 0xf, false);                        \
+    v = fmaxf(v, __int_as_float(_o));                                                      \
+  }
+#define KVR_DPP_ADD(v, ctrl, rmask)                                                            \
+  {                                                                                            \
+    const int _o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, rmask, 0xf, false); \
+    v += __int_as_float(_o);                                                                   \
+  }
+
+// Max over the wave, returned wave-uniform.  Each step is one v_max_f32 with a
+// DPP source (the compiler's own lowering of a DPP move plus fmaxf costs four
+// instructions a step, which is most of a pick's latency); lanes whose DPP
+// source is out of range keep their value.  s_nop 1 covers the two wait states
+// a DPP read needs after a VALU write of the same register.
+__device__ __forceinline__ float wave_max_uniform(float v) {
+  asm volatile(
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// Orders LDS traffic between the lanes of one wave.  Lanes of a wave run in
+// lock-step and the LDS pipeline is in order, but the compiler reasons per
+// thread: without a fence it may forward a lane's own earlier store to a load
+// that another lane has overwritten in between.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// max(a, b) as the hardware does it (a NaN operand yields the other one), without
+// the canonicalising self-max the compiler adds around fmaxf on loaded values
+__device__ __forceinline__ float hw_max(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+// max / sum over each half of the wave (lanes 0-31 and 32-63); valid in lanes 31 and 63
+__device__ __forceinline__ float half_max_at_31(float v) {
+  KVR_DPP_MAX(v, 0x111, 0xf) KVR_DPP_MAX(v, 0x112, 0xf) KVR_DPP_MAX(v, 0x114, 0xf)
+  KVR_DPP_MAX(v, 0x118, 0xf) KVR_DPP_MAX(v, 0x142, 0xa)
+  return v;
+}
+__device__ __forceinline__ float half_sum_at_31(float v) {
+  KVR_DPP_ADD(v, 0x111, 0xf) KVR_DPP_ADD(v, 0x112, 0xf) KVR_DPP_ADD(v, 0x114, 0xf)
+  KVR_DPP_ADD(v, 0x118, 0xf) KVR_DPP_ADD(v, 0x142, 0xa)
+  return v;
+}
+
+// One head's [n,128] bf16 rows: coalesced 16-byte loads into registers (rows beyond n read
+// as zero, so MFMA fragments of padded blocks are zero), then into the padded LDS stage.
+template <int NT>
+__device__ __forceinline__ void load_rows(const char* __restrict__ src, long long stride_tok, int n,
+                                          int tid, uint4 (&reg)[NT * 32 * 16 / kDenseThreads]) {
+  constexpr int kIters = NT * 32 * 16 / kDenseThreads;
+  const int chunk = tid & 15, r0 = tid >> 4;
+#pragma unroll
+  for (int k = 0; k < kIters; ++k) {
+    const int row = r0 + 16 * k;
+    reg[k] = make_uint4(0u, 0u, 0u, 0u);
+    if (row < n) reg[k] = *reinterpret_cast<const uint4*>(src + (row * stride_tok + chunk * 8) * 2);
+  }
+}
+template <int NT>
+__device__ __forceinline__ void store_rows(char* stage, int tid,
+                                           const uint4 (&reg)[NT * 32 * 16 / kDenseThreads]) {
+  constexpr int kIters = NT * 32 * 16 / kDenseThreads;
+  const int chunk = tid & 15, r0 = tid >> 4;
+#pragma unroll
+  for (int k = 0; k < kIters; ++k)
+    *reinterpret_cast<uint4*>(stage + (r0 + 16 * k) * kRowPitch + chunk * 16) = reg[k];
+}
+
+__device__ __forceinline__ bf16x8 frag_at(const char* stage, int block, int ks, int lane) {
+  const int row = block * 32 + (lane & 31), hf = lane >> 5;
+  return *reinterpret_cast<const bf16x8*>(stage + row * kRowPitch + ks * 32 + hf * 16);
+}
+
+}  // namespace kvr

@@ -24,7 +24,16 @@ bool dense_supported(const Layout& lay, int b, int G, bool has_q);
 hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int G, const float* s_in,
                                const Layout& lay, int b, float lambda, float eps, float* s_out,
                                int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
-                               void* K_out, void* V_out, hipStream_t st);
+                               void* K_out, void* V_out, hipStream_t st, bool only_marked = false);
+
+// Fused path for bf16 heads with 128 < n <= 256 and given scores: tokens that the score bound
+// s_j < s_(b) - lambda excludes from every pick are dropped first; heads left with at most 128
+// candidates are finished, the others get idx_sorted[h*b] = -1 and must be passed to
+// launch_retain_dense(..., only_marked = true) afterwards.
+bool pruned_supported(const Layout& lay, int b, float lambda, bool has_q);
+hipError_t launch_retain_pruned(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                                float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
+                                float* pick_gain, void* K_out, void* V_out, hipStream_t st);
 
 // Speculative row-block path for bf16 heads with 256 < n <= 4096 (selection plus
 // optional compaction; scores come in through s).

@@ -19,83 +19,15 @@
 //
 // LDS: the packed triangle (n=192: 74 KB, n=256: 132 KB) reuses the space the
 // rows were staged in, so two heads fit a CU at n <= 192.
-#include "kvr_device.hpp"
+#include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 
 namespace kvr {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-constexpr int kDenseThreads = 256;
-constexpr int kRowPitch = 272;   // bytes per staged row: 256 + 16 so that 8 consecutive rows hit distinct banks
 constexpr int kMaxB = 256;
-
-__host__ __device__ constexpr int dense_tri_floats(int NT) { return (NT * 32) * (NT * 32 + 1) / 2; }
-__host__ __device__ constexpr int dense_region_a(int NT) {
-  const int tri = dense_tri_floats(NT) * 4, stage = NT * 32 * kRowPitch;
-  return ((tri > stage ? tri : stage) + 15) & ~15;
-}
 __host__ __device__ constexpr int dense_smem_bytes(int NT) {
   // region A | s_l[N32] | rinv[N32] | red[64] | idx_l[kMaxB] | order_l[kMaxB] | gain_l[kMaxB]
   return dense_region_a(NT) + NT * 32 * 4 * 2 + 64 * 4 + kMaxB * 4 * 3;
-}
-
-#define KVR_DPP_MAX(v, ctrl, rmask)                                                        \
-  {                                                                                        \
-    const int _o = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), ctrl, \
-                                               rmask, 0xf, false);                        \
-    v = fmaxf(v, __int_as_float(_o));                                                      \
-  }
-#define KVR_DPP_ADD(v, ctrl, rmask)                                                            \
-  {                                                                                            \
-    const int _o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, rmask, 0xf, false); \
-    v += __int_as_float(_o);                                                                   \
-  }
-
-// Max over the wave, returned wave-uniform.  Each step is one v_max_f32 with a
-// DPP source (the compiler's own lowering of a DPP move plus fmaxf costs four
-// instructions a step, which is most of a pick's latency); lanes whose DPP
-// source is out of range keep their value.  s_nop 1 covers the two wait states
-// a DPP read needs after a VALU write of the same register.
-__device__ __forceinline__ float wave_max_uniform(float v) {
-  asm volatile(
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-      "s_nop 1"
-      : "+v"(v));
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-// Orders LDS traffic between the lanes of one wave.  Lanes of a wave run in
-// lock-step and the LDS pipeline is in order, but the compiler reasons per
-// thread: without a fence it may forward a lane's own earlier store to a load
-// that another lane has overwritten in between.
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-// max(a, b) as the hardware does it (a NaN operand yields the other one), without
-// the canonicalising self-max the compiler adds around fmaxf on loaded values
-__device__ __forceinline__ float hw_max(float a, float b) {
-  float r;
-  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
-// max / sum over each half of the wave (lanes 0-31 and 32-63); valid in lanes 31 and 63
-__device__ __forceinline__ float half_max_at_31(float v) {
-  KVR_DPP_MAX(v, 0x111, 0xf) KVR_DPP_MAX(v, 0x112, 0xf) KVR_DPP_MAX(v, 0x114, 0xf)
-  KVR_DPP_MAX(v, 0x118, 0xf) KVR_DPP_MAX(v, 0x142, 0xa)
-  return v;
-}
-__device__ __forceinline__ float half_sum_at_31(float v) {
-  KVR_DPP_ADD(v, 0x111, 0xf) KVR_DPP_ADD(v, 0x112, 0xf) KVR_DPP_ADD(v, 0x114, 0xf)
-  KVR_DPP_ADD(v, 0x118, 0xf) KVR_DPP_ADD(v, 0x142, 0xa)
-  return v;
 }
 
 struct DenseArgs {
@@ -105,36 +37,8 @@ struct DenseArgs {
   long long stride_head, stride_tok;   // elements
   int n, b, G, heads;
   float lambda, eps;
+  int only_marked;                     // process only heads whose idx_sorted[h*b] is -1
 };
-
-// One head's [n,128] bf16 rows: coalesced 16-byte loads into registers (rows beyond n read
-// as zero, so MFMA fragments of padded blocks are zero), then into the padded LDS stage.
-template <int NT>
-__device__ __forceinline__ void load_rows(const char* __restrict__ src, long long stride_tok, int n,
-                                          int tid, uint4 (&reg)[NT * 32 * 16 / kDenseThreads]) {
-  constexpr int kIters = NT * 32 * 16 / kDenseThreads;
-  const int chunk = tid & 15, r0 = tid >> 4;
-#pragma unroll
-  for (int k = 0; k < kIters; ++k) {
-    const int row = r0 + 16 * k;
-    reg[k] = make_uint4(0u, 0u, 0u, 0u);
-    if (row < n) reg[k] = *reinterpret_cast<const uint4*>(src + (row * stride_tok + chunk * 8) * 2);
-  }
-}
-template <int NT>
-__device__ __forceinline__ void store_rows(char* stage, int tid,
-                                           const uint4 (&reg)[NT * 32 * 16 / kDenseThreads]) {
-  constexpr int kIters = NT * 32 * 16 / kDenseThreads;
-  const int chunk = tid & 15, r0 = tid >> 4;
-#pragma unroll
-  for (int k = 0; k < kIters; ++k)
-    *reinterpret_cast<uint4*>(stage + (r0 + 16 * k) * kRowPitch + chunk * 16) = reg[k];
-}
-
-__device__ __forceinline__ bf16x8 frag_at(const char* stage, int block, int ks, int lane) {
-  const int row = block * 32 + (lane & 31), hf = lane >> 5;
-  return *reinterpret_cast<const bf16x8*>(stage + row * kRowPitch + ks * 32 + hf * 16);
-}
 
 // Workgroups are persistent: each walks over heads blockIdx.x, blockIdx.x + gridDim.x, ...
 // While one wave runs the pick chain of a head, the rows (and scores) of the workgroup's next
@@ -168,13 +72,29 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     if (need_v) load_rows<NT>(a.V + hh * a.stride_head * 2, a.stride_tok, n, tid, vpre);
     if (!a.Q && tid < N32) spre = tid < n ? a.s_in[static_cast<long long>(hh) * n + tid] : -INFINITY;
   };
-  if (static_cast<int>(blockIdx.x) < a.heads) prefetch(blockIdx.x, tid0);
+  // First head at or after h0 on this workgroup's stride that is to be processed.  With
+  // only_marked set, an earlier kernel has already finished every head it did not mark; 64
+  // marks are looked at per round trip to memory.
+  auto next_head = [&](int h0) -> int {
+    if (!a.only_marked) return h0;
+    const int ln = tid0 & 63;
+    for (long long base = h0; base < a.heads; base += 64ll * gridDim.x) {
+      const long long hh = base + static_cast<long long>(ln) * gridDim.x;
+      const bool todo = hh < a.heads && a.idx_sorted[hh * a.b] == -1;
+      const unsigned long long m = __ballot(todo);
+      if (m) return static_cast<int>(base) + (__ffsll(static_cast<long long>(m)) - 1) * static_cast<int>(gridDim.x);
+    }
+    return a.heads;
+  };
+  int h = next_head(blockIdx.x);
+  if (h < a.heads) prefetch(h, tid0);
 
 #ifdef KVR_STATS
   long long st_acc[4] = {0, 0, 0, 0};
   long long st_x[2] = {0, 0};
 #endif
-  for (int h = blockIdx.x; h < a.heads; h += gridDim.x) {
+  while (h < a.heads) {
+    const int h_next = next_head(h + gridDim.x);
     const long long head_off = h * a.stride_head * 2;  // bytes
     // The thread index is made opaque once per head: otherwise every per-lane LDS address of
     // the body is loop-invariant, gets hoisted out of the head loop and lives in registers.
@@ -372,7 +292,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     const long long st1 = __builtin_readcyclecounter();
 #endif
     // the next head of this workgroup starts its trip from HBM now
-    if (h + static_cast<int>(gridDim.x) < a.heads) prefetch(h + gridDim.x, tid);
+    if (h_next < a.heads) prefetch(h_next, tid);
 
     // ---------------------------------------------------------------- greedy
     if (wave == 0) {
@@ -539,6 +459,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
       }
     }
 #endif
+    h = h_next;
   }
 }
 
@@ -549,8 +470,9 @@ bool dense_supported(const Layout& lay, int b, int G, bool has_q) {
 hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int G, const float* s_in,
                                const Layout& lay, int b, float lambda, float eps, float* s_out,
                                int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
-                               void* K_out, void* V_out, hipStream_t st) {
+                               void* K_out, void* V_out, hipStream_t st, bool only_marked) {
   DenseArgs a;
+  a.only_marked = only_marked ? 1 : 0;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V);
   a.Q = static_cast<const char*>(Q); a.s_in = s_in; a.s_out = s_out;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;

@@ -1,0 +1,397 @@
+// Fused retention step for bf16 heads with 128 < n <= 256 tokens whose scores are
+// given, after an exact reduction of the candidate set.
+//
+// Reduction.  Let s_(b) be the b-th largest score of the head.  While fewer than
+// b tokens are selected, one of the b best-scored tokens is still unselected, and
+// its marginal gain s_i - lambda * max(0, max cos) (paper Eq. 2) is at least
+// s_(b) - lambda because a cosine never exceeds 1.  The greedy argmax (Eq. 3)
+// therefore never falls on a token with s_j < s_(b) - lambda: its gain is at most
+// s_j.  Such tokens are dropped before anything of V is read; the survivors keep
+// their token order, so "lowest index wins a tie" is unchanged, and Algorithm 1
+// runs on them exactly as it would on the whole head.  A small safety margin
+// covers the rounding of the fp32 cosines (which can exceed 1 by a few ulp).
+//
+// When at most 128 tokens survive, the head needs a 128-token cosine triangle
+// (33 KB of LDS) instead of a 192- or 256-token one, and four workgroups instead
+// of two or one share a CU, which is what bounds the throughput of the b
+// dependent picks.  Heads with more survivors are marked (idx_sorted[h*b] = -1)
+// and left to the full-size kernel, which runs afterwards on marked heads only.
+//
+// Waves are specialised: wave 0 runs the pick chain of head h while waves 1-3
+// find the survivors of the workgroup's next head and start its row gather.
+#include "kvr_dense_common.hpp"
+#include "kvr_kernels.hpp"
+
+namespace kvr {
+
+constexpr int kPrN = 128;                    // survivors a workgroup can hold
+constexpr int kPrLoaders = 192;              // threads of waves 1-3
+constexpr int kPrRowsPerIter = kPrLoaders / 16;
+constexpr int kPrIters = (kPrN + kPrRowsPerIter - 1) / kPrRowsPerIter;
+
+struct PrunedArgs {
+  const char* K; const char* V; const float* s;
+  int32_t* idx_sorted; int32_t* pick_order; float* pick_gain;
+  char* K_out; char* V_out;
+  long long stride_head, stride_tok;         // elements
+  int n, b, heads;
+  float lambda, eps;
+};
+
+constexpr int pruned_region_a() { return dense_region_a(4); }
+constexpr int pruned_smem_bytes() {
+  // region A | s_c[2][128] | tok_c[2][128] | rinv[128] | idx_l[128] | order_l[128] | gain_l[128] | meta[16]
+  return pruned_region_a() + 2 * kPrN * 4 * 2 + kPrN * 4 * 4 + 64;
+}
+
+// Scales one 32x32 tile of raw dot products to cosines and writes it into the packed
+// triangle (element (i,j), j <= i, at i(i+1)/2 + j).  The diagonal entry holds +inf: reading
+// the row of a pick drives the pick's own m to +inf and its gain to -inf, which is how a
+// selected token leaves the race.
+__device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, const f32x16& acc,
+                                               int I, int J, int lane) {
+  const int hf = lane >> 5;
+  const int j = J * 32 + (lane & 31);
+  const float rc = rinv[j];
+  int i = I * 32 + hf * 4;                            // first of this lane's rows in the tile
+  int off = i * (i + 1) / 2 + j;
+  const bool diag = I == J;
+#pragma unroll
+  for (int R = 0; R < 4; ++R) {
+    const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
+    const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+    int o = off;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float c = acc[R * 4 + q] * rrow[q] * rc;
+      if (diag && j == i + q) c = INFINITY;
+      if (!diag || j <= i + q) tri[o] = c;
+      o += i + q + 1;
+    }
+    off += 8 * i + 36;                                // T(i+8) - T(i)
+    i += 8;
+  }
+}
+
+__global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedArgs a) {
+  extern __shared__ __align__(16) char smem[];
+  char* stage = smem;                                 // gathered rows ...
+  float* tri = reinterpret_cast<float*>(smem);        // ... later the packed cosine triangle
+  float* s_c = reinterpret_cast<float*>(smem + pruned_region_a());   // [2][128] survivor scores
+  int32_t* tok_c = reinterpret_cast<int32_t*>(s_c + 2 * kPrN);       // [2][128] survivor tokens
+  float* rinv = reinterpret_cast<float*>(tok_c + 2 * kPrN);
+  int32_t* idx_l = reinterpret_cast<int32_t*>(rinv + kPrN);
+  int32_t* order_l = idx_l + kPrN;
+  float* gain_l = reinterpret_cast<float*>(order_l + kPrN);
+  int32_t* meta = reinterpret_cast<int32_t*>(gain_l + kPrN);         // [buf] head, [2+buf] survivors
+
+  const int tid0 = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
+  const int n = a.n, b = a.b;
+
+  uint4 vpre[kPrIters];                               // gathered rows of the head in preparation (waves 1-3)
+
+  // Waves 1-3, each on its own: survivors of the first head hh, hh + gridDim.x, ... that
+  // fits, then the gather of their V rows into registers.  The three waves compute the same
+  // survivor list (each needs it for its share of the rows); wave 1 publishes it.
+  auto prepare = [&](int hh, int buf, int tid) {
+    const int lane = tid & 63;
+    float sv[4];
+    unsigned long long keep[4];
+    int ns = 0;
+    for (; hh < a.heads; hh += gridDim.x) {
+      const float* sp = a.s + static_cast<long long>(hh) * n;
+      uint32_t key[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int j = lane + 64 * q;
+        sv[q] = j < n ? sp[j] : -INFINITY;
+        key[q] = j < n ? ordered_key(sv[q] + 0.0f) : 0u;
+      }
+      uint32_t T = 0;                                 // becomes the key of the b-th largest score
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cnt += __popcll(__ballot(key[q] >= cand));
+        if (cnt >= b) T = cand;
+      }
+      const float sb = key_to_float(T);
+      const float thr = sb - a.lambda * 1.00001f - 1e-5f * fabsf(sb);
+      ns = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        keep[q] = __ballot(lane + 64 * q < n && !(sv[q] < thr));
+        ns += __popcll(keep[q]);
+      }
+      if (ns <= kPrN) break;
+      if (wave == 1 && lane == 0) a.idx_sorted[static_cast<long long>(hh) * b] = -1;
+    }
+    if (hh < a.heads) {
+      float* sc = s_c + buf * kPrN;
+      int32_t* tc = tok_c + buf * kPrN;
+      int base = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if ((keep[q] >> lane) & 1ull) {
+          const int c = base + __popcll(keep[q] & ((1ull << lane) - 1ull));
+          tc[c] = lane + 64 * q;                      // the same value from each of the three waves
+          if (wave == 1) sc[c] = sv[q];
+        }
+        base += __popcll(keep[q]);
+      }
+      if (wave == 1)
+        for (int c = ns + lane; c < kPrN; c += kWave) sc[c] = -INFINITY;   // padding never competes
+      wave_lds_sync();                                // tc[] of this wave's own lanes is read below
+      const int tl = tid - kWave, r0 = tl >> 4, chunk = tl & 15;
+      const char* vb = a.V + hh * a.stride_head * 2 + chunk * 16;
+#pragma unroll
+      for (int k = 0; k < kPrIters; ++k) {
+        const int c = r0 + kPrRowsPerIter * k;
+        vpre[k] = make_uint4(0u, 0u, 0u, 0u);         // rows past the survivors read as zero
+        if (c < ns) vpre[k] = *reinterpret_cast<const uint4*>(vb + tc[c] * a.stride_tok * 2);
+      }
+    }
+    if (wave == 1 && lane == 0) {
+      meta[buf] = hh < a.heads ? hh : a.heads;
+      meta[2 + buf] = ns;
+    }
+  };
+
+  int buf = 0;
+  if (wave != 0) prepare(blockIdx.x, 0, tid0);
+  __syncthreads();
+  int h = __builtin_amdgcn_readfirstlane(meta[0]);
+  while (h < a.heads) {
+    // The thread index is made opaque once per head so that per-lane LDS addresses are not
+    // hoisted out of the head loop into registers.
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, hf = lane >> 5;
+    const int ns = __builtin_amdgcn_readfirstlane(meta[2 + buf]);
+    const float* s_cur = s_c + buf * kPrN;
+    const int32_t* tok_cur = tok_c + buf * kPrN;
+    const long long head_off = h * a.stride_head * 2;  // bytes
+
+    if (wave != 0) {
+      const int tl = tid - kWave, r0 = tl >> 4, chunk = tl & 15;
+#pragma unroll
+      for (int k = 0; k < kPrIters; ++k) {
+        const int c = r0 + kPrRowsPerIter * k;
+        if (c < kPrN) *reinterpret_cast<uint4*>(stage + c * kRowPitch + chunk * 16) = vpre[k];
+      }
+    }
+    __syncthreads();
+
+    // ------------------------------------------------ Gram -> packed cosines
+    // Ten lower-triangular 32x32 tiles over four waves; tile rows that hold no survivor are
+    // skipped.  wave 0: (3,3) (0,0); wave 1: (3,0..2); wave 2: (2,0..2); wave 3: (1,0..1).
+    f32x16 acc[3];
+    const int nblk = (ns + 31) >> 5;                  // token blocks in use
+    const int rowI = wave == 0 ? 3 : 4 - wave;
+    const int ntile = (wave == 0 || wave == 3) ? 2 : 3;
+    auto tile_of = [&](int sl, int& I, int& J) -> bool {
+      if (wave == 0) { I = sl == 0 ? 3 : 0; J = I; }
+      else { I = rowI; J = sl; }
+      return sl < ntile && I < nblk;
+    };
+#pragma unroll
+    for (int sl = 0; sl < 3; ++sl) {
+      int I, J;
+      acc[sl] = f32x16{0};
+      if (tile_of(sl, I, J)) {
+        // both fragments come from LDS at every k-step: with four workgroups on a CU there are
+        // no registers to keep a row block resident
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+          acc[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_at(stage, I, ks, lane),
+                                                            frag_at(stage, J, ks, lane), acc[sl], 0, 0, 0);
+        if (I == J) {                                 // squared norms sit on the diagonal
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int il = (r >> 2) * 8 + hf * 4 + (r & 3);
+            if (il == (lane & 31)) rinv[I * 32 + il] = acc[sl][r];
+          }
+        }
+      }
+    }
+    __syncthreads();                                  // gathered rows are dead from here on
+    if (tid < kPrN) rinv[tid] = 1.0f / (sqrtf(rinv[tid]) + a.eps);
+    __syncthreads();
+#pragma unroll
+    for (int sl = 0; sl < 3; ++sl) {
+      int I, J;
+      if (tile_of(sl, I, J)) write_cos_tile(tri, rinv, acc[sl], I, J, lane);
+    }
+    __syncthreads();
+
+    if (wave != 0) {
+      prepare(h + gridDim.x, buf ^ 1, tid);
+    } else {
+      // ---------------------------------------------------------------- greedy
+      // Survivor c lives in lane c%64, slot c/64.  Picks are collected one per lane and flushed
+      // to LDS every 64 picks.
+      constexpr int NQ = 2;
+      float sreg[NQ], mreg[NQ];
+      int ja[NQ], tja[NQ];
+      typedef __attribute__((address_space(3))) const float* lds_fp;
+      const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
+          (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const int j = lane + 64 * q;
+        sreg[q] = s_cur[j];                            // -inf beyond the survivors
+        mreg[q] = 0.f;
+        ja[q] = j * 4 + tri0;
+        tja[q] = (j * (j + 1) / 2) * 4 + tri0;
+      }
+      const float nlam = -a.lambda;
+      int rec_i = 0;
+      float rec_g = 0.f;
+      int t = 0;
+      bool finite = true;
+      auto pick = [&](float& amax) -> int {
+        float av[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
+        amax = wave_max_uniform(hw_max(av[0], av[1]));
+        int i = -1;
+#pragma unroll
+        for (int q = NQ - 1; q >= 0; --q) {
+          const unsigned long long eq = __ballot(av[q] == amax);
+          if (eq) i = (__ffsll(static_cast<long long>(eq)) - 1) + 64 * q;
+        }
+        return amax > -INFINITY ? i : -1;
+      };
+      auto record = [&](int i, float g) {
+        if (lane == (t & 63)) { rec_i = i; rec_g = g; }
+        if ((t & 63) == 63) { order_l[t - 63 + lane] = rec_i; gain_l[t - 63 + lane] = rec_g; }
+      };
+      // all picks but the last read the row of the pick; its diagonal entry (+inf) retires it
+      for (; t + 1 < b; ++t) {
+        float amax;
+        const int i = pick(amax);
+        if (i < 0) { finite = false; break; }
+        record(i, amax);
+        const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
+        float c[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          const int a0 = ti4 + ja[q], a1 = tja[q] + i4;       // element (i,j) sits at max(T(i)+j, T(j)+i)
+          c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a0 > a1 ? a0 : a1)));
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
+      }
+      if (finite) {
+        float amax;
+        const int i = pick(amax);
+        if (i < 0) finite = false;
+        else { record(i, amax); ++t; }
+      }
+      if (t & 63) {                                    // picks still held in registers
+        if (lane < (t & 63)) { order_l[(t & ~63) + lane] = rec_i; gain_l[(t & ~63) + lane] = rec_g; }
+      }
+      if (!finite) {
+        // Non-finite scores or rows only: fill up with the lowest survivors not yet picked
+        // (there are at least b survivors).
+        wave_lds_sync();
+        for (; t < b; ++t) {
+          int i = -1;
+#pragma unroll
+          for (int q = NQ - 1; q >= 0; --q) {
+            const int j = lane + 64 * q;
+            bool free_tok = j < ns;
+            for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
+            const unsigned long long al = __ballot(free_tok);
+            if (al) i = (__ffsll(static_cast<long long>(al)) - 1) + 64 * q;
+          }
+          if (lane == 0) { order_l[t] = i; gain_l[t] = -INFINITY; }
+          wave_lds_sync();
+        }
+      }
+      // sort(S): flag the picked survivors, ascending order by prefix popcount, then back to
+      // token indices (the survivor list is ascending in the token index).
+      int32_t* flag = reinterpret_cast<int32_t*>(rinv);   // rinv is dead by now
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) flag[lane + 64 * q] = 0;
+      wave_lds_sync();
+      for (int u = lane; u < b; u += kWave) flag[min(max(order_l[u], 0), kPrN - 1)] = 1;
+      wave_lds_sync();
+      int off = 0;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const int j = lane + 64 * q;
+        const bool picked = flag[j] != 0;
+        const unsigned long long sel = __ballot(picked);
+        if (picked) {
+          const int rank = __popcll(sel & ((1ull << lane) - 1ull));
+          idx_l[off + rank] = tok_cur[j];
+        }
+        off += __popcll(sel);
+      }
+      for (int u = lane; u < b; u += kWave) order_l[u] = tok_cur[min(max(order_l[u], 0), kPrN - 1)];
+    }
+    __syncthreads();
+
+    // ------------------------------------------------- outputs and compaction
+    const long long ob = static_cast<long long>(h) * b;
+    for (int t = tid; t < b; t += kDenseThreads) {
+      a.idx_sorted[ob + t] = idx_l[t];
+      if (a.pick_order) a.pick_order[ob + t] = order_l[t];
+      if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
+    }
+    if (a.K_out || a.V_out) {
+      const int chunk = tid & 15;
+      for (int t0 = 0; t0 < b; t0 += kDenseThreads / 16) {
+        const int t = t0 + (tid >> 4);
+        if (t < b) {
+          const int it = min(max(idx_l[t], 0), n - 1);   // never read outside the head, whatever the scores were
+          const long long src = head_off + (it * a.stride_tok + chunk * 8) * 2;
+          const long long dst = ((ob + t) * kD + chunk * 8) * 2;
+          uint4 kv, vv;
+          if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
+          if (a.V_out) vv = *reinterpret_cast<const uint4*>(a.V + src);
+          if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kv;
+          if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vv;
+        }
+      }
+    }
+    h = __builtin_amdgcn_readfirstlane(meta[buf ^ 1]);                              // published before the barrier above
+    buf ^= 1;
+  }
+}
+
+bool pruned_supported(const Layout& lay, int b, float lambda, bool has_q) {
+  return lay.dtype == DT_BF16 && !has_q && lay.n > kPrN && lay.n <= 256 && b > 1 && b <= kPrN &&
+         lambda > 0.0f;
+}
+
+hipError_t launch_retain_pruned(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                                float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
+                                float* pick_gain, void* K_out, void* V_out, hipStream_t st) {
+  PrunedArgs a;
+  a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s = s;
+  a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
+  a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);
+  a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
+  a.n = lay.n; a.b = b; a.heads = lay.heads; a.lambda = lambda; a.eps = eps;
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+  }
+  constexpr int smem = pruned_smem_bytes();
+  static_assert(4 * smem <= 160 * 1024, "four workgroups must share a CU's LDS");
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&retain_pruned_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (e != hipSuccess) return e;
+  const int blocks = lay.heads < cus * 4 ? lay.heads : cus * 4;
+  hipLaunchKernelGGL(retain_pruned_kernel, dim3(blocks), dim3(kDenseThreads), smem, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace kvr

@@ -119,6 +119,33 @@ def test_ragged_sizes(n, b, dtype):
     assert rep["heads"] == 3
 
 
+@pytest.mark.parametrize("n,b,lam", [(129, 2, 0.05), (192, 64, 0.5), (192, 64, 0.02), (256, 128, 0.3),
+                                     (256, 100, 1.0), (200, 128, 1e-4)])
+def test_score_bound_reduction_mixed_heads(n, b, lam):
+    # given scores whose spread differs per head: some heads keep few candidates under the bound
+    # s_j >= s_(b) - lambda (finished by the reduced-footprint kernel), others keep nearly all
+    # (handed on to the full-size kernel); quantised scores put ties on the bound itself
+    h = 12
+    K, V, _ = _mk(h, n, 7000 + n + b)
+    g = torch.Generator().manual_seed(n * 131 + b)
+    s = torch.randn((h, n), generator=g).exp()
+    scale = torch.tensor([4.0, 1.0, 0.25, 0.05, 2.0, 1.0, 8.0, 0.5, 1.0, 3.0, 0.01, 1.5]).view(h, 1)
+    s = s * scale
+    s[5] = torch.floor(s[5] * 4) / 4
+    s[9] = torch.floor(s[9] * 2) / 2
+    # near-duplicate value rows so that the penalty matters among the survivors
+    V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
+    s = s.to(DEV)
+    data = {"K": K, "V": V, "s": s}
+    out = B().kvr_retain(K, V, b, lam, 1e-6, s=s)
+    torch.cuda.synchronize()
+    rep = _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, range(h))
+    assert rep["heads"] == h
+    sel = B().kvr_select_greedy(V, s, b, lam, 1e-6)
+    torch.cuda.synchronize()
+    assert torch.equal(sel[0], out.idx_sorted) and torch.equal(sel[1], out.pick_order)
+
+
 def test_exactly_representable_inputs_match_with_zero_near_ties():
     # signed basis rows (norm 1, eps 0) with duplicates, dyadic scores and
     # lambda: every quantity is exact in fp32, so the picks must be the
