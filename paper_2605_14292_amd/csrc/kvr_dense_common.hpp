@@ -41,8 +41,7 @@ __device__ __forceinline__ float wave_max_uniform(float v) {
       "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
       "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
       "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-      "s_nop 1"
+      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf"
       : "+v"(v));
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
@@ -61,6 +60,30 @@ __device__ __forceinline__ float hw_max(float a, float b) {
   float r;
   asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
   return r;
+}
+// ra[lane ln] = va, rb[lane ln] = vb for wave-uniform va, vb, ln; the other lanes keep their
+// values.  The lane select goes through m0 because a VALU instruction reads one SGPR only.
+__device__ __forceinline__ void write_lane2(int& ra, int& rb, int va, int vb, int ln) {
+  asm("s_mov_b32 m0, %4\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
+      : "+v"(ra), "+v"(rb)
+      : "s"(va), "s"(vb), "s"(ln)
+      : "m0");
+}
+// Index of the winning token when tokens 2*lane and 2*lane+1 live in lane `lane`: e0 / e1 are
+// the lanes whose even / odd token equals the maximum.  The lowest such lane wins and its even
+// token goes first.  Returns -1 when both masks are empty.
+__device__ __forceinline__ int first_of_pairs(unsigned long long e0, unsigned long long e1) {
+  int i, L;
+  unsigned long long any;
+  asm("s_or_b64 %1, %3, %4\n\t"
+      "s_ff1_i32_b64 %2, %1\n\t"          // -1 for an empty mask
+      "s_lshl_b32 %0, %2, 1\n\t"
+      "s_bitcmp0_b64 %3, %2\n\t"          // scc = even token of that lane is not a winner
+      "s_addc_u32 %0, %0, 0"
+      : "=&s"(i), "=&s"(any), "=&s"(L)
+      : "s"(e0), "s"(e1)
+      : "scc");
+  return i;
 }
 // max / sum over each half of the wave (lanes 0-31 and 32-63); valid in lanes 31 and 63
 __device__ __forceinline__ float half_max_at_31(float v) {

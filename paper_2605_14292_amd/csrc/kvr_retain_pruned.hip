@@ -158,6 +158,9 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     }
   };
 
+#ifdef KVR_STATS
+  long long st_acc[6] = {0, 0, 0, 0, 0, 0};
+#endif
   int buf = 0;
   if (wave != 0) prepare(blockIdx.x, 0, tid0);
   __syncthreads();
@@ -172,6 +175,9 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     const float* s_cur = s_c + buf * kPrN;
     const int32_t* tok_cur = tok_c + buf * kPrN;
     const long long head_off = h * a.stride_head * 2;  // bytes
+#ifdef KVR_STATS
+    const long long st0 = __builtin_readcyclecounter();
+#endif
 
     if (wave != 0) {
       const int tl = tid - kWave, r0 = tl >> 4, chunk = tl & 15;
@@ -225,82 +231,61 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     }
     __syncthreads();
 
+#ifdef KVR_STATS
+    const long long st1 = __builtin_readcyclecounter();
+    long long st2 = st1;
+#endif
     if (wave != 0) {
       prepare(h + gridDim.x, buf ^ 1, tid);
     } else {
       // ---------------------------------------------------------------- greedy
-      // Survivor c lives in lane c%64, slot c/64.  Picks are collected one per lane and flushed
-      // to LDS every 64 picks.
-      constexpr int NQ = 2;
-      float sreg[NQ], mreg[NQ];
-      int ja[NQ], tja[NQ];
+      // A single wave issues one instruction every few cycles, so the time of a pick is its
+      // instruction count.  Survivors 2*lane and 2*lane+1 live in lane `lane`: the lowest lane
+      // holding the maximum then also holds the lowest tied index.  Pick u of a 64-pick chunk
+      // is parked in lane u of two registers (v_writelane) and the chunk is written out once.
+      // Nothing is checked per pick: non-finite input is detected afterwards from the gains.
       typedef __attribute__((address_space(3))) const float* lds_fp;
       const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
           (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const int j = lane + 64 * q;
-        sreg[q] = s_cur[j];                            // -inf beyond the survivors
-        mreg[q] = 0.f;
-        ja[q] = j * 4 + tri0;
-        tja[q] = (j * (j + 1) / 2) * 4 + tri0;
-      }
+      const int j0 = 2 * lane;
+      const float2 s01 = *reinterpret_cast<const float2*>(s_cur + j0);   // -inf beyond the survivors
+      const float s0 = s01.x, s1 = s01.y;
+      float m0 = 0.f, m1 = 0.f;
+      const int ja0 = j0 * 4 + tri0, ja1 = ja0 + 4;                       // column offsets of the lane's tokens
+      const int tja0 = j0 * (j0 + 1) * 2 + tri0, tja1 = (j0 + 1) * (j0 + 2) * 2 + tri0;   // their row starts
       const float nlam = -a.lambda;
-      int rec_i = 0;
-      float rec_g = 0.f;
-      int t = 0;
-      bool finite = true;
-      auto pick = [&](float& amax) -> int {
-        float av[NQ];
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
-        amax = wave_max_uniform(hw_max(av[0], av[1]));
-        int i = -1;
-#pragma unroll
-        for (int q = NQ - 1; q >= 0; --q) {
-          const unsigned long long eq = __ballot(av[q] == amax);
-          if (eq) i = (__ffsll(static_cast<long long>(eq)) - 1) + 64 * q;
+      int bad_t = b;                                   // first pick without a finite gain
+      for (int c0 = 0; c0 < b; c0 += 64) {
+        const int cnt = __builtin_amdgcn_readfirstlane(b - c0 < 64 ? b - c0 : 64);
+        int rec_i = 0, rec_g = 0;
+        for (int u = 0; u < cnt; ++u) {
+          const float av0 = fmaf(nlam, m0, s0), av1 = fmaf(nlam, m1, s1);
+          const float amax = wave_max_uniform(hw_max(av0, av1));
+          const unsigned long long e0 = __ballot(av0 == amax), e1 = __ballot(av1 == amax);
+          const int i = first_of_pairs(e0, e1);          // -1 when nothing compares equal (NaN)
+          // element (i,j) of the triangle sits at max(T(i)+j, T(j)+i); both reads stay inside the
+          // triangle for any i in [-1, 127]
+          const int ti4 = i * (i + 1) * 2;
+          const int a00 = ti4 + ja0, a01 = tja0 + i * 4, a10 = ti4 + ja1, a11 = tja1 + i * 4;
+          const float c0v = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a00 > a01 ? a00 : a01)));
+          const float c1v = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a10 > a11 ? a10 : a11)));
+          write_lane2(rec_i, rec_g, i, __float_as_int(amax), u);
+          m0 = hw_max(m0, c0v);                          // the diagonal entry (+inf) retires the pick
+          m1 = hw_max(m1, c1v);
         }
-        return amax > -INFINITY ? i : -1;
-      };
-      auto record = [&](int i, float g) {
-        if (lane == (t & 63)) { rec_i = i; rec_g = g; }
-        if ((t & 63) == 63) { order_l[t - 63 + lane] = rec_i; gain_l[t - 63 + lane] = rec_g; }
-      };
-      // all picks but the last read the row of the pick; its diagonal entry (+inf) retires it
-      for (; t + 1 < b; ++t) {
-        float amax;
-        const int i = pick(amax);
-        if (i < 0) { finite = false; break; }
-        record(i, amax);
-        const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
-        float c[NQ];
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-          const int a0 = ti4 + ja[q], a1 = tja[q] + i4;       // element (i,j) sits at max(T(i)+j, T(j)+i)
-          c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a0 > a1 ? a0 : a1)));
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
+        const float g = __int_as_float(rec_g);
+        if (lane < cnt) { order_l[c0 + lane] = rec_i; gain_l[c0 + lane] = g; }
+        const unsigned long long bad = __ballot(lane < cnt && !(g > -INFINITY));
+        if (bad && bad_t == b) bad_t = c0 + __ffsll(static_cast<long long>(bad)) - 1;
       }
-      if (finite) {
-        float amax;
-        const int i = pick(amax);
-        if (i < 0) finite = false;
-        else { record(i, amax); ++t; }
-      }
-      if (t & 63) {                                    // picks still held in registers
-        if (lane < (t & 63)) { order_l[(t & ~63) + lane] = rec_i; gain_l[(t & ~63) + lane] = rec_g; }
-      }
-      if (!finite) {
-        // Non-finite scores or rows only: fill up with the lowest survivors not yet picked
-        // (there are at least b survivors).
+      if (bad_t < b) {
+        // Non-finite scores or rows only: keep the picks made before the first one without a
+        // finite gain, fill up with the lowest survivors not yet picked (there are at least b).
         wave_lds_sync();
-        for (; t < b; ++t) {
+        for (int t = bad_t; t < b; ++t) {
           int i = -1;
 #pragma unroll
-          for (int q = NQ - 1; q >= 0; --q) {
+          for (int q = 1; q >= 0; --q) {
             const int j = lane + 64 * q;
             bool free_tok = j < ns;
             for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
@@ -311,6 +296,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
           wave_lds_sync();
         }
       }
+      constexpr int NQ = 2;
       // sort(S): flag the picked survivors, ascending order by prefix popcount, then back to
       // token indices (the survivor list is ascending in the token index).
       int32_t* flag = reinterpret_cast<int32_t*>(rinv);   // rinv is dead by now
@@ -333,7 +319,13 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       }
       for (int u = lane; u < b; u += kWave) order_l[u] = tok_cur[min(max(order_l[u], 0), kPrN - 1)];
     }
+#ifdef KVR_STATS
+    st2 = __builtin_readcyclecounter();
+#endif
     __syncthreads();
+#ifdef KVR_STATS
+    const long long st3 = __builtin_readcyclecounter();
+#endif
 
     // ------------------------------------------------- outputs and compaction
     const long long ob = static_cast<long long>(h) * b;
@@ -358,6 +350,17 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         }
       }
     }
+#ifdef KVR_STATS
+    {
+      const long long st4 = __builtin_readcyclecounter();
+      st_acc[0] += st1 - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2; st_acc[3] += st4 - st3;
+      st_acc[4] += ns; st_acc[5] += 1;
+      if ((tid == 0 || tid == 64) && a.pick_gain && b >= 16) {
+        float* o = a.pick_gain + ob + b - 1 - (tid == 64 ? 8 : 0);
+        for (int k = 0; k < 5; ++k) o[-k] = static_cast<float>(st_acc[k]) / st_acc[5];
+      }
+    }
+#endif
     h = __builtin_amdgcn_readfirstlane(meta[buf ^ 1]);                              // published before the barrier above
     buf ^= 1;
   }
