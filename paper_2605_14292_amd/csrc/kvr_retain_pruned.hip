@@ -40,8 +40,8 @@ struct PrunedArgs {
 
 constexpr int pruned_region_a() { return dense_region_a(4); }
 constexpr int pruned_smem_bytes() {
-  // region A | s_c[2][128] | tok_c[2][128] | rinv[128] | idx_l[128] | order_l[128] | gain_l[128] | meta[16]
-  return pruned_region_a() + 2 * kPrN * 4 * 2 + kPrN * 4 * 4 + 64;
+  // region A | s_c[2][128] | tok_c[2][128] | rinv[128] | idx_l[2][128] | order_l[2][128] | gain_l[2][128] | meta[16: head, survivors, best left-out score, redo flag; two of each]
+  return pruned_region_a() + 2 * kPrN * 4 * 2 + kPrN * 4 + 2 * kPrN * 4 * 3 + 64;
 }
 
 // Scales one 32x32 tile of raw dot products to cosines and writes it into the packed
@@ -80,10 +80,10 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
   float* s_c = reinterpret_cast<float*>(smem + pruned_region_a());   // [2][128] survivor scores
   int32_t* tok_c = reinterpret_cast<int32_t*>(s_c + 2 * kPrN);       // [2][128] survivor tokens
   float* rinv = reinterpret_cast<float*>(tok_c + 2 * kPrN);
-  int32_t* idx_l = reinterpret_cast<int32_t*>(rinv + kPrN);
-  int32_t* order_l = idx_l + kPrN;
-  float* gain_l = reinterpret_cast<float*>(order_l + kPrN);
-  int32_t* meta = reinterpret_cast<int32_t*>(gain_l + kPrN);         // [buf] head, [2+buf] survivors
+  int32_t* idx_l2 = reinterpret_cast<int32_t*>(rinv + kPrN);          // [2][128] each: the lists of head h
+  int32_t* order_l2 = idx_l2 + 2 * kPrN;                             // are written out while head h+1 is
+  float* gain_l2 = reinterpret_cast<float*>(order_l2 + 2 * kPrN);     // in its pick chain
+  int32_t* meta = reinterpret_cast<int32_t*>(gain_l2 + 2 * kPrN);         // [buf] head, [2+buf] survivors
 
   const int tid0 = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
@@ -94,11 +94,12 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
   // Waves 1-3, each on its own: survivors of the first head hh, hh + gridDim.x, ... that
   // fits, then the gather of their V rows into registers.  The three waves compute the same
   // survivor list (each needs it for its share of the rows); wave 1 publishes it.
-  auto prepare = [&](int hh, int buf, int tid) {
+  auto survivors = [&](int hh, int buf, int tid, int& ns_out) -> int {
     const int lane = tid & 63;
     float sv[4];
     unsigned long long keep[4];
     int ns = 0;
+    float excl = -INFINITY;                           // best score among the candidates left out
     for (; hh < a.heads; hh += gridDim.x) {
       const float* sp = a.s + static_cast<long long>(hh) * n;
       uint32_t key[4];
@@ -124,7 +125,34 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         keep[q] = __ballot(lane + 64 * q < n && !(sv[q] < thr));
         ns += __popcll(keep[q]);
       }
+      excl = -INFINITY;
       if (ns <= kPrN) break;
+      // More candidates than fit: keep the best-scored kPrN of them (fewer when scores tie at
+      // the cut) and remember the best score left out; the pick chain is then valid if that
+      // score stays below the gain of every pick, which is checked once the chain is done.
+      uint32_t T2 = 0;
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = T2 | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cnt += __popcll(__ballot(key[q] >= cand));
+        if (cnt >= kPrN) T2 = cand;
+      }
+      int cnt_ge = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) cnt_ge += __popcll(__ballot(key[q] >= T2));
+      const uint32_t cut = cnt_ge == kPrN ? T2 : T2 + 1u;   // T2 < 0xffffffff here: kPrN < n tokens reach it
+      ns = 0;
+      float out_best = -INFINITY;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const bool valid = lane + 64 * q < n;
+        keep[q] = __ballot(valid && key[q] >= cut);
+        ns += __popcll(keep[q]);
+        if (valid && key[q] < cut) out_best = fmaxf(out_best, sv[q]);
+      }
+      excl = wave_max_uniform(out_best);
+      if (ns >= b && ns <= kPrN) break;
       if (wave == 1 && lane == 0) a.idx_sorted[static_cast<long long>(hh) * b] = -1;
     }
     if (hh < a.heads) {
@@ -142,7 +170,20 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       }
       if (wave == 1)
         for (int c = ns + lane; c < kPrN; c += kWave) sc[c] = -INFINITY;   // padding never competes
-      wave_lds_sync();                                // tc[] of this wave's own lanes is read below
+    }
+    if (wave == 1 && lane == 0) {
+      meta[buf] = hh < a.heads ? hh : a.heads;
+      meta[2 + buf] = ns;
+      meta[4 + buf] = __float_as_int(excl);
+    }
+    ns_out = ns;
+    return hh;
+  };
+  // Rows of the survivors of head hh (list in buffer buf) into registers.
+  auto gather = [&](int hh, int buf, int ns, int tid) {
+    if (hh < a.heads) {
+      const int32_t* tc = tok_c + buf * kPrN;
+      wave_lds_sync();                                // tc[] was written by this wave's own lanes
       const int tl = tid - kWave, r0 = tl >> 4, chunk = tl & 15;
       const char* vb = a.V + hh * a.stride_head * 2 + chunk * 16;
 #pragma unroll
@@ -152,9 +193,48 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         if (c < ns) vpre[k] = *reinterpret_cast<const uint4*>(vb + tc[c] * a.stride_tok * 2);
       }
     }
-    if (wave == 1 && lane == 0) {
-      meta[buf] = hh < a.heads ? hh : a.heads;
-      meta[2 + buf] = ns;
+  };
+
+  // Results of head hh (lists in buffer lb) to HBM and the compaction of its kept rows, by the
+  // nthr threads t0 = 0..nthr-1 (nthr a multiple of 16).  Rows move in batches of kOutBatch per
+  // 16-thread group: all loads of a batch are in flight before its first store.
+  constexpr int kOutBatch = 2;
+  auto out_lists = [&](int hh, int lb, int t0, int nthr) {
+    const long long ob = static_cast<long long>(hh) * b;
+    const bool redo = meta[6 + lb] != 0;                 // the head is left to the full-size kernel
+    for (int t = t0; t < b; t += nthr) {
+      a.idx_sorted[ob + t] = (redo && t == 0) ? -1 : idx_l2[lb * kPrN + t];
+      if (a.pick_order) a.pick_order[ob + t] = order_l2[lb * kPrN + t];
+      if (a.pick_gain) a.pick_gain[ob + t] = gain_l2[lb * kPrN + t];
+    }
+  };
+  uint4 kr[kOutBatch], vr[kOutBatch];
+  auto out_load = [&](int hh, int lb, int t0, int nthr, int first) {
+    const int32_t* il = idx_l2 + lb * kPrN;
+    const long long head_off = hh * a.stride_head * 2 + (t0 & 15) * 16;   // bytes
+#pragma unroll
+    for (int k = 0; k < kOutBatch; ++k) {
+      const int t = first + (t0 >> 4) + k * (nthr >> 4);
+      kr[k] = make_uint4(0u, 0u, 0u, 0u);
+      vr[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (t < b) {
+        const int it = min(max(il[t], 0), n - 1);        // never read outside the head, whatever the scores were
+        const long long src = head_off + it * a.stride_tok * 2;
+        if (a.K_out) kr[k] = *reinterpret_cast<const uint4*>(a.K + src);
+        if (a.V_out) vr[k] = *reinterpret_cast<const uint4*>(a.V + src);
+      }
+    }
+  };
+  auto out_store = [&](int hh, int t0, int nthr, int first) {
+    const long long ob = static_cast<long long>(hh) * b;
+#pragma unroll
+    for (int k = 0; k < kOutBatch; ++k) {
+      const int t = first + (t0 >> 4) + k * (nthr >> 4);
+      if (t < b) {
+        const long long dst = ((ob + t) * kD + (t0 & 15) * 8) * 2;
+        if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kr[k];
+        if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vr[k];
+      }
     }
   };
 
@@ -162,7 +242,12 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
   long long st_acc[6] = {0, 0, 0, 0, 0, 0};
 #endif
   int buf = 0;
-  if (wave != 0) prepare(blockIdx.x, 0, tid0);
+  int hprev = -1;                                     // head whose results are still in LDS
+  if (wave != 0) {
+    int ns0;
+    const int h0 = survivors(blockIdx.x, 0, tid0, ns0);
+    gather(h0, 0, ns0, tid0);
+  }
   __syncthreads();
   int h = __builtin_amdgcn_readfirstlane(meta[0]);
   while (h < a.heads) {
@@ -174,7 +259,9 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     const int ns = __builtin_amdgcn_readfirstlane(meta[2 + buf]);
     const float* s_cur = s_c + buf * kPrN;
     const int32_t* tok_cur = tok_c + buf * kPrN;
-    const long long head_off = h * a.stride_head * 2;  // bytes
+    int32_t* idx_l = idx_l2 + buf * kPrN;
+    int32_t* order_l = order_l2 + buf * kPrN;
+    float* gain_l = gain_l2 + buf * kPrN;
 #ifdef KVR_STATS
     const long long st0 = __builtin_readcyclecounter();
 #endif
@@ -236,7 +323,22 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     long long st2 = st1;
 #endif
     if (wave != 0) {
-      prepare(h + gridDim.x, buf ^ 1, tid);
+      // the previous head's kept rows start their trip first, the next head's survivor search
+      // runs while they are in flight
+      const int tl = tid - kWave;
+      constexpr int kStep = kOutBatch * (kPrLoaders / 16);
+      if (hprev >= 0) out_load(hprev, buf ^ 1, tl, kPrLoaders, 0);
+      int ns_n;
+      const int h_n = survivors(h + gridDim.x, buf ^ 1, tid, ns_n);
+      if (hprev >= 0) {
+        out_lists(hprev, buf ^ 1, tl, kPrLoaders);
+        out_store(hprev, tl, kPrLoaders, 0);
+        for (int first = kStep; first < b; first += kStep) {
+          out_load(hprev, buf ^ 1, tl, kPrLoaders, first);
+          out_store(hprev, tl, kPrLoaders, first);
+        }
+      }
+      gather(h_n, buf ^ 1, ns_n, tid);   // lands while wave 0 is still in its chain
     } else {
       // ---------------------------------------------------------------- greedy
       // A single wave issues one instruction every few cycles, so the time of a pick is its
@@ -255,6 +357,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       const int tja0 = j0 * (j0 + 1) * 2 + tri0, tja1 = (j0 + 1) * (j0 + 2) * 2 + tri0;   // their row starts
       const float nlam = -a.lambda;
       int bad_t = b;                                   // first pick without a finite gain
+      float last_g = -INFINITY;                        // gain of the final pick, the smallest of all
       for (int c0 = 0; c0 < b; c0 += 64) {
         const int cnt = __builtin_amdgcn_readfirstlane(b - c0 < 64 ? b - c0 : 64);
         int rec_i = 0, rec_g = 0;
@@ -275,8 +378,16 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         }
         const float g = __int_as_float(rec_g);
         if (lane < cnt) { order_l[c0 + lane] = rec_i; gain_l[c0 + lane] = g; }
+        last_g = __int_as_float(__builtin_amdgcn_readlane(rec_g, cnt - 1));
         const unsigned long long bad = __ballot(lane < cnt && !(g > -INFINITY));
         if (bad && bad_t == b) bad_t = c0 + __ffsll(static_cast<long long>(bad)) - 1;
+      }
+      {
+        // Candidates that were left out for lack of room must lie below every pick's gain;
+        // otherwise (or when the gains are not finite) the head goes to the full-size kernel.
+        const float excl = __int_as_float(meta[4 + buf]);
+        const bool ok = excl < last_g - 1e-5f * (fabsf(last_g) + a.lambda);
+        if (lane == 0) meta[6 + buf] = (ok || excl == -INFINITY) ? 0 : 1;
       }
       if (bad_t < b) {
         // Non-finite scores or rows only: keep the picks made before the first one without a
@@ -327,42 +438,28 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     const long long st3 = __builtin_readcyclecounter();
 #endif
 
-    // ------------------------------------------------- outputs and compaction
-    const long long ob = static_cast<long long>(h) * b;
-    for (int t = tid; t < b; t += kDenseThreads) {
-      a.idx_sorted[ob + t] = idx_l[t];
-      if (a.pick_order) a.pick_order[ob + t] = order_l[t];
-      if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
-    }
-    if (a.K_out || a.V_out) {
-      const int chunk = tid & 15;
-      for (int t0 = 0; t0 < b; t0 += kDenseThreads / 16) {
-        const int t = t0 + (tid >> 4);
-        if (t < b) {
-          const int it = min(max(idx_l[t], 0), n - 1);   // never read outside the head, whatever the scores were
-          const long long src = head_off + (it * a.stride_tok + chunk * 8) * 2;
-          const long long dst = ((ob + t) * kD + chunk * 8) * 2;
-          uint4 kv, vv;
-          if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
-          if (a.V_out) vv = *reinterpret_cast<const uint4*>(a.V + src);
-          if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kv;
-          if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vv;
-        }
-      }
+#ifdef KVR_STATS
+    st_acc[0] += st1 - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2;
+    st_acc[4] += ns; st_acc[5] += 1;
+#endif
+    hprev = h;
+    h = __builtin_amdgcn_readfirstlane(meta[buf ^ 1]);   // published before the barrier above
+    buf ^= 1;
+  }
+  if (hprev >= 0) {
+    constexpr int kStep = kOutBatch * (kDenseThreads / 16);
+    out_lists(hprev, buf ^ 1, tid0, kDenseThreads);
+    for (int first = 0; first < b; first += kStep) {
+      out_load(hprev, buf ^ 1, tid0, kDenseThreads, first);
+      out_store(hprev, tid0, kDenseThreads, first);
     }
 #ifdef KVR_STATS
-    {
-      const long long st4 = __builtin_readcyclecounter();
-      st_acc[0] += st1 - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2; st_acc[3] += st4 - st3;
-      st_acc[4] += ns; st_acc[5] += 1;
-      if ((tid == 0 || tid == 64) && a.pick_gain && b >= 16) {
-        float* o = a.pick_gain + ob + b - 1 - (tid == 64 ? 8 : 0);
-        for (int k = 0; k < 5; ++k) o[-k] = static_cast<float>(st_acc[k]) / st_acc[5];
-      }
+    __syncthreads();
+    if ((tid0 == 0 || tid0 == 64) && a.pick_gain && b >= 16) {
+      float* o = a.pick_gain + static_cast<long long>(hprev) * b + b - 1 - (tid0 == 64 ? 8 : 0);
+      for (int k = 0; k < 5; ++k) o[-k] = static_cast<float>(st_acc[k]) / st_acc[5];
     }
 #endif
-    h = __builtin_amdgcn_readfirstlane(meta[buf ^ 1]);                              // published before the barrier above
-    buf ^= 1;
   }
 }
 
