@@ -64,6 +64,9 @@ __device__ __forceinline__ float hw_max(float a, float b) {
 // ra[lane ln] = va, rb[lane ln] = vb for wave-uniform va, vb, ln; the other lanes keep their
 // values.  The lane select goes through m0 because a VALU instruction reads one SGPR only.
 __device__ __forceinline__ void write_lane2(int& ra, int& rb, int va, int vb, int ln) {
+  va = __builtin_amdgcn_readfirstlane(va);             // no-ops when the compiler knows them uniform
+  vb = __builtin_amdgcn_readfirstlane(vb);
+  ln = __builtin_amdgcn_readfirstlane(ln);
   asm("s_mov_b32 m0, %4\n\tv_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
       : "+v"(ra), "+v"(rb)
       : "s"(va), "s"(vb), "s"(ln)
@@ -84,6 +87,25 @@ __device__ __forceinline__ int first_of_pairs(unsigned long long e0, unsigned lo
       : "s"(e0), "s"(e1)
       : "scc");
   return i;
+}
+// The same for NQ tokens per lane (token NQ*lane + q in slot q): lowest lane first, lowest slot
+// within the lane.  -1 - (NQ - 1) .. -1 when all masks are empty (callers treat any negative
+// value as "none").
+template <int NQ>
+__device__ __forceinline__ int first_of_slots(const unsigned long long (&e)[NQ]) {
+  if constexpr (NQ == 2) {
+    return first_of_pairs(e[0], e[1]);
+  } else {
+    unsigned long long any = e[0];
+#pragma unroll
+    for (int q = 1; q < NQ; ++q) any |= e[q];
+    int L;
+    asm("s_ff1_i32_b64 %0, %1" : "=s"(L) : "s"(any));   // -1 for an empty mask
+    int qsel = NQ - 1;
+#pragma unroll
+    for (int q = NQ - 2; q >= 0; --q) qsel = ((e[q] >> (L & 63)) & 1ull) ? q : qsel;
+    return NQ * L + (L < 0 ? 0 : qsel);
+  }
 }
 // max / sum over each half of the wave (lanes 0-31 and 32-63); valid in lanes 31 and 63
 __device__ __forceinline__ float half_max_at_31(float v) {

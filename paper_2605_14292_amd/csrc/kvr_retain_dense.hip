@@ -296,93 +296,69 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
 
     // ---------------------------------------------------------------- greedy
     if (wave == 0) {
-      // Token j lives in lane j%64, slot j/64.  Picks are collected one per lane and flushed to
-      // LDS every 64 picks.
-      float sreg[NQ], mreg[NQ];
-      int jb4[NQ], tjb4[NQ];
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const int j = lane + 64 * q;
-        sreg[q] = s_l[j];                              // -inf beyond n
-        mreg[q] = 0.f;
-        jb4[q] = j * 4;
-        tjb4[q] = (j * (j + 1) / 2) * 4;
-      }
-      const float nlam = -a.lambda;
+      // A single wave issues one instruction every few cycles, so the time of a pick is its
+      // instruction count.  Tokens NQ*lane .. NQ*lane+NQ-1 live in lane `lane`: the lowest lane
+      // holding the maximum then also holds the lowest tied index.  Pick u of a 64-pick chunk
+      // is parked in lane u of two registers (v_writelane) and the chunk is written out once.
+      // Nothing is checked per pick: non-finite input is detected afterwards from the gains.
       typedef __attribute__((address_space(3))) const float* lds_fp;
-      // LDS byte address of the triangle, folded into the per-lane offsets once
       const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
           (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
+      float sreg[NQ], mreg[NQ];
       int ja[NQ], tja[NQ];
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) { ja[q] = jb4[q] + tri0; tja[q] = tjb4[q] + tri0; }
-      int rec_i = 0;
-      float rec_g = 0.f;
-      int t = 0;
-      bool finite = true;
-      // One pick: gains, DPP max, lowest tied index.  Returns the token, or -1 when no finite
-      // gain is left (non-finite input only).
-      auto pick = [&](float& amax) -> int {
-        float av[NQ];
+      for (int q = 0; q < NQ; ++q) {
+        const int j = NQ * lane + q;
+        sreg[q] = s_l[j];                              // -inf beyond n
+        mreg[q] = 0.f;
+        ja[q] = j * 4 + tri0;                          // column offset of the token
+        tja[q] = j * (j + 1) * 2 + tri0;               // start of its row
+      }
+      const float nlam = -a.lambda;
+      int bad_t = b;                                   // first pick without a finite gain
+      for (int c0 = 0; c0 < b; c0 += 64) {
+        const int cnt = __builtin_amdgcn_readfirstlane(b - c0 < 64 ? b - c0 : 64);
+        int rec_i = 0, rec_g = 0;
+        for (int u = 0; u < cnt; ++u) {
+          float av[NQ];
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
-        float best = av[0];
+          for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
+          float best = av[0];
 #pragma unroll
-        for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
-        amax = wave_max_uniform(best);
-        int i = -1;
+          for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
+          const float amax = wave_max_uniform(best);
+          unsigned long long e[NQ];
 #pragma unroll
-        for (int q = NQ - 1; q >= 0; --q) {
-          const unsigned long long eq = __ballot(av[q] == amax);
-          if (eq) i = (__ffsll(static_cast<long long>(eq)) - 1) + 64 * q;
-        }
-        return amax > -INFINITY ? i : -1;
-      };
-      auto record = [&](int i, float g) {
-        if (lane == (t & 63)) { rec_i = i; rec_g = g; }
-        if ((t & 63) == 63) { order_l[t - 63 + lane] = rec_i; gain_l[t - 63 + lane] = rec_g; }
-      };
-      if (diverse) {
-        // all picks but the last read the row of the pick; its diagonal entry (+inf) retires it
-        for (; t + 1 < b; ++t) {
-          float amax;
-          const int i = pick(amax);
-          if (i < 0) { finite = false; break; }
-          record(i, amax);
-          const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
-          float c[NQ];                                 // all slots' reads in flight before the first use
+          for (int q = 0; q < NQ; ++q) e[q] = __ballot(av[q] == amax);
+          const int i = first_of_slots<NQ>(e);         // negative when nothing compares equal (NaN)
+          write_lane2(rec_i, rec_g, i, __float_as_int(amax), u);
+          if (diverse) {
+            // element (i,j) of the triangle sits at max(T(i)+j, T(j)+i); the diagonal entry
+            // (+inf) retires the pick.  For any i in [-NQ, n) both addresses stay in the triangle.
+            const int ti4 = i * (i + 1) * 2, i4 = i * 4;
+            float c[NQ];
 #pragma unroll
-          for (int q = 0; q < NQ; ++q) {
-            const int a0 = ti4 + ja[q], a1 = tja[q] + i4;     // element (i,j) sits at max(T(i)+j, T(j)+i)
-            c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a0 > a1 ? a0 : a1)));
+            for (int q = 0; q < NQ; ++q) {
+              const int a0 = ti4 + ja[q], a1 = tja[q] + i4;
+              c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a0 > a1 ? a0 : a1)));
+            }
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
+          } else {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) sreg[q] = (NQ * lane + q == i) ? -INFINITY : sreg[q];
           }
-          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-          for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
         }
-      } else {
-        for (; t + 1 < b; ++t) {
-          float amax;
-          const int i = pick(amax);
-          if (i < 0) { finite = false; break; }
-          record(i, amax);
-#pragma unroll
-          for (int q = 0; q < NQ; ++q) sreg[q] = (jb4[q] == i * 4) ? -INFINITY : sreg[q];
-        }
+        const float g = __int_as_float(rec_g);
+        if (lane < cnt) { order_l[c0 + lane] = rec_i; gain_l[c0 + lane] = g; }
+        const unsigned long long bad = __ballot(lane < cnt && !(g > -INFINITY));
+        if (bad && bad_t == b) bad_t = c0 + __ffsll(static_cast<long long>(bad)) - 1;
       }
-      if (finite) {
-        float amax;
-        const int i = pick(amax);
-        if (i < 0) finite = false;
-        else { record(i, amax); ++t; }
-      }
-      if (t & 63) {                                    // picks still held in registers
-        if (lane < (t & 63)) { order_l[(t & ~63) + lane] = rec_i; gain_l[(t & ~63) + lane] = rec_g; }
-      }
-      if (!finite) {
-        // Non-finite input only: fill up with the lowest tokens that are not in the pick list.
+      if (bad_t < b) {
+        // Non-finite input only: keep the picks made before the first one without a finite
+        // gain and fill up with the lowest tokens that are not in the pick list.
         wave_lds_sync();
-        for (; t < b; ++t) {
+        for (int t = bad_t; t < b; ++t) {
           int i = -1;
 #pragma unroll
           for (int q = NQ - 1; q >= 0; --q) {

@@ -24,43 +24,18 @@
 // Layout: one workgroup per head, W wave64s, token j = 64*S*w + 64*k + lane in
 // wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
 // lane's registers for the whole event.
-#include "kvr_device.hpp"
+#include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 
 namespace kvr {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kPool = 128;          // pool size
 constexpr int kPoolMaxB = 256;      // pick lists kept in LDS
 constexpr int kPoolMaxPend = 32;    // picks per epoch (two 16-row MFMA operands)
 constexpr int kPoolPitch = 272;     // bytes per staged row (256 + 16)
 constexpr int kPoolChunk = 16;      // tokens staged per step and wave in the pass over V
-
-__device__ __forceinline__ float pool_wave_max(float v) {
-  asm volatile(
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-      "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-      "s_nop 1"
-      : "+v"(v));
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-__device__ __forceinline__ float pool_hw_max(float a, float b) {
-  float r;
-  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
-__device__ __forceinline__ void pool_wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 struct PoolArgs {
   const char* K; const char* V; const float* s_in;
@@ -140,8 +115,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   auto wg_argmax = [&](const float (&av)[S], float& gbest, int& ibest) {
     float best = av[0];
 #pragma unroll
-    for (int k = 1; k < S; ++k) best = pool_hw_max(best, av[k]);
-    const float amax_w = pool_wave_max(best);
+    for (int k = 1; k < S; ++k) best = hw_max(best, av[k]);
+    const float amax_w = wave_max_uniform(best);
     int i_w = -1;
 #pragma unroll
     for (int k = S - 1; k >= 0; --k) {
@@ -153,7 +128,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     const float g = lane < W ? slot_gain[par * 16 + lane] : -INFINITY;
     const int ii = lane < W ? slot_idx[par * 16 + lane] : -1;
     par ^= 1;
-    gbest = pool_wave_max(g);
+    gbest = wave_max_uniform(g);
     const unsigned long long eqw = __ballot(lane < W && g == gbest);
     ibest = eqw ? __builtin_amdgcn_readlane(ii, __ffsll(static_cast<long long>(eqw)) - 1) : -1;
   };
@@ -376,43 +351,49 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #endif
       // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
       if (w == 0) {
-        float sreg[2], mreg[2];
-        int treg[2], ja[2], tja[2];
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const int p = lane + 64 * q;
-          sreg[q] = pool_s[p]; mreg[q] = pool_m[p]; treg[q] = pool_tok[p];
-          ja[q] = p * 4; tja[q] = (p * (p + 1) / 2) * 4;
-        }
-        const int jb = jout < 0 ? 0x7fffffff : jout;
+        // Pool slots 2*lane and 2*lane+1 live in lane `lane` (slots are in token order, so the
+        // lowest slot is the lowest token).  A pick is parked in lane np of two registers; the
+        // pick lists and the pending-row tables are written once, after the loop.
+        const int p0 = 2 * lane;
+        const float s0 = pool_s[p0], s1 = pool_s[p0 + 1];
+        float m0 = pool_m[p0], m1 = pool_m[p0 + 1];
+        typedef __attribute__((address_space(3))) const float* lds_fp;
+        const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
+            (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
+        const int ja0 = p0 * 4 + tri0, ja1 = ja0 + 4;
+        const int tja0 = p0 * (p0 + 1) * 2 + tri0, tja1 = (p0 + 1) * (p0 + 2) * 2 + tri0;
+        const int jb = __builtin_amdgcn_readfirstlane(jout < 0 ? 0x7fffffff : jout);
+        const float gout_u = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(gout)));
+        const bool no_out = __builtin_amdgcn_readfirstlane(jout) < 0;
+        const int room = __builtin_amdgcn_readfirstlane(min(b - t, kPoolMaxPend));
         int np = 0, stop = 0;                        // stop: 1 = bound wins, 2 = nothing finite left
-        const char* trib = reinterpret_cast<const char*>(tri);
-        while (t < b && np < kPoolMaxPend) {
-          const float a0 = fmaf(nlam, mreg[0], sreg[0]), a1 = fmaf(nlam, mreg[1], sreg[1]);
-          const float amax = pool_wave_max(pool_hw_max(a0, a1));
-          if (!(amax > -INFINITY)) { stop = jout < 0 ? 2 : 1; break; }
+        int rec_i = 0, rec_g = 0;
+        while (np < room) {
+          const float a0 = fmaf(nlam, m0, s0), a1 = fmaf(nlam, m1, s1);
+          const float amax = wave_max_uniform(hw_max(a0, a1));
           const unsigned long long e0 = __ballot(a0 == amax), e1 = __ballot(a1 == amax);
-          const int il = e0 ? __ffsll(static_cast<long long>(e0)) - 1 : __ffsll(static_cast<long long>(e1)) - 1;
-          const int i = e0 ? il : il + 64;           // pool slots are in token order, lowest slot = lowest token
-          const int ti = __builtin_amdgcn_readlane(e0 ? treg[0] : treg[1], il);
-          if (!(amax > gout || (amax == gout && ti < jb))) { stop = 1; break; }
-          if (lane == 0) {
-            order_l[t] = ti; gain_l[t] = amax; pend_l[np] = i; pend_r[np] = pool_r[i]; pool_picked[i] = 1;
+          const int i = first_of_pairs(e0, e1);
+          if (!(amax > gout_u)) {                    // rare: the bound wins, a tie with it, or nothing finite
+            if (!(amax > -INFINITY)) { stop = no_out ? 2 : 1; break; }
+            const int ti = __builtin_amdgcn_readfirstlane(pool_tok[i < 0 ? 0 : i]);
+            if (!(amax == gout_u && ti < jb)) { stop = 1; break; }
           }
-          ++t; ++np;
-          if (t == b) break;
-          const int ti4 = (i * (i + 1) / 2) * 4, i4 = i * 4;
-          float c[2];
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const int x0 = ti4 + ja[q], x1 = tja[q] + i4;
-            c[q] = *reinterpret_cast<const float*>(trib + (x0 > x1 ? x0 : x1));
-          }
-          mreg[0] = pool_hw_max(mreg[0], c[0]);
-          mreg[1] = pool_hw_max(mreg[1], c[1]);
+          write_lane2(rec_i, rec_g, i, __float_as_int(amax), np);
+          np = __builtin_amdgcn_readfirstlane(np + 1);   // keeps the loop control on the scalar unit
+          // element (i,j) of the triangle sits at max(T(i)+j, T(j)+i); the diagonal (+inf) retires i
+          const int ti4 = i * (i + 1) * 2, i4 = i * 4;
+          const int x00 = ti4 + ja0, x01 = tja0 + i4, x10 = ti4 + ja1, x11 = tja1 + i4;
+          const float c0 = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(x00 > x01 ? x00 : x01)));
+          const float c1 = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(x10 > x11 ? x10 : x11)));
+          m0 = hw_max(m0, c0);
+          m1 = hw_max(m1, c1);
         }
-#pragma unroll
-        for (int q = 0; q < 2; ++q) pool_m[lane + 64 * q] = mreg[q];   // the pool's m is authoritative
+        pool_m[p0] = m0; pool_m[p0 + 1] = m1;        // the pool's m is authoritative
+        if (lane < np) {
+          order_l[t + lane] = pool_tok[rec_i]; gain_l[t + lane] = __int_as_float(rec_g);
+          pend_l[lane] = rec_i; pend_r[lane] = pool_r[rec_i]; pool_picked[rec_i] = 1;
+        }
+        t += np;
         if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
       }
       __syncthreads();
@@ -489,11 +470,11 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           float part[4];                             // per 16-token sub-block: max over my four picked rows
 #pragma unroll
           for (int sub = 0; sub < 4; ++sub) {
-            pool_wave_sync();
+            wave_lds_sync();
 #pragma unroll
             for (int q = 0; q < LPC; ++q)
               *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) = cur[sub][q];
-            pool_wave_sync();
+            wave_lds_sync();
             const char* fp = stage + (lane & 15) * kPoolPitch + kg * 16;
             bf16x8 bfr[4];
 #pragma unroll
@@ -501,27 +482,27 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
             f32x4 acc0 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[0][ks], bfr[ks], acc0, 0, 0, 0);
-            float pm = pool_hw_max(pool_hw_max(acc0[0] * pr[0][0], acc0[1] * pr[0][1]),
-                                   pool_hw_max(acc0[2] * pr[0][2], acc0[3] * pr[0][3]));
+            float pm = hw_max(hw_max(acc0[0] * pr[0][0], acc0[1] * pr[0][1]),
+                                   hw_max(acc0[2] * pr[0][2], acc0[3] * pr[0][3]));
             if (tiles > 1) {
               f32x4 acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
               for (int ks = 0; ks < 4; ++ks) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][ks], bfr[ks], acc1, 0, 0, 0);
-              const float pm1 = pool_hw_max(pool_hw_max(acc1[0] * pr[1][0], acc1[1] * pr[1][1]),
-                                            pool_hw_max(acc1[2] * pr[1][2], acc1[3] * pr[1][3]));
-              pm = pool_hw_max(pm, pm1);
+              const float pm1 = hw_max(hw_max(acc1[0] * pr[1][0], acc1[1] * pr[1][1]),
+                                            hw_max(acc1[2] * pr[1][2], acc1[3] * pr[1][3]));
+              pm = hw_max(pm, pm1);
             }
             part[sub] = pm;
           }
           // lane (col, kg) holds partial maxima of token col of sub-block 0..3; the owner of token
           // (sub, col) is lane (col, kg = sub).  Exchange through the wave's scratch: [sub][kg][col].
-          pool_wave_sync();
+          wave_lds_sync();
 #pragma unroll
           for (int sub = 0; sub < 4; ++sub) scratch[sub * 64 + kg * 16 + (lane & 15)] = part[sub];
-          pool_wave_sync();
+          wave_lds_sync();
           const float* sp = scratch + kg * 64 + (lane & 15);
-          const float mx = pool_hw_max(pool_hw_max(sp[0], sp[16]), pool_hw_max(sp[32], sp[48]));
-          if (pslot[k] < 0) m[k] = pool_hw_max(m[k], mx * r[k]);
+          const float mx = hw_max(hw_max(sp[0], sp[16]), hw_max(sp[32], sp[48]));
+          if (pslot[k] < 0) m[k] = hw_max(m[k], mx * r[k]);
         }
       }
 #pragma unroll
