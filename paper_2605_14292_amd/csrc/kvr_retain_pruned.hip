@@ -55,21 +55,35 @@ __device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, co
   const float rc = rinv[j];
   int i = I * 32 + hf * 4;                            // first of this lane's rows in the tile
   int off = i * (i + 1) / 2 + j;
-  const bool diag = I == J;
+  if (I != J) {                                       // two code paths: no per-element predicate off the diagonal
 #pragma unroll
-  for (int R = 0; R < 4; ++R) {
-    const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
-    const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-    int o = off;
+    for (int R = 0; R < 4; ++R) {
+      const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
+      const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+      int o = off;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float c = acc[R * 4 + q] * rrow[q] * rc;
-      if (diag && j == i + q) c = INFINITY;
-      if (!diag || j <= i + q) tri[o] = c;
-      o += i + q + 1;
+      for (int q = 0; q < 4; ++q) {
+        tri[o] = acc[R * 4 + q] * rrow[q] * rc;
+        o += i + q + 1;
+      }
+      off += 8 * i + 36;                              // T(i+8) - T(i)
+      i += 8;
     }
-    off += 8 * i + 36;                                // T(i+8) - T(i)
-    i += 8;
+  } else {
+#pragma unroll
+    for (int R = 0; R < 4; ++R) {
+      const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
+      const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+      int o = off;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float c = j == i + q ? INFINITY : acc[R * 4 + q] * rrow[q] * rc;
+        if (j <= i + q) tri[o] = c;
+        o += i + q + 1;
+      }
+      off += 8 * i + 36;
+      i += 8;
+    }
   }
 }
 
@@ -181,6 +195,8 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
   };
   // Rows of the survivors of head hh (list in buffer buf) into registers.
   auto gather = [&](int hh, int buf, int ns, int tid) {
+#pragma unroll
+    for (int k = 0; k < kPrIters; ++k) vpre[k] = make_uint4(0u, 0u, 0u, 0u);   // rows past the survivors read as zero
     if (hh < a.heads) {
       const int32_t* tc = tok_c + buf * kPrN;
       wave_lds_sync();                                // tc[] was written by this wave's own lanes
@@ -189,9 +205,30 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #pragma unroll
       for (int k = 0; k < kPrIters; ++k) {
         const int c = r0 + kPrRowsPerIter * k;
-        vpre[k] = make_uint4(0u, 0u, 0u, 0u);         // rows past the survivors read as zero
         if (c < ns) vpre[k] = *reinterpret_cast<const uint4*>(vb + tc[c] * a.stride_tok * 2);
       }
+    }
+  };
+
+  // Inverse norms 1/(||V_c|| + eps) of the gathered rows (Eq. 1): eight elements per lane, the
+  // sixteen lanes of a row form one DPP row whose last lane ends up with the total.  Runs while
+  // wave 0 is still in its chain, once the rows have landed.
+  float rn[kPrIters];
+  auto norms = [&]() {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+#pragma unroll
+    for (int k = 0; k < kPrIters; ++k) {
+      const uint32_t wds[4] = {vpre[k].x, vpre[k].y, vpre[k].z, vpre[k].w};
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bf16x2 x = __builtin_bit_cast(bf16x2, wds[e]);
+        ss = __builtin_amdgcn_fdot2_f32_bf16(x, x, ss, false);
+      }
+      KVR_DPP_ADD(ss, 0x111, 0xf) KVR_DPP_ADD(ss, 0x112, 0xf) KVR_DPP_ADD(ss, 0x114, 0xf)
+      KVR_DPP_ADD(ss, 0x118, 0xf)
+      rn[k] = 1.0f / (sqrtf(ss) + a.eps);
+      __builtin_amdgcn_sched_barrier(0);              // one row at a time: no registers for eleven in flight
     }
   };
 
@@ -239,7 +276,8 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
   };
 
 #ifdef KVR_STATS
-  long long st_acc[6] = {0, 0, 0, 0, 0, 0};
+  long long st_acc[7] = {0, 0, 0, 0, 0, 0, 0};
+  const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime();
 #endif
   int buf = 0;
   int hprev = -1;                                     // head whose results are still in LDS
@@ -247,6 +285,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     int ns0;
     const int h0 = survivors(blockIdx.x, 0, tid0, ns0);
     gather(h0, 0, ns0, tid0);
+    norms();
   }
   __syncthreads();
   int h = __builtin_amdgcn_readfirstlane(meta[0]);
@@ -271,10 +310,16 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #pragma unroll
       for (int k = 0; k < kPrIters; ++k) {
         const int c = r0 + kPrRowsPerIter * k;
-        if (c < kPrN) *reinterpret_cast<uint4*>(stage + c * kRowPitch + chunk * 16) = vpre[k];
+        if (c < kPrN) {
+          *reinterpret_cast<uint4*>(stage + c * kRowPitch + chunk * 16) = vpre[k];
+          if (chunk == 15) rinv[c] = rn[k];
+        }
       }
     }
     __syncthreads();
+#ifdef KVR_STATS
+    const long long stA = __builtin_readcyclecounter();
+#endif
 
     // ------------------------------------------------ Gram -> packed cosines
     // Ten lower-triangular 32x32 tiles over four waves; tile rows that hold no survivor are
@@ -299,18 +344,12 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         for (int ks = 0; ks < 8; ++ks)
           acc[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_at(stage, I, ks, lane),
                                                             frag_at(stage, J, ks, lane), acc[sl], 0, 0, 0);
-        if (I == J) {                                 // squared norms sit on the diagonal
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int il = (r >> 2) * 8 + hf * 4 + (r & 3);
-            if (il == (lane & 31)) rinv[I * 32 + il] = acc[sl][r];
-          }
-        }
       }
     }
     __syncthreads();                                  // gathered rows are dead from here on
-    if (tid < kPrN) rinv[tid] = 1.0f / (sqrtf(rinv[tid]) + a.eps);
-    __syncthreads();
+#ifdef KVR_STATS
+    const long long stB = __builtin_readcyclecounter();
+#endif
 #pragma unroll
     for (int sl = 0; sl < 3; ++sl) {
       int I, J;
@@ -327,9 +366,14 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       // runs while they are in flight
       const int tl = tid - kWave;
       constexpr int kStep = kOutBatch * (kPrLoaders / 16);
+#pragma unroll
+      for (int k = 0; k < kOutBatch; ++k) {            // nothing of the previous head's rows is carried over
+        kr[k] = vr[k] = make_uint4(0u, 0u, 0u, 0u);
+      }
       if (hprev >= 0) out_load(hprev, buf ^ 1, tl, kPrLoaders, 0);
       int ns_n;
       const int h_n = survivors(h + gridDim.x, buf ^ 1, tid, ns_n);
+      gather(h_n, buf ^ 1, ns_n, tid);   // in flight from here to the end of wave 0's chain
       if (hprev >= 0) {
         out_lists(hprev, buf ^ 1, tl, kPrLoaders);
         out_store(hprev, tl, kPrLoaders, 0);
@@ -338,7 +382,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
           out_store(hprev, tl, kPrLoaders, first);
         }
       }
-      gather(h_n, buf ^ 1, ns_n, tid);   // lands while wave 0 is still in its chain
+      norms();
     } else {
       // ---------------------------------------------------------------- greedy
       // A single wave issues one instruction every few cycles, so the time of a pick is its
@@ -429,6 +473,13 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         off += __popcll(sel);
       }
       for (int u = lane; u < b; u += kWave) order_l[u] = tok_cur[min(max(order_l[u], 0), kPrN - 1)];
+      // Wave 0 never holds gathered rows.  Saying so (no instruction is emitted) keeps the row
+      // registers of the other branch from being carried, as far as the compiler can tell,
+      // through this branch and with it through the whole loop body.
+#pragma unroll
+      for (int k = 0; k < kPrIters; ++k) {
+        asm volatile("" : "=v"(vpre[k].x), "=v"(vpre[k].y), "=v"(vpre[k].z), "=v"(vpre[k].w), "=v"(rn[k]));
+      }
     }
 #ifdef KVR_STATS
     st2 = __builtin_readcyclecounter();
@@ -439,7 +490,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #endif
 
 #ifdef KVR_STATS
-    st_acc[0] += st1 - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2;
+    st_acc[0] += stA - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2; st_acc[3] += stB - stA; st_acc[6] += st1 - stB;
     st_acc[4] += ns; st_acc[5] += 1;
 #endif
     hprev = h;
@@ -458,6 +509,9 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     if ((tid0 == 0 || tid0 == 64) && a.pick_gain && b >= 16) {
       float* o = a.pick_gain + static_cast<long long>(hprev) * b + b - 1 - (tid0 == 64 ? 8 : 0);
       for (int k = 0; k < 5; ++k) o[-k] = static_cast<float>(st_acc[k]) / st_acc[5];
+      o[-5] = static_cast<float>(st_acc[6]) / st_acc[5];
+      o[-6] = static_cast<float>(rt0 & 0xffffffull);
+      o[-7] = static_cast<float>(__builtin_amdgcn_s_memrealtime() & 0xffffffull);
     }
 #endif
   }
