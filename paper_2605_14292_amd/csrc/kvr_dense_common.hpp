@@ -54,6 +54,12 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits until every
+// global store of the wave has been acknowledged by memory, which costs microseconds after a
+// burst of output rows and is needed by nobody: no wave reads what another one wrote to HBM.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 // max(a, b) as the hardware does it (a NaN operand yields the other one), without
 // the canonicalising self-max the compiler adds around fmaxf on loaded values
 __device__ __forceinline__ float hw_max(float a, float b) {

@@ -108,6 +108,13 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
   // Waves 1-3, each on its own: survivors of the first head hh, hh + gridDim.x, ... that
   // fits, then the gather of their V rows into registers.  The three waves compute the same
   // survivor list (each needs it for its share of the rows); wave 1 publishes it.
+  float s_pre[4];                                     // scores of head s_pre_h, fetched ahead of time
+  int s_pre_h = -1;
+  auto load_scores = [&](int hh, int lane, float (&dst)[4]) {
+    const float* sp = a.s + static_cast<long long>(hh) * n;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dst[q] = lane + 64 * q < n ? sp[lane + 64 * q] : -INFINITY;
+  };
   auto survivors = [&](int hh, int buf, int tid, int& ns_out) -> int {
     const int lane = tid & 63;
     float sv[4];
@@ -115,16 +122,19 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     int ns = 0;
     float excl = -INFINITY;                           // best score among the candidates left out
     for (; hh < a.heads; hh += gridDim.x) {
-      const float* sp = a.s + static_cast<long long>(hh) * n;
+      if (hh == s_pre_h) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sv[q] = s_pre[q];
+      } else {
+        load_scores(hh, lane, sv);
+      }
       uint32_t key[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int j = lane + 64 * q;
-        sv[q] = j < n ? sp[j] : -INFINITY;
-        key[q] = j < n ? ordered_key(sv[q] + 0.0f) : 0u;
-      }
-      uint32_t T = 0;                                 // becomes the key of the b-th largest score
-      for (int bit = 31; bit >= 0; --bit) {
+      for (int q = 0; q < 4; ++q) key[q] = lane + 64 * q < n ? ordered_key(sv[q] + 0.0f) : 0u;
+      // Bit-wise search for the b-th largest key, leading 16 bits only: the result is at most
+      // s_(b), so the bound below stays valid and is looser by less than one part in 128.
+      uint32_t T = 0;
+      for (int bit = 31; bit >= 16; --bit) {
         const uint32_t cand = T | (1u << bit);
         int cnt = 0;
 #pragma unroll
@@ -190,6 +200,8 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       meta[2 + buf] = ns;
       meta[4 + buf] = __float_as_int(excl);
     }
+    s_pre_h = hh < a.heads ? hh + static_cast<int>(gridDim.x) : -1;
+    if (s_pre_h >= 0 && s_pre_h < a.heads) load_scores(s_pre_h, lane, s_pre);
     ns_out = ns;
     return hh;
   };
@@ -234,8 +246,10 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 
   // Results of head hh (lists in buffer lb) to HBM and the compaction of its kept rows, by the
   // nthr threads t0 = 0..nthr-1 (nthr a multiple of 16).  Rows move in batches of kOutBatch per
-  // 16-thread group: all loads of a batch are in flight before its first store.
-  constexpr int kOutBatch = 2;
+  // 16-thread group.  The loads of a batch are straight-line code (row indices past b are
+  // clamped, not branched around): with branches in between the compiler loses count of what is
+  // in flight and waits for everything, acknowledged stores included, before each store.
+  constexpr int kOutBatch = 6;
   auto out_lists = [&](int hh, int lb, int t0, int nthr) {
     const long long ob = static_cast<long long>(hh) * b;
     const bool redo = meta[6 + lb] != 0;                 // the head is left to the full-size kernel
@@ -246,17 +260,26 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     }
   };
   uint4 kr[kOutBatch], vr[kOutBatch];
+  const bool copy_both = a.K_out && a.V_out;
   auto out_load = [&](int hh, int lb, int t0, int nthr, int first) {
     const int32_t* il = idx_l2 + lb * kPrN;
     const long long head_off = hh * a.stride_head * 2 + (t0 & 15) * 16;   // bytes
+    if (copy_both) {
 #pragma unroll
-    for (int k = 0; k < kOutBatch; ++k) {
-      const int t = first + (t0 >> 4) + k * (nthr >> 4);
-      kr[k] = make_uint4(0u, 0u, 0u, 0u);
-      vr[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (t < b) {
+      for (int k = 0; k < kOutBatch; ++k) {
+        const int t = min(first + (t0 >> 4) + k * (nthr >> 4), b - 1);
         const int it = min(max(il[t], 0), n - 1);        // never read outside the head, whatever the scores were
         const long long src = head_off + it * a.stride_tok * 2;
+        kr[k] = *reinterpret_cast<const uint4*>(a.K + src);
+        vr[k] = *reinterpret_cast<const uint4*>(a.V + src);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < kOutBatch; ++k) {
+        const int t = min(first + (t0 >> 4) + k * (nthr >> 4), b - 1);
+        const int it = min(max(il[t], 0), n - 1);
+        const long long src = head_off + it * a.stride_tok * 2;
+        kr[k] = vr[k] = make_uint4(0u, 0u, 0u, 0u);
         if (a.K_out) kr[k] = *reinterpret_cast<const uint4*>(a.K + src);
         if (a.V_out) vr[k] = *reinterpret_cast<const uint4*>(a.V + src);
       }
@@ -278,6 +301,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #ifdef KVR_STATS
   long long st_acc[7] = {0, 0, 0, 0, 0, 0, 0};
   const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime();
+  long long lst[3] = {0, 0, 0};
 #endif
   int buf = 0;
   int hprev = -1;                                     // head whose results are still in LDS
@@ -287,7 +311,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     gather(h0, 0, ns0, tid0);
     norms();
   }
-  __syncthreads();
+  lds_barrier();
   int h = __builtin_amdgcn_readfirstlane(meta[0]);
   while (h < a.heads) {
     // The thread index is made opaque once per head so that per-lane LDS addresses are not
@@ -316,7 +340,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
 #ifdef KVR_STATS
     const long long stA = __builtin_readcyclecounter();
 #endif
@@ -346,7 +370,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
                                                             frag_at(stage, J, ks, lane), acc[sl], 0, 0, 0);
       }
     }
-    __syncthreads();                                  // gathered rows are dead from here on
+    lds_barrier();                                  // gathered rows are dead from here on
 #ifdef KVR_STATS
     const long long stB = __builtin_readcyclecounter();
 #endif
@@ -355,7 +379,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       int I, J;
       if (tile_of(sl, I, J)) write_cos_tile(tri, rinv, acc[sl], I, J, lane);
     }
-    __syncthreads();
+    lds_barrier();
 
 #ifdef KVR_STATS
     const long long st1 = __builtin_readcyclecounter();
@@ -373,6 +397,9 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       if (hprev >= 0) out_load(hprev, buf ^ 1, tl, kPrLoaders, 0);
       int ns_n;
       const int h_n = survivors(h + gridDim.x, buf ^ 1, tid, ns_n);
+#ifdef KVR_STATS
+      const long long lq0 = __builtin_readcyclecounter();
+#endif
       gather(h_n, buf ^ 1, ns_n, tid);   // in flight from here to the end of wave 0's chain
       if (hprev >= 0) {
         out_lists(hprev, buf ^ 1, tl, kPrLoaders);
@@ -382,7 +409,13 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
           out_store(hprev, tl, kPrLoaders, first);
         }
       }
+#ifdef KVR_STATS
+      const long long lq1 = __builtin_readcyclecounter();
+#endif
       norms();
+#ifdef KVR_STATS
+      lst[0] += lq0 - st1; lst[1] += lq1 - lq0; lst[2] += __builtin_readcyclecounter() - lq1;
+#endif
     } else {
       // ---------------------------------------------------------------- greedy
       // A single wave issues one instruction every few cycles, so the time of a pick is its
@@ -400,6 +433,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       const int ja0 = j0 * 4 + tri0, ja1 = ja0 + 4;                       // column offsets of the lane's tokens
       const int tja0 = j0 * (j0 + 1) * 2 + tri0, tja1 = (j0 + 1) * (j0 + 2) * 2 + tri0;   // their row starts
       const float nlam = -a.lambda;
+      __builtin_amdgcn_s_setprio(3);                   // the chain goes first when it shares a SIMD with loader waves
       int bad_t = b;                                   // first pick without a finite gain
       float last_g = -INFINITY;                        // gain of the final pick, the smallest of all
       for (int c0 = 0; c0 < b; c0 += 64) {
@@ -426,6 +460,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         const unsigned long long bad = __ballot(lane < cnt && !(g > -INFINITY));
         if (bad && bad_t == b) bad_t = c0 + __ffsll(static_cast<long long>(bad)) - 1;
       }
+      __builtin_amdgcn_s_setprio(0);
       {
         // Candidates that were left out for lack of room must lie below every pick's gain;
         // otherwise (or when the gains are not finite) the head goes to the full-size kernel.
@@ -484,7 +519,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #ifdef KVR_STATS
     st2 = __builtin_readcyclecounter();
 #endif
-    __syncthreads();
+    lds_barrier();
 #ifdef KVR_STATS
     const long long st3 = __builtin_readcyclecounter();
 #endif
@@ -505,12 +540,13 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       out_store(hprev, tid0, kDenseThreads, first);
     }
 #ifdef KVR_STATS
-    __syncthreads();
+    lds_barrier();
     if ((tid0 == 0 || tid0 == 64) && a.pick_gain && b >= 16) {
       float* o = a.pick_gain + static_cast<long long>(hprev) * b + b - 1 - (tid0 == 64 ? 8 : 0);
       for (int k = 0; k < 5; ++k) o[-k] = static_cast<float>(st_acc[k]) / st_acc[5];
       o[-5] = static_cast<float>(st_acc[6]) / st_acc[5];
       o[-6] = static_cast<float>(rt0 & 0xffffffull);
+      if (tid0 == 64) for (int k = 0; k < 3; ++k) o[-8 - k] = static_cast<float>(lst[k]) / st_acc[5];
       o[-7] = static_cast<float>(__builtin_amdgcn_s_memrealtime() & 0xffffffull);
     }
 #endif
