@@ -125,6 +125,51 @@ __device__ __forceinline__ float half_sum_at_31(float v) {
   return v;
 }
 
+// Cache update for one head: rows il[t], t < b, of K and V go to rows ob + t of the dense
+// outputs, bit for bit, by the nthr threads t0 = 0..nthr-1 (nthr a multiple of 16; 16 threads
+// per row).  BATCH rows per thread are loaded by straight-line code before the first store (row
+// numbers past b are clamped rather than branched around): with branches between them the
+// compiler loses count of what is in flight and waits for everything, acknowledged stores
+// included, before each store.  Indices are clamped into [0, n) so that nothing is read
+// outside the head whatever the scores were.
+template <int BATCH>
+__device__ __forceinline__ void compact_rows(const char* K, const char* V, char* K_out, char* V_out,
+                                             long long head_off_bytes, long long stride_tok,
+                                             const int32_t* il, int n, int b, long long ob, int t0, int nthr) {
+  const int chunk = t0 & 15, g = t0 >> 4, G = nthr >> 4;
+  const long long base = head_off_bytes + chunk * 16;
+  for (int first = 0; first < b; first += BATCH * G) {
+    uint4 kr[BATCH], vr[BATCH];
+    if (K_out && V_out) {
+#pragma unroll
+      for (int k = 0; k < BATCH; ++k) {
+        const int t = min(first + g + k * G, b - 1);
+        const long long src = base + min(max(il[t], 0), n - 1) * stride_tok * 2;
+        kr[k] = *reinterpret_cast<const uint4*>(K + src);
+        vr[k] = *reinterpret_cast<const uint4*>(V + src);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < BATCH; ++k) {
+        const int t = min(first + g + k * G, b - 1);
+        const long long src = base + min(max(il[t], 0), n - 1) * stride_tok * 2;
+        kr[k] = vr[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (K_out) kr[k] = *reinterpret_cast<const uint4*>(K + src);
+        if (V_out) vr[k] = *reinterpret_cast<const uint4*>(V + src);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) {
+      const int t = first + g + k * G;
+      if (t < b) {
+        const long long dst = ((ob + t) * kD + chunk * 8) * 2;
+        if (K_out) *reinterpret_cast<uint4*>(K_out + dst) = kr[k];
+        if (V_out) *reinterpret_cast<uint4*>(V_out + dst) = vr[k];
+      }
+    }
+  }
+}
+
 // One head's [n,128] bf16 rows: coalesced 16-byte loads into registers (rows beyond n read
 // as zero, so MFMA fragments of padded blocks are zero), then into the padded LDS stage.
 template <int NT>

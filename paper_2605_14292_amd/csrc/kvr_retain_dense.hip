@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
           qf[ks] = *reinterpret_cast<bf16x8*>(&w);
         }
       }
-      __syncthreads();
+      lds_barrier();
       constexpr int BPW = (NT + 3) / 4;              // token blocks per wave
       float z[BPW][4];
       const float scale = 0.08838834764831845f;      // 1/sqrt(128)
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
         const float v = half_max_at_31(zmax[r]);
         if ((lane & 31) == 31) red[wave * 8 + hf * 4 + r] = v;
       }
-      __syncthreads();
+      lds_barrier();
       float zsum[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
         const float v = half_sum_at_31(zsum[r]);
         if ((lane & 31) == 31) red[32 + wave * 8 + hf * 4 + r] = v;
       }
-      __syncthreads();
+      lds_barrier();
       const float invG = 1.0f / static_cast<float>(a.G);
       float w[4];
 #pragma unroll
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
           if (j < n && a.s_out) a.s_out[static_cast<long long>(h) * n + j] = p;
         }
       }
-      __syncthreads();                                // K fragments are dead; s_l is complete
+      lds_barrier();                                // K fragments are dead; s_l is complete
     } else {
       if (tid < N32) s_l[tid] = spre;
     }
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     // ------------------------------------------------ Gram -> packed cosines
     if (need_v) {
       store_rows<NT>(stage, tid, vpre);
-      __syncthreads();
+      lds_barrier();
 #ifdef KVR_STATS
       st_a = __builtin_readcyclecounter();
 #endif
@@ -236,12 +236,12 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
           }
         }
       }
-      __syncthreads();                                // staged rows are dead from here on
+      lds_barrier();                                // staged rows are dead from here on
 #ifdef KVR_STATS
       st_b = __builtin_readcyclecounter();
 #endif
       for (int j = tid; j < N32; j += kDenseThreads) rinv[j] = 1.0f / (sqrtf(rinv[j]) + a.eps);
-      __syncthreads();
+      lds_barrier();
       if (working) {
 #pragma unroll
         for (int sl = 0; sl < MAXT; ++sl) {
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
 #ifdef KVR_STATS
     const long long st1 = __builtin_readcyclecounter();
 #endif
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
         off += __popcll(sel);
       }
     }
-    __syncthreads();
+    lds_barrier();
 
 #ifdef KVR_STATS
     const long long st2 = __builtin_readcyclecounter();
@@ -404,23 +404,9 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
       if (a.pick_order) a.pick_order[ob + t] = order_l[t];
       if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
     }
-    if (a.K_out || a.V_out) {
-      const int chunk = tid & 15;
-      for (int t0 = 0; t0 < b; t0 += kDenseThreads / 16) {
-        const int t = t0 + (tid >> 4);
-        if (t < b) {
-          const int it = min(max(idx_l[t], 0), n - 1);   // never read outside the head, whatever the scores were
-          const long long src = head_off + (it * a.stride_tok + chunk * 8) * 2;
-          const long long dst = ((ob + t) * kD + chunk * 8) * 2;
-          uint4 kv, vv;
-          if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
-          if (a.V_out) vv = *reinterpret_cast<const uint4*>(a.V + src);
-          if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kv;
-          if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vv;
-        }
-      }
-    }
-    __syncthreads();                                   // idx_l / s_l are reused by the next head
+    if (a.K_out || a.V_out)
+      compact_rows<4>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idx_l, n, b, ob, tid, kDenseThreads);
+    lds_barrier();                                   // idx_l / s_l are reused by the next head
 #ifdef KVR_STATS
     {
       const long long st3 = __builtin_readcyclecounter();

@@ -565,22 +565,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     if (a.pick_order) a.pick_order[ob + u] = order_l[u];
     if (a.pick_gain) a.pick_gain[ob + u] = gain_l[u];
   }
-  if (a.K_out || a.V_out) {
-    const int chunk = tid & 15;
-    for (int t0 = 0; t0 < b; t0 += NT / 16) {
-      const int u = t0 + (tid >> 4);
-      if (u < b) {
-        const int it = min(max(idxs_l[u], 0), n - 1);
-        const long long src = head_off + (static_cast<long long>(it) * a.stride_tok + chunk * 8) * 2;
-        const long long dst = ((ob + u) * kD + chunk * 8) * 2;
-        uint4 kv, vv;
-        if (a.K_out) kv = *reinterpret_cast<const uint4*>(a.K + src);
-        if (a.V_out) vv = *reinterpret_cast<const uint4*>(a.V + src);
-        if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kv;
-        if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vv;
-      }
-    }
-  }
+  if (a.K_out || a.V_out)
+    compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
 }
 
 bool pool_supported(const Layout& lay, int b) {
