@@ -52,6 +52,9 @@ def cpu_baseline(w, data, b, lam, budget_s=12.0):
 def kernel_name(w, b, lam, has_q):
     """The kernels one kvr_retain call launches for this shape (the roofline
     object prices the whole step against the step's algorithmic bytes)."""
+    if w.dtype == "bf16" and 128 < w.n <= 256 and not has_q and 1 < b <= 128 and lam > 0:
+        return ("kvr::retain_pruned_kernel (the whole step; kvr::retain_dense_kernel follows for the heads "
+                "it marks, a few microseconds when there are none)")
     if w.dtype == "bf16" and w.n <= 256:
         return "kvr::retain_dense_kernel (the whole step is this one launch)"
     if w.dtype == "bf16" and w.n <= 4096 and b <= 256:
