@@ -130,6 +130,46 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
                void* K_out, void* V_out,
                void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Flat-signature mode: Eq. 1 as printed averages V over all layers and heads of
+ * a sequence, u_i = (1/(L*H)) sum_{l,h} V_i^(l,h), v_i = u_i/(||u_i|| + eps);
+ * one selection per sequence from one score vector, and every layer and head
+ * of the sequence keeps the same token set (paper Sec. 4.1, Eq. 1-3; the
+ * limitations paragraph names the per-head signature used by the calls above
+ * as a variant).  In the [heads, n, d] tensors the L*H heads of a sequence are
+ * `group` consecutive heads; heads must be a multiple of group.
+ *
+ * kvr_signature_flat: u_out[q, i, :] = mean over g < group of V[q*group + g, i, :]
+ *   V      device, [heads, n, d] per `lay` (bf16 or fp32)
+ *   u_out  device, dense float32 [heads/group, n, d]
+ * The sum is taken in fp32.  To select on it, call kvr_select_greedy with a
+ * KVR_F32 layout of heads/group dense heads and u_out as V.
+ */
+int kvr_signature_flat(const void* V, const kvr_layout* lay, int group, float* u_out, void* stream);
+
+/*
+ * kvr_compact with one index row per sequence:
+ * K_out[h, t, :] = K[h, idx[h / group, t], :], and the same for V.
+ *   idx  device, int32 [heads/group, b]
+ * Other arguments and rules as in kvr_compact.
+ */
+int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int group,
+                       const int32_t* idx, int b, void* K_out, void* V_out, void* stream);
+
+/*
+ * The whole flat-mode event: signature -> select (one problem per sequence) ->
+ * compaction of every head of the sequence with the shared index set.
+ *   s           device, dense float32 [heads/group, n]: one score vector per sequence
+ *   u_out       device, dense float32 [heads/group, n, d]: receives the signature
+ *               rows (required unless lambda == 0, which reads no V)
+ *   idx_sorted, pick_order, pick_gain   [heads/group, b], as in kvr_select_greedy
+ *   K_out, V_out  device, dense [heads, b, d], dtype of `lay`
+ */
+int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layout* lay, int group,
+                    int b, float lambda, float eps, float* u_out,
+                    int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                    void* K_out, void* V_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -215,3 +215,17 @@ def retain(K, V, k: int, lam: float, eps: float = 1e-6, Q=None, s=None):
     sel = alpha_select(s, V, k, lam, eps)
     sel["s"] = np.asarray(s, dtype=np.float64)
     return sel
+
+
+def retain_flat(K_all, V_all, s, k: int, lam: float, eps: float = 1e-6):
+    """Flat-signature event (Eq. 1 as printed, then Algorithm 1 once per sequence): the
+    signature rows are the mean of V over all L*H heads, one selection from one score vector,
+    and every head keeps the same token set.  K_all, V_all [L*H, n, d]; s [n]."""
+    V_all = np.asarray(V_all, dtype=np.float64)
+    u = V_all.mean(axis=0)                       # Eq. 1 before the normalisation
+    r = alpha_select(s, u, k, lam, eps)          # normalises u inside (Eq. 1), then Eq. 2-3
+    r["u"] = u
+    r["K_out"] = np.stack([compact(Kh, r["sorted"]) for Kh in np.asarray(K_all)])
+    r["V_out"] = np.stack([compact(Vh, r["sorted"]) for Vh in np.asarray(V_all)])
+    return r
+

@@ -19,7 +19,8 @@ KVR_F32, KVR_BF16 = 0, 1
 KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
-           "kvr_select_greedy", "kvr_compact", "kvr_retain")
+           "kvr_select_greedy", "kvr_compact", "kvr_retain",
+           "kvr_signature_flat", "kvr_compact_shared", "kvr_retain_flat")
 
 
 class kvr_layout(ctypes.Structure):
@@ -56,6 +57,12 @@ def _load() -> ctypes.CDLL:
     lib.kvr_retain.restype = i32
     lib.kvr_retain.argtypes = [vp, vp, vp, i32, vp, lp, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp,
                                ctypes.c_size_t, vp]
+    lib.kvr_signature_flat.restype = i32
+    lib.kvr_signature_flat.argtypes = [vp, lp, i32, vp, vp]
+    lib.kvr_compact_shared.restype = i32
+    lib.kvr_compact_shared.argtypes = [vp, vp, lp, i32, vp, i32, vp, vp, vp]
+    lib.kvr_retain_flat.restype = i32
+    lib.kvr_retain_flat.argtypes = [vp, vp, vp, lp, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp]
     return lib
 
 
@@ -184,4 +191,56 @@ def kvr_retain(K, V, b, lam, eps=1e-6, Q=None, s=None, out: RetainBuffers | None
                            _ptr(out.s_out), _ptr(out.idx_sorted), _ptr(out.pick_order),
                            _ptr(out.pick_gain), _ptr(out.K_out), _ptr(out.V_out), None, 0,
                            _stream(stream)), "kvr_retain")
+    return out
+
+
+def kvr_signature_flat(V, group, u_out=None, stream=None):
+    _need_cuda(V, u_out)
+    lay = layout_of(V)
+    if u_out is None:
+        u_out = torch.empty((lay.heads // group, lay.n, lay.d), dtype=torch.float32, device=V.device)
+    _check(_lib.kvr_signature_flat(_ptr(V), ctypes.byref(lay), group, _ptr(u_out), _stream(stream)),
+           "kvr_signature_flat")
+    return u_out
+
+
+def kvr_compact_shared(K, V, idx, group, K_out=None, V_out=None, stream=None):
+    _need_cuda(K, V, idx, K_out, V_out)
+    ref = K if K is not None else V
+    lay = layout_of(ref)
+    b = idx.shape[1]
+    if K is not None and K_out is None:
+        K_out = torch.empty((lay.heads, b, lay.d), dtype=K.dtype, device=K.device)
+    if V is not None and V_out is None:
+        V_out = torch.empty((lay.heads, b, lay.d), dtype=V.dtype, device=V.device)
+    _check(_lib.kvr_compact_shared(_ptr(K), _ptr(V), ctypes.byref(lay), group, _ptr(idx), b,
+                                   _ptr(K_out), _ptr(V_out), _stream(stream)), "kvr_compact_shared")
+    return K_out, V_out
+
+
+class FlatBuffers:
+    """Preallocated outputs of kvr_retain_flat for one shape."""
+
+    def __init__(self, heads, group, n, b, d, dtype, device, want_trace=True):
+        seqs = heads // group
+        self.u_out = torch.empty((seqs, n, d), dtype=torch.float32, device=device)
+        self.idx_sorted = torch.empty((seqs, b), dtype=torch.int32, device=device)
+        self.pick_order = torch.empty((seqs, b), dtype=torch.int32, device=device) if want_trace else None
+        self.pick_gain = torch.empty((seqs, b), dtype=torch.float32, device=device) if want_trace else None
+        self.K_out = torch.empty((heads, b, d), dtype=dtype, device=device)
+        self.V_out = torch.empty((heads, b, d), dtype=dtype, device=device)
+
+
+def kvr_retain_flat(K, V, s, group, b, lam, eps=1e-6, out: FlatBuffers | None = None,
+                    want_trace=True, stream=None):
+    _need_cuda(K, V, s)
+    lay = layout_of(K)
+    if layout_of(V).stride_head != lay.stride_head or layout_of(V).stride_tok != lay.stride_tok:
+        raise ValueError("K and V must share one layout")
+    if out is None:
+        out = FlatBuffers(lay.heads, group, lay.n, b, lay.d, K.dtype, K.device, want_trace)
+    _check(_lib.kvr_retain_flat(_ptr(K), _ptr(V), _ptr(s), ctypes.byref(lay), group, b, lam, eps,
+                                _ptr(out.u_out), _ptr(out.idx_sorted), _ptr(out.pick_order),
+                                _ptr(out.pick_gain), _ptr(out.K_out), _ptr(out.V_out),
+                                _stream(stream)), "kvr_retain_flat")
     return out

@@ -98,6 +98,8 @@ int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay, int 
   } else if (kvr::dense_supported(l, b, 0, false))
     e = kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
                                  pick_order, pick_gain, nullptr, nullptr, st);
+  else if (kvr::dense_f32_supported(l, b))
+    e = kvr::launch_select_dense_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
   else if (kvr::pool_supported(l, b))
     e = kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                 nullptr, nullptr, st);
@@ -168,10 +170,62 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
                                                     pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
-  if (kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) !=
-      hipSuccess)
-    return KVR_ERR_HIP;
+  const hipError_t es = kvr::dense_f32_supported(l, b)
+      ? kvr::launch_select_dense_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st)
+      : kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
+  if (es != hipSuccess) return KVR_ERR_HIP;
   if (kvr::launch_compact(K, V, l, idx_sorted, b, K_out, V_out, st) != hipSuccess)
+    return KVR_ERR_HIP;
+  return KVR_OK;
+}
+
+int kvr_signature_flat(const void* V, const kvr_layout* lay, int group, float* u_out, void* stream) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (!V || !u_out || group < 1 || lay->heads % group != 0) return KVR_ERR_ARG;
+  if (!aligned16(V) || !aligned16(u_out)) return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_signature_flat(V, to_dev(lay), group, u_out, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
+int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int group, const int32_t* idx,
+                       int b, void* K_out, void* V_out, void* stream) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (b < 1 || b > lay->n || !idx || group < 1 || lay->heads % group != 0) return KVR_ERR_ARG;
+  if ((K == nullptr) != (K_out == nullptr) || (V == nullptr) != (V_out == nullptr)) return KVR_ERR_ARG;
+  if (!K && !V) return KVR_ERR_ARG;
+  if ((K && (!aligned16(K) || !aligned16(K_out))) || (V && (!aligned16(V) || !aligned16(V_out))))
+    return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_compact(K, V, to_dev(lay), idx, b, K_out, V_out,
+                                           static_cast<hipStream_t>(stream), group);
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
+int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layout* lay, int group, int b,
+                    float lambda, float eps, float* u_out, int32_t* idx_sorted, int32_t* pick_order,
+                    float* pick_gain, void* K_out, void* V_out, void* stream) {
+  const int rc = check_select(lay, b, lambda, eps);
+  if (rc) return rc;
+  if (!K || !V || !s || !idx_sorted || !K_out || !V_out) return KVR_ERR_ARG;
+  if (group < 1 || lay->heads % group != 0) return KVR_ERR_ARG;
+  if (lambda != 0.0f && !u_out) return KVR_ERR_ARG;    // the signature rows need somewhere to live
+  if (!aligned16(K) || !aligned16(V) || !aligned16(s) || !aligned16(K_out) || !aligned16(V_out) ||
+      (u_out && !aligned16(u_out)))
+    return KVR_ERR_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const kvr::Layout l = to_dev(lay);
+  kvr::Layout lu = l;                                   // the per-sequence problems: fp32 rows, dense
+  lu.heads = l.heads / group; lu.dtype = KVR_F32;
+  lu.stride_tok = l.d; lu.stride_head = static_cast<long long>(l.n) * l.d;
+  if (lambda != 0.0f && b > 1 &&
+      kvr::launch_signature_flat(V, l, group, u_out, st) != hipSuccess)
+    return KVR_ERR_HIP;
+  const hipError_t es = kvr::dense_f32_supported(lu, b)
+      ? kvr::launch_select_dense_f32(u_out, s, lu, b, lambda, eps, idx_sorted, pick_order, pick_gain, st)
+      : kvr::launch_select_generic(u_out, s, lu, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
+  if (es != hipSuccess) return KVR_ERR_HIP;
+  if (kvr::launch_compact(K, V, l, idx_sorted, b, K_out, V_out, st, group) != hipSuccess)
     return KVR_ERR_HIP;
   return KVR_OK;
 }

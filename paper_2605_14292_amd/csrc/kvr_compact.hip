@@ -11,12 +11,13 @@ constexpr int kCompactThreads = 256;
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const char* __restrict__ K, const char* __restrict__ V, Layout lay, int ebytes,
-    const int32_t* __restrict__ idx, int b, char* __restrict__ K_out, char* __restrict__ V_out) {
+    const int32_t* __restrict__ idx, int idx_group, int b, char* __restrict__ K_out,
+    char* __restrict__ V_out) {
   const int h = blockIdx.x;
   const int c = threadIdx.x & 15;
   const int t = blockIdx.y * (kCompactThreads / 16) + (threadIdx.x >> 4);
   if (t >= b) return;
-  int i = idx[static_cast<long long>(h) * b + t];
+  int i = idx[static_cast<long long>(h / idx_group) * b + t];   // idx_group heads share one index row
   i = min(max(i, 0), lay.n - 1);
   const int row_bytes = lay.d * ebytes;
   const long long src = (h * lay.stride_head + i * lay.stride_tok) * ebytes;
@@ -28,11 +29,11 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
 }
 
 hipError_t launch_compact(const void* K, const void* V, const Layout& lay, const int32_t* idx,
-                          int b, void* K_out, void* V_out, hipStream_t st) {
+                          int b, void* K_out, void* V_out, hipStream_t st, int idx_group) {
   const int ebytes = lay.dtype == DT_BF16 ? 2 : 4;
   dim3 grid(lay.heads, (b + kCompactThreads / 16 - 1) / (kCompactThreads / 16));
   hipLaunchKernelGGL(compact_kernel, grid, dim3(kCompactThreads), 0, st,
-                     static_cast<const char*>(K), static_cast<const char*>(V), lay, ebytes, idx, b,
+                     static_cast<const char*>(K), static_cast<const char*>(V), lay, ebytes, idx, idx_group, b,
                      static_cast<char*>(K_out), static_cast<char*>(V_out));
   return hipGetLastError();
 }

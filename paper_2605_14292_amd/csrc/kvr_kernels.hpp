@@ -15,8 +15,18 @@ hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay,
 hipError_t launch_select_generic(const void* V, const float* s, const Layout& lay, int b,
                                  float lambda, float eps, int32_t* idx_sorted,
                                  int32_t* pick_order, float* pick_gain, hipStream_t st);
+// idx_group consecutive heads share one row of idx (1: every head has its own).
 hipError_t launch_compact(const void* K, const void* V, const Layout& lay, const int32_t* idx,
-                          int b, void* K_out, void* V_out, hipStream_t st);
+                          int b, void* K_out, void* V_out, hipStream_t st, int idx_group = 1);
+
+// Mean of V over each run of `group` consecutive heads: u_out is dense fp32 [heads/group, n, d].
+hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, float* u_out, hipStream_t st);
+
+// Selection for heads with fp32 rows and n <= 256 (no compaction).
+bool dense_f32_supported(const Layout& lay, int b);
+hipError_t launch_select_dense_f32(const void* V, const float* s, const Layout& lay, int b, float lambda,
+                                   float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                                   hipStream_t st);
 
 // Fused path for bf16 heads with n <= 256 (any of K/Q/K_out/V_out may be null
 // to skip scoring or compaction).

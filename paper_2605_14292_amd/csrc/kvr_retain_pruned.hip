@@ -44,49 +44,6 @@ constexpr int pruned_smem_bytes() {
   return pruned_region_a() + 2 * kPrN * 4 * 2 + kPrN * 4 + 2 * kPrN * 4 * 3 + 64;
 }
 
-// Scales one 32x32 tile of raw dot products to cosines and writes it into the packed
-// triangle (element (i,j), j <= i, at i(i+1)/2 + j).  The diagonal entry holds +inf: reading
-// the row of a pick drives the pick's own m to +inf and its gain to -inf, which is how a
-// selected token leaves the race.
-__device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, const f32x16& acc,
-                                               int I, int J, int lane) {
-  const int hf = lane >> 5;
-  const int j = J * 32 + (lane & 31);
-  const float rc = rinv[j];
-  int i = I * 32 + hf * 4;                            // first of this lane's rows in the tile
-  int off = i * (i + 1) / 2 + j;
-  if (I != J) {                                       // two code paths: no per-element predicate off the diagonal
-#pragma unroll
-    for (int R = 0; R < 4; ++R) {
-      const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
-      const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-      int o = off;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        tri[o] = acc[R * 4 + q] * rrow[q] * rc;
-        o += i + q + 1;
-      }
-      off += 8 * i + 36;                              // T(i+8) - T(i)
-      i += 8;
-    }
-  } else {
-#pragma unroll
-    for (int R = 0; R < 4; ++R) {
-      const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
-      const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-      int o = off;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float c = j == i + q ? INFINITY : acc[R * 4 + q] * rrow[q] * rc;
-        if (j <= i + q) tri[o] = c;
-        o += i + q + 1;
-      }
-      off += 8 * i + 36;
-      i += 8;
-    }
-  }
-}
-
 __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedArgs a) {
   extern __shared__ __align__(16) char smem[];
   char* stage = smem;                                 // gathered rows ...

@@ -86,3 +86,20 @@ def test_binding_refuses_cpu_tensors():
     s = torch.zeros((1, 8))
     with pytest.raises(ValueError):
         B.kvr_select_greedy(V, s, 2, 0.5)
+
+
+def test_flat_mode_argument_errors_are_host_side():
+    L = B.lib()
+    fake = ctypes.c_void_p(0x1000)
+    lay = _lay(heads=6)
+    assert L.kvr_signature_flat(fake, ctypes.byref(lay), 4, fake, None) == B.KVR_ERR_ARG      # 6 % 4 != 0
+    assert L.kvr_signature_flat(fake, ctypes.byref(lay), 0, fake, None) == B.KVR_ERR_ARG
+    assert L.kvr_signature_flat(None, ctypes.byref(lay), 3, fake, None) == B.KVR_ERR_ARG
+    assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 4, fake, 8, fake, fake, None) == B.KVR_ERR_ARG
+    assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 3, None, 8, fake, fake, None) == B.KVR_ERR_ARG
+    rf = L.kvr_retain_flat
+    assert rf(fake, fake, fake, ctypes.byref(lay), 3, 8, 0.5, 1e-6, None, fake, None, None, fake, fake, None) == B.KVR_ERR_ARG
+    assert rf(fake, fake, fake, ctypes.byref(lay), 4, 8, 0.5, 1e-6, fake, fake, None, None, fake, fake, None) == B.KVR_ERR_ARG
+    assert rf(fake, fake, fake, ctypes.byref(lay), 3, 65, 0.5, 1e-6, fake, fake, None, None, fake, fake, None) == B.KVR_ERR_ARG
+    assert rf(fake, fake, None, ctypes.byref(lay), 3, 8, 0.5, 1e-6, fake, fake, None, None, fake, fake, None) == B.KVR_ERR_ARG
+

@@ -249,3 +249,50 @@ def test_runs_are_deterministic_and_stream_independent():
     st.synchronize()
     for f in ("idx_sorted", "pick_order", "pick_gain", "K_out", "V_out", "s_out"):
         assert torch.equal(getattr(a, f), getattr(b2, f)), f
+
+
+# ---------------------------------------------------------------- flat-signature mode
+def _flat_case(seqs, group, n, seed, dtype):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    heads = seqs * group
+    # heads of a sequence share a token geometry (cluster centres per token) plus head noise, so
+    # that the mean over heads keeps a structure worth penalising
+    base = torch.randn((seqs, 1, 12, 128), generator=g)[:, :, torch.randint(0, 12, (n,), generator=g)]
+    V = (base + 0.5 * torch.randn((seqs, group, n, 128), generator=g)).reshape(heads, n, 128).to(dtype)
+    K = torch.randn((heads, n, 128), generator=g).to(dtype)
+    s = torch.randn((seqs, n), generator=g).exp()
+    return K.to(DEV), V.to(DEV), s.to(DEV)
+
+
+@pytest.mark.parametrize("seqs,group,n,b,lam,dtype", [
+    (3, 8, 192, 64, 0.5, torch.bfloat16), (2, 32, 77, 30, 0.3, torch.bfloat16),
+    (2, 5, 256, 128, 1.0, torch.bfloat16), (2, 4, 300, 40, 0.5, torch.bfloat16),
+    (2, 6, 130, 20, 0.5, torch.float32), (2, 3, 64, 64, 0.0, torch.bfloat16)])
+def test_flat_signature_mode(seqs, group, n, b, lam, dtype):
+    K, V, s = _flat_case(seqs, group, n, 9000 + n + group, dtype)
+    out = B().kvr_retain_flat(K, V, s, group, b, lam, 1e-6)
+    torch.cuda.synchronize()
+    V64 = W.to_f64(V).reshape(seqs, group, n, 128)
+    Kb, Vb = _bits(K).reshape(seqs, group, n, -1), _bits(V).reshape(seqs, group, n, -1)
+    for q in range(seqs):
+        u64 = V64[q].mean(axis=0)
+        if lam != 0.0:
+            np.testing.assert_allclose(out.u_out[q].cpu().numpy(), u64, rtol=0, atol=2e-6 * np.abs(V64[q]).max())
+        s64 = W.to_f64(s[q])
+        idx = out.idx_sorted[q].cpu().numpy()
+        P.check_head(s64, u64, b, lam, 1e-6, out.pick_order[q].cpu().numpy(), out.pick_gain[q].cpu().numpy(), idx)
+        for g in range(group):
+            h = q * group + g
+            np.testing.assert_array_equal(_bits(out.K_out[h]), O.compact(Kb[q, g], idx))
+            np.testing.assert_array_equal(_bits(out.V_out[h]), O.compact(Vb[q, g], idx))
+    # the three steps called one by one give the same result
+    if lam != 0.0:
+        u = B().kvr_signature_flat(V, group)
+        assert torch.equal(u, out.u_out)
+        lay = B().layout_of(u)
+        sel = B().kvr_select_greedy(u, s, b, lam, 1e-6, lay=lay)
+        assert torch.equal(sel[0], out.idx_sorted) and torch.equal(sel[1], out.pick_order)
+    Ko, Vo = B().kvr_compact_shared(K, V, out.idx_sorted, group)
+    torch.cuda.synchronize()
+    assert torch.equal(Ko, out.K_out) and torch.equal(Vo, out.V_out)
+

@@ -248,3 +248,49 @@ def test_pins_catch_planted_mistakes(monkeypatch):
         return order
 
     assert no_floor(g["s"], V, g["k"], g["lambda"], 0.0) != g["order"]
+
+
+# ---------------------------------------------------------------- flat-signature mode (Eq. 1 over L*H)
+def test_flat_mode_with_one_head_is_the_per_head_selection():
+    rng = _rng(21)
+    V = rng.normal(size=(1, 30, 8)); K = rng.normal(size=(1, 30, 8)); s = rng.random(30)
+    f = O.retain_flat(K, V, s, 9, 0.6)
+    r = O.alpha_select(s, V[0], 9, 0.6)
+    assert f["order"].tolist() == r["order"].tolist()
+    np.testing.assert_array_equal(f["K_out"][0], K[0][r["sorted"]])
+
+
+def test_flat_mode_reproduces_the_hand_case_from_two_heads():
+    # two heads whose mean is the hand case's V: V +/- D averages to V exactly
+    g = json.load(open(os.path.join(GOLD, "hand_case.json")))
+    V = np.array(g["V"])
+    D = _rng(3).integers(-4, 5, size=V.shape).astype(np.float64)
+    f = O.retain_flat(np.zeros((2,) + V.shape), np.stack([V + D, V - D]), g["s"], g["k"], g["lambda"], g["eps"])
+    assert f["order"].tolist() == g["order"]
+    np.testing.assert_allclose(f["gain"], g["gain"], rtol=0, atol=1e-12)
+
+
+def test_flat_mode_cancelling_heads_give_plain_topk():
+    # V and -V average to zero rows: zero signatures, no penalty, Eq. 3 is top-k of s
+    rng = _rng(22)
+    V = rng.normal(size=(20, 6)); s = rng.random(20)
+    f = O.retain_flat(np.zeros((2, 20, 6)), np.stack([V, -V]), s, 7, 0.9)
+    assert f["order"].tolist() == O.topk_order(s, 7).tolist()
+    np.testing.assert_allclose(f["gain"], np.sort(s)[::-1][:7], rtol=0, atol=0)
+
+
+def test_flat_mode_ignores_head_order_and_common_scale_and_shares_the_index_set():
+    rng = _rng(23)
+    V = rng.normal(size=(4, 25, 8)); K = rng.normal(size=(4, 25, 8)); s = rng.random(25)
+    f = O.retain_flat(K, V, s, 10, 0.5)
+    p = [2, 0, 3, 1]
+    assert O.retain_flat(K[p], V[p], s, 10, 0.5)["order"].tolist() == f["order"].tolist()
+    assert O.retain_flat(K, 8.0 * V, s, 10, 0.5, eps=0.0)["order"].tolist() == \
+        O.retain_flat(K, V, s, 10, 0.5, eps=0.0)["order"].tolist()
+    for h in range(4):
+        np.testing.assert_array_equal(f["K_out"][h], K[h][f["sorted"]])
+        np.testing.assert_array_equal(f["V_out"][h], V[h][f["sorted"]])
+    # the mean, not the sum of per-head signatures: a head with huge rows dominates u
+    big = V.copy(); big[0] *= 1e6
+    assert O.retain_flat(K, big, s, 10, 0.5)["order"].tolist() == O.alpha_select(s, big[0], 10, 0.5)["order"].tolist()
+
