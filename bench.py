@@ -49,6 +49,30 @@ def cpu_baseline(w, data, b, lam, budget_s=12.0):
                       "rate extrapolates linearly over heads)"}
 
 
+def cpu_baseline_flat(w, data, s, group, b, lam, budget_s=12.0):
+    """The fp64 oracle's flat-mode event on a bounded sample of sequences."""
+    from oracle import alpha_oracle as O
+    from paper_2605_14292_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    done, t_used = 0, 0.0
+    for q in range(w.seqs):
+        sl = slice(q * group, (q + 1) * group)
+        K64, V64, s64 = W.to_f64(data["K"][sl]), W.to_f64(data["V"][sl]), W.to_f64(s[q])
+        t0 = time.perf_counter()
+        O.retain_flat(K64, V64, s64, b, lam, 1e-6)
+        t_used += time.perf_counter() - t0
+        done += 1
+        if t_used >= budget_s:
+            break
+    return {"value": done * group / t_used, "unit": "head-events/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {w.seqs} sequences ({group} heads each) of {w.name}, flat-signature mode "
+                      f"(fp64 numpy oracle, {t_used:.1f} s, rate extrapolates linearly over sequences)"}
+
+
 def kernel_name(w, b, lam, has_q):
     """The kernels one kvr_retain call launches for this shape (the roofline
     object prices the whole step against the step's algorithmic bytes)."""
@@ -75,6 +99,10 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--b", type=int, default=None)
     ap.add_argument("--lam", type=float, default=None)
+    ap.add_argument("--flat", action="store_true",
+                    help="flat-signature mode (Eq. 1 over all layers and heads of a sequence): one "
+                         "selection per sequence, every head keeps the same tokens; needs a workload "
+                         "with given scores (c3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -104,11 +132,21 @@ def main():
     b = w.b if args.b is None else args.b
     lam = w.lam if args.lam is None else args.lam
     data = W.generate(w, seed=args.seed, device=dev)
-    out = B.RetainBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, "Q" in data, want_trace=False)
     Q, s = data.get("Q"), data.get("s")
+    group = w.layers * w.kv_heads
+    if args.flat:
+        if s is None:
+            sys.exit("bench.py: --flat needs a workload whose scores are given (c3)")
+        s = s.view(w.seqs, group, w.n)[:, 0].contiguous()     # one score vector per sequence
+        out = B.FlatBuffers(w.heads, group, w.n, b, w.d, w.torch_dtype, dev, want_trace=False)
 
-    def step():
-        B.kvr_retain(data["K"], data["V"], b, lam, 1e-6, Q=Q, s=s, out=out)
+        def step():
+            B.kvr_retain_flat(data["K"], data["V"], s, group, b, lam, 1e-6, out=out)
+    else:
+        out = B.RetainBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, "Q" in data, want_trace=False)
+
+        def step():
+            B.kvr_retain(data["K"], data["V"], b, lam, 1e-6, Q=Q, s=s, out=out)
 
     for _ in range(args.warmup):
         step()
@@ -127,11 +165,13 @@ def main():
     dev_avg_ms = sum(dev_ms) / len(dev_ms)
 
     bytes_step = w.algorithmic_bytes_per_head(b, lam) * w.heads
+    if args.flat:       # scores and indices are per sequence, not per head
+        bytes_step -= (4 * w.n + 4 * b) * (w.heads - w.seqs)
     achieved = bytes_step / (dev_avg_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"{w.name}:b{b}:lam{lam}")
+        traffic = json.load(open(tpath)).get(f"{w.name}{'flat' if args.flat else ''}:b{b}:lam{lam}")
     line = {
         "metric": "retention events/sec (heads*events)",
         "value": w.heads / (wall / args.steps),
@@ -140,16 +180,18 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.what}", "heads": w.heads, "n": w.n, "b": b,
+        "config": {"workload": f"{w.name}: {w.what}" + (", flat-signature mode (one selection per sequence)"
+                                                        if args.flat else ""), "heads": w.heads, "n": w.n, "b": b,
                    "d": w.d, "lambda": lam, "scores": w.scores, "G": w.G if w.scores == "computed" else 0},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": kernel_name(w, b, lam, Q is not None), "device_ms_avg": dev_avg_ms,
+                     "kernel": ("kvr::signature_flat_kernel + kvr::select_dense_f32_kernel + kvr::compact_kernel (whole step)"
+                                if args.flat else kernel_name(w, b, lam, Q is not None)), "device_ms_avg": dev_avg_ms,
                      "device_ms_median": dev_ms[len(dev_ms) // 2],
                      "algorithmic_bytes_per_step": bytes_step},
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w, data, b, lam)
+        line["cpu_baseline"] = cpu_baseline_flat(w, data, s, group, b, lam) if args.flat else cpu_baseline(w, data, b, lam)
     print(json.dumps(line), flush=True)
 
 

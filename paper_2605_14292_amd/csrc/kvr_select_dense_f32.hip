@@ -1,6 +1,7 @@
 // Algorithm 1 (paper Sec. 4.1, Eq. 1-3) for heads of n <= 256 tokens whose rows are fp32: the
 // flat-signature mode, whose signature rows are means over layers and heads and so are not
-// bf16 numbers, and fp32 caches.  One workgroup (four wave64s) per head:
+// bf16 numbers, and fp32 caches.  One workgroup of sixteen wave64s per head (such launches have
+// few heads, so the latency of one head is what counts):
 //
 //   rows     staged in LDS as fp32, 129-float pitch (column reads of 32 rows hit 32 banks)
 //   Gram     lower-triangular 32x32 tiles on the fp32 MFMA (32x32x2, fp32 products and sums)
@@ -16,6 +17,8 @@ namespace kvr {
 
 constexpr int kF32Pitch = 129;                 // floats per staged row
 constexpr int kF32MaxB = 256;
+constexpr int kF32Threads = 1024;
+constexpr int kF32Waves = kF32Threads / 64;
 
 __host__ __device__ constexpr int f32_region_a(int NT) {
   const int tri = dense_tri_floats(NT) * 4, stage = NT * 32 * kF32Pitch * 4;
@@ -35,11 +38,11 @@ struct F32Args {
 };
 
 template <int NT>
-__global__ __launch_bounds__(kDenseThreads, 1) void select_dense_f32_kernel(F32Args a) {
+__global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Args a) {
   constexpr int N32 = NT * 32;
   constexpr int NQ = NT / 2;
   constexpr int NTILES = NT * (NT + 1) / 2;
-  constexpr int MAXT = (NTILES + 3) / 4;
+  constexpr int MAXT = (NTILES + kF32Waves - 1) / kF32Waves;
   extern __shared__ __align__(16) char smem[];
   float* stage = reinterpret_cast<float*>(smem);
   float* tri = reinterpret_cast<float*>(smem);
@@ -62,7 +65,7 @@ __global__ __launch_bounds__(kDenseThreads, 1) void select_dense_f32_kernel(F32A
   if (diverse) {
     // rows -> LDS, 32 threads per row (float4 each), rows past n read as zero
     const float* Vh = a.V + h * a.stride_head;
-    for (int r = tid >> 5; r < N32; r += kDenseThreads / 32) {
+    for (int r = tid >> 5; r < N32; r += kF32Threads / 32) {
       float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
       if (r < n) x = *reinterpret_cast<const float4*>(Vh + r * a.stride_tok + (tid & 31) * 4);
       float* d = stage + r * kF32Pitch + (tid & 31) * 4;
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(kDenseThreads, 1) void select_dense_f32_kernel(F32A
     // tile t of the lower triangle: row block I, column block J <= I
 #pragma unroll
     for (int sl = 0; sl < MAXT; ++sl) {
-      const int tile = wave + 4 * sl;
+      const int tile = wave + kF32Waves * sl;
       acc[sl] = f32x16_t{0};
       if (tile < NTILES) {
         int I = 0;
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(kDenseThreads, 1) void select_dense_f32_kernel(F32A
     __syncthreads();
 #pragma unroll
     for (int sl = 0; sl < MAXT; ++sl) {
-      const int tile = wave + 4 * sl;
+      const int tile = wave + kF32Waves * sl;
       if (tile < NTILES) {
         int I = 0;
         while ((I + 1) * (I + 2) / 2 <= tile) ++I;
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(kDenseThreads, 1) void select_dense_f32_kernel(F32A
   }
   __syncthreads();
   const long long ob = static_cast<long long>(h) * b;
-  for (int t = tid; t < b; t += kDenseThreads) {
+  for (int t = tid; t < b; t += kF32Threads) {
     a.idx_sorted[ob + t] = idx_l[t];
     if (a.pick_order) a.pick_order[ob + t] = order_l[t];
     if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
@@ -221,7 +224,7 @@ hipError_t launch_select_dense_f32(const void* V, const float* s, const Layout& 
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(lay.heads), dim3(kDenseThreads), smem, st, a);
+    hipLaunchKernelGGL(kern, dim3(lay.heads), dim3(kF32Threads), smem, st, a);
     return hipGetLastError();
   };
   if (lay.n <= 64) return go(&select_dense_f32_kernel<2>, f32_smem_bytes(2));

@@ -3,16 +3,17 @@
 // selection kernel, which takes u as its rows).  The L*H heads of a sequence are `group`
 // consecutive heads of the [heads, n, d] tensor.
 //
-// HBM-bound streaming reduction: a workgroup owns four tokens of one sequence; its 256 threads
-// are 4 tokens x 16 column chunks (eight elements each) x 4 slices of the group, every thread
-// sums its slice in fp32 with eight loads in flight, the four slices meet in LDS.
+// HBM-bound streaming reduction: a workgroup owns eight tokens of one sequence (2 KB contiguous
+// per head); its 512 threads are 8 tokens x 16 column chunks (eight elements each) x 4 slices of
+// the group, every thread sums its slice in fp32 with sixteen loads in flight, the four slices
+// meet in LDS.
 #include "kvr_device.hpp"
 #include "kvr_kernels.hpp"
 
 namespace kvr {
 
-constexpr int kSigThreads = 256;
-constexpr int kSigTok = 4;                     // tokens per workgroup
+constexpr int kSigThreads = 512;
+constexpr int kSigTok = 8;                     // tokens per workgroup
 constexpr int kSigSlices = 4;                  // slices of the group per token
 
 template <int DT>
@@ -21,7 +22,7 @@ __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char*
   __shared__ float part[kSigSlices][kSigTok * 16][8];
   const int seq = blockIdx.y;
   const int tid = threadIdx.x;
-  const int chunk = tid & 15, tk = (tid >> 4) & (kSigTok - 1), slice = tid >> 6;
+  const int chunk = tid & 15, tk = (tid >> 4) & (kSigTok - 1), slice = tid / (kSigTok * 16);
   const int tok = blockIdx.x * kSigTok + tk;
   constexpr int eb = DT == DT_BF16 ? 2 : 4;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -29,17 +30,30 @@ __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char*
     const char* p = V + ((static_cast<long long>(seq) * group) * lay.stride_head +
                          static_cast<long long>(tok) * lay.stride_tok + chunk * 8) * eb;
     const long long hstep = lay.stride_head * eb;
-    int g = slice;
-    for (; g + 7 * kSigSlices < group; g += 8 * kSigSlices) {
-      float x[8][8];
+    // slice k sums heads [k*per, (k+1)*per): neighbouring loads of a thread are one head apart
+    const int per = (group + kSigSlices - 1) / kSigSlices;
+    int g = slice * per;
+    const int gend = min(group, g + per);
+    for (; g + 15 < gend; g += 16) {
+      uint4 w[16];                                // sixteen loads in flight per thread
 #pragma unroll
-      for (int u = 0; u < 8; ++u) load8<DT>(p + (g + u * kSigSlices) * hstep, x[u]);
+      for (int u = 0; u < 16; ++u) {
+        if constexpr (DT == DT_BF16) w[u] = *reinterpret_cast<const uint4*>(p + (g + u) * hstep);
+      }
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < 16; ++u) {
+        float x[8];
+        if constexpr (DT == DT_BF16) {
+          x[0] = bf16_lo(w[u].x); x[1] = bf16_hi(w[u].x); x[2] = bf16_lo(w[u].y); x[3] = bf16_hi(w[u].y);
+          x[4] = bf16_lo(w[u].z); x[5] = bf16_hi(w[u].z); x[6] = bf16_lo(w[u].w); x[7] = bf16_hi(w[u].w);
+        } else {
+          load8<DT>(p + (g + u) * hstep, x);
+        }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += x[u][e];
+        for (int e = 0; e < 8; ++e) acc[e] += x[e];
+      }
     }
-    for (; g < group; g += kSigSlices) {
+    for (; g < gend; ++g) {
       float x[8];
       load8<DT>(p + g * hstep, x);
 #pragma unroll
@@ -47,7 +61,7 @@ __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char*
     }
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) part[slice][tid & 63][e] = acc[e];
+  for (int e = 0; e < 8; ++e) part[slice][tid % (kSigTok * 16)][e] = acc[e];
   __syncthreads();
   if (slice == 0 && tok < lay.n) {
     const float inv = 1.0f / static_cast<float>(group);
