@@ -124,7 +124,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       if (eq) i_w = base + 64 * k + (__ffsll(static_cast<long long>(eq)) - 1);
     }
     if (lane == 0) { slot_gain[par * 16 + w] = amax_w; slot_idx[par * 16 + w] = i_w; }
-    __syncthreads();
+    lds_barrier();
     const float g = lane < W ? slot_gain[par * 16 + lane] : -INFINITY;
     const int ii = lane < W ? slot_idx[par * 16 + lane] : -1;
     par ^= 1;
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     for (int k = 0; k < S; ++k) key[k] = tok[k] < n ? ordered_key(s[k] + 0.0f) : 0u;   // -0 counts as +0
     auto wg_count = [&](int c_w) -> int {
       if (lane == 0) cnt_l[par * 16 + w] = c_w;
-      __syncthreads();
+      lds_barrier();
       int c = 0;
 #pragma unroll
       for (int u = 0; u < W; ++u) c += cnt_l[par * 16 + u];
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     }
     // per-wave prefixes: selected-before (for the ascending index list) and equal-before (ties in token order)
     if (lane == 0) { cnt_l[par * 16 + w] = above_w; wcount[w] = equal_w; }
-    __syncthreads();
+    lds_barrier();
     int above_all = 0, above_before = 0, equal_before = 0;
 #pragma unroll
     for (int u = 0; u < W; ++u) {
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       pos += __popcll(inm);
       eq_seen += __popcll(eqm);
     }
-    __syncthreads();
+    lds_barrier();
     // rank of each selected token in (score descending, index ascending) order
     for (int e = tid; e < b; e += NT) {
       const uint32_t ke = sel_key[e];
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           if (c16 == 0) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
         }
       }
-      __syncthreads();
+      lds_barrier();
 #pragma unroll
       for (int k = 0; k < S; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
     }
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         if (tk >= 0) x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(tk) * a.stride_tok + (tid & 15) * 8) * 2);
         *reinterpret_cast<uint4*>(prow + p * kPoolPitch + (tid & 15) * 16) = x;
       }
-      __syncthreads();
+      lds_barrier();
       {
         const int hf = lane >> 5;
         for (int tile = w; tile < 10; tile += W) {   // lower-triangular 32x32 tiles of the 128 x 128 matrix
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           }
         }
       }
-      __syncthreads();
+      lds_barrier();
 #ifdef KVR_STATS
       const long long c2 = __builtin_readcyclecounter();
 #endif
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         t += np;
         if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
       }
-      __syncthreads();
+      lds_barrier();
 #ifdef KVR_STATS
       const long long c3 = __builtin_readcyclecounter();
       st[0] += c1 - c0; st[1] += c2 - c1; st[2] += c3 - c2; st[4] += 1;
@@ -422,7 +422,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         break;
       }
       if (np == 0) { starved = true; break; }        // cannot happen on finite input: the best token is in the pool
-      __syncthreads();                               // everyone is done with the triangle (the stages alias it)
+      lds_barrier();                               // everyone is done with the triangle (the stages alias it)
       // ================= 4. one pass over V: the epoch's picks against every outside token =================
       if (np > 0) {
         const int kg = lane >> 4;
@@ -507,13 +507,13 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       }
 #pragma unroll
       for (int k = 0; k < S; ++k) pslot[k] = -1;
-      __syncthreads();                               // stages are dead: the next epoch reuses the area
+      lds_barrier();                               // stages are dead: the next epoch reuses the area
 #ifdef KVR_STATS
       st[3] += __builtin_readcyclecounter() - c3;
 #endif
     }
 #ifdef KVR_STATS
-    __syncthreads();
+    lds_barrier();
     if (tid == 0 && b >= 8) {
       for (int q = 0; q < 5; ++q) gain_l[b - 1 - q] = static_cast<float>(st[q]);
     }
@@ -521,12 +521,12 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   }
 
   // ---- sort(S): flag the picked tokens, ascending indices by prefix counts
-  __syncthreads();
+  lds_barrier();
 #pragma unroll
   for (int k = 0; k < S; ++k) flag[base + 64 * k + lane] = 0;
-  __syncthreads();
+  lds_barrier();
   for (int u = tid; u < t; u += NT) flag[order_l[u]] = 1;
-  __syncthreads();
+  lds_barrier();
   if (starved) {
     if (tid == 0) {                                  // non-finite input only: lowest unpicked tokens fill up
       int j = 0;
@@ -535,7 +535,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         order_l[u] = j; gain_l[u] = -INFINITY; flag[j] = 1;
       }
     }
-    __syncthreads();
+    lds_barrier();
   }
   {
     unsigned long long sel[S];
@@ -546,7 +546,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       cnt += __popcll(sel[k]);
     }
     if (lane == 0) wcount[w] = cnt;
-    __syncthreads();
+    lds_barrier();
     int off = 0;
     for (int u = 0; u < w; ++u) off += wcount[u];
 #pragma unroll
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       off += __popcll(sel[k]);
     }
   }
-  __syncthreads();
+  lds_barrier();
   const long long ob = static_cast<long long>(h) * b;
   for (int u = tid; u < b; u += NT) {
     a.idx_sorted[ob + u] = idxs_l[u];

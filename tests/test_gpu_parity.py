@@ -296,3 +296,71 @@ def test_flat_signature_mode(seqs, group, n, b, lam, dtype):
     torch.cuda.synchronize()
     assert torch.equal(Ko, out.K_out) and torch.equal(Vo, out.V_out)
 
+
+@pytest.mark.parametrize("n,b,dtype", [(192, 64, torch.bfloat16), (100, 40, torch.bfloat16), (256, 128, torch.bfloat16),
+                                       (150, 50, torch.float32)])
+def test_non_finite_scores_still_give_distinct_indices_in_range(n, b, dtype):
+    # unspecified picks, but never an index outside [0, n), never a duplicate, and finite heads
+    # of the same launch are untouched (short heads only: these kernels run a fixed number of steps)
+    h = 6
+    K, V, s = _mk(h, n, 4242 + n, dtype)
+    s = s.clone()
+    s[0, ::3] = float("nan")
+    s[1, :] = float("-inf")
+    s[2, 5] = float("inf"); s[2, 7] = float("inf")
+    s[3, : n - b // 2] = float("nan")            # fewer finite scores than the budget
+    V = V.clone()
+    V[4, 3] = 0                                  # a zero row: zero signature, never penalised
+    out = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s)
+    torch.cuda.synchronize()
+    idx = out.idx_sorted.cpu().numpy()
+    order = out.pick_order.cpu().numpy()
+    for hh in range(h):
+        assert idx[hh].min() >= 0 and idx[hh].max() < n
+        assert len(set(idx[hh].tolist())) == b and np.all(np.diff(idx[hh]) > 0)
+        assert sorted(order[hh].tolist()) == idx[hh].tolist()
+    data = {"K": K, "V": V, "s": s}
+    _check_heads(W.WORKLOADS["c3"], data, out, b, 0.5, 1e-6, [4, 5])
+    assert order[2][0] == 5 and order[2][1] == 7          # +inf scores go first, lowest index first
+
+
+def test_flat_mode_is_deterministic_and_group_one_is_the_per_head_selection():
+    K, V, s = _flat_case(4, 1, 160, 77, torch.bfloat16)
+    a = B().kvr_retain_flat(K, V, s, 1, 50, 0.5, 1e-6)
+    c = B().kvr_retain_flat(K, V, s, 1, 50, 0.5, 1e-6)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx_sorted, c.idx_sorted) and torch.equal(a.pick_gain, c.pick_gain)
+    assert torch.equal(a.u_out, V.float())                  # the mean of one head is the head
+    data = {"K": K, "V": V, "s": s}
+    per_head = B().kvr_retain(K, V, 50, 0.5, 1e-6, s=s)
+    torch.cuda.synchronize()
+    _check_heads(W.WORKLOADS["c3"], data, per_head, 50, 0.5, 1e-6, range(4))
+    for q in range(4):
+        P.check_head(W.to_f64(s[q]), W.to_f64(V[q]), 50, 0.5, 1e-6, a.pick_order[q].cpu().numpy(),
+                     a.pick_gain[q].cpu().numpy(), a.idx_sorted[q].cpu().numpy())
+    K2, V2, s2 = _flat_case(2, 16, 192, 78, torch.bfloat16)
+    x = B().kvr_retain_flat(K2, V2, s2, 16, 64, 0.5, 1e-6)
+    y = B().kvr_retain_flat(K2, V2, s2, 16, 64, 0.5, 1e-6)
+    torch.cuda.synchronize()
+    assert torch.equal(x.u_out, y.u_out) and torch.equal(x.pick_order, y.pick_order) and torch.equal(x.V_out, y.V_out)
+
+
+def test_flat_mode_full_size_sampled_sequences():
+    # c3's shape in the launch configuration bench.py --flat times: 32 sequences x 256 heads
+    w = W.WORKLOADS["c3"]
+    data = W.generate(w, seed=0, device=DEV)
+    group = w.layers * w.kv_heads
+    s = data["s"].view(w.seqs, group, w.n)[:, 0].contiguous()
+    out = B().kvr_retain_flat(data["K"], data["V"], s, group, w.b, w.lam, 1e-6)
+    torch.cuda.synchronize()
+    for q in (0, 13, 31):
+        sl = slice(q * group, (q + 1) * group)
+        u64 = W.to_f64(data["V"][sl]).mean(axis=0)
+        idx = out.idx_sorted[q].cpu().numpy()
+        P.check_head(W.to_f64(s[q]), u64, w.b, w.lam, 1e-6, out.pick_order[q].cpu().numpy(),
+                     out.pick_gain[q].cpu().numpy(), idx)
+        for g in (0, 100, 255):
+            h = q * group + g
+            np.testing.assert_array_equal(_bits(out.K_out[h]), O.compact(_bits(data["K"][h]), idx))
+            np.testing.assert_array_equal(_bits(out.V_out[h]), O.compact(_bits(data["V"][h]), idx))
+
