@@ -73,6 +73,46 @@ def cpu_baseline_flat(w, data, s, group, b, lam, budget_s=12.0):
                       f"(fp64 numpy oracle, {t_used:.1f} s, rate extrapolates linearly over sequences)"}
 
 
+def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False):
+    """A short run of another benchmark configuration at its full size, for the
+    `other_configs` object: the default workload carries the headline figures, the others are
+    reported beside it from the same process."""
+    import torch
+    from paper_2605_14292_amd import binding as B
+    from paper_2605_14292_amd import workloads as W
+    w = W.WORKLOADS[name]
+    lam = w.lam if lam is None else lam
+    data = W.generate(w, seed=seed, device="cuda:0")
+    Q, s = data.get("Q"), data.get("s")
+    group = w.layers * w.kv_heads
+    if flat:
+        s = s.view(w.seqs, group, w.n)[:, 0].contiguous()
+        out = B.FlatBuffers(w.heads, group, w.n, w.b, w.d, w.torch_dtype, "cuda:0", want_trace=False)
+        step = lambda: B.kvr_retain_flat(data["K"], data["V"], s, group, w.b, lam, 1e-6, out=out)
+    else:
+        out = B.RetainBuffers(w.heads, w.n, w.b, w.d, w.torch_dtype, "cuda:0", "Q" in data, want_trace=False)
+        step = lambda: B.kvr_retain(data["K"], data["V"], w.b, lam, 1e-6, Q=Q, s=s, out=out)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        step()
+    z.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(z) / steps
+    bytes_step = w.algorithmic_bytes_per_head(w.b, lam) * w.heads
+    if flat:
+        bytes_step -= (4 * w.n + 4 * w.b) * (w.heads - w.seqs)
+    del data, out
+    torch.cuda.empty_cache()
+    return {"ms_per_step": ms, "head_events_per_s": w.heads / (ms * 1e-3), "steps": steps,
+            "algorithmic_GBps": bytes_step / (ms * 1e-3) / 1e9,
+            "frac_of_hbm_peak": bytes_step / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "heads": w.heads, "n": w.n, "b": w.b, "lambda": lam}
+
+
 def kernel_name(w, b, lam, has_q):
     """The kernels one kvr_retain call launches for this shape (the roofline
     object prices the whole step against the step's algorithmic bytes)."""
@@ -104,6 +144,8 @@ def main():
                          "selection per sequence, every head keeps the same tokens; needs a workload "
                          "with given scores (c3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other benchmark configurations")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (reference point for "
@@ -192,6 +234,17 @@ def main():
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline_flat(w, data, s, group, b, lam) if args.flat else cpu_baseline(w, data, b, lam)
+    default_run = (args.workload == "c3" and not args.flat and args.b is None and args.lam is None)
+    if default_run and not args.no_other_configs:
+        del data, out
+        torch.cuda.empty_cache()
+        line["other_configs"] = {
+            "c2": time_other("c2", steps=20, warmup=5, seed=args.seed),
+            "c3 flat-signature mode": time_other("c3", seed=args.seed, flat=True),
+            "c5": time_other("c5", seed=args.seed),
+            "c5 lambda=0": time_other("c5", seed=args.seed, lam=0.0),
+            "c4": time_other("c4", seed=args.seed),
+        }
     print(json.dumps(line), flush=True)
 
 
