@@ -168,6 +168,118 @@ __device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, co
   }
 }
 
+// Algorithm 1's pick chain (Eq. 2-3) on one wave, for a head whose cosines sit in the packed
+// triangle `tri` (element (i,j), j <= i, at i(i+1)/2 + j, +inf on the diagonal) and whose scores
+// sit in s_l (-inf for padding).  A single wave issues one instruction every few cycles, so the
+// time of a pick is its instruction count: tokens NQ*lane .. NQ*lane+NQ-1 live in lane `lane`,
+// so that the lowest lane holding the maximum also holds the lowest tied index; pick u of a
+// 64-pick chunk is parked in lane u of two registers (v_writelane) and the chunk is written to
+// order_l / gain_l once; nothing is checked per pick.  Non-finite input is detected afterwards
+// from the logged gains: the picks before the first one without a finite gain are kept and the
+// list is filled up with the lowest tokens < n_live not yet in it.  `diverse` false is the
+// lambda = 0 branch (top-b, the triangle is not read).  Returns the gain of the last pick.
+template <int NQ>
+__device__ __forceinline__ float pick_chain(const float* s_l, const float* tri, int32_t* order_l, float* gain_l,
+                                            int n_live, int b, float lambda, bool diverse, int lane) {
+  typedef __attribute__((address_space(3))) const float* lds_fp;
+  const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
+  float sreg[NQ], mreg[NQ];
+  int ja[NQ], tja[NQ];
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    const int j = NQ * lane + q;
+    sreg[q] = s_l[j];
+    mreg[q] = 0.f;
+    ja[q] = j * 4 + tri0;                              // column offset of the token
+    tja[q] = j * (j + 1) * 2 + tri0;                   // start of its row
+  }
+  const float nlam = -lambda;
+  int bad_t = b;                                       // first pick without a finite gain
+  float last_g = -INFINITY;
+  for (int c0 = 0; c0 < b; c0 += 64) {
+    const int cnt = __builtin_amdgcn_readfirstlane(b - c0 < 64 ? b - c0 : 64);
+    int rec_i = 0, rec_g = 0;
+    for (int u = 0; u < cnt; ++u) {
+      float av[NQ];
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
+      float best = av[0];
+#pragma unroll
+      for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
+      const float amax = wave_max_uniform(best);
+      unsigned long long e[NQ];
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) e[q] = __ballot(av[q] == amax);
+      const int i = first_of_slots<NQ>(e);             // negative when nothing compares equal (NaN)
+      write_lane2(rec_i, rec_g, i, __float_as_int(amax), u);
+      if (diverse) {
+        // element (i,j) sits at max(T(i)+j, T(j)+i); the diagonal entry (+inf) retires the pick.
+        // For any i in [-NQ, 64*NQ) both addresses stay inside the triangle.
+        const int ti4 = i * (i + 1) * 2, i4 = i * 4;
+        float c[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          const int a0 = ti4 + ja[q], a1 = tja[q] + i4;
+          c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a0 > a1 ? a0 : a1)));
+        }
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
+      } else {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) sreg[q] = (NQ * lane + q == i) ? -INFINITY : sreg[q];
+      }
+    }
+    const float g = __int_as_float(rec_g);
+    if (lane < cnt) { order_l[c0 + lane] = rec_i; gain_l[c0 + lane] = g; }
+    last_g = __int_as_float(__builtin_amdgcn_readlane(rec_g, cnt - 1));
+    const unsigned long long bad = __ballot(lane < cnt && !(g > -INFINITY));
+    if (bad && bad_t == b) bad_t = c0 + __ffsll(static_cast<long long>(bad)) - 1;
+  }
+  if (bad_t < b) {
+    wave_lds_sync();
+    for (int t = bad_t; t < b; ++t) {
+      int i = -1;
+#pragma unroll
+      for (int q = NQ - 1; q >= 0; --q) {
+        const int j = lane + 64 * q;
+        bool free_tok = j < n_live;
+        for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
+        const unsigned long long al = __ballot(free_tok);
+        if (al) i = (__ffsll(static_cast<long long>(al)) - 1) + 64 * q;
+      }
+      if (lane == 0) { order_l[t] = i; gain_l[t] = -INFINITY; }
+      wave_lds_sync();
+    }
+    last_g = -INFINITY;
+  }
+  return last_g;
+}
+
+// sort(S) on one wave: flags the b picks of order_l (indices < 64*NQ), writes them in ascending
+// order to idx_l by prefix popcounts.  With a map (ascending in its argument), idx_l and
+// order_l are translated through it.  `flag` is scratch for 64*NQ ints.
+template <int NQ>
+__device__ __forceinline__ void sort_picks(int32_t* order_l, int32_t* idx_l, int32_t* flag, int b, int lane,
+                                           const int32_t* map) {
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) flag[lane + 64 * q] = 0;
+  wave_lds_sync();                                     // order_l was written by other lanes
+  for (int u = lane; u < b; u += kWave) flag[min(max(order_l[u], 0), 64 * NQ - 1)] = 1;
+  wave_lds_sync();                                     // flags are set by other lanes
+  int off = 0;
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    const int j = lane + 64 * q;
+    const bool picked = flag[j] != 0;
+    const unsigned long long sel = __ballot(picked);
+    if (picked) idx_l[off + __popcll(sel & ((1ull << lane) - 1ull))] = map ? map[j] : j;
+    off += __popcll(sel);
+  }
+  if (map)
+    for (int u = lane; u < b; u += kWave) order_l[u] = map[min(max(order_l[u], 0), 64 * NQ - 1)];
+}
+
 // Cache update for one head: rows il[t], t < b, of K and V go to rows ob + t of the dense
 // outputs, bit for bit, by the nthr threads t0 = 0..nthr-1 (nthr a multiple of 16; 16 threads
 // per row).  BATCH rows per thread are loaded by straight-line code before the first store (row

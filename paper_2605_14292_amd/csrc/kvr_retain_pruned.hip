@@ -375,96 +375,18 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #endif
     } else {
       // ---------------------------------------------------------------- greedy
-      // A single wave issues one instruction every few cycles, so the time of a pick is its
-      // instruction count.  Survivors 2*lane and 2*lane+1 live in lane `lane`: the lowest lane
-      // holding the maximum then also holds the lowest tied index.  Pick u of a 64-pick chunk
-      // is parked in lane u of two registers (v_writelane) and the chunk is written out once.
-      // Nothing is checked per pick: non-finite input is detected afterwards from the gains.
-      typedef __attribute__((address_space(3))) const float* lds_fp;
-      const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
-          (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
-      const int j0 = 2 * lane;
-      const float2 s01 = *reinterpret_cast<const float2*>(s_cur + j0);   // -inf beyond the survivors
-      const float s0 = s01.x, s1 = s01.y;
-      float m0 = 0.f, m1 = 0.f;
-      const int ja0 = j0 * 4 + tri0, ja1 = ja0 + 4;                       // column offsets of the lane's tokens
-      const int tja0 = j0 * (j0 + 1) * 2 + tri0, tja1 = (j0 + 1) * (j0 + 2) * 2 + tri0;   // their row starts
-      const float nlam = -a.lambda;
       __builtin_amdgcn_s_setprio(3);                   // the chain goes first when it shares a SIMD with loader waves
-      int bad_t = b;                                   // first pick without a finite gain
-      float last_g = -INFINITY;                        // gain of the final pick, the smallest of all
-      for (int c0 = 0; c0 < b; c0 += 64) {
-        const int cnt = __builtin_amdgcn_readfirstlane(b - c0 < 64 ? b - c0 : 64);
-        int rec_i = 0, rec_g = 0;
-        for (int u = 0; u < cnt; ++u) {
-          const float av0 = fmaf(nlam, m0, s0), av1 = fmaf(nlam, m1, s1);
-          const float amax = wave_max_uniform(hw_max(av0, av1));
-          const unsigned long long e0 = __ballot(av0 == amax), e1 = __ballot(av1 == amax);
-          const int i = first_of_pairs(e0, e1);          // -1 when nothing compares equal (NaN)
-          // element (i,j) of the triangle sits at max(T(i)+j, T(j)+i); both reads stay inside the
-          // triangle for any i in [-1, 127]
-          const int ti4 = i * (i + 1) * 2;
-          const int a00 = ti4 + ja0, a01 = tja0 + i * 4, a10 = ti4 + ja1, a11 = tja1 + i * 4;
-          const float c0v = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a00 > a01 ? a00 : a01)));
-          const float c1v = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a10 > a11 ? a10 : a11)));
-          write_lane2(rec_i, rec_g, i, __float_as_int(amax), u);
-          m0 = hw_max(m0, c0v);                          // the diagonal entry (+inf) retires the pick
-          m1 = hw_max(m1, c1v);
-        }
-        const float g = __int_as_float(rec_g);
-        if (lane < cnt) { order_l[c0 + lane] = rec_i; gain_l[c0 + lane] = g; }
-        last_g = __int_as_float(__builtin_amdgcn_readlane(rec_g, cnt - 1));
-        const unsigned long long bad = __ballot(lane < cnt && !(g > -INFINITY));
-        if (bad && bad_t == b) bad_t = c0 + __ffsll(static_cast<long long>(bad)) - 1;
-      }
+      const float last_g = pick_chain<2>(s_cur, tri, order_l, gain_l, ns, b, a.lambda, true, lane);
       __builtin_amdgcn_s_setprio(0);
       {
-        // Candidates that were left out for lack of room must lie below every pick's gain;
-        // otherwise (or when the gains are not finite) the head goes to the full-size kernel.
+        // Candidates that were left out for lack of room must lie below every pick's gain (the
+        // last pick's is the smallest); otherwise the head goes to the full-size kernel.
         const float excl = __int_as_float(meta[4 + buf]);
         const bool ok = excl < last_g - 1e-5f * (fabsf(last_g) + a.lambda);
         if (lane == 0) meta[6 + buf] = (ok || excl == -INFINITY) ? 0 : 1;
       }
-      if (bad_t < b) {
-        // Non-finite scores or rows only: keep the picks made before the first one without a
-        // finite gain, fill up with the lowest survivors not yet picked (there are at least b).
-        wave_lds_sync();
-        for (int t = bad_t; t < b; ++t) {
-          int i = -1;
-#pragma unroll
-          for (int q = 1; q >= 0; --q) {
-            const int j = lane + 64 * q;
-            bool free_tok = j < ns;
-            for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
-            const unsigned long long al = __ballot(free_tok);
-            if (al) i = (__ffsll(static_cast<long long>(al)) - 1) + 64 * q;
-          }
-          if (lane == 0) { order_l[t] = i; gain_l[t] = -INFINITY; }
-          wave_lds_sync();
-        }
-      }
-      constexpr int NQ = 2;
-      // sort(S): flag the picked survivors, ascending order by prefix popcount, then back to
-      // token indices (the survivor list is ascending in the token index).
-      int32_t* flag = reinterpret_cast<int32_t*>(rinv);   // rinv is dead by now
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) flag[lane + 64 * q] = 0;
-      wave_lds_sync();
-      for (int u = lane; u < b; u += kWave) flag[min(max(order_l[u], 0), kPrN - 1)] = 1;
-      wave_lds_sync();
-      int off = 0;
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const int j = lane + 64 * q;
-        const bool picked = flag[j] != 0;
-        const unsigned long long sel = __ballot(picked);
-        if (picked) {
-          const int rank = __popcll(sel & ((1ull << lane) - 1ull));
-          idx_l[off + rank] = tok_cur[j];
-        }
-        off += __popcll(sel);
-      }
-      for (int u = lane; u < b; u += kWave) order_l[u] = tok_cur[min(max(order_l[u], 0), kPrN - 1)];
+      // back to token indices: the survivor list is ascending in the token index
+      sort_picks<2>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, tok_cur);
       // Wave 0 never holds gathered rows.  Saying so (no instruction is emitted) keeps the row
       // registers of the other branch from being carried, as far as the compiler can tell,
       // through this branch and with it through the whole loop body.

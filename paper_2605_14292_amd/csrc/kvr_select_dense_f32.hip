@@ -112,92 +112,8 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
   __syncthreads();
 
   if (wave == 0) {
-    // the pick loop of the bf16 kernels: tokens NQ*lane .. NQ*lane+NQ-1 live in lane `lane`
-    typedef __attribute__((address_space(3))) const float* lds_fp;
-    const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
-        (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
-    float sreg[NQ], mreg[NQ];
-    int ja[NQ], tja[NQ];
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int j = NQ * lane + q;
-      sreg[q] = s_l[j];
-      mreg[q] = 0.f;
-      ja[q] = j * 4 + tri0;
-      tja[q] = j * (j + 1) * 2 + tri0;
-    }
-    const float nlam = -a.lambda;
-    int bad_t = b;
-    for (int c0 = 0; c0 < b; c0 += 64) {
-      const int cnt = __builtin_amdgcn_readfirstlane(b - c0 < 64 ? b - c0 : 64);
-      int rec_i = 0, rec_g = 0;
-      for (int u = 0; u < cnt; ++u) {
-        float av[NQ];
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mreg[q], sreg[q]);
-        float best = av[0];
-#pragma unroll
-        for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
-        const float amax = wave_max_uniform(best);
-        unsigned long long e[NQ];
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) e[q] = __ballot(av[q] == amax);
-        const int i = first_of_slots<NQ>(e);
-        write_lane2(rec_i, rec_g, i, __float_as_int(amax), u);
-        if (diverse) {
-          const int ti4 = i * (i + 1) * 2, i4 = i * 4;
-          float c[NQ];
-#pragma unroll
-          for (int q = 0; q < NQ; ++q) {
-            const int a0 = ti4 + ja[q], a1 = tja[q] + i4;
-            c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(a0 > a1 ? a0 : a1)));
-          }
-#pragma unroll
-          for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
-        } else {
-#pragma unroll
-          for (int q = 0; q < NQ; ++q) sreg[q] = (NQ * lane + q == i) ? -INFINITY : sreg[q];
-        }
-      }
-      const float g = __int_as_float(rec_g);
-      if (lane < cnt) { order_l[c0 + lane] = rec_i; gain_l[c0 + lane] = g; }
-      const unsigned long long bad = __ballot(lane < cnt && !(g > -INFINITY));
-      if (bad && bad_t == b) bad_t = c0 + __ffsll(static_cast<long long>(bad)) - 1;
-    }
-    if (bad_t < b) {
-      // non-finite input only: keep the picks before the first one without a finite gain and
-      // fill up with the lowest tokens that are not in the pick list
-      wave_lds_sync();
-      for (int t = bad_t; t < b; ++t) {
-        int i = -1;
-#pragma unroll
-        for (int q = NQ - 1; q >= 0; --q) {
-          const int j = lane + 64 * q;
-          bool free_tok = j < n;
-          for (int u = 0; u < t; ++u) free_tok = free_tok && order_l[u] != j;
-          const unsigned long long al = __ballot(free_tok);
-          if (al) i = (__ffsll(static_cast<long long>(al)) - 1) + 64 * q;
-        }
-        if (lane == 0) { order_l[t] = i; gain_l[t] = -INFINITY; }
-        wave_lds_sync();
-      }
-    }
-    // sort(S): flag the picked tokens, then ascending indices by prefix popcount
-    int32_t* flag = reinterpret_cast<int32_t*>(rinv);
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) flag[lane + 64 * q] = 0;
-    wave_lds_sync();
-    for (int u = lane; u < b; u += kWave) flag[min(max(order_l[u], 0), N32 - 1)] = 1;
-    wave_lds_sync();
-    int off = 0;
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int j = lane + 64 * q;
-      const bool picked = flag[j] != 0;
-      const unsigned long long sel = __ballot(picked);
-      if (picked) idx_l[off + __popcll(sel & ((1ull << lane) - 1ull))] = j;
-      off += __popcll(sel);
-    }
+    pick_chain<NQ>(s_l, tri, order_l, gain_l, n, b, a.lambda, diverse, lane);
+    sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, nullptr);
   }
   __syncthreads();
   const long long ob = static_cast<long long>(h) * b;
