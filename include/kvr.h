@@ -170,6 +170,41 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
                     int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                     void* K_out, void* V_out, void* stream);
 
+/*
+ * The event inside a budget allocator's frame (the paper names stacking the
+ * selector inside per-head / per-layer budget allocators as a composition,
+ * Sec. 2 and the limitations paragraph; protected tokens are this library's
+ * reading, the paper is silent on them):
+ *   n_h   device, int32 [heads] or NULL: only tokens j < n_h[h] are candidates
+ *         (NULL: all n)
+ *   b_h   device, int32 [heads] or NULL: budget of head h, b_h[h] <= b_max and
+ *         <= n_h[h] (NULL: b_max everywhere)
+ *   keep  device, uint8 [heads, n] or NULL: non-zero marks protected tokens
+ *         (sinks, a recent window).  They are members of S from the start, count
+ *         towards b_h and penalise similar tokens through Eq. 2 like any other
+ *         member; the greedy fill of Eq. 3 continues from there.  More protected
+ *         tokens than b_h gives an unspecified subset of them.
+ *   pos_in / pos_out  device, int32 [heads, n] / [heads, b_max] or NULL: position
+ *         ids carried along with the kept rows
+ *   s_work  device, float32 [heads, n], required: receives the scores the
+ *         selection ran on (computed from Q when Q is given, masked to -inf past
+ *         n_h, protected tokens raised by a per-head offset)
+ *   idx_sorted, pick_order (required), pick_gain   [heads, b_max]: the first
+ *         b_h[h] entries are valid, the rest are -1 (-inf for gains).  In
+ *         pick_order the protected tokens come first, in no particular order,
+ *         with pick_gain +inf.
+ *   K_out, V_out  device, dense [heads, b_max, d] or NULL: rows t < b_h[h] are
+ *         written, the others are left as they were
+ * Exactly one of (Q, G) and s_in, as in kvr_retain.  The picks for budget b_h
+ * are the first b_h picks of the run for b_max, so the work per head is that of
+ * b_max.
+ */
+int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                        const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
+                        const uint8_t* keep, const int32_t* pos_in, float lambda, float eps,
+                        float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                        void* K_out, void* V_out, int32_t* pos_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -229,3 +229,27 @@ def retain_flat(K_all, V_all, s, k: int, lam: float, eps: float = 1e-6):
     r["V_out"] = np.stack([compact(Vh, r["sorted"]) for Vh in np.asarray(V_all)])
     return r
 
+
+def select_budgeted(s, V, n_h: int, b_h: int, keep=None, lam: float = 0.5, eps: float = 1e-6):
+    """Algorithm 1 inside a budget allocator's frame: only the first n_h tokens are candidates,
+    the tokens flagged in `keep` (sinks, recent window) are members of S from the start and count
+    towards the budget b_h, and the greedy fill of Eq. 3 continues from there until |S| = b_h.
+    Eq. 2 is evaluated from scratch at every step (no running state).  Returns the protected
+    tokens (ascending), the greedy picks in pick order with their gains, and sort(S)."""
+    s = np.asarray(s, dtype=np.float64)[:n_h]
+    Vh = signatures(np.asarray(V, dtype=np.float64)[:n_h], eps)
+    prot = [] if keep is None else [int(j) for j in np.flatnonzero(np.asarray(keep)[:n_h])]
+    if len(prot) > b_h:
+        raise ValueError("more protected tokens than budget")
+    S = list(prot)
+    order, gain = [], []
+    cos = Vh @ Vh.T
+    while len(S) < b_h:
+        red = np.maximum(0.0, cos[:, S].max(axis=1)) if S else np.zeros(len(s))   # Eq. 2's inner maximum over all of S
+        g = s - lam * red
+        g[S] = NEG_INF
+        i = _argmax_lowest(g)
+        order.append(i); gain.append(g[i]); S.append(i)
+    return {"protected": np.array(prot, dtype=np.int64), "order": np.array(order, dtype=np.int64),
+            "gain": np.array(gain, dtype=np.float64), "sorted": np.array(sorted(S), dtype=np.int64)}
+

@@ -20,7 +20,7 @@ KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1
 
 EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
            "kvr_select_greedy", "kvr_compact", "kvr_retain",
-           "kvr_signature_flat", "kvr_compact_shared", "kvr_retain_flat")
+           "kvr_signature_flat", "kvr_compact_shared", "kvr_retain_flat", "kvr_retain_budgeted")
 
 
 class kvr_layout(ctypes.Structure):
@@ -63,6 +63,9 @@ def _load() -> ctypes.CDLL:
     lib.kvr_compact_shared.argtypes = [vp, vp, lp, i32, vp, i32, vp, vp, vp]
     lib.kvr_retain_flat.restype = i32
     lib.kvr_retain_flat.argtypes = [vp, vp, vp, lp, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp]
+    lib.kvr_retain_budgeted.restype = i32
+    lib.kvr_retain_budgeted.argtypes = [vp, vp, vp, i32, vp, lp, vp, vp, i32, vp, vp, f32, f32,
+                                        vp, vp, vp, vp, vp, vp, vp, vp]
     return lib
 
 
@@ -244,3 +247,37 @@ def kvr_retain_flat(K, V, s, group, b, lam, eps=1e-6, out: FlatBuffers | None = 
                                 _ptr(out.pick_gain), _ptr(out.K_out), _ptr(out.V_out),
                                 _stream(stream)), "kvr_retain_flat")
     return out
+
+
+class BudgetBuffers:
+    """Preallocated outputs of kvr_retain_budgeted for one shape."""
+
+    def __init__(self, heads, n, b_max, d, dtype, device, with_pos=False):
+        self.s_work = torch.empty((heads, n), dtype=torch.float32, device=device)
+        self.idx_sorted = torch.empty((heads, b_max), dtype=torch.int32, device=device)
+        self.pick_order = torch.empty((heads, b_max), dtype=torch.int32, device=device)
+        self.pick_gain = torch.empty((heads, b_max), dtype=torch.float32, device=device)
+        self.K_out = torch.zeros((heads, b_max, d), dtype=dtype, device=device)
+        self.V_out = torch.zeros((heads, b_max, d), dtype=dtype, device=device)
+        self.pos_out = torch.empty((heads, b_max), dtype=torch.int32, device=device) if with_pos else None
+
+
+def kvr_retain_budgeted(K, V, b_max, lam, eps=1e-6, Q=None, s=None, n_h=None, b_h=None, keep=None,
+                        pos=None, out: BudgetBuffers | None = None, stream=None):
+    _need_cuda(K, V, Q, s, n_h, b_h, keep, pos)
+    lay = layout_of(K)
+    if layout_of(V).stride_head != lay.stride_head or layout_of(V).stride_tok != lay.stride_tok:
+        raise ValueError("K and V must share one layout")
+    for t, dt in ((n_h, torch.int32), (b_h, torch.int32), (keep, torch.uint8), (pos, torch.int32)):
+        if t is not None and (t.dtype != dt or not t.is_contiguous()):
+            raise ValueError("n_h, b_h, pos must be contiguous int32 and keep contiguous uint8")
+    if out is None:
+        out = BudgetBuffers(lay.heads, lay.n, b_max, lay.d, K.dtype, K.device, pos is not None)
+    G = 0 if Q is None else Q.shape[1]
+    _check(_lib.kvr_retain_budgeted(_ptr(K), _ptr(V), _ptr(Q), G, _ptr(s), ctypes.byref(lay), _ptr(n_h),
+                                    _ptr(b_h), b_max, _ptr(keep), _ptr(pos), lam, eps, _ptr(out.s_work),
+                                    _ptr(out.idx_sorted), _ptr(out.pick_order), _ptr(out.pick_gain),
+                                    _ptr(out.K_out), _ptr(out.V_out), _ptr(out.pos_out), _stream(stream)),
+           "kvr_retain_budgeted")
+    return out
+

@@ -39,6 +39,30 @@ int check_select(const kvr_layout* lay, int b, float lambda, float eps) {
   return KVR_OK;
 }
 
+// Selection without compaction: the kernel is chosen by shape only.
+hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int b, float lambda, float eps,
+                       int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, hipStream_t st) {
+  if (kvr::pruned_supported(l, b, lambda, false)) {
+    const hipError_t e = kvr::launch_retain_pruned(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order,
+                                                   pick_gain, nullptr, nullptr, st);
+    if (e != hipSuccess) return e;
+    return kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
+                                    pick_order, pick_gain, nullptr, nullptr, st, true);
+  }
+  if (kvr::dense_supported(l, b, 0, false))
+    return kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
+                                    pick_order, pick_gain, nullptr, nullptr, st);
+  if (kvr::dense_f32_supported(l, b))
+    return kvr::launch_select_dense_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
+  if (kvr::pool_supported(l, b))
+    return kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
+                                   nullptr, nullptr, st);
+  if (kvr::blocked_supported(l, b))
+    return kvr::launch_select_blocked(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
+                                      nullptr, nullptr, st);
+  return kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -86,28 +110,8 @@ int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay, int 
   if (!s || !idx_sorted) return KVR_ERR_ARG;
   if (lambda != 0.0f && !V) return KVR_ERR_ARG;
   if ((V && !aligned16(V)) || !aligned16(s)) return KVR_ERR_ARG;
-  const kvr::Layout l = to_dev(lay);
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  hipError_t e;
-  if (kvr::pruned_supported(l, b, lambda, false)) {
-    e = kvr::launch_retain_pruned(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
-                                  nullptr, nullptr, st);
-    if (e == hipSuccess)
-      e = kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
-                                   pick_order, pick_gain, nullptr, nullptr, st, true);
-  } else if (kvr::dense_supported(l, b, 0, false))
-    e = kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
-                                 pick_order, pick_gain, nullptr, nullptr, st);
-  else if (kvr::dense_f32_supported(l, b))
-    e = kvr::launch_select_dense_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
-  else if (kvr::pool_supported(l, b))
-    e = kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
-                                nullptr, nullptr, st);
-  else if (kvr::blocked_supported(l, b))
-    e = kvr::launch_select_blocked(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
-                                   nullptr, nullptr, st);
-  else
-    e = kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
+  const hipError_t e = select_only(V, s, to_dev(lay), b, lambda, eps, idx_sorted, pick_order, pick_gain,
+                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
 }
 
@@ -175,6 +179,37 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
       : kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
   if (es != hipSuccess) return KVR_ERR_HIP;
   if (kvr::launch_compact(K, V, l, idx_sorted, b, K_out, V_out, st) != hipSuccess)
+    return KVR_ERR_HIP;
+  return KVR_OK;
+}
+
+int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                        const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
+                        const uint8_t* keep, const int32_t* pos_in, float lambda, float eps,
+                        float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                        void* K_out, void* V_out, int32_t* pos_out, void* stream) {
+  const int rc = check_select(lay, b_max, lambda, eps);
+  if (rc) return rc;
+  if (!V || !s_work || !idx_sorted || !pick_order) return KVR_ERR_ARG;
+  if ((Q == nullptr) == (s_in == nullptr)) return KVR_ERR_ARG;
+  if (Q && (G < 1 || !K)) return KVR_ERR_ARG;
+  if (Q && G > KVR_MAX_G) return KVR_ERR_UNSUPPORTED;
+  if ((K_out && !K) || (pos_out && !pos_in)) return KVR_ERR_ARG;
+  if (!aligned16(V) || !aligned16(s_work) || (K && !aligned16(K)) || (Q && !aligned16(Q)) ||
+      (s_in && !aligned16(s_in)) || (K_out && !aligned16(K_out)) || (V_out && !aligned16(V_out)))
+    return KVR_ERR_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const kvr::Layout l = to_dev(lay);
+  const float* src = s_in;
+  if (Q) {
+    if (kvr::launch_score(K, Q, G, l, s_work, st) != hipSuccess) return KVR_ERR_HIP;
+    src = s_work;
+  }
+  if (kvr::launch_budget_prepare(src, l, n_h, keep, lambda, s_work, st) != hipSuccess) return KVR_ERR_HIP;
+  if (select_only(V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)
+    return KVR_ERR_HIP;
+  if (kvr::launch_budget_finalize(K, V, l, b_h, b_max, keep, pos_in, idx_sorted, pick_order, pick_gain,
+                                  K_out, V_out, pos_out, st) != hipSuccess)
     return KVR_ERR_HIP;
   return KVR_OK;
 }

@@ -364,3 +364,61 @@ def test_flat_mode_full_size_sampled_sequences():
             np.testing.assert_array_equal(_bits(out.K_out[h]), O.compact(_bits(data["K"][h]), idx))
             np.testing.assert_array_equal(_bits(out.V_out[h]), O.compact(_bits(data["V"][h]), idx))
 
+
+# ---------------------------------------------------------------- budgets and protected tokens
+@pytest.mark.parametrize("n,b_max,lam,dtype,computed", [
+    (192, 64, 0.5, torch.bfloat16, False), (256, 100, 0.3, torch.bfloat16, True), (120, 48, 0.7, torch.bfloat16, False),
+    (600, 64, 0.5, torch.bfloat16, False), (150, 40, 0.5, torch.float32, False)])
+def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
+    h = 8
+    K, V, s = _mk(h, n, 5100 + n, dtype)
+    g = torch.Generator().manual_seed(n)
+    s = (torch.randn((h, n), generator=g).exp() * (0.02 if computed else 1.0)).to(DEV)
+    V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]      # near-duplicates: the penalty matters
+    # head 2 has fewer candidates than b_max: the run for b_max runs dry, its budget does not
+    n_h = torch.tensor([n, n - 7, b_max - 10, n, n, n - 1, b_max + 3, n], dtype=torch.int32)
+    b_h = torch.tensor([b_max, b_max - 5, b_max // 2, 12, b_max, 9, b_max, 1], dtype=torch.int32)
+    keep = torch.zeros((h, n), dtype=torch.uint8)
+    keep[0, :4] = 1; keep[0, n - 8:] = 1                           # sinks and a recent window
+    keep[1, :2] = 1
+    keep[3, torch.randperm(n, generator=g)[:10]] = 1
+    keep[5, n - 1 - 3: n - 1] = 1                                  # inside n_h = n - 1
+    keep[7, 17] = 1                                                # budget 1, taken by the protected token
+    pos = (torch.arange(n, dtype=torch.int32)[None, :] * 3 + torch.arange(h, dtype=torch.int32)[:, None]).contiguous()
+    Q = torch.randn((h, 4, 128), generator=g).to(dtype).to(DEV) if computed else None
+    out = B().kvr_retain_budgeted(K, V, b_max, lam, 1e-6, Q=Q, s=None if computed else s, n_h=n_h.to(DEV),
+                                  b_h=b_h.to(DEV), keep=keep.to(DEV), pos=pos.to(DEV))
+    torch.cuda.synchronize()
+    Kb, Vb = _bits(K), _bits(V)
+    for hh in range(h):
+        nh, bh = int(n_h[hh]), int(b_h[hh])
+        V64 = W.to_f64(V[hh])
+        s64 = O.score_softmax_mean(W.to_f64(K[hh]), W.to_f64(Q[hh])) if computed else W.to_f64(s[hh])
+        kp = keep[hh].numpy().astype(bool)
+        ref = O.select_budgeted(s64, V64, nh, bh, kp, lam, 1e-6)
+        order = out.pick_order[hh].cpu().numpy(); gain = out.pick_gain[hh].cpu().numpy().astype(np.float64)
+        idx = out.idx_sorted[hh].cpu().numpy()
+        npz = len(ref["protected"])
+        assert np.all(order[bh:] == -1) and np.all(idx[bh:] == -1)
+        assert sorted(order[:npz].tolist()) == ref["protected"].tolist() and np.all(np.isinf(gain[:npz]))
+        assert sorted(order[:bh].tolist()) == idx[:bh].tolist() and idx[:bh].max() < nh
+        # the greedy picks after the protected ones: every one must be the fp64 argmax of Eq. 2 on
+        # the HIP path's own prefix, or within the near-tie bound of it
+        Vh = O.signatures(V64[:nh], 1e-6); cos = Vh @ Vh.T
+        S = list(order[:npz])
+        for t in range(npz, bh):
+            red = np.maximum(0.0, cos[:, S].max(axis=1)) if S else np.zeros(nh)
+            gt = s64[:nh] - lam * red
+            gt[S] = -np.inf
+            i = int(order[t])
+            scale = np.abs(s64[i]) + lam * red[i]
+            assert gt.max() - gt[i] <= P.NEAR_TIE * max(scale, 1e-30), (hh, t)
+            assert abs(gain[t] - gt[i]) <= P.GAIN_RTOL * max(scale, 1e-30), (hh, t)
+            S.append(i)
+        assert len(ref["order"]) == bh - npz
+        np.testing.assert_array_equal(_bits(out.K_out[hh])[:bh], O.compact(Kb[hh], idx[:bh]))
+        np.testing.assert_array_equal(_bits(out.V_out[hh])[:bh], O.compact(Vb[hh], idx[:bh]))
+        assert not _bits(out.K_out[hh])[bh:].any()                 # rows past the budget are untouched (zeros)
+        np.testing.assert_array_equal(out.pos_out[hh].cpu().numpy()[:bh], pos[hh].numpy()[idx[:bh]])
+        assert np.all(out.pos_out[hh].cpu().numpy()[bh:] == -1)
+

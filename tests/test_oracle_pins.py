@@ -294,3 +294,48 @@ def test_flat_mode_ignores_head_order_and_common_scale_and_shares_the_index_set(
     big = V.copy(); big[0] *= 1e6
     assert O.retain_flat(K, big, s, 10, 0.5)["order"].tolist() == O.alpha_select(s, big[0], 10, 0.5)["order"].tolist()
 
+
+# ---------------------------------------------------------------- budgets and protected tokens
+def test_budgeted_without_protection_is_algorithm1_and_a_prefix_for_smaller_budgets():
+    rng = _rng(31)
+    V = rng.normal(size=(40, 8)); s = rng.random(40)
+    full = O.alpha_select(s, V, 15, 0.6)
+    r = O.select_budgeted(s, V, 40, 15, None, 0.6)
+    assert r["order"].tolist() == full["order"].tolist()
+    np.testing.assert_allclose(r["gain"], full["gain"], rtol=0, atol=1e-12)
+    assert O.select_budgeted(s, V, 40, 6, None, 0.6)["order"].tolist() == full["order"][:6].tolist()
+    # only the first n_h tokens are candidates: the same as running on the truncated arrays
+    t = O.select_budgeted(s, V, 25, 10, None, 0.6)
+    assert t["order"].tolist() == O.alpha_select(s[:25], V[:25], 10, 0.6)["order"].tolist()
+
+
+def test_budgeted_gains_follow_eq2_with_the_protected_set_included():
+    rng = _rng(32)
+    V = rng.normal(size=(30, 6)); s = rng.random(30)
+    keep = np.zeros(30, dtype=bool); keep[[0, 1, 28, 29]] = True        # sinks and a recent window
+    r = O.select_budgeted(s, V, 30, 12, keep, 0.8)
+    assert r["protected"].tolist() == [0, 1, 28, 29] and len(r["order"]) == 8
+    assert set(r["protected"]) <= set(r["sorted"]) and len(set(r["sorted"].tolist())) == 12
+    Vh = O.signatures(V, 1e-6)
+    S = list(r["protected"])
+    for i, g in zip(r["order"], r["gain"]):
+        ref = O.marginal_gains(s, Vh, S, 0.8)        # the plain-loop form of Eq. 2
+        assert i == int(np.flatnonzero(ref == ref.max())[0]) and abs(ref[i] - g) < 1e-12
+        S.append(int(i))
+
+
+def test_protecting_what_greedy_picks_first_changes_nothing_and_duplicates_of_protected_rows_are_penalised():
+    rng = _rng(33)
+    V = rng.normal(size=(30, 6)); s = rng.random(30)
+    full = O.alpha_select(s, V, 10, 0.5)
+    keep = np.zeros(30, dtype=bool); keep[full["order"][:4]] = True
+    r = O.select_budgeted(s, V, 30, 10, keep, 0.5)
+    assert r["order"].tolist() == full["order"][4:].tolist()
+    assert r["sorted"].tolist() == full["sorted"].tolist()
+    # a copy of a protected row carries the full penalty from the first greedy step on
+    V2 = V.copy(); V2[7] = V2[0]; s2 = s.copy(); s2[7] = s.max() + 0.1
+    keep2 = np.zeros(30, dtype=bool); keep2[0] = True
+    r2 = O.select_budgeted(s2, V2, 30, 3, keep2, 2.0)
+    assert 7 not in r2["order"].tolist()
+    assert O.select_budgeted(s2, V2, 30, 3, keep2, 0.0)["order"][0] == 7
+
