@@ -73,6 +73,34 @@ def cpu_baseline_flat(w, data, s, group, b, lam, budget_s=12.0):
                       f"(fp64 numpy oracle, {t_used:.1f} s, rate extrapolates linearly over sequences)"}
 
 
+def cpu_baseline_budgeted(w, data, b_h, keep, lam, budget_s=12.0):
+    """The fp64 oracle's budgeted selection + compaction on a bounded sample of heads."""
+    import numpy as np
+    from oracle import alpha_oracle as O
+    from paper_2605_14292_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    rng = np.random.default_rng(11)
+    bh, kp = b_h.cpu().numpy(), keep.cpu().numpy().astype(bool)
+    done, t_used = 0, 0.0
+    for h in rng.permutation(w.heads):
+        K64, V64 = W.to_f64(data["K"][h]), W.to_f64(data["V"][h])
+        t0 = time.perf_counter()
+        s64 = O.score_softmax_mean(K64, W.to_f64(data["Q"][h])) if "Q" in data else W.to_f64(data["s"][h])
+        r = O.select_budgeted(s64, V64, w.n, int(bh[h]), kp[h], lam, 1e-6)
+        O.compact(K64, r["sorted"]); O.compact(V64, r["sorted"])
+        t_used += time.perf_counter() - t0
+        done += 1
+        if t_used >= budget_s:
+            break
+    return {"value": done / t_used, "unit": "head-events/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {w.heads} heads of {w.name}, budget-allocator frame (fp64 numpy oracle, "
+                      f"{t_used:.1f} s, rate extrapolates linearly over heads)"}
+
+
 def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False):
     """A short run of another benchmark configuration at its full size, for the
     `other_configs` object: the default workload carries the headline figures, the others are
@@ -143,6 +171,9 @@ def main():
                     help="flat-signature mode (Eq. 1 over all layers and heads of a sequence): one "
                          "selection per sequence, every head keeps the same tokens; needs a workload "
                          "with given scores (c3)")
+    ap.add_argument("--budgeted", action="store_true",
+                    help="budget-allocator frame: per-head budgets b_h in [b/2, b], 4 sink tokens and a "
+                         "recent window of 16 protected per head, position ids carried along")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short runs of the other benchmark configurations")
@@ -184,6 +215,18 @@ def main():
 
         def step():
             B.kvr_retain_flat(data["K"], data["V"], s, group, b, lam, 1e-6, out=out)
+    elif args.budgeted:
+        g = torch.Generator(device=dev).manual_seed(args.seed + 17)
+        b_h = torch.randint(b // 2, b + 1, (w.heads,), generator=g, device=dev, dtype=torch.int32)
+        keep = torch.zeros((w.heads, w.n), dtype=torch.uint8, device=dev)
+        keep[:, :4] = 1
+        keep[:, w.n - 16:] = 1
+        pos = torch.arange(w.n, dtype=torch.int32, device=dev).repeat(w.heads, 1).contiguous()
+        out = B.BudgetBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, with_pos=True)
+        mean_bh = float(b_h.float().mean().item())
+
+        def step():
+            B.kvr_retain_budgeted(data["K"], data["V"], b, lam, 1e-6, Q=Q, s=s, b_h=b_h, keep=keep, pos=pos, out=out)
     else:
         out = B.RetainBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, "Q" in data, want_trace=False)
 
@@ -209,11 +252,15 @@ def main():
     bytes_step = w.algorithmic_bytes_per_head(b, lam) * w.heads
     if args.flat:       # scores and indices are per sequence, not per head
         bytes_step -= (4 * w.n + 4 * b) * (w.heads - w.seqs)
+    if args.budgeted:   # kept rows follow the per-head budgets; the keep mask and position ids are read
+        e = w.elem_bytes
+        rows = (3 if w.scores == "given" else 2) * w.d * e       # K in (given scores only), K out, V out
+        bytes_step += int((mean_bh - b) * rows * w.heads) + (w.n + 4 * w.n + 4 * b) * w.heads
     achieved = bytes_step / (dev_avg_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"{w.name}{'flat' if args.flat else ''}:b{b}:lam{lam}")
+        traffic = json.load(open(tpath)).get(f"{w.name}{'flat' if args.flat else ''}{'budgeted' if args.budgeted else ''}:b{b}:lam{lam}")
     line = {
         "metric": "retention events/sec (heads*events)",
         "value": w.heads / (wall / args.steps),
@@ -223,18 +270,28 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.what}" + (", flat-signature mode (one selection per sequence)"
-                                                        if args.flat else ""), "heads": w.heads, "n": w.n, "b": b,
+                                                        if args.flat else "")
+                                + (", budget-allocator frame (b_h in [b/2, b], 20 protected tokens per head)"
+                                   if args.budgeted else ""), "heads": w.heads, "n": w.n, "b": b,
                    "d": w.d, "lambda": lam, "scores": w.scores, "G": w.G if w.scores == "computed" else 0},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": ("kvr::signature_flat_kernel + kvr::select_dense_f32_kernel + kvr::compact_kernel (whole step)"
-                                if args.flat else kernel_name(w, b, lam, Q is not None)), "device_ms_avg": dev_avg_ms,
+                                if args.flat else
+                                "kvr::budget_prepare_kernel + selection kernels of the shape + kvr::budget_finalize_kernel (whole step)"
+                                if args.budgeted else kernel_name(w, b, lam, Q is not None)), "device_ms_avg": dev_avg_ms,
                      "device_ms_median": dev_ms[len(dev_ms) // 2],
                      "algorithmic_bytes_per_step": bytes_step},
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline_flat(w, data, s, group, b, lam) if args.flat else cpu_baseline(w, data, b, lam)
-    default_run = (args.workload == "c3" and not args.flat and args.b is None and args.lam is None)
+        if args.flat:
+            line["cpu_baseline"] = cpu_baseline_flat(w, data, s, group, b, lam)
+        elif args.budgeted:
+            line["cpu_baseline"] = cpu_baseline_budgeted(w, data, b_h, keep, lam)
+        else:
+            line["cpu_baseline"] = cpu_baseline(w, data, b, lam)
+    default_run = (args.workload == "c3" and not args.flat and not args.budgeted and args.b is None
+                   and args.lam is None)
     if default_run and not args.no_other_configs:
         del data, out
         torch.cuda.empty_cache()
