@@ -287,12 +287,21 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       const long long c1 = __builtin_readcyclecounter();
 #endif
       // ================= 2. pool rows -> LDS, cosine triangle on MFMA =================
-      for (int p0 = 0; p0 < kPool; p0 += NT / 16) {
-        const int p = p0 + (tid >> 4);
-        const int tk = pool_tok[p];
-        uint4 x = make_uint4(0u, 0u, 0u, 0u);
-        if (tk >= 0) x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(tk) * a.stride_tok + (tid & 15) * 8) * 2);
-        *reinterpret_cast<uint4*>(prow + p * kPoolPitch + (tid & 15) * 16) = x;
+      {
+        // all row loads of a thread are issued before the first one is stored: with the loads
+        // and stores interleaved, every load waits for the one before it
+        constexpr int kGat = kPool * 16 / NT;          // rows per thread
+        uint4 x[kGat];
+#pragma unroll
+        for (int k = 0; k < kGat; ++k) {
+          const int tk = pool_tok[k * (NT / 16) + (tid >> 4)];
+          const int tkc = tk < 0 ? 0 : tk;              // an empty slot reads row 0 and stores zeros
+          x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(tkc) * a.stride_tok + (tid & 15) * 8) * 2);
+          if (tk < 0) x[k] = make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int k = 0; k < kGat; ++k)
+          *reinterpret_cast<uint4*>(prow + (k * (NT / 16) + (tid >> 4)) * kPoolPitch + (tid & 15) * 16) = x[k];
       }
       lds_barrier();
       {
