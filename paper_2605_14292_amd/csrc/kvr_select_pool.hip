@@ -35,6 +35,7 @@ constexpr int kPool = 128;          // pool size
 constexpr int kPoolMaxB = 256;      // pick lists kept in LDS
 constexpr int kPoolMaxPend = 32;    // picks per epoch (two 16-row MFMA operands)
 constexpr int kPoolPitch = 272;     // bytes per staged row (256 + 16)
+constexpr int kSelBits = 16;        // leading bits of a gain's ordered key used to choose the pool
 constexpr int kPoolChunk = 16;      // tokens staged per step and wave in the pass over V
 
 struct PoolArgs {
@@ -245,9 +246,11 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       float g[S];
       uint32_t key[S];
 #pragma unroll
-      for (int k = 0; k < S; ++k) { g[k] = fmaf(nlam, m[k], s[k]); key[k] = ordered_key(g[k]); }
+      // Keys are cut to their leading kSelBits bits: the pool only has to be a good guess (the
+      // race against the exact outside bound keeps the picks exact), and the search is shorter.
+      for (int k = 0; k < S; ++k) { g[k] = fmaf(nlam, m[k], s[k]); key[k] = ordered_key(g[k]) >> (32 - kSelBits); }
       uint32_t tau = 0;                              // largest key value with at least Q keys >= it
-      for (int bit = 31; bit >= 0; --bit) {
+      for (int bit = kSelBits - 1; bit >= 0; --bit) {
         const uint32_t cand = tau | (1u << bit);
         int c = 0;
 #pragma unroll
