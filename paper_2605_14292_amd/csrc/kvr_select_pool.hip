@@ -218,16 +218,24 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the first read of V from HBM
     {
       const int c16 = tid & 15;
-      for (int j0 = 0; j0 < n; j0 += NT / 16) {
-        const int j = j0 + (tid >> 4);
-        if (j < n) {
-          float x[8];
-          load8<DT_BF16>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2, x);
+      constexpr int kNB = 8;                         // rows per thread in flight (straight-line loads)
+      for (int j0 = 0; j0 < n; j0 += kNB * (NT / 16)) {
+        uint4 w8[kNB];
+#pragma unroll
+        for (int u = 0; u < kNB; ++u) {
+          const int j = min(j0 + u * (NT / 16) + (tid >> 4), n - 1);
+          w8[u] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2);
+        }
+#pragma unroll
+        for (int u = 0; u < kNB; ++u) {
+          const int j = j0 + u * (NT / 16) + (tid >> 4);
+          const float x[8] = {bf16_lo(w8[u].x), bf16_hi(w8[u].x), bf16_lo(w8[u].y), bf16_hi(w8[u].y),
+                              bf16_lo(w8[u].z), bf16_hi(w8[u].z), bf16_lo(w8[u].w), bf16_hi(w8[u].w)};
           float ss = 0.f;
 #pragma unroll
           for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
           ss = group16_sum(ss);
-          if (c16 == 0) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
+          if (c16 == 0 && j < n) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
         }
       }
       lds_barrier();
