@@ -218,7 +218,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the first read of V from HBM
     {
       const int c16 = tid & 15;
-      constexpr int kNB = 8;                         // rows per thread in flight (straight-line loads)
+      constexpr int kNB = 16;                        // rows per thread in flight (straight-line loads)
       for (int j0 = 0; j0 < n; j0 += kNB * (NT / 16)) {
         uint4 w8[kNB];
 #pragma unroll
