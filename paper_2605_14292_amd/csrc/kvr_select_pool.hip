@@ -88,6 +88,9 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   // ... or the per-wave row stages of the pass over V
 
   const int h = blockIdx.x;
+#ifdef KVR_STATS
+  const long long st_begin = __builtin_readcyclecounter();
+#endif
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = a.n, b = a.b;
@@ -245,6 +248,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 
 #ifdef KVR_STATS
     long long st[6] = {0, 0, 0, 0, 0, 0};
+    st[5] = __builtin_readcyclecounter() - st_begin;   // prologue: scores, norm pass
 #endif
     while (t < b) {
 #ifdef KVR_STATS
@@ -535,7 +539,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #ifdef KVR_STATS
     lds_barrier();
     if (tid == 0 && b >= 8) {
-      for (int q = 0; q < 5; ++q) gain_l[b - 1 - q] = static_cast<float>(st[q]);
+      for (int q = 0; q < 6; ++q) gain_l[b - 1 - q] = static_cast<float>(st[q]);
     }
 #endif
   }
@@ -587,6 +591,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   }
   if (a.K_out || a.V_out)
     compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
+#ifdef KVR_STATS
+  if (tid == 0 && a.pick_gain && b >= 8)
+    a.pick_gain[ob + b - 7] = static_cast<float>(__builtin_readcyclecounter() - st_begin);   // whole head
+#endif
 }
 
 bool pool_supported(const Layout& lay, int b) {
