@@ -469,35 +469,38 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
             pr[at][i] = ri < np ? pend_r[ri] : 0.f;
           }
         }
-        uint4 pre[4][LPC];                           // the next 64 tokens of this wave, in flight
-        auto fetch = [&](int kk) {
+        // Two 64-token groups of this wave are in flight: the registers of a 16-token sub-block
+        // are refilled for the group after next as soon as they have been written to the stage.
+        // Rows past n are clamped to the last row (their results belong to padding tokens, whose
+        // scores are -inf), so the loads are straight-line code.
+        constexpr int kDepth = 2;
+        uint4 preA[4][LPC], preB[4][LPC];              // even and odd groups
+        auto fetch = [&](int kk, int sub, int slot) {
           int row0 = base + (lane >> 4);
           asm volatile("" : "+v"(row0));             // keep the unrolled pass from hoarding addresses
 #pragma unroll
-          for (int sub = 0; sub < 4; ++sub)
-#pragma unroll
-            for (int q = 0; q < LPC; ++q) {
-              const int row = row0 + (kk * 4 + sub) * CH + 4 * q;
-              pre[sub][q] = make_uint4(0u, 0u, 0u, 0u);
-              if (row < n) pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
-            }
+          for (int q = 0; q < LPC; ++q) {
+            const int row = min(row0 + (kk * 4 + sub) * CH + 4 * q, n - 1);
+            const uint4 x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
+            if (slot == 0) preA[sub][q] = x; else preB[sub][q] = x;
+          }
         };
-        fetch(0);
+#pragma unroll
+        for (int g = 0; g < kDepth; ++g)
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub)
+            if (g < S) fetch(g, sub, g);
 #pragma unroll
         for (int k = 0; k < S; ++k) {
-          uint4 cur[4][LPC];
-#pragma unroll
-          for (int sub = 0; sub < 4; ++sub)
-#pragma unroll
-            for (int q = 0; q < LPC; ++q) cur[sub][q] = pre[sub][q];
-          if (k + 1 < S) fetch(k + 1);
           float part[4];                             // per 16-token sub-block: max over my four picked rows
 #pragma unroll
           for (int sub = 0; sub < 4; ++sub) {
             wave_lds_sync();
 #pragma unroll
             for (int q = 0; q < LPC; ++q)
-              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) = cur[sub][q];
+              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) =
+                  (k % kDepth == 0) ? preA[sub][q] : preB[sub][q];
+            if (k + kDepth < S) fetch(k + kDepth, sub, k % kDepth);
             wave_lds_sync();
             const char* fp = stage + (lane & 15) * kPoolPitch + kg * 16;
             bf16x8 bfr[4];
