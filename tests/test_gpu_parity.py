@@ -422,3 +422,25 @@ def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
         np.testing.assert_array_equal(out.pos_out[hh].cpu().numpy()[:bh], pos[hh].numpy()[idx[:bh]])
         assert np.all(out.pos_out[hh].cpu().numpy()[bh:] == -1)
 
+
+@pytest.mark.parametrize("n,b,dtype,G", [(8192, 24, torch.bfloat16, 0), (8192, 16, torch.float32, 64),
+                                         (4096, 1024, torch.bfloat16, 0), (4096, 256, torch.bfloat16, 8),
+                                         (256, 256, torch.bfloat16, 0), (192, 192, torch.float32, 0)])
+def test_maximum_sizes(n, b, dtype, G):
+    # the limits of the header (n = 8192, G = 64), of the pool (b = 256) and blocked (b = 1024)
+    # kernels, and budgets that keep every token
+    K, V, s = _mk(1, n, 8800 + n + b, dtype)
+    g = torch.Generator().manual_seed(n + b)
+    if G:
+        Q = torch.randn((1, G, 128), generator=g).to(dtype).to(DEV)
+        out = B().kvr_retain(K, V, b, 0.5, 1e-6, Q=Q)
+        data = {"K": K, "V": V, "Q": Q}
+    else:
+        out = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s)
+        data = {"K": K, "V": V, "s": s}
+    torch.cuda.synchronize()
+    rep = _check_heads(W.WORKLOADS["c3"], data, out, b, 0.5, 1e-6, [0])
+    assert rep["heads"] == 1
+    if b == n:
+        assert out.idx_sorted[0].cpu().tolist() == list(range(n))
+
