@@ -184,7 +184,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (heads shard with no exchange; "
-                 "see DESIGN.md); --gpus must be 1")
+                 "each GPU would run these kernels on its own slice); --gpus must be 1")
 
     import torch
     from paper_2605_14292_amd import binding as B

@@ -1,6 +1,6 @@
 """Comparison of the HIP path's picks with the fp64 oracle.
 
-The bar (stated by the benchmark spec and derived in the design doc):
+The bar:
   * index sets and pick order equal to the free-running oracle's, except at
     picks where the oracle's best two marginal gains are within NEAR_TIE
     (relative) of each other; after such a pick the two runs may legitimately
