@@ -186,6 +186,11 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
  *         tokens than b_h gives an unspecified subset of them.
  *   pos_in / pos_out  device, int32 [heads, n] / [heads, b_max] or NULL: position
  *         ids carried along with the kept rows
+ *   lambda_h  device, float32 [heads] or NULL: per-head penalty weights, all > 0
+ *         (the paper lists a lambda schedule among its untested extensions).  Head h
+ *         is selected with lambda_h[h]; `lambda` must then be > 0 and only sets the
+ *         scale the kernels run at (argmax of s - lambda_h m = argmax of
+ *         (lambda/lambda_h) s - lambda m); pick_gain is reported for lambda_h[h]
  *   s_work  device, float32 [heads, n], required: receives the scores the
  *         selection ran on (computed from Q when Q is given, masked to -inf past
  *         n_h, protected tokens raised by a per-head offset)
@@ -201,8 +206,8 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
  */
 int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, const float* s_in,
                         const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
-                        const uint8_t* keep, const int32_t* pos_in, float lambda, float eps,
-                        float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                        const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
+                        float eps, float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                         void* K_out, void* V_out, int32_t* pos_out, void* stream);
 
 #ifdef __cplusplus

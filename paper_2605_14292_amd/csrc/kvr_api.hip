@@ -185,8 +185,8 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
 
 int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, const float* s_in,
                         const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
-                        const uint8_t* keep, const int32_t* pos_in, float lambda, float eps,
-                        float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                        const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
+                        float eps, float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                         void* K_out, void* V_out, int32_t* pos_out, void* stream) {
   const int rc = check_select(lay, b_max, lambda, eps);
   if (rc) return rc;
@@ -195,6 +195,7 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
   if (Q && (G < 1 || !K)) return KVR_ERR_ARG;
   if (Q && G > KVR_MAX_G) return KVR_ERR_UNSUPPORTED;
   if ((K_out && !K) || (pos_out && !pos_in)) return KVR_ERR_ARG;
+  if (lambda_h && !(lambda > 0.0f)) return KVR_ERR_ARG;   // per-head values rescale a positive launch lambda
   if (!aligned16(V) || !aligned16(s_work) || (K && !aligned16(K)) || (Q && !aligned16(Q)) ||
       (s_in && !aligned16(s_in)) || (K_out && !aligned16(K_out)) || (V_out && !aligned16(V_out)))
     return KVR_ERR_ARG;
@@ -205,10 +206,11 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
     if (kvr::launch_score(K, Q, G, l, s_work, st) != hipSuccess) return KVR_ERR_HIP;
     src = s_work;
   }
-  if (kvr::launch_budget_prepare(src, l, n_h, keep, lambda, s_work, st) != hipSuccess) return KVR_ERR_HIP;
+  if (kvr::launch_budget_prepare(src, l, n_h, keep, lambda_h, lambda, s_work, st) != hipSuccess)
+    return KVR_ERR_HIP;
   if (select_only(V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)
     return KVR_ERR_HIP;
-  if (kvr::launch_budget_finalize(K, V, l, b_h, b_max, keep, pos_in, idx_sorted, pick_order, pick_gain,
+  if (kvr::launch_budget_finalize(K, V, l, b_h, b_max, keep, lambda_h, lambda, pos_in, idx_sorted, pick_order, pick_gain,
                                   K_out, V_out, pos_out, st) != hipSuccess)
     return KVR_ERR_HIP;
   return KVR_OK;

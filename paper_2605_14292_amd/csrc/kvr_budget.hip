@@ -7,6 +7,9 @@
 //             protected token then wins before any other one, so after |protected| picks S is the
 //             protected set and m holds its penalties, whatever the order they went in; from
 //             there the picks are exactly Algorithm 1's continuation.
+//             A per-head lambda_h is folded in here too: the argmax of s - lambda_h m is the
+//             argmax of (lambda/lambda_h) s - lambda m, so the head's scores are scaled and the
+//             kernels run with the one lambda of the launch; finalize scales the gains back.
 //   finalize  Algorithm 1's picks for budget b_h are the first b_h picks of the run for
 //             b_max >= b_h (each pick depends on the earlier ones only): the first b_h picks are
 //             flagged in a bitmap, read out ascending, and the rows (and position ids) at those
@@ -20,14 +23,16 @@ constexpr int kBudThreads = 256;
 
 __global__ __launch_bounds__(kBudThreads) void budget_prepare_kernel(
     const float* __restrict__ s_src, int n, const int32_t* __restrict__ n_h,
-    const uint8_t* __restrict__ keep, float lambda, float* __restrict__ s_work) {
+    const uint8_t* __restrict__ keep, const float* __restrict__ lambda_h, float lambda,
+    float* __restrict__ s_work) {
   __shared__ float red_lo[kBudThreads / 64], red_hi[kBudThreads / 64];
   const int h = blockIdx.x, tid = threadIdx.x;
   const long long base = static_cast<long long>(h) * n;
   const int nh = n_h ? min(max(n_h[h], 0), n) : n;
+  const float sc = lambda_h ? lambda / lambda_h[h] : 1.0f;     // lambda_h > 0 by contract
   float lo = INFINITY, hi = -INFINITY;
   for (int j = tid; j < nh; j += kBudThreads) {
-    const float v = s_src[base + j];
+    const float v = s_src[base + j] * sc;
     if (v > -INFINITY && v < INFINITY) { lo = fminf(lo, v); hi = fmaxf(hi, v); }
   }
 #pragma unroll
@@ -44,7 +49,7 @@ __global__ __launch_bounds__(kBudThreads) void budget_prepare_kernel(
   for (int j = tid; j < n; j += kBudThreads) {
     float v = -INFINITY;
     if (j < nh) {
-      v = s_src[base + j];
+      v = s_src[base + j] * sc;
       if (keep && keep[base + j]) v += C;
     }
     s_work[base + j] = v;
@@ -54,7 +59,7 @@ __global__ __launch_bounds__(kBudThreads) void budget_prepare_kernel(
 __global__ __launch_bounds__(kBudThreads) void budget_finalize_kernel(
     const char* __restrict__ K, const char* __restrict__ V, Layout lay, int ebytes,
     const int32_t* __restrict__ b_h, int b_max, const uint8_t* __restrict__ keep,
-    const int32_t* __restrict__ pos_in, int32_t* __restrict__ idx_sorted,
+    const float* __restrict__ lambda_h, float lambda, const int32_t* __restrict__ pos_in, int32_t* __restrict__ idx_sorted,
     int32_t* __restrict__ pick_order, float* __restrict__ pick_gain, char* __restrict__ K_out,
     char* __restrict__ V_out, int32_t* __restrict__ pos_out) {
   extern __shared__ __align__(16) int32_t sm[];
@@ -65,6 +70,7 @@ __global__ __launch_bounds__(kBudThreads) void budget_finalize_kernel(
   const int h = blockIdx.x, tid = threadIdx.x;
   const long long ob = static_cast<long long>(h) * b_max;
   const int bh = b_h ? min(max(b_h[h], 0), b_max) : b_max;
+  const float unscale = lambda_h ? lambda_h[h] / lambda : 1.0f;
   for (int w = tid; w < words; w += kBudThreads) bits[w] = 0u;
   for (int t = tid; t < b_max; t += kBudThreads) il[t] = -1;
   __syncthreads();
@@ -72,8 +78,12 @@ __global__ __launch_bounds__(kBudThreads) void budget_finalize_kernel(
     const int i = pick_order[ob + t];
     if (t < bh) {
       if (i >= 0 && i < n) atomicOr(&bits[i >> 5], 1u << (i & 31));
-      if (keep && i >= 0 && i < n && keep[static_cast<long long>(h) * n + i] && pick_gain)
-        pick_gain[ob + t] = INFINITY;                          // kept unconditionally, not by its gain
+      if (pick_gain) {
+        if (keep && i >= 0 && i < n && keep[static_cast<long long>(h) * n + i])
+          pick_gain[ob + t] = INFINITY;                        // kept unconditionally, not by its gain
+        else if (lambda_h)
+          pick_gain[ob + t] *= unscale;                        // back to s - lambda_h m
+      }
     } else {
       pick_order[ob + t] = -1;
       if (pick_gain) pick_gain[ob + t] = -INFINITY;
@@ -130,22 +140,24 @@ __global__ __launch_bounds__(kBudThreads) void budget_finalize_kernel(
 }
 
 hipError_t launch_budget_prepare(const float* s_src, const Layout& lay, const int32_t* n_h,
-                                 const uint8_t* keep, float lambda, float* s_work, hipStream_t st) {
+                                 const uint8_t* keep, const float* lambda_h, float lambda, float* s_work,
+                                 hipStream_t st) {
   hipLaunchKernelGGL(budget_prepare_kernel, dim3(lay.heads), dim3(kBudThreads), 0, st, s_src, lay.n, n_h,
-                     keep, lambda, s_work);
+                     keep, lambda_h, lambda, s_work);
   return hipGetLastError();
 }
 
 hipError_t launch_budget_finalize(const void* K, const void* V, const Layout& lay, const int32_t* b_h,
-                                  int b_max, const uint8_t* keep, const int32_t* pos_in, int32_t* idx_sorted,
-                                  int32_t* pick_order, float* pick_gain, void* K_out, void* V_out,
-                                  int32_t* pos_out, hipStream_t st) {
+                                  int b_max, const uint8_t* keep, const float* lambda_h, float lambda,
+                                  const int32_t* pos_in, int32_t* idx_sorted, int32_t* pick_order,
+                                  float* pick_gain, void* K_out, void* V_out, int32_t* pos_out,
+                                  hipStream_t st) {
   const int words = (lay.n + 31) >> 5;
   const size_t smem = (2 * static_cast<size_t>(words) + b_max) * 4;
   const int ebytes = lay.dtype == DT_BF16 ? 2 : 4;
   hipLaunchKernelGGL(budget_finalize_kernel, dim3(lay.heads), dim3(kBudThreads), smem, st,
                      static_cast<const char*>(K), static_cast<const char*>(V), lay, ebytes, b_h, b_max, keep,
-                     pos_in, idx_sorted, pick_order, pick_gain, static_cast<char*>(K_out),
+                     lambda_h, lambda, pos_in, idx_sorted, pick_order, pick_gain, static_cast<char*>(K_out),
                      static_cast<char*>(V_out), pos_out);
   return hipGetLastError();
 }

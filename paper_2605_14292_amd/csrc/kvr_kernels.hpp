@@ -48,11 +48,13 @@ hipError_t launch_retain_pruned(const void* K, const void* V, const float* s, co
 // Budget allocator frame (per-head candidate counts, budgets, protected tokens): score masking
 // and offsets before the selection, prefix cut, ascending read-out and row copy after it.
 hipError_t launch_budget_prepare(const float* s_src, const Layout& lay, const int32_t* n_h,
-                                 const uint8_t* keep, float lambda, float* s_work, hipStream_t st);
+                                 const uint8_t* keep, const float* lambda_h, float lambda, float* s_work,
+                                 hipStream_t st);
 hipError_t launch_budget_finalize(const void* K, const void* V, const Layout& lay, const int32_t* b_h,
-                                  int b_max, const uint8_t* keep, const int32_t* pos_in, int32_t* idx_sorted,
-                                  int32_t* pick_order, float* pick_gain, void* K_out, void* V_out,
-                                  int32_t* pos_out, hipStream_t st);
+                                  int b_max, const uint8_t* keep, const float* lambda_h, float lambda,
+                                  const int32_t* pos_in, int32_t* idx_sorted, int32_t* pick_order,
+                                  float* pick_gain, void* K_out, void* V_out, int32_t* pos_out,
+                                  hipStream_t st);
 
 // Speculative row-block path for bf16 heads with 256 < n <= 4096 (selection plus
 // optional compaction; scores come in through s).

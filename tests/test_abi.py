@@ -110,13 +110,14 @@ def test_budgeted_argument_errors_are_host_side():
     lay = _lay()
     rb = L.kvr_retain_budgeted
     ok_tail = (fake, fake, fake, fake, fake, fake, None, None)        # s_work .. stream
-    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 65, None, None, 0.5, 1e-6, *ok_tail) == B.KVR_ERR_ARG
-    assert rb(fake, fake, None, 0, None, ctypes.byref(lay), None, None, 8, None, None, 0.5, 1e-6, *ok_tail) == B.KVR_ERR_ARG
-    assert rb(fake, fake, fake, 1, fake, ctypes.byref(lay), None, None, 8, None, None, 0.5, 1e-6, *ok_tail) == B.KVR_ERR_ARG
-    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 8, None, None, 0.5, 1e-6,
+    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 65, None, None, None, 0.5, 1e-6, *ok_tail) == B.KVR_ERR_ARG
+    assert rb(fake, fake, None, 0, None, ctypes.byref(lay), None, None, 8, None, None, None, 0.5, 1e-6, *ok_tail) == B.KVR_ERR_ARG
+    assert rb(fake, fake, fake, 1, fake, ctypes.byref(lay), None, None, 8, None, None, None, 0.5, 1e-6, *ok_tail) == B.KVR_ERR_ARG
+    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 8, None, None, None, 0.5, 1e-6,
               None, fake, fake, fake, fake, fake, None, None) == B.KVR_ERR_ARG                       # no s_work
-    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 8, None, None, 0.5, 1e-6,
+    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 8, None, None, None, 0.5, 1e-6,
               fake, fake, None, fake, fake, fake, None, None) == B.KVR_ERR_ARG                       # no pick_order
-    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 8, None, None, 0.5, 1e-6,
+    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 8, None, None, None, 0.5, 1e-6,
               fake, fake, fake, fake, fake, fake, fake, None) == B.KVR_ERR_ARG                       # pos_out without pos_in
+    assert rb(fake, fake, None, 0, fake, ctypes.byref(lay), None, None, 8, None, None, fake, 0.0, 1e-6, *ok_tail) == B.KVR_ERR_ARG   # lambda_h needs lambda > 0
 

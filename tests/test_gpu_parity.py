@@ -444,3 +444,24 @@ def test_maximum_sizes(n, b, dtype, G):
     if b == n:
         assert out.idx_sorted[0].cpu().tolist() == list(range(n))
 
+
+@pytest.mark.parametrize("n,b_max", [(192, 64), (600, 48)])
+def test_budgeted_per_head_lambda(n, b_max):
+    # head h runs with lambda_h[h]: the kernels see scores scaled by lambda/lambda_h and the one
+    # launch lambda, the gains come back on the head's own scale
+    h = 6
+    K, V, s = _mk(h, n, 6100 + n)
+    V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
+    lam_h = torch.tensor([0.05, 0.25, 0.5, 1.0, 2.0, 0.5], dtype=torch.float32)
+    b_h = torch.tensor([b_max, b_max, b_max - 3, b_max, 7, b_max], dtype=torch.int32)
+    out = B().kvr_retain_budgeted(K, V, b_max, 0.5, 1e-6, s=s, b_h=b_h.to(DEV), lam_h=lam_h.to(DEV))
+    torch.cuda.synchronize()
+    for hh in range(h):
+        bh, lam = int(b_h[hh]), float(lam_h[hh])
+        P.check_head(W.to_f64(s[hh]), W.to_f64(V[hh]), bh, lam, 1e-6, out.pick_order[hh].cpu().numpy()[:bh],
+                     out.pick_gain[hh].cpu().numpy()[:bh], out.idx_sorted[hh].cpu().numpy()[:bh])
+    # heads 2 and 5 share lambda = the launch lambda: their scores went through unscaled
+    same = B().kvr_retain(K[5:6].contiguous(), V[5:6].contiguous(), b_max, 0.5, 1e-6, s=s[5:6].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(same.pick_order[0], out.pick_order[5]) and torch.equal(same.pick_gain[0], out.pick_gain[5])
+
