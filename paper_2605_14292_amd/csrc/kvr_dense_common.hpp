@@ -95,22 +95,23 @@ __device__ __forceinline__ int first_of_pairs(unsigned long long e0, unsigned lo
   return i;
 }
 // The same for NQ tokens per lane (token NQ*lane + q in slot q): lowest lane first, lowest slot
-// within the lane.  -1 - (NQ - 1) .. -1 when all masks are empty (callers treat any negative
-// value as "none").
+// within the lane.  Negative (-NQ .. -1) when all masks are empty.
 template <int NQ>
 __device__ __forceinline__ int first_of_slots(const unsigned long long (&e)[NQ]) {
   if constexpr (NQ == 2) {
     return first_of_pairs(e[0], e[1]);
   } else {
-    unsigned long long any = e[0];
+    // slot q's first winner is token NQ*ff1(e[q]) + q; an empty mask gives -NQ + q, which is
+    // huge as an unsigned number, so the unsigned minimum over the slots is the answer
+    unsigned best = 0xffffffffu;
 #pragma unroll
-    for (int q = 1; q < NQ; ++q) any |= e[q];
-    int L;
-    asm("s_ff1_i32_b64 %0, %1" : "=s"(L) : "s"(any));   // -1 for an empty mask
-    int qsel = NQ - 1;
-#pragma unroll
-    for (int q = NQ - 2; q >= 0; --q) qsel = ((e[q] >> (L & 63)) & 1ull) ? q : qsel;
-    return NQ * L + (L < 0 ? 0 : qsel);
+    for (int q = 0; q < NQ; ++q) {
+      int L;
+      asm("s_ff1_i32_b64 %0, %1" : "=s"(L) : "s"(e[q]));   // -1 for an empty mask
+      const unsigned cand = static_cast<unsigned>(L * NQ + q);
+      best = cand < best ? cand : best;
+    }
+    return static_cast<int>(best);
   }
 }
 // max / sum over each half of the wave (lanes 0-31 and 32-63); valid in lanes 31 and 63
@@ -178,9 +179,9 @@ __device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, co
 // from the logged gains: the picks before the first one without a finite gain are kept and the
 // list is filled up with the lowest tokens < n_live not yet in it.  `diverse` false is the
 // lambda = 0 branch (top-b, the triangle is not read).  Returns the gain of the last pick.
-template <int NQ>
-__device__ __forceinline__ float pick_chain(const float* s_l, const float* tri, int32_t* order_l, float* gain_l,
-                                            int n_live, int b, float lambda, bool diverse, int lane) {
+template <int NQ, bool DIVERSE>
+__device__ __forceinline__ float pick_chain_impl(const float* s_l, const float* tri, int32_t* order_l, float* gain_l,
+                                                 int n_live, int b, float lambda, int lane) {
   typedef __attribute__((address_space(3))) const float* lds_fp;
   const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
       (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
@@ -213,7 +214,7 @@ __device__ __forceinline__ float pick_chain(const float* s_l, const float* tri, 
       for (int q = 0; q < NQ; ++q) e[q] = __ballot(av[q] == amax);
       const int i = first_of_slots<NQ>(e);             // negative when nothing compares equal (NaN)
       write_lane2(rec_i, rec_g, i, __float_as_int(amax), u);
-      if (diverse) {
+      if constexpr (DIVERSE) {
         // element (i,j) sits at max(T(i)+j, T(j)+i); the diagonal entry (+inf) retires the pick.
         // For any i in [-NQ, 64*NQ) both addresses stay inside the triangle.
         const int ti4 = i * (i + 1) * 2, i4 = i * 4;
@@ -254,6 +255,13 @@ __device__ __forceinline__ float pick_chain(const float* s_l, const float* tri, 
     last_g = -INFINITY;
   }
   return last_g;
+}
+
+template <int NQ>
+__device__ __forceinline__ float pick_chain(const float* s_l, const float* tri, int32_t* order_l, float* gain_l,
+                                            int n_live, int b, float lambda, bool diverse, int lane) {
+  return diverse ? pick_chain_impl<NQ, true>(s_l, tri, order_l, gain_l, n_live, b, lambda, lane)
+                 : pick_chain_impl<NQ, false>(s_l, tri, order_l, gain_l, n_live, b, lambda, lane);
 }
 
 // sort(S) on one wave: flags the b picks of order_l (indices < 64*NQ), writes them in ascending
