@@ -465,3 +465,32 @@ def test_budgeted_per_head_lambda(n, b_max):
     torch.cuda.synchronize()
     assert torch.equal(same.pick_order[0], out.pick_order[5]) and torch.equal(same.pick_gain[0], out.pick_gain[5])
 
+
+@pytest.mark.parametrize("n,dtype", [(200, torch.bfloat16), (150, torch.float32), (700, torch.bfloat16)])
+def test_strided_layouts_in_every_mode(n, dtype):
+    # K and V are views into larger buffers (token stride 136, extra tokens per head): the
+    # strided calls must give what the same calls give on contiguous copies
+    h, b, group = 6, 40, 3
+    g = torch.Generator(device="cpu").manual_seed(19 + n)
+    bigk = torch.randn((h, n + 5, 136), generator=g).to(dtype).to(DEV)
+    bigv = torch.randn((h, n + 5, 136), generator=g).to(dtype).to(DEV)
+    K, V = bigk[:, :n, :128], bigv[:, :n, :128]
+    Kc, Vc = K.contiguous(), V.contiguous()
+    s = torch.randn((h, n), generator=g).exp().to(DEV)
+    a, c = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s), B().kvr_retain(Kc, Vc, b, 0.5, 1e-6, s=s)
+    torch.cuda.synchronize()
+    assert torch.equal(a.pick_order, c.pick_order) and torch.equal(a.K_out, c.K_out) and torch.equal(a.V_out, c.V_out)
+    _check_heads(W.WORKLOADS["c3"], {"K": Kc, "V": Vc, "s": s}, a, b, 0.5, 1e-6, range(h))
+    sf = s[: h // group].contiguous()
+    a, c = B().kvr_retain_flat(K, V, sf, group, b, 0.5, 1e-6), B().kvr_retain_flat(Kc, Vc, sf, group, b, 0.5, 1e-6)
+    torch.cuda.synchronize()
+    assert torch.equal(a.u_out, c.u_out) and torch.equal(a.pick_order, c.pick_order)
+    assert torch.equal(a.K_out, c.K_out) and torch.equal(a.V_out, c.V_out)
+    b_h = torch.tensor([b, b - 3, 5, b, 1, b // 2], dtype=torch.int32, device=DEV)
+    keep = torch.zeros((h, n), dtype=torch.uint8, device=DEV)
+    keep[:, :2] = 1
+    a = B().kvr_retain_budgeted(K, V, b, 0.5, 1e-6, s=s, b_h=b_h, keep=keep)
+    c = B().kvr_retain_budgeted(Kc, Vc, b, 0.5, 1e-6, s=s, b_h=b_h, keep=keep)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx_sorted, c.idx_sorted) and torch.equal(a.K_out, c.K_out) and torch.equal(a.V_out, c.V_out)
+
