@@ -247,43 +247,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
         for (int sl = 0; sl < MAXT; ++sl) {
           const int I = sl < n1 ? NT - 1 - wave : wave;
           const int J = sl < n1 ? sl : sl - n1;
-          const int j = J * 32 + (lane & 31);
-          const float rc = rinv[j];
-          int i = I * 32 + hf * 4;                    // first of this lane's rows in the tile
-          int off = i * (i + 1) / 2 + j;              // T(i) + j; T(i+1) = T(i) + i + 1
-          if (I != J) {
-#pragma unroll
-            for (int R = 0; R < 4; ++R) {
-              const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
-              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-              int o = off;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                tri[o] = acc[sl][R * 4 + q] * rrow[q] * rc;
-                o += i + q + 1;
-              }
-              off += 8 * i + 36;                      // T(i+8) - T(i)
-              i += 8;
-            }
-          } else {
-            // Diagonal tile: only j <= i is stored, and (i,i) holds +inf: reading the row of a
-            // pick drives the pick's own m to +inf and its gain to -inf, which is how a
-            // selected token leaves the race.
-#pragma unroll
-            for (int R = 0; R < 4; ++R) {
-              const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
-              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-              int o = off;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                const float c = j == i + q ? INFINITY : acc[sl][R * 4 + q] * rrow[q] * rc;
-                if (j <= i + q) tri[o] = c;
-                o += i + q + 1;
-              }
-              off += 8 * i + 36;
-              i += 8;
-            }
-          }
+          write_cos_tile(tri, rinv, acc[sl], I, J, lane);
         }
       }
     }

@@ -332,41 +332,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           for (int ks = 0; ks < 8; ++ks)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pa + ks * 32),
                                                           *reinterpret_cast<const bf16x8*>(pb + ks * 32), acc, 0, 0, 0);
-          const int j = J * 32 + (lane & 31);
-          const float rc = pool_r[j];
-          int i = I * 32 + hf * 4;
-          int off = i * (i + 1) / 2 + j;               // T(i) + j; T(i+1) = T(i) + i + 1
-          if (I != J) {
-#pragma unroll
-            for (int R = 0; R < 4; ++R) {
-              const float4 rr = *reinterpret_cast<const float4*>(pool_r + i);
-              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-              int o = off;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                tri[o] = acc[R * 4 + q] * rrow[q] * rc;
-                o += i + q + 1;
-              }
-              off += 8 * i + 36;
-              i += 8;
-            }
-          } else {
-#pragma unroll
-            for (int R = 0; R < 4; ++R) {
-              const float4 rr = *reinterpret_cast<const float4*>(pool_r + i);
-              const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
-              int o = off;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                // the diagonal holds +inf: the row of a pick retires the pick itself
-                const float c = j == i + q ? INFINITY : acc[R * 4 + q] * rrow[q] * rc;
-                if (j <= i + q) tri[o] = c;
-                o += i + q + 1;
-              }
-              off += 8 * i + 36;
-              i += 8;
-            }
-          }
+          write_cos_tile(tri, pool_r, acc, I, J, lane);   // the diagonal holds +inf: the row of a pick retires it
         }
       }
       lds_barrier();
