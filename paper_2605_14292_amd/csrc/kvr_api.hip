@@ -147,22 +147,28 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const kvr::Layout l = to_dev(lay);
   const float* s = s_in;
-  if (kvr::pruned_supported(l, b, lambda, Q != nullptr)) {
-    hipError_t e = kvr::launch_retain_pruned(K, V, s_in, l, b, lambda, eps, idx_sorted, pick_order,
-                                             pick_gain, K_out, V_out, st);
-    if (e == hipSuccess)
-      e = kvr::launch_retain_dense(K, V, nullptr, 0, s_in, l, b, lambda, eps, s_out, idx_sorted,
-                                   pick_order, pick_gain, K_out, V_out, st, true);
-    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
-  }
-  if (kvr::dense_supported(l, b, G, Q != nullptr)) {
-    const hipError_t e = kvr::launch_retain_dense(K, V, Q, G, s_in, l, b, lambda, eps, s_out, idx_sorted,
+  if (Q && kvr::dense_supported(l, b, G, true)) {       // short heads, few queries: scoring is fused too
+    const hipError_t e = kvr::launch_retain_dense(K, V, Q, G, nullptr, l, b, lambda, eps, s_out, idx_sorted,
                                                   pick_order, pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (Q) {
     if (kvr::launch_score(K, Q, G, l, s_out, st) != hipSuccess) return KVR_ERR_HIP;
     s = s_out;
+  }
+  // scores computed here are softmax means, far tighter than lambda: the score bound removes nothing
+  if (!Q && kvr::pruned_supported(l, b, lambda, false)) {
+    hipError_t e = kvr::launch_retain_pruned(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
+                                             pick_gain, K_out, V_out, st);
+    if (e == hipSuccess)
+      e = kvr::launch_retain_dense(K, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
+                                   pick_order, pick_gain, K_out, V_out, st, true);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+  }
+  if (kvr::dense_supported(l, b, 0, false)) {
+    const hipError_t e = kvr::launch_retain_dense(K, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
+                                                  pick_order, pick_gain, K_out, V_out, st);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (kvr::pool_supported(l, b)) {
     const hipError_t e = kvr::launch_select_pool(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,

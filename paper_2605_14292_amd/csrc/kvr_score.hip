@@ -171,7 +171,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
 }
 
 // ---------------------------------------------------------------------------
-// bf16, G <= 8: the logits are a thin dense contraction ([G x d] x [d x n]), so
+// bf16, G <= 32 (GQ = 8 or 32 query rows of the MFMA's 32-row operand in use): the logits are a thin dense contraction ([G x d] x [d x n]), so
 // they go through the matrix cores.  K is streamed from HBM once, 128 tokens at a
 // time: coalesced 16-byte loads into registers (the next chunk is in flight while
 // the current one is multiplied), a padded LDS stage, MFMA fragments out of LDS.
@@ -181,6 +181,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kStageTok = 128;
 constexpr int kStagePitch = 272;   // 256 + 16 bytes: consecutive rows land in different banks
 
+template <int GQ>
 __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* __restrict__ K,
                                                                    const char* __restrict__ Q, int G,
                                                                    Layout lay,
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
   char* stage = smem_raw;                                                   // [128][272]
   float* zbuf = reinterpret_cast<float*>(smem_raw + kStageTok * kStagePitch);  // [G][n]
   const int n = lay.n;
-  float* red = zbuf + G * n;                                                // [64]
+  float* red = zbuf + G * n;                                                // [2][4][GQ]
   const int h = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -232,55 +233,58 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], *reinterpret_cast<const bf16x8*>(fp + ks * 32), acc, 0, 0, 0);
     const int j = c * kStageTok + wave * 32 + (lane & 31);
     if (j < n) {
+      // lane (token, hf) holds query rows (r/4)*8 + hf*4 + r%4 of the 32x32 tile
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (hf * 4 + r < G) zbuf[(hf * 4 + r) * n + j] = acc[r] * scale;
+      for (int r = 0; r < GQ / 2; ++r) {
+        const int g = (r >> 2) * 8 + hf * 4 + (r & 3);
+        if (g < G) zbuf[g * n + j] = acc[r] * scale;
+      }
     }
   }
   __syncthreads();
   // softmax over the tokens for each query, then the mean over queries
-  float zmax[8], zsum[8];
+  float zmax[GQ], zsum[GQ];
 #pragma unroll
-  for (int g = 0; g < 8; ++g) { zmax[g] = -INFINITY; zsum[g] = 0.f; }
+  for (int g = 0; g < GQ; ++g) { zmax[g] = -INFINITY; zsum[g] = 0.f; }
   for (int j = tid; j < n; j += kScoreThreads)
 #pragma unroll
-    for (int g = 0; g < 8; ++g)
+    for (int g = 0; g < GQ; ++g)
       if (g < G) zmax[g] = fmaxf(zmax[g], zbuf[g * n + j]);
 #pragma unroll
-  for (int g = 0; g < 8; ++g) {
+  for (int g = 0; g < GQ; ++g) {
     float v = zmax[g];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    if (lane == 0) red[wave * 8 + g] = v;
+    if (lane == 0) red[wave * GQ + g] = v;
   }
   __syncthreads();
 #pragma unroll
-  for (int g = 0; g < 8; ++g) zmax[g] = fmaxf(fmaxf(red[g], red[8 + g]), fmaxf(red[16 + g], red[24 + g]));
+  for (int g = 0; g < GQ; ++g) zmax[g] = fmaxf(fmaxf(red[g], red[GQ + g]), fmaxf(red[2 * GQ + g], red[3 * GQ + g]));
   for (int j = tid; j < n; j += kScoreThreads)
 #pragma unroll
-    for (int g = 0; g < 8; ++g)
+    for (int g = 0; g < GQ; ++g)
       if (g < G) {
         const float e = __expf(zbuf[g * n + j] - zmax[g]);
         zbuf[g * n + j] = e;
         zsum[g] += e;
       }
 #pragma unroll
-  for (int g = 0; g < 8; ++g) {
+  for (int g = 0; g < GQ; ++g) {
     float v = zsum[g];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-    if (lane == 0) red[32 + wave * 8 + g] = v;
+    if (lane == 0) red[4 * GQ + wave * GQ + g] = v;
   }
   __syncthreads();
   const float invG = 1.0f / static_cast<float>(G);
-  float wgt[8];
+  float wgt[GQ];
 #pragma unroll
-  for (int g = 0; g < 8; ++g) wgt[g] = invG / (red[32 + g] + red[40 + g] + red[48 + g] + red[56 + g]);
+  for (int g = 0; g < GQ; ++g) wgt[g] = invG / (red[4 * GQ + g] + red[5 * GQ + g] + red[6 * GQ + g] + red[7 * GQ + g]);
   float* so = s_out + static_cast<long long>(h) * n;
   for (int j = tid; j < n; j += kScoreThreads) {
     float p = 0.f;
 #pragma unroll
-    for (int g = 0; g < 8; ++g)
+    for (int g = 0; g < GQ; ++g)
       if (g < G) p = fmaf(zbuf[g * n + j], wgt[g], p);
     so[j] = p;
   }
@@ -288,14 +292,19 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
 
 hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay, float* s_out,
                         hipStream_t st) {
-  if (lay.dtype == DT_BF16 && G <= 8 && static_cast<long long>(G) * lay.n <= 24576) {
-    const int smem_m = kStageTok * kStagePitch + (G * lay.n + 64) * 4;
-    const hipError_t em = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem_m);
-    if (em != hipSuccess) return em;
-    hipLaunchKernelGGL(score_mfma_kernel, dim3(lay.heads), dim3(kScoreThreads), smem_m, st,
-                       static_cast<const char*>(K), static_cast<const char*>(Q), G, lay, s_out);
-    return hipGetLastError();
+  // the logits of a head (G x n floats) wait in LDS beside the 35 KB stage
+  if (lay.dtype == DT_BF16 && G <= 32 && static_cast<long long>(G) * lay.n <= (G <= 8 ? 24576 : 31488)) {
+    const int gq = G <= 8 ? 8 : 32;
+    const int smem_m = kStageTok * kStagePitch + (G * lay.n + 8 * gq) * 4;
+    auto go_m = [&](auto kern) -> hipError_t {
+      const hipError_t em = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_m);
+      if (em != hipSuccess) return em;
+      hipLaunchKernelGGL(kern, dim3(lay.heads), dim3(kScoreThreads), smem_m, st,
+                         static_cast<const char*>(K), static_cast<const char*>(Q), G, lay, s_out);
+      return hipGetLastError();
+    };
+    return gq == 8 ? go_m(&score_mfma_kernel<8>) : go_m(&score_mfma_kernel<32>);
   }
   const bool zfits = static_cast<long long>(G) * lay.n <= kZMaxFloats;
   const size_t smem = (static_cast<size_t>(zfits ? G * lay.n : 0) + lay.n + 2 * kGT * 4) * 4;

@@ -494,3 +494,18 @@ def test_strided_layouts_in_every_mode(n, dtype):
     torch.cuda.synchronize()
     assert torch.equal(a.idx_sorted, c.idx_sorted) and torch.equal(a.K_out, c.K_out) and torch.equal(a.V_out, c.V_out)
 
+
+@pytest.mark.parametrize("n,G", [(200, 12), (256, 32), (900, 28), (984, 32), (1500, 20)])
+def test_scores_from_a_wide_query_window(n, G):
+    # G up to 32 queries per head (an observation window of several steps times the grouped
+    # queries) go through the matrix-core scorer as long as the logits fit the LDS
+    h, b = 3, 40
+    K, V, _ = _mk(h, n, 7700 + n + G)
+    g = torch.Generator().manual_seed(G * 1000 + n)
+    Q = torch.randn((h, G, 128), generator=g).to(torch.bfloat16).to(DEV)
+    out = B().kvr_retain(K, V, b, 0.5, 1e-6, Q=Q)
+    s = B().kvr_score(K, Q)
+    torch.cuda.synchronize()
+    torch.testing.assert_close(s, out.s_out, rtol=2e-5, atol=0)
+    _check_heads(W.WORKLOADS["c2"], {"K": K, "V": V, "Q": Q}, out, b, 0.5, 1e-6, range(h))
+
