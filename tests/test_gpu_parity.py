@@ -509,3 +509,42 @@ def test_scores_from_a_wide_query_window(n, G):
     torch.testing.assert_close(s, out.s_out, rtol=2e-5, atol=0)
     _check_heads(W.WORKLOADS["c2"], {"K": K, "V": V, "Q": Q}, out, b, 0.5, 1e-6, range(h))
 
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
+    # forty seeded cases per seed across every kernel the dispatch can choose: head lengths 1..4096,
+    # budgets 1..n, lambda in {0, .05, .5, 1, 3}, bf16 and fp32 rows, given scores of wide and tight
+    # spread (quantised now and then, so that ties occur), computed scores from 1..32 queries
+    rng = np.random.default_rng(seed)
+    for case in range(40):
+        dtype = torch.bfloat16 if rng.random() < 0.8 else torch.float32
+        nmax = 4096 if dtype == torch.bfloat16 else 600
+        n = int(rng.choice([rng.integers(1, 70), rng.integers(64, 260), rng.integers(257, nmax)]))
+        b = int(rng.integers(1, min(n, 300) + 1))
+        if rng.random() < 0.3:
+            b = min(n, int(rng.choice([1, 2, 64, 128, n])))
+        lam = float(rng.choice([0.0, 0.05, 0.5, 1.0, 3.0]))
+        h = int(rng.integers(1, 4))
+        kind = rng.choice(["given_wide", "given_tight", "computed"])
+        g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+        K = torch.randn((h, n, 128), generator=g).to(dtype).to(DEV)
+        V = torch.randn((h, n, 128), generator=g).to(dtype)
+        if rng.random() < 0.5 and n > 4:
+            V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
+        V = V.to(DEV)
+        data = {"K": K, "V": V}
+        if kind == "computed":
+            G = int(rng.choice([1, 4, 7, 8, 12, 32]))
+            data["Q"] = torch.randn((h, G, 128), generator=g).to(dtype).to(DEV)
+        else:
+            s = torch.randn((h, n), generator=g).exp() * (1.0 if kind == "given_wide" else 0.01)
+            if rng.random() < 0.2:
+                s = torch.floor(s * 4) / 4
+            data["s"] = s.to(DEV)
+        out = B().kvr_retain(K, V, b, lam, 1e-6, Q=data.get("Q"), s=data.get("s"))
+        torch.cuda.synchronize()
+        try:
+            _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, range(h))
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: n={n} b={b} lambda={lam} heads={h} {kind} {dtype}: {e}") from e
+
