@@ -157,6 +157,24 @@ int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int 
                        const int32_t* idx, int b, void* K_out, void* V_out, void* stream);
 
 /*
+ * The cache update of Algorithm 1's return value done inside the cache's own
+ * storage, as an eviction step of a serving loop does it (the paper's method
+ * returns sort(S) and leaves the storage to the caller):
+ *   K[h, t, :] = K[h, idx[h / group, t], :] for t < b, the same for V and for
+ *   pos[h, t] = pos[h, idx[h / group, t]]; rows t >= b keep their old contents.
+ *   K, V  device, [heads, n, d] per `lay`, updated in place; either may be NULL
+ *   idx   device, int32 [heads/group, b].  Each row must be strictly ascending
+ *         over its entries >= 0 (idx_sorted of the calls above is) and entry t,
+ *         when >= 0, must be >= t; entries < 0 (the padding kvr_retain_budgeted
+ *         writes past a head's own budget) move nothing.  A row that is not
+ *         ascending gives unspecified (in-bounds) contents.
+ *   pos   device, dense int32 [heads, n] or NULL
+ * Overlapping calls on the same tensors race.
+ */
+int kvr_compact_inplace(void* K, void* V, const kvr_layout* lay, int group,
+                        const int32_t* idx, int b, int32_t* pos, void* stream);
+
+/*
  * The whole flat-mode event: signature -> select (one problem per sequence) ->
  * compaction of every head of the sequence with the shared index set.
  *   s           device, dense float32 [heads/group, n]: one score vector per sequence

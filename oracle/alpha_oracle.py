@@ -207,6 +207,19 @@ def compact(X: np.ndarray, idx_sorted: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(X)[np.asarray(idx_sorted)])
 
 
+def compact_inplace(X: np.ndarray, idx_sorted: np.ndarray) -> np.ndarray:
+    """The cache update done in the cache's own rows, one row after the other as a serving
+    loop would: row t receives row idx_sorted[t], lowest t first; entries < 0 move nothing and
+    rows past the list keep their contents.  For the strictly ascending list Algorithm 1
+    returns (sort(S), so idx_sorted[t] >= t) no source row has been overwritten when it is
+    read, and the front of the result equals compact(X, idx_sorted)."""
+    Y = np.array(X, copy=True)
+    for t, i in enumerate(np.asarray(idx_sorted).tolist()):
+        if i >= 0:
+            Y[t] = Y[i]
+    return Y
+
+
 def retain(K, V, k: int, lam: float, eps: float = 1e-6, Q=None, s=None):
     """Whole event for one head: score (unless given), select, and the
     sorted index set.  K, V are float64 views of the cached rows."""

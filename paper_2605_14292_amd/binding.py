@@ -20,7 +20,8 @@ KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1
 
 EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
            "kvr_select_greedy", "kvr_compact", "kvr_retain",
-           "kvr_signature_flat", "kvr_compact_shared", "kvr_retain_flat", "kvr_retain_budgeted")
+           "kvr_signature_flat", "kvr_compact_shared", "kvr_compact_inplace", "kvr_retain_flat",
+           "kvr_retain_budgeted")
 
 
 class kvr_layout(ctypes.Structure):
@@ -61,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.kvr_signature_flat.argtypes = [vp, lp, i32, vp, vp]
     lib.kvr_compact_shared.restype = i32
     lib.kvr_compact_shared.argtypes = [vp, vp, lp, i32, vp, i32, vp, vp, vp]
+    lib.kvr_compact_inplace.restype = i32
+    lib.kvr_compact_inplace.argtypes = [vp, vp, lp, i32, vp, i32, vp, vp]
     lib.kvr_retain_flat.restype = i32
     lib.kvr_retain_flat.argtypes = [vp, vp, vp, lp, i32, i32, f32, f32, vp, vp, vp, vp, vp, vp, vp]
     lib.kvr_retain_budgeted.restype = i32
@@ -219,6 +222,20 @@ def kvr_compact_shared(K, V, idx, group, K_out=None, V_out=None, stream=None):
     _check(_lib.kvr_compact_shared(_ptr(K), _ptr(V), ctypes.byref(lay), group, _ptr(idx), b,
                                    _ptr(K_out), _ptr(V_out), _stream(stream)), "kvr_compact_shared")
     return K_out, V_out
+
+
+def kvr_compact_inplace(K, V, idx, group=1, pos=None, stream=None):
+    """Moves the kept rows to the front of each head inside K and V (and pos) themselves."""
+    _need_cuda(K, V, idx, pos)
+    ref = K if K is not None else V
+    if ref is None:
+        raise ValueError("kvr_compact_inplace needs K or V (the layout comes from them)")
+    lay = layout_of(ref)
+    if pos is not None and (pos.dtype != torch.int32 or tuple(pos.shape) != (lay.heads, lay.n)
+                            or not pos.is_contiguous()):
+        raise ValueError("pos must be a contiguous int32 [heads, n] tensor")
+    _check(_lib.kvr_compact_inplace(_ptr(K), _ptr(V), ctypes.byref(lay), group, _ptr(idx), idx.shape[1],
+                                    _ptr(pos), _stream(stream)), "kvr_compact_inplace")
 
 
 class FlatBuffers:

@@ -245,6 +245,18 @@ int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int 
   return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
 }
 
+int kvr_compact_inplace(void* K, void* V, const kvr_layout* lay, int group, const int32_t* idx, int b,
+                        int32_t* pos, void* stream) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (b < 1 || b > lay->n || !idx || group < 1 || lay->heads % group != 0) return KVR_ERR_ARG;
+  if (!K && !V && !pos) return KVR_ERR_ARG;
+  if ((K && !aligned16(K)) || (V && !aligned16(V))) return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_compact_inplace(K, V, to_dev(lay), idx, group, b, pos,
+                                                   static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
 int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layout* lay, int group, int b,
                     float lambda, float eps, float* u_out, int32_t* idx_sorted, int32_t* pick_order,
                     float* pick_gain, void* K_out, void* V_out, void* stream) {

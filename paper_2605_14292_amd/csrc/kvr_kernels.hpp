@@ -18,6 +18,10 @@ hipError_t launch_select_generic(const void* V, const float* s, const Layout& la
 // idx_group consecutive heads share one row of idx (1: every head has its own).
 hipError_t launch_compact(const void* K, const void* V, const Layout& lay, const int32_t* idx,
                           int b, void* K_out, void* V_out, hipStream_t st, int idx_group = 1);
+// The same move inside K and V themselves (rows 0..b-1 of each head receive the kept rows);
+// pos: dense int32 [heads, n] moved alike, or null.  Index rows must be strictly ascending.
+hipError_t launch_compact_inplace(void* K, void* V, const Layout& lay, const int32_t* idx, int idx_group,
+                                  int b, int32_t* pos, hipStream_t st);
 
 // Mean of V over each run of `group` consecutive heads: u_out is dense fp32 [heads/group, n, d].
 hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, float* u_out, hipStream_t st);

@@ -97,6 +97,12 @@ def test_flat_mode_argument_errors_are_host_side():
     assert L.kvr_signature_flat(None, ctypes.byref(lay), 3, fake, None) == B.KVR_ERR_ARG
     assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 4, fake, 8, fake, fake, None) == B.KVR_ERR_ARG
     assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 3, None, 8, fake, fake, None) == B.KVR_ERR_ARG
+    ci = L.kvr_compact_inplace
+    assert ci(fake, fake, ctypes.byref(lay), 4, fake, 8, None, None) == B.KVR_ERR_ARG      # 6 % 4 != 0
+    assert ci(fake, fake, ctypes.byref(lay), 1, None, 8, None, None) == B.KVR_ERR_ARG      # no index list
+    assert ci(None, None, ctypes.byref(lay), 1, fake, 8, None, None) == B.KVR_ERR_ARG      # nothing to move
+    assert ci(fake, fake, ctypes.byref(lay), 1, fake, 65, None, None) == B.KVR_ERR_ARG     # b > n
+    assert ci(ctypes.c_void_p(0x1004), fake, ctypes.byref(lay), 1, fake, 8, None, None) == B.KVR_ERR_ARG
     rf = L.kvr_retain_flat
     assert rf(fake, fake, fake, ctypes.byref(lay), 3, 8, 0.5, 1e-6, None, fake, None, None, fake, fake, None) == B.KVR_ERR_ARG
     assert rf(fake, fake, fake, ctypes.byref(lay), 4, 8, 0.5, 1e-6, fake, fake, None, None, fake, fake, None) == B.KVR_ERR_ARG

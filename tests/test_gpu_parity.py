@@ -510,6 +510,88 @@ def test_scores_from_a_wide_query_window(n, G):
     _check_heads(W.WORKLOADS["c2"], {"K": K, "V": V, "Q": Q}, out, b, 0.5, 1e-6, range(h))
 
 
+def _random_index_rows(rows, n, b, seed, kind):
+    """Strictly ascending index rows of the kinds an eviction step produces, -1 padded."""
+    rng = np.random.default_rng(seed)
+    idx = np.full((rows, b), -1, dtype=np.int32)
+    for r in range(rows):
+        if kind == "shift":                   # every destination is the source of the row before it
+            m = min(b, n - 1)
+            idx[r, :m] = np.arange(1, m + 1)
+        elif kind == "identity_prefix":       # a kept prefix (sinks), then a sparse tail
+            keep = b // 2
+            idx[r, :keep] = np.arange(keep)
+            idx[r, keep:] = keep + np.sort(rng.choice(n - keep, size=b - keep, replace=False))
+        elif kind == "ragged":                # per-head budgets: a valid prefix, then padding
+            m = int(rng.integers(0, b + 1))
+            idx[r, :m] = np.sort(rng.choice(n, size=m, replace=False))
+        else:
+            idx[r] = np.sort(rng.choice(n, size=b, replace=False))
+    return idx
+
+
+@pytest.mark.parametrize("kind", ["random", "shift", "identity_prefix", "ragged"])
+@pytest.mark.parametrize("n,b,dtype,strided", [
+    (192, 64, torch.bfloat16, False), (1, 1, torch.bfloat16, False), (100, 100, torch.float32, False),
+    (777, 300, torch.bfloat16, True), (4096, 4095, torch.bfloat16, False), (1500, 257, torch.float32, True),
+    (8192, 4100, torch.bfloat16, False)])
+def test_inplace_compaction(kind, n, b, dtype, strided):
+    heads = 6 if n <= 4096 else 2
+    g = torch.Generator().manual_seed(n * 7 + b)
+    if strided:     # rows padded to 160 elements, heads padded by 3 rows
+        Kbuf = torch.randn((heads, n + 3, 160), generator=g).to(dtype).to(DEV)
+        Vbuf = torch.randn((heads, n + 3, 160), generator=g).to(dtype).to(DEV)
+        K, V = Kbuf[:, :n, :128], Vbuf[:, :n, :128]
+    else:
+        Kbuf = torch.randn((heads, n, 128), generator=g).to(dtype).to(DEV)
+        Vbuf = torch.randn((heads, n, 128), generator=g).to(dtype).to(DEV)
+        K, V = Kbuf, Vbuf
+    K0, V0, Kbuf0 = _bits(K), _bits(V), _bits(Kbuf)
+    idx = _random_index_rows(heads, n, b, n + b, kind)
+    pos0 = (np.arange(n, dtype=np.int32)[None, :] * 5 + np.arange(heads, dtype=np.int32)[:, None] * 100003)
+    pos = torch.from_numpy(pos0.copy()).to(DEV)
+    B().kvr_compact_inplace(K, V, torch.from_numpy(idx).to(DEV), pos=pos)
+    torch.cuda.synchronize()
+    K1, V1, p1 = _bits(K), _bits(V), pos.cpu().numpy()
+    for h in range(heads):
+        np.testing.assert_array_equal(K1[h], O.compact_inplace(K0[h], idx[h]))
+        np.testing.assert_array_equal(V1[h], O.compact_inplace(V0[h], idx[h]))
+        np.testing.assert_array_equal(p1[h], O.compact_inplace(pos0[h], idx[h]))
+    if strided:     # the padding between rows and heads is not written
+        Kb1 = _bits(Kbuf)
+        np.testing.assert_array_equal(Kb1[:, :, 128:], Kbuf0[:, :, 128:])
+        np.testing.assert_array_equal(Kb1[:, n:], Kbuf0[:, n:])
+
+
+def test_inplace_compaction_after_a_budgeted_selection_and_with_a_shared_list():
+    """The eviction step as a serving loop runs it: select without output rows, then move the
+    rows inside the cache; and flat mode, where the heads of a sequence share one index row."""
+    h, n, b_max = 8, 192, 64
+    K, V, s = _mk(h, n, 9100)
+    b_h = torch.tensor([64, 10, 1, 33, 64, 5, 64, 17], dtype=torch.int32)
+    pos = torch.arange(n, dtype=torch.int32).repeat(h, 1).contiguous().to(DEV)
+    out = B().kvr_retain_budgeted(K, V, b_max, 0.5, 1e-6, s=s, b_h=b_h.to(DEV), pos=pos)
+    torch.cuda.synchronize()
+    Kc, Vc, pc = K.clone(), V.clone(), pos.clone()
+    B().kvr_compact_inplace(Kc, Vc, out.idx_sorted, pos=pc)
+    torch.cuda.synchronize()
+    for hh in range(h):
+        bh = int(b_h[hh])
+        np.testing.assert_array_equal(_bits(Kc[hh])[:bh], _bits(out.K_out[hh])[:bh])      # same rows as the
+        np.testing.assert_array_equal(_bits(Vc[hh])[:bh], _bits(out.V_out[hh])[:bh])      # out-of-place call
+        np.testing.assert_array_equal(_bits(Kc[hh])[bh:], _bits(K[hh])[bh:])
+        np.testing.assert_array_equal(pc[hh].cpu().numpy()[:bh], out.pos_out[hh].cpu().numpy()[:bh])
+    # shared list: 3 sequences of 4 heads
+    K, V, _ = _mk(12, 300, 9200)
+    idx = _random_index_rows(3, 300, 77, 4, "random")
+    K0, V0 = _bits(K), _bits(V)
+    B().kvr_compact_inplace(K, None, torch.from_numpy(idx).to(DEV), group=4)      # K only
+    torch.cuda.synchronize()
+    for hh in range(12):
+        np.testing.assert_array_equal(_bits(K[hh]), O.compact_inplace(K0[hh], idx[hh // 4]))
+    np.testing.assert_array_equal(_bits(V), V0)
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
     # forty seeded cases per seed across every kernel the dispatch can choose: head lengths 1..4096,

@@ -230,6 +230,22 @@ def test_compact_is_a_row_gather():
 
 
 # ---------------------------------------- a planted mistake must break a pin
+
+def test_inplace_compaction_equals_the_gather_for_ascending_lists():
+    rng = np.random.default_rng(5)
+    for n, b in [(1, 1), (7, 7), (40, 13), (64, 1), (200, 199)]:
+        X = rng.integers(0, 1 << 16, size=(n, 4))
+        idx = np.sort(rng.choice(n, size=b, replace=False))
+        Y = O.compact_inplace(X, idx)
+        assert Y[:b].tolist() == X[idx].tolist()          # the textbook gather
+        assert Y[b:].tolist() == X[b:].tolist()           # the tail is not touched
+    # padding moves nothing; a shift by one is the case where every destination is the previous source
+    X = np.arange(12).reshape(6, 2)
+    assert O.compact_inplace(X, np.array([1, 4, -1, -1]))[:, 0].tolist() == [2, 8, 4, 6, 8, 10]
+    assert O.compact_inplace(X, np.arange(1, 6))[:, 0].tolist() == [2, 4, 6, 8, 10, 10]
+    # the precondition matters: a descending list reads rows that were already replaced
+    assert O.compact_inplace(X, np.array([1, 0]))[:2, 0].tolist() != X[[1, 0], 0].tolist()
+
 def test_pins_catch_planted_mistakes(monkeypatch):
     g = json.load(open(os.path.join(GOLD, "hand_case.json")))
     V = np.array(g["V"])
