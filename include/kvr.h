@@ -157,6 +157,26 @@ int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int 
                        const int32_t* idx, int b, void* K_out, void* V_out, void* stream);
 
 /*
+ * The one-term modular scoring variant the paper tested and rejected (table of
+ * negative gates, scoring family, "variant_b"; Sec. 5 discusses why a modular
+ * term cannot do what the set-conditioned penalty does): a prior added to the
+ * base score, the cosine of the token's value row with the head's mean value
+ * direction,
+ *   s_out[h,i] = s_in[h,i] + lambda_p * (V_i . dir) / ((||V_i|| + eps) (||dir|| + eps)),
+ *   dir = (1/n) sum_j V[h,j,:]
+ * (the paper gives the term as lambda cos(V, dir) only; the mean over the head's
+ * n candidate rows and the eps of Eq. 1 in both norms are this library's
+ * reading).  Top-b of s_out, kvr_select_greedy with lambda = 0, is that variant;
+ * passing s_out to Algorithm 1 composes the two.
+ *   V      device, [heads, n, d] per `lay`
+ *   s_in   device, dense float32 [heads, n]
+ *   s_out  device, dense float32 [heads, n]; may be s_in
+ *   lambda_p  any finite weight (negative weights favour rows unlike the mean)
+ */
+int kvr_score_prior(const void* V, const kvr_layout* lay, const float* s_in, float lambda_p, float eps,
+                    float* s_out, void* stream);
+
+/*
  * The cache update of Algorithm 1's return value done inside the cache's own
  * storage, as an eviction step of a serving loop does it (the paper's method
  * returns sort(S) and leaves the storage to the caller):

@@ -75,6 +75,16 @@ def score_softmax_mean(K: np.ndarray, Q: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Eq. 1
 # --------------------------------------------------------------------------
+def score_mean_direction_prior(s, V, lam_p: float, eps: float = 1e-6) -> np.ndarray:
+    """The modular one-term variant the paper tested and rejected (table of negative gates,
+    scoring family): s_i + lam_p * cos(V_i, dir), dir the mean of the head's value rows.
+    Reading: the mean is over the head's n candidate rows, and both norms carry Eq. 1's eps."""
+    V = np.asarray(V, dtype=np.float64)
+    d = V.mean(axis=0)
+    cos = (V @ d) / ((np.sqrt((V * V).sum(axis=1)) + eps) * (np.sqrt((d * d).sum()) + eps))
+    return np.asarray(s, dtype=np.float64) + lam_p * cos
+
+
 def signatures(V: np.ndarray, eps: float) -> np.ndarray:
     """v_i = u_i / (||u_i||_2 + eps), one layer and one head (u_i = V_i)."""
     V = np.asarray(V, dtype=np.float64)

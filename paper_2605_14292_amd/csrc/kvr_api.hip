@@ -245,6 +245,17 @@ int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int 
   return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
 }
 
+int kvr_score_prior(const void* V, const kvr_layout* lay, const float* s_in, float lambda_p, float eps,
+                    float* s_out, void* stream) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (!V || !s_in || !s_out || !aligned16(V)) return KVR_ERR_ARG;
+  if (std::isnan(lambda_p) || std::isinf(lambda_p) || !(eps >= 0.0f) || std::isinf(eps)) return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_score_prior(V, to_dev(lay), s_in, lambda_p, eps, s_out,
+                                               static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
 int kvr_compact_inplace(void* K, void* V, const kvr_layout* lay, int group, const int32_t* idx, int b,
                         int32_t* pos, void* stream) {
   const int rc = check_layout(lay);

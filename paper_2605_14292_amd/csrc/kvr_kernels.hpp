@@ -23,6 +23,10 @@ hipError_t launch_compact(const void* K, const void* V, const Layout& lay, const
 hipError_t launch_compact_inplace(void* K, void* V, const Layout& lay, const int32_t* idx, int idx_group,
                                   int b, int32_t* pos, hipStream_t st);
 
+// s_out = s_in + lambda_p * cos(V_i, mean_j V_j) per head; s_out may be s_in.
+hipError_t launch_score_prior(const void* V, const Layout& lay, const float* s_in, float lambda_p, float eps,
+                              float* s_out, hipStream_t st);
+
 // Mean of V over each run of `group` consecutive heads: u_out is dense fp32 [heads/group, n, d].
 hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, float* u_out, hipStream_t st);
 

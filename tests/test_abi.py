@@ -97,6 +97,11 @@ def test_flat_mode_argument_errors_are_host_side():
     assert L.kvr_signature_flat(None, ctypes.byref(lay), 3, fake, None) == B.KVR_ERR_ARG
     assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 4, fake, 8, fake, fake, None) == B.KVR_ERR_ARG
     assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 3, None, 8, fake, fake, None) == B.KVR_ERR_ARG
+    sp = L.kvr_score_prior
+    assert sp(None, ctypes.byref(lay), fake, 0.5, 1e-6, fake, None) == B.KVR_ERR_ARG
+    assert sp(fake, ctypes.byref(lay), None, 0.5, 1e-6, fake, None) == B.KVR_ERR_ARG
+    assert sp(fake, ctypes.byref(lay), fake, float("nan"), 1e-6, fake, None) == B.KVR_ERR_ARG
+    assert sp(fake, ctypes.byref(lay), fake, 0.5, -1.0, fake, None) == B.KVR_ERR_ARG
     ci = L.kvr_compact_inplace
     assert ci(fake, fake, ctypes.byref(lay), 4, fake, 8, None, None) == B.KVR_ERR_ARG      # 6 % 4 != 0
     assert ci(fake, fake, ctypes.byref(lay), 1, None, 8, None, None) == B.KVR_ERR_ARG      # no index list

@@ -592,6 +592,48 @@ def test_inplace_compaction_after_a_budgeted_selection_and_with_a_shared_list():
     np.testing.assert_array_equal(_bits(V), V0)
 
 
+@pytest.mark.parametrize("n,dtype,strided", [(1, torch.bfloat16, False), (17, torch.float32, False), (300, torch.float32, False), (256, torch.bfloat16, True), (1024, torch.bfloat16, False),
+                                             (192, torch.bfloat16, False), (777, torch.bfloat16, True),
+                                             (1500, torch.float32, True), (4096, torch.bfloat16, False),
+                                             (8192, torch.bfloat16, False)])
+def test_mean_direction_prior_scores(n, dtype, strided):
+    """The rejected modular variant: s + lambda_p cos(V_i, mean row).  Scores to the 1e-4 bar, on
+    the scale |s| + |lambda_p|; top-b of them is then the ordinary lambda = 0 path."""
+    heads = 5
+    g = torch.Generator().manual_seed(n)
+    if strided:
+        Vbuf = torch.randn((heads, n + 2, 136), generator=g).to(dtype).to(DEV)
+        V = Vbuf[:, :n, :128]
+    else:
+        V = torch.randn((heads, n, 128), generator=g).to(dtype).to(DEV)
+    V[1] = V[1] + 2.0                       # a head with a strong common direction
+    m = V[2, 1::2].shape[0]
+    if m:
+        V[2, 1::2] = -V[2, 0:2 * m:2]       # rows cancelling in pairs: dir is 0 (n even) or one row / n
+    V[3] = 0                                # all-zero head: dir = 0, every cosine 0
+    s = torch.randn((heads, n), generator=g).to(DEV)
+    for lam_p in (0.5, -1.25):
+        out = B().kvr_score_prior(V, s, lam_p, 1e-6)
+        torch.cuda.synchronize()
+        for h in range(heads):
+            want = O.score_mean_direction_prior(W.to_f64(s[h]), W.to_f64(V[h]), lam_p, 1e-6)
+            got = out[h].cpu().numpy().astype(np.float64)
+            scale = np.abs(W.to_f64(s[h])) + abs(lam_p)
+            assert np.all(np.abs(got - want) <= P.GAIN_RTOL * scale), (h, np.abs(got - want).max())
+        np.testing.assert_array_equal(out[3].cpu().numpy(), s[3].cpu().numpy())
+    # in place, and as the input of the lambda = 0 selection
+    s2 = s.clone()
+    B().kvr_score_prior(V, s2, 0.5, 1e-6, s_out=s2)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(s2.cpu().numpy(), B().kvr_score_prior(V, s, 0.5, 1e-6).cpu().numpy())
+    b = max(1, n // 3)
+    _, order, _ = B().kvr_select_greedy(V, s2, b, 0.0)
+    torch.cuda.synchronize()
+    for h in range(heads):
+        want = O.topk_order(s2[h].cpu().numpy().astype(np.float64), b)
+        np.testing.assert_array_equal(order[h].cpu().numpy(), want)
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
     # forty seeded cases per seed across every kernel the dispatch can choose: head lengths 1..4096,

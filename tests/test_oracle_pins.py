@@ -355,3 +355,35 @@ def test_protecting_what_greedy_picks_first_changes_nothing_and_duplicates_of_pr
     assert 7 not in r2["order"].tolist()
     assert O.select_budgeted(s2, V2, 30, 3, keep2, 0.0)["order"][0] == 7
 
+
+
+# ------------------------------------------------------------ the rejected modular prior
+def test_mean_direction_prior_closed_forms_and_brute_force():
+    """Table of negative gates, scoring family: s + lambda cos(V, dir)."""
+    import math
+    n, d = 9, 16
+    # one-hot rows: dir = (1/n) sum e_i, cos(e_i, dir) = 1/sqrt(n)
+    V = np.eye(d)[:n]
+    out = O.score_mean_direction_prior(np.zeros(n), V, 2.0, 0.0)
+    np.testing.assert_allclose(out, 2.0 / math.sqrt(n), rtol=1e-14)
+    # identical rows: cosine 1 (up to eps); the base score passes through
+    V = np.tile(np.arange(1.0, d + 1), (n, 1))
+    s = np.linspace(-1, 1, n)
+    np.testing.assert_allclose(O.score_mean_direction_prior(s, V, 0.5, 0.0), s + 0.5, rtol=1e-14)
+    # rows cancelling in pairs: dir = 0, the eps keeps the term finite and zero
+    V = np.concatenate([np.ones((4, d)), -np.ones((4, d))])
+    np.testing.assert_array_equal(O.score_mean_direction_prior(np.ones(8), V, 3.0, 1e-6), np.ones(8))
+    # a row opposite to the mean gets the negative sign; scaling a row does not change its cosine
+    V = np.array([[1.0, 0.0], [1.0, 0.0], [1.0, 0.0], [-1.0, 0.0], [7.0, 0.0]])
+    out = O.score_mean_direction_prior(np.zeros(5), V, 1.0, 0.0)
+    np.testing.assert_allclose(out, [1, 1, 1, -1, 1], rtol=1e-14)
+    # brute force with plain loops
+    rng = np.random.default_rng(3)
+    V = rng.normal(size=(7, 5)); s = rng.normal(size=7); eps = 1e-3
+    dirv = [sum(V[j][e] for j in range(7)) / 7 for e in range(5)]
+    nd = math.sqrt(sum(x * x for x in dirv))
+    for i in range(7):
+        dot = sum(V[i][e] * dirv[e] for e in range(5))
+        ni = math.sqrt(sum(V[i][e] ** 2 for e in range(5)))
+        want = s[i] + 0.7 * dot / ((ni + eps) * (nd + eps))
+        assert abs(O.score_mean_direction_prior(s, V, 0.7, eps)[i] - want) < 1e-13
