@@ -58,7 +58,7 @@ typedef enum {
 typedef enum { KVR_F32 = 0, KVR_BF16 = 1 } kvr_dtype;
 
 #define KVR_MAX_N 8192     /* candidates per head */
-#define KVR_MAX_G 64       /* grouped queries per KV head */
+#define KVR_MAX_G 256      /* queries per KV head (observation window x grouped heads) */
 
 /* Layout of a [heads, n, d] tensor of cached rows; d is contiguous. */
 typedef struct {
@@ -155,6 +155,22 @@ int kvr_signature_flat(const void* V, const kvr_layout* lay, int group, float* u
  */
 int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int group,
                        const int32_t* idx, int b, void* K_out, void* V_out, void* stream);
+
+/*
+ * Token-axis pooling of the base scores, the smoothing step of the
+ * observation-window scorers the paper builds on and compares against (Sec. 2;
+ * Sec. 4.1 takes s as given and the paper does not restate the step):
+ *   s_out[h,i] = max (KVR_POOL_MAX) or mean (KVR_POOL_MEAN) of s_in[h,j] over
+ *   |j - i| <= kernel/2.
+ * Window positions outside [0, n) are skipped by the maximum and count as zeros
+ * in the mean, whose divisor is always `kernel` (this library's reading).
+ *   s_in, s_out  device, dense float32 [heads, n]; must not be the same buffer
+ *   kernel       odd, 1 <= kernel <= KVR_MAX_POOL; heads <= 65535 per call
+ */
+#define KVR_POOL_MAX 0
+#define KVR_POOL_MEAN 1
+#define KVR_MAX_POOL 63
+int kvr_score_pool(const float* s_in, int heads, int n, int kernel, int mode, float* s_out, void* stream);
 
 /*
  * The one-term modular scoring variant the paper tested and rejected (table of

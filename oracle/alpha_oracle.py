@@ -75,6 +75,20 @@ def score_softmax_mean(K: np.ndarray, Q: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Eq. 1
 # --------------------------------------------------------------------------
+def score_pool(s, kernel: int, mean: bool = False) -> np.ndarray:
+    """Pooling of a score row over the window of `kernel` (odd) tokens centred on each token,
+    the smoothing step of observation-window scorers (the scorer family of Sec. 2; the paper
+    does not restate it).  Reading: positions outside the row are skipped by the maximum and
+    count as zeros in the mean, whose divisor is always `kernel`."""
+    s = np.asarray(s, dtype=np.float64)
+    n, half = len(s), kernel // 2
+    out = np.empty(n)
+    for i in range(n):
+        win = s[max(i - half, 0): min(i + half, n - 1) + 1]
+        out[i] = win.sum() / kernel if mean else win.max()
+    return out
+
+
 def score_mean_direction_prior(s, V, lam_p: float, eps: float = 1e-6) -> np.ndarray:
     """The modular one-term variant the paper tested and rejected (table of negative gates,
     scoring family): s_i + lam_p * cos(V_i, dir), dir the mean of the head's value rows.

@@ -20,7 +20,7 @@ KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1
 
 EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
            "kvr_select_greedy", "kvr_compact", "kvr_retain",
-           "kvr_signature_flat", "kvr_compact_shared", "kvr_compact_inplace", "kvr_score_prior", "kvr_retain_flat",
+           "kvr_signature_flat", "kvr_compact_shared", "kvr_compact_inplace", "kvr_score_prior", "kvr_score_pool", "kvr_retain_flat",
            "kvr_retain_budgeted")
 
 
@@ -62,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.kvr_signature_flat.argtypes = [vp, lp, i32, vp, vp]
     lib.kvr_compact_shared.restype = i32
     lib.kvr_compact_shared.argtypes = [vp, vp, lp, i32, vp, i32, vp, vp, vp]
+    lib.kvr_score_pool.restype = i32
+    lib.kvr_score_pool.argtypes = [vp, i32, i32, i32, i32, vp, vp]
     lib.kvr_score_prior.restype = i32
     lib.kvr_score_prior.argtypes = [vp, lp, vp, f32, f32, vp, vp]
     lib.kvr_compact_inplace.restype = i32
@@ -224,6 +226,21 @@ def kvr_compact_shared(K, V, idx, group, K_out=None, V_out=None, stream=None):
     _check(_lib.kvr_compact_shared(_ptr(K), _ptr(V), ctypes.byref(lay), group, _ptr(idx), b,
                                    _ptr(K_out), _ptr(V_out), _stream(stream)), "kvr_compact_shared")
     return K_out, V_out
+
+
+KVR_POOL_MAX, KVR_POOL_MEAN = 0, 1
+
+
+def kvr_score_pool(s, kernel, mode=KVR_POOL_MAX, s_out=None, stream=None):
+    """Max or mean of each score row over a centred window of `kernel` (odd) tokens."""
+    _need_cuda(s, s_out)
+    if s.dtype != torch.float32 or s.dim() != 2 or not s.is_contiguous():
+        raise ValueError("s must be a contiguous float32 [heads, n] tensor")
+    if s_out is None:
+        s_out = torch.empty_like(s)
+    _check(_lib.kvr_score_pool(_ptr(s), s.shape[0], s.shape[1], kernel, mode, _ptr(s_out), _stream(stream)),
+           "kvr_score_pool")
+    return s_out
 
 
 def kvr_score_prior(V, s, lam_p, eps=1e-6, s_out=None, stream=None):

@@ -245,6 +245,16 @@ int kvr_compact_shared(const void* K, const void* V, const kvr_layout* lay, int 
   return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
 }
 
+int kvr_score_pool(const float* s_in, int heads, int n, int kernel, int mode, float* s_out, void* stream) {
+  if (!s_in || !s_out || s_in == s_out) return KVR_ERR_ARG;
+  if (heads < 1 || heads > 65535 || n < 1 || n > KVR_MAX_N) return KVR_ERR_ARG;
+  if (kernel < 1 || kernel > KVR_MAX_POOL || (kernel & 1) == 0) return KVR_ERR_ARG;
+  if (mode != KVR_POOL_MAX && mode != KVR_POOL_MEAN) return KVR_ERR_ARG;
+  const hipError_t e = kvr::launch_score_pool(s_in, heads, n, kernel, mode == KVR_POOL_MEAN, s_out,
+                                              static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
 int kvr_score_prior(const void* V, const kvr_layout* lay, const float* s_in, float lambda_p, float eps,
                     float* s_out, void* stream) {
   const int rc = check_layout(lay);

@@ -12,6 +12,10 @@ struct Layout {
 
 hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay,
                         float* s_out, hipStream_t st);
+// bf16 scores for up to 256 queries per head and any n: two passes over K on the matrix cores.
+bool score_wide_supported(const Layout& lay, int G);
+hipError_t launch_score_wide(const void* K, const void* Q, int G, const Layout& lay, float* s_out,
+                             hipStream_t st);
 hipError_t launch_select_generic(const void* V, const float* s, const Layout& lay, int b,
                                  float lambda, float eps, int32_t* idx_sorted,
                                  int32_t* pick_order, float* pick_gain, hipStream_t st);
@@ -23,6 +27,9 @@ hipError_t launch_compact(const void* K, const void* V, const Layout& lay, const
 hipError_t launch_compact_inplace(void* K, void* V, const Layout& lay, const int32_t* idx, int idx_group,
                                   int b, int32_t* pos, hipStream_t st);
 
+// Pooling of each score row over a centred window of `kernel` (odd) tokens: maximum, or mean if `mean`.
+hipError_t launch_score_pool(const float* s_in, int heads, int n, int kernel, int mean, float* s_out,
+                             hipStream_t st);
 // s_out = s_in + lambda_p * cos(V_i, mean_j V_j) per head; s_out may be s_in.
 hipError_t launch_score_prior(const void* V, const Layout& lay, const float* s_in, float lambda_p, float eps,
                               float* s_out, hipStream_t st);

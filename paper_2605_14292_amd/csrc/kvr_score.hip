@@ -306,6 +306,7 @@ hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay, 
     };
     return gq == 8 ? go_m(&score_mfma_kernel<8>) : go_m(&score_mfma_kernel<32>);
   }
+  if (score_wide_supported(lay, G)) return launch_score_wide(K, Q, G, lay, s_out, st);
   const bool zfits = static_cast<long long>(G) * lay.n <= kZMaxFloats;
   const size_t smem = (static_cast<size_t>(zfits ? G * lay.n : 0) + lay.n + 2 * kGT * 4) * 4;
   dim3 grid(lay.heads), block(kScoreThreads);

@@ -51,7 +51,7 @@ def test_argument_errors_are_host_side():
     big_n = _lay(n=8193)
     assert L.kvr_score(fake, fake, 1, ctypes.byref(big_n), fake, None) == B.KVR_ERR_UNSUPPORTED
     assert L.kvr_score(fake, fake, 0, ctypes.byref(lay), fake, None) == B.KVR_ERR_ARG
-    assert L.kvr_score(fake, fake, 65, ctypes.byref(lay), fake, None) == B.KVR_ERR_UNSUPPORTED
+    assert L.kvr_score(fake, fake, 257, ctypes.byref(lay), fake, None) == B.KVR_ERR_UNSUPPORTED
     assert L.kvr_score(None, fake, 1, ctypes.byref(lay), fake, None) == B.KVR_ERR_ARG
     odd = ctypes.c_void_p(0x1004)
     assert L.kvr_score(odd, fake, 1, ctypes.byref(lay), fake, None) == B.KVR_ERR_ARG
@@ -97,6 +97,14 @@ def test_flat_mode_argument_errors_are_host_side():
     assert L.kvr_signature_flat(None, ctypes.byref(lay), 3, fake, None) == B.KVR_ERR_ARG
     assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 4, fake, 8, fake, fake, None) == B.KVR_ERR_ARG
     assert L.kvr_compact_shared(fake, fake, ctypes.byref(lay), 3, None, 8, fake, fake, None) == B.KVR_ERR_ARG
+    pl = L.kvr_score_pool
+    other = ctypes.c_void_p(0x2000)
+    assert pl(fake, 4, 64, 7, 0, fake, None) == B.KVR_ERR_ARG        # in place
+    assert pl(fake, 4, 64, 6, 0, other, None) == B.KVR_ERR_ARG       # even window
+    assert pl(fake, 4, 64, 65, 0, other, None) == B.KVR_ERR_ARG      # window too wide
+    assert pl(fake, 4, 64, 7, 2, other, None) == B.KVR_ERR_ARG       # unknown mode
+    assert pl(fake, 0, 64, 7, 0, other, None) == B.KVR_ERR_ARG
+    assert pl(None, 4, 64, 7, 0, other, None) == B.KVR_ERR_ARG
     sp = L.kvr_score_prior
     assert sp(None, ctypes.byref(lay), fake, 0.5, 1e-6, fake, None) == B.KVR_ERR_ARG
     assert sp(fake, ctypes.byref(lay), None, 0.5, 1e-6, fake, None) == B.KVR_ERR_ARG

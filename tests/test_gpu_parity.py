@@ -423,11 +423,11 @@ def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
         assert np.all(out.pos_out[hh].cpu().numpy()[bh:] == -1)
 
 
-@pytest.mark.parametrize("n,b,dtype,G", [(8192, 24, torch.bfloat16, 0), (8192, 16, torch.float32, 64),
+@pytest.mark.parametrize("n,b,dtype,G", [(8192, 24, torch.bfloat16, 0), (8192, 16, torch.float32, 256),
                                          (4096, 1024, torch.bfloat16, 0), (4096, 256, torch.bfloat16, 8),
                                          (256, 256, torch.bfloat16, 0), (192, 192, torch.float32, 0)])
 def test_maximum_sizes(n, b, dtype, G):
-    # the limits of the header (n = 8192, G = 64), of the pool (b = 256) and blocked (b = 1024)
+    # the limits of the header (n = 8192, G = 256), of the pool (b = 256) and blocked (b = 1024)
     # kernels, and budgets that keep every token
     K, V, s = _mk(1, n, 8800 + n + b, dtype)
     g = torch.Generator().manual_seed(n + b)
@@ -508,6 +508,63 @@ def test_scores_from_a_wide_query_window(n, G):
     torch.cuda.synchronize()
     torch.testing.assert_close(s, out.s_out, rtol=2e-5, atol=0)
     _check_heads(W.WORKLOADS["c2"], {"K": K, "V": V, "Q": Q}, out, b, 0.5, 1e-6, range(h))
+
+
+@pytest.mark.parametrize("n,G,sharp,strided", [
+    (1, 40, 1.0, False), (33, 200, 1.0, False), (1000, 33, 1.0, False), (1500, 20, 4.0, False),
+    (4096, 8, 1.0, False), (777, 100, 2.0, True), (4096, 256, 1.0, False), (8192, 64, 1.0, False),
+    (2050, 255, 6.0, False)])
+def test_scores_from_an_observation_window_of_up_to_256_queries(n, G, sharp, strided):
+    """W recent positions x grouped heads as one wide Q: the two-pass matrix-core scorer (any n, G <= 256).
+    `sharp` scales the queries: peaked softmaxes, logits tens of units apart."""
+    h = 3
+    g = torch.Generator().manual_seed(G * 10000 + n)
+    if strided:
+        Kbuf = torch.randn((h, n + 5, 192), generator=g).to(torch.bfloat16).to(DEV)
+        K = Kbuf[:, :n, 32:160]
+    else:
+        K = torch.randn((h, n, 128), generator=g).to(torch.bfloat16).to(DEV)
+    Q = (torch.randn((h, G, 128), generator=g) * sharp).to(torch.bfloat16).to(DEV)
+    Q[1, G // 2] = 0                                   # a query with a flat softmax
+    s = B().kvr_score(K, Q)
+    torch.cuda.synchronize()
+    for hh in range(h):
+        s64 = O.score_softmax_mean(W.to_f64(K[hh]), W.to_f64(Q[hh]))
+        P.check_scores(s[hh].cpu().numpy(), s64)
+        assert abs(float(s[hh].sum()) - 1.0) < 1e-4    # a mean of softmaxes sums to one
+    # the whole event on these scores
+    if n >= 64:
+        V = torch.randn((h, n, 128), generator=g).to(torch.bfloat16).to(DEV)
+        out = B().kvr_retain(K.contiguous(), V, 24, 0.5, 1e-6, Q=Q)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.s_out.cpu().numpy(), s.cpu().numpy())
+        _check_heads(W.WORKLOADS["c2"], {"K": K.contiguous(), "V": V, "Q": Q}, out, 24, 0.5, 1e-6, range(h))
+
+
+@pytest.mark.parametrize("n,kernel", [(1, 7), (6, 3), (192, 7), (1000, 13), (4096, 5), (300, 63), (257, 1)])
+def test_score_pooling(n, kernel):
+    heads = 7
+    g = torch.Generator().manual_seed(n + kernel)
+    s = torch.randn((heads, n), generator=g).exp().to(DEV)
+    mx = B().kvr_score_pool(s, kernel, B().KVR_POOL_MAX)
+    mean = B().kvr_score_pool(s, kernel, B().KVR_POOL_MEAN)
+    torch.cuda.synchronize()
+    for h in range(heads):
+        s64 = W.to_f64(s[h])
+        np.testing.assert_array_equal(mx[h].cpu().numpy().astype(np.float64), O.score_pool(s64, kernel))
+        want = O.score_pool(s64, kernel, mean=True)
+        got = mean[h].cpu().numpy().astype(np.float64)
+        scale = O.score_pool(np.abs(s64), kernel, mean=True)
+        assert np.all(np.abs(got - want) <= 1e-5 * scale)
+    # pooled scores feed the selection like any others
+    if n >= 6:
+        V = torch.randn((heads, n, 128), generator=g).to(torch.bfloat16).to(DEV)
+        b = max(1, n // 4)
+        idx, order, gain = B().kvr_select_greedy(V, mx, b, 0.5)
+        torch.cuda.synchronize()
+        for h in (0, heads - 1):
+            P.check_head(W.to_f64(mx[h]), W.to_f64(V[h]), b, 0.5, 1e-6, order[h].cpu().numpy(),
+                         gain[h].cpu().numpy(), idx[h].cpu().numpy())
 
 
 def _random_index_rows(rows, n, b, seed, kind):

@@ -387,3 +387,22 @@ def test_mean_direction_prior_closed_forms_and_brute_force():
         ni = math.sqrt(sum(V[i][e] ** 2 for e in range(5)))
         want = s[i] + 0.7 * dot / ((ni + eps) * (nd + eps))
         assert abs(O.score_mean_direction_prior(s, V, 0.7, eps)[i] - want) < 1e-13
+
+
+# ------------------------------------------------------------ score pooling
+def test_score_pooling_matches_the_library_pooling_and_hand_values():
+    """The smoothing step of observation-window scorers (Sec. 2's scorer family)."""
+    import torch
+    import torch.nn.functional as F
+    s = np.array([1.0, 5.0, 2.0, 0.0, -3.0, 4.0])
+    assert O.score_pool(s, 3).tolist() == [5, 5, 5, 2, 4, 4]
+    np.testing.assert_allclose(O.score_pool(s, 3, mean=True), [2, 8 / 3, 7 / 3, -1 / 3, 1 / 3, 1 / 3], rtol=1e-15)
+    assert O.score_pool(s, 1).tolist() == s.tolist() and O.score_pool(s, 1, mean=True).tolist() == s.tolist()
+    assert O.score_pool(s, 63).tolist() == [5.0] * 6              # window wider than the row
+    rng = np.random.default_rng(11)
+    for n, k in [(1, 7), (9, 5), (40, 7), (100, 13), (33, 63)]:
+        x = rng.normal(size=n)
+        t = torch.from_numpy(x)[None, None]
+        np.testing.assert_array_equal(O.score_pool(x, k), F.max_pool1d(t, k, stride=1, padding=k // 2)[0, 0].numpy())
+        np.testing.assert_allclose(O.score_pool(x, k, mean=True),
+                                   F.avg_pool1d(t, k, stride=1, padding=k // 2)[0, 0].numpy(), rtol=1e-12, atol=1e-15)
