@@ -155,7 +155,10 @@ def kernel_name(w, b, lam, has_q):
         tail = ["kvr::select_blocked_kernel", "kvr::compact_kernel"]
     else:
         tail = ["kvr::select_generic_kernel", "kvr::compact_kernel"]
-    parts = (["kvr::score_mfma_kernel" if w.dtype == "bf16" else "kvr::score_kernel"] if has_q else []) + tail
+    fits_lds = w.G <= 32 and w.G * w.n <= (24576 if w.G <= 8 else 31488)
+    score = ("kvr::score_kernel" if w.dtype != "bf16" else
+             "kvr::score_mfma_kernel" if fits_lds else "kvr::score_wide_kernel")
+    parts = ([score] if has_q else []) + tail
     return " + ".join(parts) + " (whole step; the select kernel dominates)"
 
 
@@ -174,6 +177,9 @@ def main():
     ap.add_argument("--budgeted", action="store_true",
                     help="budget-allocator frame: per-head budgets b_h in [b/2, b], 4 sink tokens and a "
                          "recent window of 16 protected per head, position ids carried along")
+    ap.add_argument("--window", type=int, default=1,
+                    help="observation window: the scores are computed from WINDOW positions x the workload's "
+                         "grouped queries (G * WINDOW <= 256 queries per head; workloads with computed scores)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short runs of the other benchmark configurations")
@@ -202,6 +208,12 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
         return
     w = W.WORKLOADS[args.workload]
+    if args.window != 1:
+        import dataclasses
+        if w.scores != "computed" or args.window < 1 or w.G * args.window > 256:
+            sys.exit("bench.py: --window needs a workload with computed scores and G * WINDOW <= 256")
+        w = dataclasses.replace(w, G=w.G * args.window,
+                                what=w.what + f", observation window of {args.window} positions")
     b = w.b if args.b is None else args.b
     lam = w.lam if args.lam is None else args.lam
     data = W.generate(w, seed=args.seed, device=dev)
@@ -260,7 +272,8 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"{w.name}{'flat' if args.flat else ''}{'budgeted' if args.budgeted else ''}:b{b}:lam{lam}")
+        traffic = json.load(open(tpath)).get(f"{w.name}{'flat' if args.flat else ''}{'budgeted' if args.budgeted else ''}"
+                                               f"{'window%d' % args.window if args.window != 1 else ''}:b{b}:lam{lam}")
     line = {
         "metric": "retention events/sec (heads*events)",
         "value": w.heads / (wall / args.steps),

@@ -14,6 +14,14 @@
 // the sum over queries is a sum over its own registers.
 // One workgroup per head; wave w takes the 32-token tiles w, w+4, ...; the queries wait
 // in LDS (272-byte pitch).  Everything is done in base 2: z2 = z * log2(e).
+// Bound: for G of a few dozen the two reads of K (fabric rate); for G = 256 the matrix
+// cores and the vector ALU together -- a 32x32 block costs 8 MFMAs and about 60 vector
+// instructions (16 of them exponentials) per pass, the two kinds of work share the SIMD's
+// issue port and overlap only partly across waves (measured on this chip: a wave of MFMA
+// chains beside a wave of fma+exp+add on one SIMD takes 0.76 of the sum of their times).
+// Variants measured and not kept because they change nothing: query fragments prefetched
+// one block ahead, two token tiles per query fragment (half the LDS reads, independent
+// accumulator chains), sixteen waves per workgroup.
 #include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 
