@@ -101,10 +101,13 @@ def cpu_baseline_budgeted(w, data, b_h, keep, lam, budget_s=12.0):
                       f"{t_used:.1f} s, rate extrapolates linearly over heads)"}
 
 
-def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False):
+def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False, cold=False):
     """A short run of another benchmark configuration at its full size, for the
     `other_configs` object: the default workload carries the headline figures, the others are
-    reported beside it from the same process."""
+    reported beside it from the same process.  `cold`: the small configurations (c1, c2) fit the
+    256 MiB memory-side cache, so a loop over one set of buffers times cache hits; with `cold` every
+    step takes the next of enough copies of the inputs to exceed that cache several times over, and
+    the hot figure (one set of buffers) is reported beside it."""
     import torch
     from paper_2605_14292_amd import binding as B
     from paper_2605_14292_amd import workloads as W
@@ -120,25 +123,44 @@ def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False):
     else:
         out = B.RetainBuffers(w.heads, w.n, w.b, w.d, w.torch_dtype, "cuda:0", "Q" in data, want_trace=False)
         step = lambda: B.kvr_retain(data["K"], data["V"], w.b, lam, 1e-6, Q=Q, s=s, out=out)
+
+    def timed(fn, k):
+        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(k):
+            fn(i)
+        z.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(z) / k
+
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(steps):
-        step()
-    z.record()
-    torch.cuda.synchronize()
-    ms = a.elapsed_time(z) / steps
+    ms = timed(lambda i: step(), steps)
+    cold_ms, copies = None, 0
+    if cold and not flat:
+        set_bytes = sum(v.numel() * v.element_size() for v in data.values())
+        copies = int(min(4096, max(16, -(-1_000_000_000 // set_bytes))))
+        sets = [data] + [{k: v.clone() for k, v in data.items()} for _ in range(copies - 1)]
+        cstep = lambda i: B.kvr_retain(sets[i % copies]["K"], sets[i % copies]["V"], w.b, lam, 1e-6,
+                                       Q=sets[i % copies].get("Q"), s=sets[i % copies].get("s"), out=out)
+        torch.cuda.synchronize()
+        cold_ms = timed(cstep, copies)          # every set once: none of it is in a cache
+        del sets
     bytes_step = w.algorithmic_bytes_per_head(w.b, lam) * w.heads
     if flat:
         bytes_step -= (4 * w.n + 4 * w.b) * (w.heads - w.seqs)
     del data, out
     torch.cuda.empty_cache()
-    return {"ms_per_step": ms, "head_events_per_s": w.heads / (ms * 1e-3), "steps": steps,
-            "algorithmic_GBps": bytes_step / (ms * 1e-3) / 1e9,
-            "frac_of_hbm_peak": bytes_step / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "heads": w.heads, "n": w.n, "b": w.b, "lambda": lam}
+    res = {"ms_per_step": ms, "head_events_per_s": w.heads / (ms * 1e-3), "steps": steps,
+           "algorithmic_GBps": bytes_step / (ms * 1e-3) / 1e9,
+           "frac_of_hbm_peak": bytes_step / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "heads": w.heads, "n": w.n, "b": w.b, "lambda": lam}
+    if cold_ms is not None:
+        res.update({"inputs": "hot: one set of buffers, served by the memory-side cache",
+                    "ms_per_step_cold": cold_ms, "cold_input_sets": copies,
+                    "head_events_per_s_cold": w.heads / (cold_ms * 1e-3)})
+    return res
 
 
 def kernel_name(w, b, lam, has_q):
@@ -261,6 +283,19 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     dev_avg_ms = ev0.elapsed_time(ev1) / args.steps
 
+    # a plain device copy of 1 GiB, for the fraction of what a streaming kernel reaches on this machine
+    csrc = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    cdst = torch.empty_like(csrc)
+    cdst.copy_(csrc)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        cdst.copy_(csrc)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * csrc.numel() * 4 * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del csrc, cdst
+
     bytes_step = w.algorithmic_bytes_per_head(b, lam) * w.heads
     if args.flat:       # scores and indices are per sequence, not per head
         bytes_step -= (4 * w.n + 4 * b) * (w.heads - w.seqs)
@@ -289,6 +324,7 @@ def main():
                    "d": w.d, "lambda": lam, "scores": w.scores, "G": w.G if w.scores == "computed" else 0},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "device_copy_GBps": copy_gbps, "frac_of_device_copy": achieved / copy_gbps,
                      "kernel": ("kvr::signature_flat_kernel + kvr::select_dense_f32_kernel + kvr::compact_kernel (whole step)"
                                 if args.flat else
                                 "kvr::budget_prepare_kernel + selection kernels of the shape + kvr::budget_finalize_kernel (whole step)"
@@ -308,7 +344,8 @@ def main():
         del data, out
         torch.cuda.empty_cache()
         line["other_configs"] = {
-            "c2": time_other("c2", steps=20, warmup=5, seed=args.seed),
+            "c1": time_other("c1", steps=20, warmup=5, seed=args.seed, cold=True),
+            "c2": time_other("c2", steps=20, warmup=5, seed=args.seed, cold=True),
             "c3 flat-signature mode": time_other("c3", seed=args.seed, flat=True),
             "c5": time_other("c5", seed=args.seed),
             "c5 lambda=0": time_other("c5", seed=args.seed, lam=0.0),
