@@ -54,6 +54,9 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
                                     pick_order, pick_gain, nullptr, nullptr, st);
   if (kvr::dense_f32_supported(l, b))
     return kvr::launch_select_dense_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
+  if (kvr::topb_supported(l, b, lambda))
+    return kvr::launch_select_topb(nullptr, nullptr, s, l, b, idx_sorted, pick_order, pick_gain, nullptr,
+                                   nullptr, st);
   if (kvr::pool_supported(l, b))
     return kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                    nullptr, nullptr, st);
@@ -170,6 +173,11 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
                                                   pick_order, pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
+  if (kvr::topb_supported(l, b, lambda) && l.dtype == KVR_BF16) {
+    const hipError_t e = kvr::launch_select_topb(K, V, s, l, b, idx_sorted, pick_order, pick_gain, K_out,
+                                                 V_out, st);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+  }
   if (kvr::pool_supported(l, b)) {
     const hipError_t e = kvr::launch_select_pool(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
                                                  pick_gain, K_out, V_out, st);
@@ -180,10 +188,8 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
                                                     pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
-  const hipError_t es = kvr::dense_f32_supported(l, b)
-      ? kvr::launch_select_dense_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st)
-      : kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
-  if (es != hipSuccess) return KVR_ERR_HIP;
+  if (select_only(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)
+    return KVR_ERR_HIP;
   if (kvr::launch_compact(K, V, l, idx_sorted, b, K_out, V_out, st) != hipSuccess)
     return KVR_ERR_HIP;
   return KVR_OK;
@@ -297,10 +303,8 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
   if (lambda != 0.0f && b > 1 &&
       kvr::launch_signature_flat(V, l, group, u_out, st) != hipSuccess)
     return KVR_ERR_HIP;
-  const hipError_t es = kvr::dense_f32_supported(lu, b)
-      ? kvr::launch_select_dense_f32(u_out, s, lu, b, lambda, eps, idx_sorted, pick_order, pick_gain, st)
-      : kvr::launch_select_generic(u_out, s, lu, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
-  if (es != hipSuccess) return KVR_ERR_HIP;
+  if (select_only(u_out, s, lu, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)
+    return KVR_ERR_HIP;
   if (kvr::launch_compact(K, V, l, idx_sorted, b, K_out, V_out, st, group) != hipSuccess)
     return KVR_ERR_HIP;
   return KVR_OK;

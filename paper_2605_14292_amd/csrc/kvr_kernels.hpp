@@ -12,6 +12,12 @@ struct Layout {
 
 hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay,
                         float* s_out, hipStream_t st);
+// lambda = 0 for heads of more than 256 tokens: top-b of the scores (any dtype: V is not read), and
+// the compaction of the kept rows when K_out / V_out are given (bf16 layouts only).
+bool topb_supported(const Layout& lay, int b, float lambda);
+hipError_t launch_select_topb(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                              int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
+                              void* V_out, hipStream_t st);
 // bf16 scores for up to 256 queries per head and any n: two passes over K on the matrix cores.
 bool score_wide_supported(const Layout& lay, int G);
 hipError_t launch_score_wide(const void* K, const void* Q, int G, const Layout& lay, float* s_out,

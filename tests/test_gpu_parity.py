@@ -200,6 +200,38 @@ def test_lambda_zero_reads_no_values_and_is_stable_topb():
         np.testing.assert_array_equal(gain[hh].cpu().numpy(), sn[hh][want])
 
 
+@pytest.mark.parametrize("n,b,dtype", [(257, 1, torch.bfloat16), (1000, 64, torch.bfloat16), (1024, 128, torch.bfloat16),
+                                       (4096, 1024, torch.bfloat16), (5000, 300, torch.bfloat16), (8192, 1000, torch.bfloat16),
+                                       (2048, 2047, torch.bfloat16), (700, 256, torch.float32), (3000, 17, torch.float32)])
+@pytest.mark.parametrize("kind", ["wide", "quantised", "constant", "nonfinite"])
+def test_lambda_zero_on_long_heads_is_the_stable_topb(n, b, dtype, kind):
+    """Algorithm 1's explicit lambda = 0 branch on heads of more than 256 tokens: bit-exact top-b with
+    ties to the lower index, whatever the scores hold, and the kept rows."""
+    h = 4
+    K, V, s = _mk(h, n, 4400 + n + b, dtype)
+    if kind == "quantised":
+        s = torch.floor(s * 8) / 8                         # many exact ties across the threshold
+    elif kind == "constant":
+        s = torch.zeros_like(s); s[1] = -0.0; s[2, ::3] = 1.0
+    elif kind == "nonfinite":
+        s[0, ::5] = float("inf"); s[1, 1::4] = float("-inf"); s[2, ::7] = float("nan"); s[3, :] = float("nan")
+    out = B().kvr_retain(K, V, b, 0.0, 1e-6, s=s)
+    torch.cuda.synchronize()
+    sn = s.cpu().numpy()
+    for hh in range(h):
+        idx, order = out.idx_sorted[hh].cpu().numpy(), out.pick_order[hh].cpu().numpy()
+        if kind == "nonfinite" and hh >= 2:                # NaN has no order: distinct, in range, rows kept
+            assert len(set(idx.tolist())) == b and idx.min() >= 0 and idx.max() < n
+            assert np.all(np.diff(idx) > 0) and sorted(order.tolist()) == idx.tolist()
+        else:
+            want = np.argsort(-(sn[hh] + 0.0), kind="stable")[:b]
+            np.testing.assert_array_equal(order, want)
+            np.testing.assert_array_equal(idx, np.sort(want))
+            np.testing.assert_array_equal(out.pick_gain[hh].cpu().numpy(), sn[hh][want] + 0.0)
+        np.testing.assert_array_equal(_bits(out.K_out[hh]), O.compact(_bits(K[hh]), idx))
+        np.testing.assert_array_equal(_bits(out.V_out[hh]), O.compact(_bits(V[hh]), idx))
+
+
 def test_strided_layout_and_separate_calls_equal_retain():
     h, n, b, G = 6, 200, 48, 3
     g = torch.Generator(device="cpu").manual_seed(9)
