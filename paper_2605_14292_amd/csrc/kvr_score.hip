@@ -172,14 +172,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
 
 // ---------------------------------------------------------------------------
 // bf16, G <= 32 (GQ = 8 or 32 query rows of the MFMA's 32-row operand in use): the logits are a thin dense contraction ([G x d] x [d x n]), so
-// they go through the matrix cores.  K is streamed from HBM once, 128 tokens at a
-// time: coalesced 16-byte loads into registers (the next chunk is in flight while
-// the current one is multiplied), a padded LDS stage, MFMA fragments out of LDS.
-// The logits of the head wait in LDS for the softmax.
+// they go through the matrix cores.  K is streamed from HBM once, straight into MFMA
+// operand registers.  The logits of the head wait in LDS for the softmax.
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-constexpr int kStageTok = 128;
-constexpr int kStagePitch = 272;   // 256 + 16 bytes: consecutive rows land in different banks
 
 template <int GQ>
 __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* __restrict__ K,
@@ -187,8 +183,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
                                                                    Layout lay,
                                                                    float* __restrict__ s_out) {
   extern __shared__ __align__(16) char smem_raw[];
-  char* stage = smem_raw;                                                   // [128][272]
-  float* zbuf = reinterpret_cast<float*>(smem_raw + kStageTok * kStagePitch);  // [G][n]
+  float* zbuf = reinterpret_cast<float*>(smem_raw);                         // [G][n]
   const int n = lay.n;
   float* red = zbuf + G * n;                                                // [2][4][GQ]
   const int h = blockIdx.x;
@@ -206,32 +201,30 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
       qf[ks] = *reinterpret_cast<bf16x8*>(&w);
     }
   }
-  const int chunk16 = tid & 15, r0 = tid >> 4;
-  const int nchunks = (n + kStageTok - 1) / kStageTok;
-  uint4 reg[8];
-  auto fetch = [&](int c) {
+  // Wave w takes the 32-token tiles w, w+4, ...: the rows go straight into the registers in the
+  // MFMA operand layout (lane l: token l % 32, eight consecutive k at 8 * (l / 32) per step; the
+  // two halves of a row are 32 contiguous bytes per request), the next tile is in flight while
+  // the current one is multiplied, and no wave waits for another until the softmax.
+  const int ntiles = (n + 31) >> 5;
+  const long long tok_bytes = lay.stride_tok * 2;
+  bf16x8 kf[8], kn[8];
+  auto fetch = [&](int t, bf16x8 (&dst)[8]) {
+    const char* p = Kh + min(t * 32 + (lane & 31), n - 1) * tok_bytes + hf * 16;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int row = c * kStageTok + r0 + 16 * k;
-      reg[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (row < n) reg[k] = *reinterpret_cast<const uint4*>(Kh + (static_cast<long long>(row) * lay.stride_tok + chunk16 * 8) * 2);
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint4 w = *reinterpret_cast<const uint4*>(p + ks * 32);
+      dst[ks] = *reinterpret_cast<const bf16x8*>(&w);
     }
   };
-  fetch(0);
   const float scale = 0.08838834764831845f;
-  for (int c = 0; c < nchunks; ++c) {
-    __syncthreads();                                   // the stage is free again
-#pragma unroll
-    for (int k = 0; k < 8; ++k)
-      *reinterpret_cast<uint4*>(stage + (r0 + 16 * k) * kStagePitch + chunk16 * 16) = reg[k];
-    __syncthreads();
-    if (c + 1 < nchunks) fetch(c + 1);
+  if (wave < ntiles) fetch(wave, kf);
+  for (int t = wave; t < ntiles; t += 4) {
+    if (t + 4 < ntiles) fetch(t + 4, kn);
     f32x16 acc = {0};
-    const char* fp = stage + (wave * 32 + (lane & 31)) * kStagePitch + hf * 16;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], *reinterpret_cast<const bf16x8*>(fp + ks * 32), acc, 0, 0, 0);
-    const int j = c * kStageTok + wave * 32 + (lane & 31);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf[ks], acc, 0, 0, 0);
+    const int j = t * 32 + (lane & 31);
     if (j < n) {
       // lane (token, hf) holds query rows (r/4)*8 + hf*4 + r%4 of the 32x32 tile
 #pragma unroll
@@ -239,6 +232,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
         const int g = (r >> 2) * 8 + hf * 4 + (r & 3);
         if (g < G) zbuf[g * n + j] = acc[r] * scale;
       }
+    }
+    if (t + 4 < ntiles) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) kf[ks] = kn[ks];
     }
   }
   __syncthreads();
@@ -292,10 +289,10 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
 
 hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay, float* s_out,
                         hipStream_t st) {
-  // the logits of a head (G x n floats) wait in LDS beside the 35 KB stage
+  // the logits of a head (G x n floats) wait in LDS
   if (lay.dtype == DT_BF16 && G <= 32 && static_cast<long long>(G) * lay.n <= (G <= 8 ? 24576 : 31488)) {
     const int gq = G <= 8 ? 8 : 32;
-    const int smem_m = kStageTok * kStagePitch + (G * lay.n + 8 * gq) * 4;
+    const int smem_m = (G * lay.n + 8 * gq) * 4;
     auto go_m = [&](auto kern) -> hipError_t {
       const hipError_t em = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem_m);
