@@ -3,18 +3,19 @@
 // selection kernel, which takes u as its rows).  The L*H heads of a sequence are `group`
 // consecutive heads of the [heads, n, d] tensor.
 //
-// HBM-bound streaming reduction: a workgroup owns eight tokens of one sequence (2 KB contiguous
-// per head); its 512 threads are 8 tokens x 16 column chunks (eight elements each) x 4 slices of
-// the group, every thread sums its slice in fp32 with sixteen loads in flight, the four slices
-// meet in LDS.
+// HBM-bound streaming reduction: a workgroup owns four tokens of one sequence (1 KB contiguous
+// per head, one wave's request); its 512 threads are 4 tokens x 16 column chunks (eight elements
+// each) x 8 slices of the group, every thread sums its slice in fp32 with sixteen loads in flight,
+// the slices meet in LDS.  Four tokens rather than eight per workgroup: 1536 workgroups fill the
+// resident slots of 256 CUs in whole rounds on the benchmark shape (66-68 us against 76 us).
 #include "kvr_device.hpp"
 #include "kvr_kernels.hpp"
 
 namespace kvr {
 
 constexpr int kSigThreads = 512;
-constexpr int kSigTok = 8;                     // tokens per workgroup
-constexpr int kSigSlices = 4;                  // slices of the group per token
+constexpr int kSigTok = 4;                     // tokens per workgroup
+constexpr int kSigSlices = kSigThreads / (16 * kSigTok);   // slices of the group per token
 
 template <int DT>
 __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char* __restrict__ V, Layout lay,
@@ -67,8 +68,12 @@ __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char*
     const float inv = 1.0f / static_cast<float>(group);
     float o[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      o[e] = ((part[0][tid][e] + part[1][tid][e]) + (part[2][tid][e] + part[3][tid][e])) * inv;
+    for (int e = 0; e < 8; ++e) {
+      float t = part[0][tid][e];
+#pragma unroll
+      for (int q = 1; q < kSigSlices; ++q) t += part[q][tid][e];
+      o[e] = t * inv;
+    }
     float* dst = u_out + (static_cast<long long>(seq) * lay.n + tok) * kD + chunk * 8;
     *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
     *reinterpret_cast<float4*>(dst + 4) = make_float4(o[4], o[5], o[6], o[7]);
