@@ -48,7 +48,7 @@ struct PoolArgs {
 };
 
 template <int W, int S> struct PoolCfg {
-  static constexpr int kWaveStage = kPoolChunk * kPoolPitch + 1024;   // row stage + 256-float scratch per wave
+  static constexpr int kWaveStage = kPoolChunk * kPoolPitch + 1024 + 256;   // row stage + 256-float scratch + 64 squared norms per wave
   static constexpr int kTriBytes = kPool * (kPool + 1) / 2 * 4;
   static constexpr int kUnion = (W * kWaveStage > kTriBytes ? W * kWaveStage : kTriBytes);
   // floats: slots 64 | shared 16 | wcount 16 | pool_tok,r,s,m,picked 5*128 | pend 32 | pend_r 32 |
@@ -100,6 +100,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   const int base = w * TPW;
   char* stage = uni + w * Cfg::kWaveStage;
   float* scratch = reinterpret_cast<float*>(stage + CH * kPoolPitch);
+  float* norm_x = scratch + 256;                                 // [64] squared norms of the wave's current 64 tokens
 
   float s[S], m[S], r[S];
   int tok[S], pslot[S];          // pslot: pool slot of this token in the current epoch, or -1
@@ -218,33 +219,51 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     }
     t = b;
   } else {
-    // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the first read of V from HBM
-    {
-      const int c16 = tid & 15;
-      constexpr int kNB = 16;                        // rows per thread in flight (straight-line loads)
-      for (int j0 = 0; j0 < n; j0 += kNB * (NT / 16)) {
-        uint4 w8[kNB];
+    // Inverse norms (Eq. 1) are not taken in a pass of their own: the first epoch needs them for
+    // its pool members only, which get them while their rows are gathered, and every other token
+    // gets its norm in the first epoch's pass over V, which reads the row anyway.  Until then
+    // r = 0 (it is only ever used for pool members and in that pass).
+    // With 8 slots per lane (n > 2048) the extra code of the fused form does not fit the register
+    // file (it spills into the pass over V), so those heads keep the separate norm pass.
+    constexpr bool kFuseNorms = S <= 4;
+    bool have_r = !kFuseNorms;
+    if constexpr (!kFuseNorms) {
+      // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the first read of V from HBM
+      {
+        const int c16 = tid & 15;
+        constexpr int kNB = 16;                        // rows per thread in flight (straight-line loads)
+        for (int j0 = 0; j0 < n; j0 += kNB * (NT / 16)) {
+          uint4 w8[kNB];
 #pragma unroll
-        for (int u = 0; u < kNB; ++u) {
-          const int j = min(j0 + u * (NT / 16) + (tid >> 4), n - 1);
-          w8[u] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2);
+          for (int u = 0; u < kNB; ++u) {
+            const int j = min(j0 + u * (NT / 16) + (tid >> 4), n - 1);
+            w8[u] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2);
+          }
+#pragma unroll
+          for (int u = 0; u < kNB; ++u) {
+            const int j = j0 + u * (NT / 16) + (tid >> 4);
+            const float x[8] = {bf16_lo(w8[u].x), bf16_hi(w8[u].x), bf16_lo(w8[u].y), bf16_hi(w8[u].y),
+                                bf16_lo(w8[u].z), bf16_hi(w8[u].z), bf16_lo(w8[u].w), bf16_hi(w8[u].w)};
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+            ss = group16_sum(ss);
+            if (c16 == 0 && j < n) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
+          }
         }
+        lds_barrier();
 #pragma unroll
-        for (int u = 0; u < kNB; ++u) {
-          const int j = j0 + u * (NT / 16) + (tid >> 4);
-          const float x[8] = {bf16_lo(w8[u].x), bf16_hi(w8[u].x), bf16_lo(w8[u].y), bf16_hi(w8[u].y),
-                              bf16_lo(w8[u].z), bf16_hi(w8[u].z), bf16_lo(w8[u].w), bf16_hi(w8[u].w)};
-          float ss = 0.f;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
-          ss = group16_sum(ss);
-          if (c16 == 0 && j < n) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
-        }
+        for (int k = 0; k < S; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
       }
-      lds_barrier();
-#pragma unroll
-      for (int k = 0; k < S; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
     }
+    auto sum_sq = [](const uint4& x) -> float {
+      const float e[8] = {bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y),
+                          bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)};
+      float ss = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) ss = fmaf(e[q], e[q], ss);
+      return group16_sum(ss);                        // the 16 lanes of a row hold its 16-byte chunks
+    };
 
 #ifdef KVR_STATS
     long long st[6] = {0, 0, 0, 0, 0, 0};
@@ -317,6 +336,14 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #pragma unroll
         for (int k = 0; k < kGat; ++k)
           *reinterpret_cast<uint4*>(prow + (k * (NT / 16) + (tid >> 4)) * kPoolPitch + (tid & 15) * 16) = x[k];
+        if (!have_r) {
+#pragma unroll
+          for (int k = 0; k < kGat; ++k) {
+            const int slot = k * (NT / 16) + (tid >> 4);
+            const float ss = sum_sq(x[k]);
+            if ((tid & 15) == 0) pool_r[slot] = pool_tok[slot] < 0 ? 0.f : 1.0f / (sqrtf(ss) + a.eps);
+          }
+        }
       }
       lds_barrier();
       {
@@ -399,6 +426,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       for (int k = 0; k < S; ++k) {
         if (pslot[k] >= 0) {
           m[k] = pool_m[pslot[k]];
+          if (!have_r) r[k] = pool_r[pslot[k]];
           if (pool_picked[pslot[k]]) s[k] = -INFINITY;
         }
       }
@@ -463,9 +491,14 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           for (int sub = 0; sub < 4; ++sub) {
             wave_lds_sync();
 #pragma unroll
-            for (int q = 0; q < LPC; ++q)
-              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) =
-                  (k % kDepth == 0) ? preA[sub][q] : preB[sub][q];
+            for (int q = 0; q < LPC; ++q) {
+              const uint4 x = (k % kDepth == 0) ? preA[sub][q] : preB[sub][q];
+              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kPoolPitch + (lane & 15) * 16) = x;
+              if (!have_r) {                         // row (lane >> 4) + 4q of the sub-block belongs to lane 16*sub + row
+                const float ss = sum_sq(x);
+                if ((lane & 15) == 0) norm_x[sub * 16 + (lane >> 4) + 4 * q] = ss;
+              }
+            }
             if (k + kDepth < S) fetch(k + kDepth, sub, k % kDepth);
             wave_lds_sync();
             const char* fp = stage + (lane & 15) * kPoolPitch + kg * 16;
@@ -495,9 +528,11 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           wave_lds_sync();
           const float* sp = scratch + kg * 64 + (lane & 15);
           const float mx = hw_max(hw_max(sp[0], sp[16]), hw_max(sp[32], sp[48]));
+          if (!have_r && pslot[k] < 0) r[k] = tok[k] < n ? 1.0f / (sqrtf(norm_x[lane]) + a.eps) : 0.f;
           if (pslot[k] < 0) m[k] = hw_max(m[k], mx * r[k]);
         }
       }
+      have_r = true;
 #pragma unroll
       for (int k = 0; k < S; ++k) pslot[k] = -1;
       lds_barrier();                               // stages are dead: the next epoch reuses the area
