@@ -19,7 +19,8 @@
 //   4. one pass over V applies the rows picked in the epoch (<= 32, as one or two
 //      16-row MFMA operands, 16x16x32) to every token outside the pool.
 // On the benchmark inputs an epoch serves ~20 picks, so V is streamed ~b/20
-// times.  Nothing is approximated.
+// times.  Nothing is approximated.  lambda = 0 has a kernel of its own (select_topb_kernel);
+// this one would still return the right picks for it, after passes that change nothing.
 //
 // Layout: one workgroup per head, W wave64s, token j = 64*S*w + 64*k + lane in
 // wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   int32_t* order_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64);
   float* gain_l = smem + 96 + 5 * kPool + 64 + kPoolMaxB;
   int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64 + 2 * kPoolMaxB);
-  float* rn = smem + Cfg::kFixedFloats - TPW * W;                // [n padded] inverse norms, later pick flags
+  float* rn = smem + Cfg::kFixedFloats - TPW * W;                // [n padded] pick flags for the final ascending read-out
   int32_t* flag = reinterpret_cast<int32_t*>(rn);
   char* prow = reinterpret_cast<char*>(smem + Cfg::kFixedFloats);   // [P][272 B] pool rows
   char* uni = prow + kPool * kPoolPitch;
@@ -96,7 +97,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   const int n = a.n, b = a.b;
   const long long head_off = h * a.stride_head * 2;             // bytes
   const char* Vh = a.V + head_off;
-  const bool diverse = a.lambda != 0.0f;
   const int base = w * TPW;
   char* stage = uni + w * Cfg::kWaveStage;
   float* scratch = reinterpret_cast<float*>(stage + CH * kPoolPitch);
@@ -143,119 +143,12 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     wg_argmax(s, gmax, i);
     if (!(gmax > -INFINITY)) starved = true;
     else { if (tid == 0) { order_l[0] = i; gain_l[0] = gmax; } t = 1; }
-  } else if (!diverse) {
-    // lambda = 0: plain top-b of the scores (ties to the lower index); V is never read.  The b-th
-    // largest score key is found bit by bit (one workgroup-wide count per bit), the selected
-    // tokens are ranked among themselves, which gives the pick order.
-    int32_t* cnt_l = reinterpret_cast<int32_t*>(slot_gain);     // [2][16] per-wave counts
-    uint32_t* sel_key = reinterpret_cast<uint32_t*>(rn);        // [b]
-    int32_t* sel_tok = reinterpret_cast<int32_t*>(rn) + kPoolMaxB;
-    uint32_t key[S];
-#pragma unroll
-    for (int k = 0; k < S; ++k) key[k] = tok[k] < n ? ordered_key(s[k] + 0.0f) : 0u;   // -0 counts as +0
-    auto wg_count = [&](int c_w) -> int {
-      if (lane == 0) cnt_l[par * 16 + w] = c_w;
-      lds_barrier();
-      int c = 0;
-#pragma unroll
-      for (int u = 0; u < W; ++u) c += cnt_l[par * 16 + u];
-      par ^= 1;
-      return c;
-    };
-    uint32_t tau = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = tau | (1u << bit);
-      int c_w = 0;
-#pragma unroll
-      for (int k = 0; k < S; ++k) c_w += __popcll(__ballot(key[k] >= cand));
-      if (wg_count(c_w) >= b) tau = cand;
-    }
-    int above_w = 0, equal_w = 0;
-#pragma unroll
-    for (int k = 0; k < S; ++k) {
-      above_w += __popcll(__ballot(key[k] > tau));
-      equal_w += __popcll(__ballot(key[k] == tau));
-    }
-    // per-wave prefixes: selected-before (for the ascending index list) and equal-before (ties in token order)
-    if (lane == 0) { cnt_l[par * 16 + w] = above_w; wcount[w] = equal_w; }
-    lds_barrier();
-    int above_all = 0, above_before = 0, equal_before = 0;
-#pragma unroll
-    for (int u = 0; u < W; ++u) {
-      above_all += cnt_l[par * 16 + u];
-      if (u < w) { above_before += cnt_l[par * 16 + u]; equal_before += wcount[u]; }
-    }
-    par ^= 1;
-    const int need_eq = b - above_all;                 // >= 1 by construction of tau
-    int eq_taken_before = equal_before < need_eq ? equal_before : need_eq;
-    int pos = above_before + eq_taken_before;          // selected tokens before this wave, in token order
-    int eq_seen = equal_before;
-#pragma unroll
-    for (int k = 0; k < S; ++k) {
-      const bool above = key[k] > tau, equal = key[k] == tau;
-      const unsigned long long eqm = __ballot(equal);
-      const int my_eq = eq_seen + __popcll(eqm & ((1ull << lane) - 1ull));
-      const bool in = above || (equal && my_eq < need_eq);
-      const unsigned long long inm = __ballot(in);
-      if (in) {
-        const int p = pos + __popcll(inm & ((1ull << lane) - 1ull));
-        sel_key[p] = key[k];
-        sel_tok[p] = tok[k];
-      }
-      pos += __popcll(inm);
-      eq_seen += __popcll(eqm);
-    }
-    lds_barrier();
-    // rank of each selected token in (score descending, index ascending) order
-    for (int e = tid; e < b; e += NT) {
-      const uint32_t ke = sel_key[e];
-      int rank = 0;
-      for (int f = 0; f < b; ++f) {
-        const uint32_t kf = sel_key[f];
-        rank += (kf > ke || (kf == ke && f < e)) ? 1 : 0;      // the list is in token order: f < e <=> lower index
-      }
-      order_l[rank] = sel_tok[e];
-      gain_l[rank] = key_to_float(ke);
-    }
-    t = b;
   } else {
     // Inverse norms (Eq. 1) are not taken in a pass of their own: the first epoch needs them for
     // its pool members only, which get them while their rows are gathered, and every other token
     // gets its norm in the first epoch's pass over V, which reads the row anyway.  Until then
     // r = 0 (it is only ever used for pool members and in that pass).
-    // With 8 slots per lane (n > 2048) the extra code of the fused form does not fit the register
-    // file (it spills into the pass over V), so those heads keep the separate norm pass.
-    constexpr bool kFuseNorms = S <= 4;
-    bool have_r = !kFuseNorms;
-    if constexpr (!kFuseNorms) {
-      // ---- inverse norms (Eq. 1): 16 lanes per row, coalesced; the first read of V from HBM
-      {
-        const int c16 = tid & 15;
-        constexpr int kNB = 16;                        // rows per thread in flight (straight-line loads)
-        for (int j0 = 0; j0 < n; j0 += kNB * (NT / 16)) {
-          uint4 w8[kNB];
-#pragma unroll
-          for (int u = 0; u < kNB; ++u) {
-            const int j = min(j0 + u * (NT / 16) + (tid >> 4), n - 1);
-            w8[u] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(j) * a.stride_tok + c16 * 8) * 2);
-          }
-#pragma unroll
-          for (int u = 0; u < kNB; ++u) {
-            const int j = j0 + u * (NT / 16) + (tid >> 4);
-            const float x[8] = {bf16_lo(w8[u].x), bf16_hi(w8[u].x), bf16_lo(w8[u].y), bf16_hi(w8[u].y),
-                                bf16_lo(w8[u].z), bf16_hi(w8[u].z), bf16_lo(w8[u].w), bf16_hi(w8[u].w)};
-            float ss = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
-            ss = group16_sum(ss);
-            if (c16 == 0 && j < n) rn[j] = 1.0f / (sqrtf(ss) + a.eps);
-          }
-        }
-        lds_barrier();
-#pragma unroll
-        for (int k = 0; k < S; ++k) r[k] = tok[k] < n ? rn[tok[k]] : 0.f;
-      }
-    }
+    bool have_r = false;
     auto sum_sq = [](const uint4& x) -> float {
       const float e[8] = {bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y),
                           bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)};
@@ -267,7 +160,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 
 #ifdef KVR_STATS
     long long st[6] = {0, 0, 0, 0, 0, 0};
-    st[5] = __builtin_readcyclecounter() - st_begin;   // prologue: scores, norm pass
+    st[5] = __builtin_readcyclecounter() - st_begin;   // prologue: scores
 #endif
     while (t < b) {
 #ifdef KVR_STATS
@@ -467,7 +360,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         // are refilled for the group after next as soon as they have been written to the stage.
         // Rows past n are clamped to the last row (their results belong to padding tokens, whose
         // scores are -inf), so the loads are straight-line code.
-        constexpr int kDepth = 2;
+        // (one group with eight slots per lane: two do not fit the register file there)
+        constexpr int kDepth = S >= 8 ? 1 : 2;
         uint4 preA[4][LPC], preB[4][LPC];              // even and odd groups
         auto fetch = [&](int kk, int sub, int slot) {
           int row0 = base + (lane >> 4);
