@@ -71,6 +71,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_inplace_kernel(
         move[k] = u < total && i >= 0 && i != t;
         const long long src = head_off + min(max(i, 0), lay.n - 1) * tok_bytes + c * 16;
         dst[k] = head_off + t * tok_bytes + c * 16;
+        xk[k] = xv[k] = make_uint4(0u, 0u, 0u, 0u);
         if (K) xk[k] = *reinterpret_cast<const uint4*>(K + src);
         if (V) xv[k] = *reinterpret_cast<const uint4*>(V + src);
       }
