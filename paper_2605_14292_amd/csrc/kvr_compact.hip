@@ -1,6 +1,6 @@
 // Cache update of paper Sec. 4.1 / Algorithm 1's return value: keep the rows
-// at the ascending selected indices, bit for bit.  A group of 16 lanes moves
-// one row (16-byte chunks), so a wave moves four whole rows per request and
+// at the ascending selected indices, bit for bit.  A group of 16 (bf16) or 32 (fp32)
+// lanes moves one row in 16-byte units, so a wave moves whole rows per request and
 // the dense output is written fully coalesced.
 #include "kvr_device.hpp"
 #include "kvr_kernels.hpp"
@@ -9,30 +9,47 @@ namespace kvr {
 
 constexpr int kCompactThreads = 256;
 
+constexpr int kCompactUnits = 4;   // 16-byte units per thread, tensor and batch
+
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const char* __restrict__ K, const char* __restrict__ V, Layout lay, int ebytes,
     const int32_t* __restrict__ idx, int idx_group, int b, char* __restrict__ K_out,
     char* __restrict__ V_out) {
   const int h = blockIdx.x;
-  const int c = threadIdx.x & 15;
-  const int t = blockIdx.y * (kCompactThreads / 16) + (threadIdx.x >> 4);
-  if (t >= b) return;
-  int i = idx[static_cast<long long>(h / idx_group) * b + t];   // idx_group heads share one index row
-  i = min(max(i, 0), lay.n - 1);
-  const int row_bytes = lay.d * ebytes;
-  const long long src = (h * lay.stride_head + i * lay.stride_tok) * ebytes;
-  const long long dst = (static_cast<long long>(h) * b + t) * row_bytes;
-  for (int o = c * 16; o < row_bytes; o += 256) {
-    if (K) *reinterpret_cast<uint4*>(K_out + dst + o) = *reinterpret_cast<const uint4*>(K + src + o);
-    if (V) *reinterpret_cast<uint4*>(V_out + dst + o) = *reinterpret_cast<const uint4*>(V + src + o);
+  const int tid = threadIdx.x;
+  const int32_t* il = idx + static_cast<long long>(h / idx_group) * b;   // idx_group heads share one index row
+  const int cpr_shift = ebytes == 2 ? 4 : 5;               // 16-byte units per row: d = 128
+  const int total = b << cpr_shift;
+  const long long head_off = h * lay.stride_head * ebytes;
+  const long long tok_bytes = lay.stride_tok * ebytes;
+  const long long out_off = static_cast<long long>(h) * total * 16;
+  // one workgroup per head; every thread has its batch of loads in flight before the first store
+  for (int u0 = 0; u0 < total; u0 += kCompactThreads * kCompactUnits) {
+    uint4 xk[kCompactUnits], xv[kCompactUnits];
+#pragma unroll
+    for (int k = 0; k < kCompactUnits; ++k) {
+      const int u = min(u0 + k * kCompactThreads + tid, total - 1);
+      const int i = min(max(il[u >> cpr_shift], 0), lay.n - 1);
+      const long long src = head_off + i * tok_bytes + (u & ((1 << cpr_shift) - 1)) * 16;
+      xk[k] = xv[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (K) xk[k] = *reinterpret_cast<const uint4*>(K + src);
+      if (V) xv[k] = *reinterpret_cast<const uint4*>(V + src);
+    }
+#pragma unroll
+    for (int k = 0; k < kCompactUnits; ++k) {
+      const int u = u0 + k * kCompactThreads + tid;
+      if (u < total) {
+        if (K) *reinterpret_cast<uint4*>(K_out + out_off + u * 16ll) = xk[k];
+        if (V) *reinterpret_cast<uint4*>(V_out + out_off + u * 16ll) = xv[k];
+      }
+    }
   }
 }
 
 hipError_t launch_compact(const void* K, const void* V, const Layout& lay, const int32_t* idx,
                           int b, void* K_out, void* V_out, hipStream_t st, int idx_group) {
   const int ebytes = lay.dtype == DT_BF16 ? 2 : 4;
-  dim3 grid(lay.heads, (b + kCompactThreads / 16 - 1) / (kCompactThreads / 16));
-  hipLaunchKernelGGL(compact_kernel, grid, dim3(kCompactThreads), 0, st,
+  hipLaunchKernelGGL(compact_kernel, dim3(lay.heads), dim3(kCompactThreads), 0, st,
                      static_cast<const char*>(K), static_cast<const char*>(V), lay, ebytes, idx, idx_group, b,
                      static_cast<char*>(K_out), static_cast<char*>(V_out));
   return hipGetLastError();
