@@ -24,7 +24,8 @@
  * Common rules
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and return without synchronising.
- *   - Inputs are read-only; outputs must not alias inputs or each other.
+ *   - Inputs are read-only; outputs must not alias inputs or each other,
+ *     except where a call says otherwise (kvr_compact_inplace, kvr_score_prior).
  *   - The library allocates no device memory and keeps no state between
  *     calls.  `workspace` is reserved for future kernels: every entry point
  *     accepts NULL / 0 as long as kvr_workspace_bytes() reports 0 for the
