@@ -55,7 +55,8 @@ bool dense_supported(const Layout& lay, int b, int G, bool has_q);
 hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int G, const float* s_in,
                                const Layout& lay, int b, float lambda, float eps, float* s_out,
                                int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
-                               void* K_out, void* V_out, hipStream_t st, bool only_marked = false);
+                               void* K_out, void* V_out, hipStream_t st, bool only_marked = false,
+                               const int32_t* b_h = nullptr);
 
 // Fused path for bf16 heads with 128 < n <= 256 and given scores: tokens that the score bound
 // s_j < s_(b) - lambda excludes from every pick are dropped first; heads left with at most 128
@@ -64,7 +65,8 @@ hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int 
 bool pruned_supported(const Layout& lay, int b, float lambda, bool has_q);
 hipError_t launch_retain_pruned(const void* K, const void* V, const float* s, const Layout& lay, int b,
                                 float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
-                                float* pick_gain, void* K_out, void* V_out, hipStream_t st);
+                                float* pick_gain, void* K_out, void* V_out, hipStream_t st,
+                                const int32_t* b_h = nullptr);
 
 // Budget allocator frame (per-head candidate counts, budgets, protected tokens): score masking
 // and offsets before the selection, prefix cut, ascending read-out and row copy after it.

@@ -38,6 +38,7 @@ struct DenseArgs {
   int n, b, G, heads;
   float lambda, eps;
   int only_marked;                     // process only heads whose idx_sorted[h*b] is -1
+  const int32_t* b_h;                  // per-head budgets <= b (rows of the outputs stay b apart), or null
 };
 
 // Workgroups are persistent: each walks over heads blockIdx.x, blockIdx.x + gridDim.x, ...
@@ -259,9 +260,12 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     if (h_next < a.heads) prefetch(h_next, tid);
 
     // ---------------------------------------------------------------- greedy
+    // the head's own budget: its picks are the first bh picks of a run for b, so the chain stops there
+    const int bh = a.b_h ? __builtin_amdgcn_readfirstlane(min(max(a.b_h[h], 0), b)) : b;
     if (wave == 0) {
-      pick_chain<NQ>(s_l, tri, order_l, gain_l, n, b, a.lambda, diverse, lane);
-      sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, nullptr);   // rinv is dead by now
+      const int brun = bh < 1 ? 1 : bh;
+      pick_chain<NQ>(s_l, tri, order_l, gain_l, n, brun, a.lambda, diverse, lane);
+      sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), brun, lane, nullptr);   // rinv is dead by now
     }
     lds_barrier();
 
@@ -270,13 +274,13 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
 #endif
     // ------------------------------------------------- outputs and compaction
     const long long ob = static_cast<long long>(h) * b;
-    for (int t = tid; t < b; t += kDenseThreads) {
-      a.idx_sorted[ob + t] = idx_l[t];
-      if (a.pick_order) a.pick_order[ob + t] = order_l[t];
-      if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
+    for (int t = tid; t < b; t += kDenseThreads) {              // entries past the head's budget are padding
+      a.idx_sorted[ob + t] = t < bh ? idx_l[t] : -1;
+      if (a.pick_order) a.pick_order[ob + t] = t < bh ? order_l[t] : -1;
+      if (a.pick_gain) a.pick_gain[ob + t] = t < bh ? gain_l[t] : -INFINITY;
     }
-    if (a.K_out || a.V_out)
-      compact_rows<4>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idx_l, n, b, ob, tid, kDenseThreads);
+    if ((a.K_out || a.V_out) && bh > 0)
+      compact_rows<4>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idx_l, n, bh, ob, tid, kDenseThreads);
     lds_barrier();                                   // idx_l / s_l are reused by the next head
 #ifdef KVR_STATS
     {
@@ -303,9 +307,10 @@ bool dense_supported(const Layout& lay, int b, int G, bool has_q) {
 hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int G, const float* s_in,
                                const Layout& lay, int b, float lambda, float eps, float* s_out,
                                int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
-                               void* K_out, void* V_out, hipStream_t st, bool only_marked) {
+                               void* K_out, void* V_out, hipStream_t st, bool only_marked, const int32_t* b_h) {
   DenseArgs a;
   a.only_marked = only_marked ? 1 : 0;
+  a.b_h = b_h;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V);
   a.Q = static_cast<const char*>(Q); a.s_in = s_in; a.s_out = s_out;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;

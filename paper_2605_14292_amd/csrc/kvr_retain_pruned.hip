@@ -36,11 +36,12 @@ struct PrunedArgs {
   long long stride_head, stride_tok;         // elements
   int n, b, heads;
   float lambda, eps;
+  const int32_t* b_h;                        // per-head budgets <= b (output rows stay b apart), or null
 };
 
 constexpr int pruned_region_a() { return dense_region_a(4); }
 constexpr int pruned_smem_bytes() {
-  // region A | s_c[2][128] | tok_c[2][128] | rinv[128] | idx_l[2][128] | order_l[2][128] | gain_l[2][128] | meta[16: head, survivors, best left-out score, redo flag; two of each]
+  // region A | s_c[2][128] | tok_c[2][128] | rinv[128] | idx_l[2][128] | order_l[2][128] | gain_l[2][128] | meta[16: head, survivors, best left-out score, redo flag, picks to run, budget; two of each]
   return pruned_region_a() + 2 * kPrN * 4 * 2 + kPrN * 4 + 2 * kPrN * 4 * 3 + 64;
 }
 
@@ -77,6 +78,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     float sv[4];
     unsigned long long keep[4];
     int ns = 0;
+    int bq = b, bt = b;                               // budget of the head: its picks are the first bq of a run for b
     float excl = -INFINITY;                           // best score among the candidates left out
     for (; hh < a.heads; hh += gridDim.x) {
       if (hh == s_pre_h) {
@@ -85,6 +87,8 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       } else {
         load_scores(hh, lane, sv);
       }
+      bt = a.b_h ? __builtin_amdgcn_readfirstlane(min(max(a.b_h[hh], 0), b)) : b;
+      bq = bt < 1 ? 1 : bt;                          // a head with budget 0 still runs one pick; nothing of it is written
       uint32_t key[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) key[q] = lane + 64 * q < n ? ordered_key(sv[q] + 0.0f) : 0u;
@@ -96,7 +100,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         int cnt = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) cnt += __popcll(__ballot(key[q] >= cand));
-        if (cnt >= b) T = cand;
+        if (cnt >= bq) T = cand;
       }
       const float sb = key_to_float(T);
       const float thr = sb - a.lambda * 1.00001f - 1e-5f * fabsf(sb);
@@ -133,7 +137,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         if (valid && key[q] < cut) out_best = fmaxf(out_best, sv[q]);
       }
       excl = wave_max_uniform(out_best);
-      if (ns >= b && ns <= kPrN) break;
+      if (ns >= bq && ns <= kPrN) break;
       if (wave == 1 && lane == 0) a.idx_sorted[static_cast<long long>(hh) * b] = -1;
     }
     if (hh < a.heads) {
@@ -156,6 +160,8 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       meta[buf] = hh < a.heads ? hh : a.heads;
       meta[2 + buf] = ns;
       meta[4 + buf] = __float_as_int(excl);
+      meta[8 + buf] = bq;
+      meta[10 + buf] = bt;
     }
     s_pre_h = hh < a.heads ? hh + static_cast<int>(gridDim.x) : -1;
     if (s_pre_h >= 0 && s_pre_h < a.heads) load_scores(s_pre_h, lane, s_pre);
@@ -207,24 +213,24 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
   // clamped, not branched around): with branches in between the compiler loses count of what is
   // in flight and waits for everything, acknowledged stores included, before each store.
   constexpr int kOutBatch = 6;
-  auto out_lists = [&](int hh, int lb, int t0, int nthr) {
+  auto out_lists = [&](int hh, int lb, int t0, int nthr, int bq) {
     const long long ob = static_cast<long long>(hh) * b;
     const bool redo = meta[6 + lb] != 0;                 // the head is left to the full-size kernel
-    for (int t = t0; t < b; t += nthr) {
-      a.idx_sorted[ob + t] = (redo && t == 0) ? -1 : idx_l2[lb * kPrN + t];
-      if (a.pick_order) a.pick_order[ob + t] = order_l2[lb * kPrN + t];
-      if (a.pick_gain) a.pick_gain[ob + t] = gain_l2[lb * kPrN + t];
+    for (int t = t0; t < b; t += nthr) {                 // entries past the head's budget are padding
+      a.idx_sorted[ob + t] = ((redo && t == 0) || t >= bq) ? -1 : idx_l2[lb * kPrN + t];
+      if (a.pick_order) a.pick_order[ob + t] = t < bq ? order_l2[lb * kPrN + t] : -1;
+      if (a.pick_gain) a.pick_gain[ob + t] = t < bq ? gain_l2[lb * kPrN + t] : -INFINITY;
     }
   };
   uint4 kr[kOutBatch], vr[kOutBatch];
   const bool copy_both = a.K_out && a.V_out;
-  auto out_load = [&](int hh, int lb, int t0, int nthr, int first) {
+  auto out_load = [&](int hh, int lb, int t0, int nthr, int first, int bq) {
     const int32_t* il = idx_l2 + lb * kPrN;
     const long long head_off = hh * a.stride_head * 2 + (t0 & 15) * 16;   // bytes
     if (copy_both) {
 #pragma unroll
       for (int k = 0; k < kOutBatch; ++k) {
-        const int t = min(first + (t0 >> 4) + k * (nthr >> 4), b - 1);
+        const int t = min(first + (t0 >> 4) + k * (nthr >> 4), bq - 1);
         const int it = min(max(il[t], 0), n - 1);        // never read outside the head, whatever the scores were
         const long long src = head_off + it * a.stride_tok * 2;
         kr[k] = *reinterpret_cast<const uint4*>(a.K + src);
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     } else {
 #pragma unroll
       for (int k = 0; k < kOutBatch; ++k) {
-        const int t = min(first + (t0 >> 4) + k * (nthr >> 4), b - 1);
+        const int t = min(first + (t0 >> 4) + k * (nthr >> 4), bq - 1);
         const int it = min(max(il[t], 0), n - 1);
         const long long src = head_off + it * a.stride_tok * 2;
         kr[k] = vr[k] = make_uint4(0u, 0u, 0u, 0u);
@@ -242,12 +248,12 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       }
     }
   };
-  auto out_store = [&](int hh, int t0, int nthr, int first) {
+  auto out_store = [&](int hh, int t0, int nthr, int first, int bq) {
     const long long ob = static_cast<long long>(hh) * b;
 #pragma unroll
     for (int k = 0; k < kOutBatch; ++k) {
       const int t = first + (t0 >> 4) + k * (nthr >> 4);
-      if (t < b) {
+      if (t < bq) {
         const long long dst = ((ob + t) * kD + (t0 & 15) * 8) * 2;
         if (a.K_out) *reinterpret_cast<uint4*>(a.K_out + dst) = kr[k];
         if (a.V_out) *reinterpret_cast<uint4*>(a.V_out + dst) = vr[k];
@@ -262,6 +268,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #endif
   int buf = 0;
   int hprev = -1;                                     // head whose results are still in LDS
+  int bprev = b;                                      // and its budget
   if (wave != 0) {
     int ns0;
     const int h0 = survivors(blockIdx.x, 0, tid0, ns0);
@@ -277,6 +284,8 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63, hf = lane >> 5;
     const int ns = __builtin_amdgcn_readfirstlane(meta[2 + buf]);
+    const int bh = __builtin_amdgcn_readfirstlane(meta[8 + buf]);
+    const int bout = __builtin_amdgcn_readfirstlane(meta[10 + buf]);
     const float* s_cur = s_c + buf * kPrN;
     const int32_t* tok_cur = tok_c + buf * kPrN;
     int32_t* idx_l = idx_l2 + buf * kPrN;
@@ -351,7 +360,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       for (int k = 0; k < kOutBatch; ++k) {            // nothing of the previous head's rows is carried over
         kr[k] = vr[k] = make_uint4(0u, 0u, 0u, 0u);
       }
-      if (hprev >= 0) out_load(hprev, buf ^ 1, tl, kPrLoaders, 0);
+      if (hprev >= 0) out_load(hprev, buf ^ 1, tl, kPrLoaders, 0, bprev);
       int ns_n;
       const int h_n = survivors(h + gridDim.x, buf ^ 1, tid, ns_n);
 #ifdef KVR_STATS
@@ -359,11 +368,11 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
 #endif
       gather(h_n, buf ^ 1, ns_n, tid);   // in flight from here to the end of wave 0's chain
       if (hprev >= 0) {
-        out_lists(hprev, buf ^ 1, tl, kPrLoaders);
-        out_store(hprev, tl, kPrLoaders, 0);
-        for (int first = kStep; first < b; first += kStep) {
-          out_load(hprev, buf ^ 1, tl, kPrLoaders, first);
-          out_store(hprev, tl, kPrLoaders, first);
+        out_lists(hprev, buf ^ 1, tl, kPrLoaders, bprev);
+        out_store(hprev, tl, kPrLoaders, 0, bprev);
+        for (int first = kStep; first < bprev; first += kStep) {
+          out_load(hprev, buf ^ 1, tl, kPrLoaders, first, bprev);
+          out_store(hprev, tl, kPrLoaders, first, bprev);
         }
       }
 #ifdef KVR_STATS
@@ -376,7 +385,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     } else {
       // ---------------------------------------------------------------- greedy
       __builtin_amdgcn_s_setprio(3);                   // the chain goes first when it shares a SIMD with loader waves
-      const float last_g = pick_chain<2>(s_cur, tri, order_l, gain_l, ns, b, a.lambda, true, lane);
+      const float last_g = pick_chain<2>(s_cur, tri, order_l, gain_l, ns, bh, a.lambda, true, lane);
       __builtin_amdgcn_s_setprio(0);
       {
         // Candidates that were left out for lack of room must lie below every pick's gain (the
@@ -386,7 +395,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         if (lane == 0) meta[6 + buf] = (ok || excl == -INFINITY) ? 0 : 1;
       }
       // back to token indices: the survivor list is ascending in the token index
-      sort_picks<2>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, tok_cur);
+      sort_picks<2>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), bh, lane, tok_cur);
       // Wave 0 never holds gathered rows.  Saying so (no instruction is emitted) keeps the row
       // registers of the other branch from being carried, as far as the compiler can tell,
       // through this branch and with it through the whole loop body.
@@ -408,15 +417,16 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     st_acc[4] += ns; st_acc[5] += 1;
 #endif
     hprev = h;
+    bprev = bout;
     h = __builtin_amdgcn_readfirstlane(meta[buf ^ 1]);   // published before the barrier above
     buf ^= 1;
   }
   if (hprev >= 0) {
     constexpr int kStep = kOutBatch * (kDenseThreads / 16);
-    out_lists(hprev, buf ^ 1, tid0, kDenseThreads);
-    for (int first = 0; first < b; first += kStep) {
-      out_load(hprev, buf ^ 1, tid0, kDenseThreads, first);
-      out_store(hprev, tid0, kDenseThreads, first);
+    out_lists(hprev, buf ^ 1, tid0, kDenseThreads, bprev);
+    for (int first = 0; first < bprev; first += kStep) {
+      out_load(hprev, buf ^ 1, tid0, kDenseThreads, first, bprev);
+      out_store(hprev, tid0, kDenseThreads, first, bprev);
     }
 #ifdef KVR_STATS
     lds_barrier();
@@ -439,8 +449,9 @@ bool pruned_supported(const Layout& lay, int b, float lambda, bool has_q) {
 
 hipError_t launch_retain_pruned(const void* K, const void* V, const float* s, const Layout& lay, int b,
                                 float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
-                                float* pick_gain, void* K_out, void* V_out, hipStream_t st) {
+                                float* pick_gain, void* K_out, void* V_out, hipStream_t st, const int32_t* b_h) {
   PrunedArgs a;
+  a.b_h = b_h;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s = s;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);
