@@ -232,8 +232,8 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
  * reading, the paper is silent on them):
  *   n_h   device, int32 [heads] or NULL: only tokens j < n_h[h] are candidates
  *         (NULL: all n)
- *   b_h   device, int32 [heads] or NULL: budget of head h, b_h[h] <= b_max and
- *         <= n_h[h] (NULL: b_max everywhere)
+ *   b_h   device, int32 [heads] or NULL: budget of head h, 0 <= b_h[h] <= b_max
+ *         and <= n_h[h] (NULL: b_max everywhere); a budget of 0 keeps nothing
  *   keep  device, uint8 [heads, n] or NULL: non-zero marks protected tokens
  *         (sinks, a recent window).  They are members of S from the start, count
  *         towards b_h and penalise similar tokens through Eq. 2 like any other

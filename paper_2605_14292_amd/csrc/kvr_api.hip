@@ -221,8 +221,8 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
   if (kvr::launch_budget_prepare(src, l, n_h, keep, lambda_h, lambda, s_work, st) != hipSuccess)
     return KVR_ERR_HIP;
   // Short bf16 heads: the fused kernels take the per-head budgets themselves (the chain of a head
-  // stops at its own budget and the kept rows are written by the kernel that selected them); the
-  // finalize step is then left with the padding, the gains of protected tokens and the position ids.
+  // stops at its own budget; lists, padding and kept rows are written by the kernel that selected
+  // them); what is left is elementwise: the gains of protected tokens, per-head lambdas, position ids.
   const bool fused = (K_out == nullptr) == (V_out == nullptr) && (!K_out || K) &&
                      (kvr::pruned_supported(l, b_max, lambda, false) || kvr::dense_supported(l, b_max, 0, false));
   if (fused) {
@@ -238,8 +238,8 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
                                    pick_gain, K_out, V_out, st, false, b_h);
     }
     if (e != hipSuccess) return KVR_ERR_HIP;
-    if (kvr::launch_budget_finalize(nullptr, nullptr, l, b_h, b_max, keep, lambda_h, lambda, pos_in, idx_sorted,
-                                    pick_order, pick_gain, nullptr, nullptr, pos_out, st) != hipSuccess)
+    if (kvr::launch_budget_fixup(l, b_max, keep, lambda_h, lambda, pos_in, idx_sorted, pick_order, pick_gain,
+                                 pos_out, st) != hipSuccess)
       return KVR_ERR_HIP;
     return KVR_OK;
   }

@@ -21,17 +21,19 @@ namespace kvr {
 
 constexpr int kBudThreads = 256;
 
+// One wave per head (four heads per workgroup): no LDS, no barrier.
 __global__ __launch_bounds__(kBudThreads) void budget_prepare_kernel(
-    const float* __restrict__ s_src, int n, const int32_t* __restrict__ n_h,
+    const float* s_src, int heads, int n, const int32_t* __restrict__ n_h,
     const uint8_t* __restrict__ keep, const float* __restrict__ lambda_h, float lambda,
-    float* __restrict__ s_work) {
-  __shared__ float red_lo[kBudThreads / 64], red_hi[kBudThreads / 64];
-  const int h = blockIdx.x, tid = threadIdx.x;
+    float* s_work) {                             // s_work may be s_src (scores computed in place)
+  const int lane = threadIdx.x & 63;
+  const int h = blockIdx.x * (kBudThreads / 64) + (threadIdx.x >> 6);
+  if (h >= heads) return;
   const long long base = static_cast<long long>(h) * n;
   const int nh = n_h ? min(max(n_h[h], 0), n) : n;
   const float sc = lambda_h ? lambda / lambda_h[h] : 1.0f;     // lambda_h > 0 by contract
   float lo = INFINITY, hi = -INFINITY;
-  for (int j = tid; j < nh; j += kBudThreads) {
+  for (int j = lane; j < nh; j += kWave) {
     const float v = s_src[base + j] * sc;
     if (v > -INFINITY && v < INFINITY) { lo = fminf(lo, v); hi = fmaxf(hi, v); }
   }
@@ -40,13 +42,9 @@ __global__ __launch_bounds__(kBudThreads) void budget_prepare_kernel(
     lo = fminf(lo, __shfl_xor(lo, off, kWave));
     hi = fmaxf(hi, __shfl_xor(hi, off, kWave));
   }
-  if ((tid & 63) == 0) { red_lo[tid >> 6] = lo; red_hi[tid >> 6] = hi; }
-  __syncthreads();
-  lo = fminf(fminf(red_lo[0], red_lo[1]), fminf(red_lo[2], red_lo[3]));
-  hi = fmaxf(fmaxf(red_hi[0], red_hi[1]), fmaxf(red_hi[2], red_hi[3]));
   // no finite score: any offset will do (the picks are unspecified then)
   const float C = hi >= lo ? ((hi - lo) + lambda + 1.0f) * 1.001f : 1.0f;
-  for (int j = tid; j < n; j += kBudThreads) {
+  for (int j = lane; j < n; j += kWave) {
     float v = -INFINITY;
     if (j < nh) {
       v = s_src[base + j] * sc;
@@ -139,11 +137,46 @@ __global__ __launch_bounds__(kBudThreads) void budget_finalize_kernel(
   }
 }
 
+// After the kernels that take the per-head budgets themselves (they write the ascending index
+// lists, the padding and the kept rows): what is left is elementwise -- a protected token's gain
+// reads +inf, gains computed at the launch lambda go back to the head's own, position ids follow
+// the kept indices.
+__global__ __launch_bounds__(kBudThreads) void budget_fixup_kernel(
+    int n, int b_max, long long total, const uint8_t* __restrict__ keep, const float* __restrict__ lambda_h,
+    float lambda, const int32_t* __restrict__ pos_in, const int32_t* __restrict__ idx_sorted,
+    const int32_t* __restrict__ pick_order, float* __restrict__ pick_gain, int32_t* __restrict__ pos_out) {
+  const long long e = static_cast<long long>(blockIdx.x) * kBudThreads + threadIdx.x;
+  if (e >= total) return;
+  const long long h = e / b_max;
+  if (pick_gain && (keep || lambda_h)) {
+    const int i = pick_order[e];
+    if (i >= 0 && i < n) {
+      if (keep && keep[h * n + i]) pick_gain[e] = INFINITY;
+      else if (lambda_h) pick_gain[e] *= lambda_h[h] / lambda;
+    }
+  }
+  if (pos_out) {
+    const int i = idx_sorted[e];
+    pos_out[e] = (i >= 0 && i < n && pos_in) ? pos_in[h * n + i] : -1;
+  }
+}
+
+hipError_t launch_budget_fixup(const Layout& lay, int b_max, const uint8_t* keep, const float* lambda_h,
+                               float lambda, const int32_t* pos_in, const int32_t* idx_sorted,
+                               const int32_t* pick_order, float* pick_gain, int32_t* pos_out, hipStream_t st) {
+  if (!(pick_gain && (keep || lambda_h)) && !pos_out) return hipSuccess;     // nothing to fix up
+  const long long total = static_cast<long long>(lay.heads) * b_max;
+  hipLaunchKernelGGL(budget_fixup_kernel, dim3(static_cast<unsigned>((total + kBudThreads - 1) / kBudThreads)),
+                     dim3(kBudThreads), 0, st, lay.n, b_max, total, keep, lambda_h, lambda, pos_in, idx_sorted,
+                     pick_order, pick_gain, pos_out);
+  return hipGetLastError();
+}
+
 hipError_t launch_budget_prepare(const float* s_src, const Layout& lay, const int32_t* n_h,
                                  const uint8_t* keep, const float* lambda_h, float lambda, float* s_work,
                                  hipStream_t st) {
-  hipLaunchKernelGGL(budget_prepare_kernel, dim3(lay.heads), dim3(kBudThreads), 0, st, s_src, lay.n, n_h,
-                     keep, lambda_h, lambda, s_work);
+  hipLaunchKernelGGL(budget_prepare_kernel, dim3((lay.heads + kBudThreads / 64 - 1) / (kBudThreads / 64)),
+                     dim3(kBudThreads), 0, st, s_src, lay.heads, lay.n, n_h, keep, lambda_h, lambda, s_work);
   return hipGetLastError();
 }
 

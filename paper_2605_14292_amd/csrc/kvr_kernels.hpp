@@ -73,6 +73,9 @@ hipError_t launch_retain_pruned(const void* K, const void* V, const float* s, co
 hipError_t launch_budget_prepare(const float* s_src, const Layout& lay, const int32_t* n_h,
                                  const uint8_t* keep, const float* lambda_h, float lambda, float* s_work,
                                  hipStream_t st);
+hipError_t launch_budget_fixup(const Layout& lay, int b_max, const uint8_t* keep, const float* lambda_h,
+                               float lambda, const int32_t* pos_in, const int32_t* idx_sorted,
+                               const int32_t* pick_order, float* pick_gain, int32_t* pos_out, hipStream_t st);
 hipError_t launch_budget_finalize(const void* K, const void* V, const Layout& lay, const int32_t* b_h,
                                   int b_max, const uint8_t* keep, const float* lambda_h, float lambda,
                                   const int32_t* pos_in, int32_t* idx_sorted, int32_t* pick_order,

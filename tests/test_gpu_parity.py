@@ -455,6 +455,40 @@ def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
         assert np.all(out.pos_out[hh].cpu().numpy()[bh:] == -1)
 
 
+@pytest.mark.parametrize("n,b_max,lam", [(192, 64, 0.5), (120, 48, 0.5), (256, 128, 0.3), (200, 32, 0.0)])
+def test_budgeted_short_heads_match_the_unbudgeted_prefix(n, b_max, lam):
+    """On short bf16 heads the fused kernels take the per-head budgets themselves.  The picks for
+    budget b_h must be the first b_h picks of the plain run for b_max (a greedy pick depends on the
+    earlier picks only), the kept rows the rows of exactly those picks, and a budget of zero
+    writes nothing."""
+    h = 24
+    K, V, s = _mk(h, n, 6100 + n)
+    g = torch.Generator().manual_seed(n + b_max)
+    s = torch.randn((h, n), generator=g).exp().to(DEV)
+    V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
+    b_h = torch.randint(1, b_max + 1, (h,), generator=g, dtype=torch.int32)
+    b_h[0], b_h[1], b_h[2], b_h[3] = b_max, 1, 0, 2
+    full = B().kvr_retain(K, V, b_max, lam, 1e-6, s=s)
+    out = B().kvr_retain_budgeted(K, V, b_max, lam, 1e-6, s=s, b_h=b_h.to(DEV))
+    torch.cuda.synchronize()
+    fo, fg = full.pick_order.cpu().numpy(), full.pick_gain.cpu().numpy()
+    Kb, Vb = _bits(K), _bits(V)
+    for hh in range(h):
+        bh = int(b_h[hh])
+        order, gain, idx = (out.pick_order[hh].cpu().numpy(), out.pick_gain[hh].cpu().numpy(),
+                            out.idx_sorted[hh].cpu().numpy())
+        np.testing.assert_array_equal(order[:bh], fo[hh][:bh])
+        # (the two runs may take a head through different kernels, whose norms differ in the last bit)
+        np.testing.assert_allclose(gain[:bh], fg[hh][:bh], rtol=1e-5)
+        np.testing.assert_array_equal(idx[:bh], np.sort(fo[hh][:bh]))
+        assert np.all(order[bh:] == -1) and np.all(idx[bh:] == -1) and np.all(np.isneginf(gain[bh:]))
+        np.testing.assert_array_equal(_bits(out.K_out[hh])[:bh], O.compact(Kb[hh], idx[:bh]))
+        np.testing.assert_array_equal(_bits(out.V_out[hh])[:bh], O.compact(Vb[hh], idx[:bh]))
+        assert not _bits(out.K_out[hh])[bh:].any() and not _bits(out.V_out[hh])[bh:].any()
+    # the plain run itself is checked against the oracle
+    _check_heads(W.WORKLOADS["c3"], {"K": K, "V": V, "s": s}, full, b_max, lam, 1e-6, range(0, h, 5))
+
+
 @pytest.mark.parametrize("n,b,dtype,G", [(8192, 24, torch.bfloat16, 0), (8192, 16, torch.float32, 256),
                                          (4096, 1024, torch.bfloat16, 0), (4096, 256, torch.bfloat16, 8),
                                          (256, 256, torch.bfloat16, 0), (192, 192, torch.float32, 0)])
