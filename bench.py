@@ -101,7 +101,7 @@ def cpu_baseline_budgeted(w, data, b_h, keep, lam, budget_s=12.0):
                       f"{t_used:.1f} s, rate extrapolates linearly over heads)"}
 
 
-def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False, cold=False):
+def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False, cold=False, budgeted=False):
     """A short run of another benchmark configuration at its full size, for the
     `other_configs` object: the default workload carries the headline figures, the others are
     reported beside it from the same process.  `cold`: the small configurations (c1, c2) fit the
@@ -120,6 +120,16 @@ def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False, cold=False
         s = s.view(w.seqs, group, w.n)[:, 0].contiguous()
         out = B.FlatBuffers(w.heads, group, w.n, w.b, w.d, w.torch_dtype, "cuda:0", want_trace=False)
         step = lambda: B.kvr_retain_flat(data["K"], data["V"], s, group, w.b, lam, 1e-6, out=out)
+    elif budgeted:      # the frame of main()'s --budgeted: b_h in [b/2, b], 4 sinks + 16 recent protected, position ids
+        g = torch.Generator(device="cuda:0").manual_seed(seed + 17)
+        b_h = torch.randint(w.b // 2, w.b + 1, (w.heads,), generator=g, device="cuda:0", dtype=torch.int32)
+        keep = torch.zeros((w.heads, w.n), dtype=torch.uint8, device="cuda:0")
+        keep[:, :4] = 1
+        keep[:, w.n - 16:] = 1
+        pos = torch.arange(w.n, dtype=torch.int32, device="cuda:0").repeat(w.heads, 1).contiguous()
+        out = B.BudgetBuffers(w.heads, w.n, w.b, w.d, w.torch_dtype, "cuda:0", with_pos=True)
+        step = lambda: B.kvr_retain_budgeted(data["K"], data["V"], w.b, lam, 1e-6, Q=Q, s=s, b_h=b_h, keep=keep,
+                                             pos=pos, out=out)
     else:
         out = B.RetainBuffers(w.heads, w.n, w.b, w.d, w.torch_dtype, "cuda:0", "Q" in data, want_trace=False)
         step = lambda: B.kvr_retain(data["K"], data["V"], w.b, lam, 1e-6, Q=Q, s=s, out=out)
@@ -150,6 +160,9 @@ def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False, cold=False
     bytes_step = w.algorithmic_bytes_per_head(w.b, lam) * w.heads
     if flat:
         bytes_step -= (4 * w.n + 4 * w.b) * (w.heads - w.seqs)
+    if budgeted:
+        rows = (3 if w.scores == "given" else 2) * w.d * w.elem_bytes
+        bytes_step += int((float(b_h.float().mean().item()) - w.b) * rows * w.heads) + (w.n + 4 * w.n + 4 * w.b) * w.heads
     del data, out
     torch.cuda.empty_cache()
     res = {"ms_per_step": ms, "head_events_per_s": w.heads / (ms * 1e-3), "steps": steps,
@@ -347,6 +360,7 @@ def main():
             "c1": time_other("c1", steps=20, warmup=5, seed=args.seed, cold=True),
             "c2": time_other("c2", steps=20, warmup=5, seed=args.seed, cold=True),
             "c3 flat-signature mode": time_other("c3", seed=args.seed, flat=True),
+            "c3 budget-allocator frame": time_other("c3", seed=args.seed, budgeted=True),
             "c5": time_other("c5", seed=args.seed),
             "c5 lambda=0": time_other("c5", seed=args.seed, lam=0.0),
             "c4": time_other("c4", seed=args.seed),
