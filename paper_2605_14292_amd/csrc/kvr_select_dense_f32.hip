@@ -3,8 +3,12 @@
 // bf16 numbers, and fp32 caches.  One workgroup of sixteen wave64s per head (such launches have
 // few heads, so the latency of one head is what counts):
 //
-//   rows     staged in LDS as fp32, 129-float pitch (column reads of 32 rows hit 32 banks)
-//   Gram     lower-triangular 32x32 tiles on the fp32 MFMA (32x32x2, fp32 products and sums)
+//   rows     staged in LDS as fp32, 132-float pitch (16-byte aligned rows; eight consecutive rows
+//            cover the 32 banks with their 16-byte pieces)
+//   Gram     lower-triangular 32x32 tiles on the fp32 MFMA (32x32x2, fp32 products and sums).  Which
+//            two of the 128 k an MFMA multiplies is free as long as both operands agree: MFMA m
+//            takes k = m for the lower half-wave and k = 64 + m for the upper one, so a lane reads
+//            64 consecutive floats of its row, four per LDS request
 //   norms    r_j = 1/(||V_j|| + eps) from the Gram diagonal              (Eq. 1)
 //   cosines  packed fp32 triangle in the space the rows were staged in   (Algorithm 1, Sims)
 //   greedy   the single-wave pick loop of the bf16 kernels                (Eq. 2-3)
@@ -15,7 +19,7 @@
 
 namespace kvr {
 
-constexpr int kF32Pitch = 129;                 // floats per staged row
+constexpr int kF32Pitch = 132;                 // floats per staged row
 constexpr int kF32MaxB = 256;
 constexpr int kF32Threads = 1024;
 constexpr int kF32Waves = kF32Threads / 64;
@@ -25,8 +29,8 @@ __host__ __device__ constexpr int f32_region_a(int NT) {
   return ((tri > stage ? tri : stage) + 15) & ~15;
 }
 __host__ __device__ constexpr int f32_smem_bytes(int NT) {
-  // region A | s_l[N32] | rinv[N32] | idx_l | order_l | gain_l
-  return f32_region_a(NT) + NT * 32 * 4 * 2 + kF32MaxB * 4 * 3;
+  // region A | s_l[N32] | rinv[N32] | idx_l | order_l | gain_l | tok_c[N32] | meta[4]
+  return f32_region_a(NT) + NT * 32 * 4 * 2 + kF32MaxB * 4 * 3 + NT * 32 * 4 + 16;
 }
 
 struct F32Args {
@@ -51,6 +55,8 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
   int32_t* idx_l = reinterpret_cast<int32_t*>(rinv + N32);
   int32_t* order_l = idx_l + kF32MaxB;
   float* gain_l = reinterpret_cast<float*>(order_l + kF32MaxB);
+  int32_t* tok_c = reinterpret_cast<int32_t*>(gain_l + kF32MaxB);     // [N32] tokens of the reduced problem
+  int32_t* meta = tok_c + N32;                                         // [0] its size, 0 = not reduced
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, hf = lane >> 5;
@@ -59,33 +65,103 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
   const int n = a.n, b = a.b;
   const bool diverse = a.lambda != 0.0f && b > 1;
 
+#ifdef KVR_STATS
+  const long long q0 = __builtin_readcyclecounter();
+  long long q1 = q0, q2 = q0, q3 = q0;
+#endif
   if (tid < N32) s_l[tid] = tid < n ? a.s[static_cast<long long>(h) * n + tid] : -INFINITY;
+  if (tid == 0) meta[0] = 0;
   typedef __attribute__((ext_vector_type(16))) float f32x16_t;
   f32x16_t acc[MAXT];
+  int ns = 0;                                       // size of the reduced problem, 0 = all n tokens
   if (diverse) {
-    // rows -> LDS, 32 threads per row (float4 each), rows past n read as zero
+    // Exact candidate reduction for heads of more than 128 tokens: a token with s_j < s_(b) - lambda
+    // never wins Eq. 3 (while fewer than b tokens are selected one of the b best-scored is free and
+    // gains at least s_(b) - lambda; the token itself gains at most s_j).  When at most 128 tokens
+    // remain, the head shrinks to them: fewer Gram tiles, two tokens per lane in the pick loop.
+    // The survivors keep their order, so ties break as before.
+    if constexpr (NT > 4) {
+      __syncthreads();
+      if (wave == 0) {
+        float sv[NQ];
+        uint32_t key[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          sv[q] = s_l[lane + 64 * q];
+          key[q] = lane + 64 * q < n ? ordered_key(sv[q] + 0.0f) : 0u;
+        }
+        // s_(b) from the leading 16 bits of the ordered keys: at most s_(b), so the bound only loosens
+        uint32_t T = 0;
+        for (int bit = 31; bit >= 16; --bit) {
+          const uint32_t cand = T | (1u << bit);
+          int cnt = 0;
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) cnt += __popcll(__ballot(key[q] >= cand));
+          if (cnt >= b) T = cand;
+        }
+        const float sb = key_to_float(T);
+        const float thr = sb - a.lambda * 1.00001f - 1e-5f * fabsf(sb);   // cosines may exceed 1 by a few ulp
+        unsigned long long keep[NQ];
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          keep[q] = __ballot(lane + 64 * q < n && !(sv[q] < thr));
+          cnt += __popcll(keep[q]);
+        }
+        if (cnt >= b && cnt <= 128) {
+          wave_lds_sync();                            // every lane holds its scores before s_l is rewritten
+          int base = 0;
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) {
+            if ((keep[q] >> lane) & 1ull) {
+              const int c = base + __popcll(keep[q] & ((1ull << lane) - 1ull));
+              tok_c[c] = lane + 64 * q;
+              s_l[c] = sv[q];
+            }
+            base += __popcll(keep[q]);
+          }
+          for (int c = cnt + lane; c < 128; c += kWave) s_l[c] = -INFINITY;   // padding never competes
+          if (lane == 0) meta[0] = cnt;
+        }
+      }
+      __syncthreads();
+      ns = meta[0];
+    }
+    // rows -> LDS, 32 threads per row (float4 each), rows past the end read as zero
     const float* Vh = a.V + h * a.stride_head;
-    for (int r = tid >> 5; r < N32; r += kF32Threads / 32) {
+    const int nrows = ns ? 128 : N32;
+    for (int r = tid >> 5; r < nrows; r += kF32Threads / 32) {
       float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < n) x = *reinterpret_cast<const float4*>(Vh + r * a.stride_tok + (tid & 31) * 4);
-      float* d = stage + r * kF32Pitch + (tid & 31) * 4;
-      d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+      const int tok = ns ? (r < ns ? tok_c[r] : -1) : (r < n ? r : -1);
+      if (tok >= 0) x = *reinterpret_cast<const float4*>(Vh + tok * a.stride_tok + (tid & 31) * 4);
+      *reinterpret_cast<float4*>(stage + r * kF32Pitch + (tid & 31) * 4) = x;
     }
     __syncthreads();
-    // tile t of the lower triangle: row block I, column block J <= I
+#ifdef KVR_STATS
+    q1 = __builtin_readcyclecounter();
+#endif
+    // tile t of the lower triangle: row block I, column block J <= I (only the blocks in use)
+    const int nblk = ns ? (ns + 31) >> 5 : NT;
+    const int ntiles = nblk * (nblk + 1) / 2;
 #pragma unroll
     for (int sl = 0; sl < MAXT; ++sl) {
       const int tile = wave + kF32Waves * sl;
       acc[sl] = f32x16_t{0};
-      if (tile < NTILES) {
+      if (tile < ntiles) {
         int I = 0;
         while ((I + 1) * (I + 2) / 2 <= tile) ++I;
         const int J = tile - I * (I + 1) / 2;
-        const float* pa = stage + (I * 32 + (lane & 31)) * kF32Pitch + hf;
-        const float* pb = stage + (J * 32 + (lane & 31)) * kF32Pitch + hf;
-#pragma unroll 8
-        for (int ks = 0; ks < kD / 2; ++ks)
-          acc[sl] = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[2 * ks], pb[2 * ks], acc[sl], 0, 0, 0);
+        const float* pa = stage + (I * 32 + (lane & 31)) * kF32Pitch + hf * (kD / 2);
+        const float* pb = stage + (J * 32 + (lane & 31)) * kF32Pitch + hf * (kD / 2);
+#pragma unroll 4
+        for (int q = 0; q < kD / 8; ++q) {
+          const float4 xa = *reinterpret_cast<const float4*>(pa + 4 * q);
+          const float4 xb = *reinterpret_cast<const float4*>(pb + 4 * q);
+          acc[sl] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.x, xb.x, acc[sl], 0, 0, 0);
+          acc[sl] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.y, xb.y, acc[sl], 0, 0, 0);
+          acc[sl] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.z, xb.z, acc[sl], 0, 0, 0);
+          acc[sl] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.w, xb.w, acc[sl], 0, 0, 0);
+        }
         if (I == J) {                                 // squared norms sit on the diagonal
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
@@ -96,12 +172,15 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
       }
     }
     __syncthreads();                                  // staged rows are dead from here on
-    if (tid < N32) rinv[tid] = 1.0f / (sqrtf(rinv[tid]) + a.eps);
+#ifdef KVR_STATS
+    q2 = __builtin_readcyclecounter();
+#endif
+    if (tid < nblk * 32) rinv[tid] = 1.0f / (sqrtf(rinv[tid]) + a.eps);
     __syncthreads();
 #pragma unroll
     for (int sl = 0; sl < MAXT; ++sl) {
       const int tile = wave + kF32Waves * sl;
-      if (tile < NTILES) {
+      if (tile < ntiles) {
         int I = 0;
         while ((I + 1) * (I + 2) / 2 <= tile) ++I;
         const int J = tile - I * (I + 1) / 2;
@@ -110,10 +189,18 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
     }
   }
   __syncthreads();
+#ifdef KVR_STATS
+  q3 = __builtin_readcyclecounter();
+#endif
 
   if (wave == 0) {
-    pick_chain<NQ>(s_l, tri, order_l, gain_l, n, b, a.lambda, diverse, lane);
-    sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, nullptr);
+    if (ns) {                                           // the reduced problem: indices go back through tok_c
+      pick_chain<2>(s_l, tri, order_l, gain_l, ns, b, a.lambda, diverse, lane);
+      sort_picks<2>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, tok_c);
+    } else {
+      pick_chain<NQ>(s_l, tri, order_l, gain_l, n, b, a.lambda, diverse, lane);
+      sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, nullptr);
+    }
   }
   __syncthreads();
   const long long ob = static_cast<long long>(h) * b;
@@ -122,6 +209,15 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
     if (a.pick_order) a.pick_order[ob + t] = order_l[t];
     if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
   }
+#ifdef KVR_STATS
+  __syncthreads();
+  if (tid == 0 && a.pick_gain && b >= 8) {
+    const long long q4 = __builtin_readcyclecounter();
+    float* o = a.pick_gain + ob + b - 1;
+    o[0] = static_cast<float>(q1 - q0); o[-1] = static_cast<float>(q2 - q1); o[-2] = static_cast<float>(q3 - q2);
+    o[-3] = static_cast<float>(q4 - q3);
+  }
+#endif
 }
 
 bool dense_f32_supported(const Layout& lay, int b) {

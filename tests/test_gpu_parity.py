@@ -146,6 +146,24 @@ def test_score_bound_reduction_mixed_heads(n, b, lam):
     assert torch.equal(sel[0], out.idx_sorted) and torch.equal(sel[1], out.pick_order)
 
 
+@pytest.mark.parametrize("n,b,lam", [(150, 16, 0.05), (192, 64, 0.5), (192, 64, 5.0), (256, 100, 0.3), (256, 128, 0.02),
+                                     (129, 2, 0.5), (200, 128, 0.5)])
+def test_fp32_rows_with_score_bound_reduction(n, b, lam):
+    # fp32 heads of more than 128 tokens: with a small lambda (relative to the spread of the scores) the
+    # kernel shrinks the head to the tokens the score bound leaves, with a large one it keeps all
+    h = 6
+    K, V, _ = _mk(h, n, 9900 + n + b, torch.float32)
+    g = torch.Generator().manual_seed(n * 3 + b)
+    s = torch.randn((h, n), generator=g).exp()
+    s[1] = torch.floor(s[1] * 4) / 4                      # ties at the bound
+    s[2, : n // 3] = 50.0                                 # a third of the tokens far above the rest
+    s = s.to(DEV)
+    V[:, n // 2:] = V[:, : n - n // 2] + 0.02 * V[:, n // 2:]
+    out = B().kvr_retain(K, V, b, lam, 1e-6, s=s)
+    torch.cuda.synchronize()
+    _check_heads(W.WORKLOADS["c1"], {"K": K, "V": V, "s": s}, out, b, lam, 1e-6, range(h))
+
+
 def test_exactly_representable_inputs_match_with_zero_near_ties():
     # signed basis rows (norm 1, eps 0) with duplicates, dyadic scores and
     # lambda: every quantity is exact in fp32, so the picks must be the
