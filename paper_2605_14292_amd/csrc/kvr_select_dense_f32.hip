@@ -75,6 +75,16 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
   f32x16_t acc[MAXT];
   int ns = 0;                                       // size of the reduced problem, 0 = all n tokens
   if (diverse) {
+    // the rows start their trip from memory before anything else: 32 threads per row (float4
+    // each), rows past n read as zero
+    const float* Vh = a.V + h * a.stride_head;
+    float4 xr[NT];
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const int r = (tid >> 5) + 32 * k;
+      xr[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < n) xr[k] = *reinterpret_cast<const float4*>(Vh + r * a.stride_tok + (tid & 31) * 4);
+    }
     // Exact candidate reduction for heads of more than 128 tokens: a token with s_j < s_(b) - lambda
     // never wins Eq. 3 (while fewer than b tokens are selected one of the b best-scored is free and
     // gains at least s_(b) - lambda; the token itself gains at most s_j).  When at most 128 tokens
@@ -113,11 +123,13 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
           int base = 0;
 #pragma unroll
           for (int q = 0; q < NQ; ++q) {
-            if ((keep[q] >> lane) & 1ull) {
-              const int c = base + __popcll(keep[q] & ((1ull << lane) - 1ull));
+            const bool kept = (keep[q] >> lane) & 1ull;
+            const int c = base + __popcll(keep[q] & ((1ull << lane) - 1ull));
+            if (kept) {
               tok_c[c] = lane + 64 * q;
               s_l[c] = sv[q];
             }
+            idx_l[lane + 64 * q] = kept ? c : -1;        // where the token's row goes (idx_l is free until the sort)
             base += __popcll(keep[q]);
           }
           for (int c = cnt + lane; c < 128; c += kWave) s_l[c] = -INFINITY;   // padding never competes
@@ -127,15 +139,16 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
       __syncthreads();
       ns = meta[0];
     }
-    // rows -> LDS, 32 threads per row (float4 each), rows past the end read as zero
-    const float* Vh = a.V + h * a.stride_head;
-    const int nrows = ns ? 128 : N32;
-    for (int r = tid >> 5; r < nrows; r += kF32Threads / 32) {
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      const int tok = ns ? (r < ns ? tok_c[r] : -1) : (r < n ? r : -1);
-      if (tok >= 0) x = *reinterpret_cast<const float4*>(Vh + tok * a.stride_tok + (tid & 31) * 4);
-      *reinterpret_cast<float4*>(stage + r * kF32Pitch + (tid & 31) * 4) = x;
+    // rows -> LDS: at their own position, or at their position in the reduced problem
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const int r = (tid >> 5) + 32 * k;
+      const int dst = ns ? idx_l[r] : r;
+      if (dst >= 0) *reinterpret_cast<float4*>(stage + dst * kF32Pitch + (tid & 31) * 4) = xr[k];
     }
+    if (ns)                                           // rows between the survivors and the end of their last block
+      for (int r = ns + (tid >> 5); r < ((ns + 31) & ~31); r += kF32Threads / 32)
+        *reinterpret_cast<float4*>(stage + r * kF32Pitch + (tid & 31) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 #ifdef KVR_STATS
     q1 = __builtin_readcyclecounter();
