@@ -415,6 +415,78 @@ def test_flat_mode_full_size_sampled_sequences():
             np.testing.assert_array_equal(_bits(out.V_out[h]), O.compact(_bits(data["V"][h]), idx))
 
 
+def test_budgeted_frame_full_size_sampled_heads():
+    # c3's shape in the launch configuration bench.py --budgeted times: 8192 heads, budgets in
+    # [b/2, b], four sink tokens and a recent window of 16 protected, position ids
+    w = W.WORKLOADS["c3"]
+    data = W.generate(w, seed=0, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(17)
+    b_h = torch.randint(w.b // 2, w.b + 1, (w.heads,), generator=g, device=DEV, dtype=torch.int32)
+    keep = torch.zeros((w.heads, w.n), dtype=torch.uint8, device=DEV)
+    keep[:, :4] = 1
+    keep[:, w.n - 16:] = 1
+    pos = (torch.arange(w.n, dtype=torch.int32, device=DEV) * 2 + 1).repeat(w.heads, 1).contiguous()
+    out = B().kvr_retain_budgeted(data["K"], data["V"], w.b, w.lam, 1e-6, s=data["s"], b_h=b_h, keep=keep, pos=pos)
+    torch.cuda.synchronize()
+    bh_all = b_h.cpu().numpy()
+    idx_all = out.idx_sorted.cpu().numpy()
+    # properties of every head: budget respected, ascending, protected tokens kept, padding
+    valid = np.arange(w.b)[None, :] < bh_all[:, None]
+    assert np.all(idx_all[~valid] == -1) and np.all(idx_all[valid] >= 0) and np.all(idx_all[valid] < w.n)
+    assert np.all((np.diff(idx_all, axis=1) > 0) | ~valid[:, 1:])
+    kept = np.zeros((w.heads, w.n), dtype=bool)
+    rows = np.repeat(np.arange(w.heads), w.b).reshape(w.heads, w.b)
+    kept[rows[valid], idx_all[valid]] = True
+    assert kept[:, :4].all() and kept[:, w.n - 16:].all()
+    kp = keep[0].cpu().numpy().astype(bool)
+    for hh in np.random.default_rng(5).choice(w.heads, size=24, replace=False):
+        bh = int(bh_all[hh])
+        s64, V64 = W.to_f64(data["s"][hh]), W.to_f64(data["V"][hh])
+        ref = O.select_budgeted(s64, V64, w.n, bh, kp, w.lam, 1e-6)
+        order = out.pick_order[hh].cpu().numpy()
+        gain = out.pick_gain[hh].cpu().numpy().astype(np.float64)
+        idx = idx_all[hh]
+        npz = len(ref["protected"])
+        assert sorted(order[:npz].tolist()) == ref["protected"].tolist() and np.all(np.isinf(gain[:npz]))
+        if order[npz:bh].tolist() == ref["order"].tolist():
+            np.testing.assert_allclose(gain[npz:bh], ref["gain"], rtol=P.GAIN_RTOL,
+                                       atol=P.GAIN_RTOL * (np.abs(s64).max() + w.lam))
+        else:                                                    # a near-tie: every pick on the HIP path's own prefix
+            Vh = O.signatures(V64, 1e-6); cos = Vh @ Vh.T
+            S = list(order[:npz])
+            for t in range(npz, bh):
+                red = np.maximum(0.0, cos[:, S].max(axis=1))
+                gt = s64 - w.lam * red
+                gt[S] = -np.inf
+                i = int(order[t])
+                scale = max(abs(s64[i]) + w.lam * red[i], 1e-30)
+                assert gt.max() - gt[i] <= P.NEAR_TIE * scale, (hh, t)
+                assert abs(gain[t] - gt[i]) <= P.GAIN_RTOL * scale, (hh, t)
+                S.append(i)
+        assert sorted(order[:bh].tolist()) == idx[:bh].tolist()
+        np.testing.assert_array_equal(_bits(out.K_out[hh])[:bh], O.compact(_bits(data["K"][hh]), idx[:bh]))
+        np.testing.assert_array_equal(_bits(out.V_out[hh])[:bh], O.compact(_bits(data["V"][hh]), idx[:bh]))
+        np.testing.assert_array_equal(out.pos_out[hh].cpu().numpy()[:bh], idx[:bh] * 2 + 1)
+
+
+def test_observation_window_scores_full_size_sampled_heads():
+    # c5 with an observation window of 32 positions (224 queries per head) and c4 with 64 (256):
+    # the configurations bench.py --window times; scores of sampled heads against the oracle
+    import dataclasses
+    for name, window, sample in (("c5", 32, 6), ("c4", 64, 3)):
+        w0 = W.WORKLOADS[name]
+        w = dataclasses.replace(w0, G=w0.G * window)
+        data = W.generate(w, seed=0, device=DEV)
+        s = B().kvr_score(data["K"], data["Q"])
+        torch.cuda.synchronize()
+        assert torch.allclose(s.sum(dim=1), torch.ones(w.heads, device=DEV), atol=2e-4)
+        for hh in np.random.default_rng(9).choice(w.heads, size=sample, replace=False):
+            s64 = O.score_softmax_mean(W.to_f64(data["K"][hh]), W.to_f64(data["Q"][hh]))
+            P.check_scores(s[hh].cpu().numpy(), s64)
+        del data, s
+        torch.cuda.empty_cache()
+
+
 # ---------------------------------------------------------------- budgets and protected tokens
 @pytest.mark.parametrize("n,b_max,lam,dtype,computed", [
     (192, 64, 0.5, torch.bfloat16, False), (256, 100, 0.3, torch.bfloat16, True), (120, 48, 0.7, torch.bfloat16, False),
