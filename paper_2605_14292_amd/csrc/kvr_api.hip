@@ -220,14 +220,19 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
   }
   if (kvr::launch_budget_prepare(src, l, n_h, keep, lambda_h, lambda, s_work, st) != hipSuccess)
     return KVR_ERR_HIP;
-  // Short bf16 heads: the fused kernels take the per-head budgets themselves (the chain of a head
+  // bf16 heads of up to 4096 tokens: the fused kernels take the per-head budgets themselves (the chain of a head
   // stops at its own budget; lists, padding and kept rows are written by the kernel that selected
   // them); what is left is elementwise: the gains of protected tokens, per-head lambdas, position ids.
+  const bool long_heads = lambda > 0.0f && kvr::pool_supported(l, b_max);
   const bool fused = (K_out == nullptr) == (V_out == nullptr) && (!K_out || K) &&
-                     (kvr::pruned_supported(l, b_max, lambda, false) || kvr::dense_supported(l, b_max, 0, false));
+                     (kvr::pruned_supported(l, b_max, lambda, false) || kvr::dense_supported(l, b_max, 0, false) ||
+                      long_heads);
   if (fused) {
     hipError_t e;
-    if (kvr::pruned_supported(l, b_max, lambda, false)) {
+    if (long_heads) {
+      e = kvr::launch_select_pool(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
+                                  V_out, st, b_h);
+    } else if (kvr::pruned_supported(l, b_max, lambda, false)) {
       e = kvr::launch_retain_pruned(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
                                     V_out, st, b_h);
       if (e == hipSuccess)

@@ -94,6 +94,7 @@ hipError_t launch_select_blocked(const void* K, const void* V, const float* s, c
 bool pool_supported(const Layout& lay, int b);
 hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
-                              float* pick_gain, void* K_out, void* V_out, hipStream_t st);
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st,
+                              const int32_t* b_h = nullptr);
 
 }  // namespace kvr

@@ -46,6 +46,7 @@ struct PoolArgs {
   long long stride_head, stride_tok;   // elements
   int n, b;
   float lambda, eps;
+  const int32_t* b_h;                  // per-head budgets <= b (output rows stay b apart), or null
 };
 
 template <int W, int S> struct PoolCfg {
@@ -58,7 +59,9 @@ template <int W, int S> struct PoolCfg {
   static constexpr int kSmemBytes = kFixedFloats * 4 + kPool * kPoolPitch + kUnion;
 };
 
-template <int W, int S>
+// BUD: per-head budgets are read from a.b_h (a variant of its own: the extra live value costs the
+// plain kernel a register it does not have).
+template <int W, int S, bool BUD>
 __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(PoolArgs a) {
   using Cfg = PoolCfg<W, S>;
   constexpr int TPW = 64 * S;
@@ -94,7 +97,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #endif
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n = a.n, b = a.b;
+  const int n = a.n;
+  // the head's own budget: its picks are the first b picks of a run for a.b (the rows of the
+  // outputs per head), so the epochs stop there
+  const int b = BUD ? min(max(a.b_h[blockIdx.x], 0), a.b) : a.b;      // a scalar load: the index is uniform
   const long long head_off = h * a.stride_head * 2;             // bytes
   const char* Vh = a.V + head_off;
   const int base = w * TPW;
@@ -481,13 +487,21 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     }
   }
   lds_barrier();
-  const long long ob = static_cast<long long>(h) * b;
+  const int bs = a.b;
+  const long long ob = static_cast<long long>(h) * bs;
   for (int u = tid; u < b; u += NT) {
     a.idx_sorted[ob + u] = idxs_l[u];
     if (a.pick_order) a.pick_order[ob + u] = order_l[u];
     if (a.pick_gain) a.pick_gain[ob + u] = gain_l[u];
   }
-  if (a.K_out || a.V_out)
+  if constexpr (BUD) {
+    for (int u = b + tid; u < bs; u += NT) {                   // entries past the head's budget are padding
+      a.idx_sorted[ob + u] = -1;
+      if (a.pick_order) a.pick_order[ob + u] = -1;
+      if (a.pick_gain) a.pick_gain[ob + u] = -INFINITY;
+    }
+  }
+  if ((a.K_out || a.V_out) && (!BUD || b > 0))
     compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
 #ifdef KVR_STATS
   if (tid == 0 && a.pick_gain && b >= 8)
@@ -501,8 +515,9 @@ bool pool_supported(const Layout& lay, int b) {
 
 hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
-                              float* pick_gain, void* K_out, void* V_out, hipStream_t st) {
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st, const int32_t* b_h) {
   PoolArgs a;
+  a.b_h = b_h;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s_in = s;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);
@@ -516,10 +531,16 @@ hipError_t launch_select_pool(const void* K, const void* V, const float* s, cons
     hipLaunchKernelGGL(kern, grid, dim3(threads), smem, st, a);
     return hipGetLastError();
   };
-  if (lay.n <= 512) return go(&select_pool_kernel<2, 4>, 128, PoolCfg<2, 4>::kSmemBytes);
-  if (lay.n <= 1024) return go(&select_pool_kernel<4, 4>, 256, PoolCfg<4, 4>::kSmemBytes);
-  if (lay.n <= 2048) return go(&select_pool_kernel<8, 4>, 512, PoolCfg<8, 4>::kSmemBytes);
-  return go(&select_pool_kernel<8, 8>, 512, PoolCfg<8, 8>::kSmemBytes);
+  if (b_h) {
+    if (lay.n <= 512) return go(&select_pool_kernel<2, 4, true>, 128, PoolCfg<2, 4>::kSmemBytes);
+    if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, true>, 256, PoolCfg<4, 4>::kSmemBytes);
+    if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, true>, 512, PoolCfg<8, 4>::kSmemBytes);
+    return go(&select_pool_kernel<8, 8, true>, 512, PoolCfg<8, 8>::kSmemBytes);
+  }
+  if (lay.n <= 512) return go(&select_pool_kernel<2, 4, false>, 128, PoolCfg<2, 4>::kSmemBytes);
+  if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, false>, 256, PoolCfg<4, 4>::kSmemBytes);
+  if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, false>, 512, PoolCfg<8, 4>::kSmemBytes);
+  return go(&select_pool_kernel<8, 8, false>, 512, PoolCfg<8, 8>::kSmemBytes);
 }
 
 }  // namespace kvr

@@ -545,13 +545,14 @@ def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
         assert np.all(out.pos_out[hh].cpu().numpy()[bh:] == -1)
 
 
-@pytest.mark.parametrize("n,b_max,lam", [(192, 64, 0.5), (120, 48, 0.5), (256, 128, 0.3), (200, 32, 0.0)])
-def test_budgeted_short_heads_match_the_unbudgeted_prefix(n, b_max, lam):
-    """On short bf16 heads the fused kernels take the per-head budgets themselves.  The picks for
+@pytest.mark.parametrize("n,b_max,lam", [(192, 64, 0.5), (120, 48, 0.5), (256, 128, 0.3), (200, 32, 0.0),
+                                         (600, 64, 0.5), (1024, 128, 0.5), (3000, 40, 1.0)])
+def test_budgeted_heads_match_the_unbudgeted_prefix(n, b_max, lam):
+    """On bf16 heads of up to 4096 tokens the fused kernels take the per-head budgets themselves.  The picks for
     budget b_h must be the first b_h picks of the plain run for b_max (a greedy pick depends on the
     earlier picks only), the kept rows the rows of exactly those picks, and a budget of zero
     writes nothing."""
-    h = 24
+    h = 24 if n <= 1024 else 8
     K, V, s = _mk(h, n, 6100 + n)
     g = torch.Generator().manual_seed(n + b_max)
     s = torch.randn((h, n), generator=g).exp().to(DEV)
