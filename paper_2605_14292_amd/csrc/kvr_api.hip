@@ -224,12 +224,15 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
   // stops at its own budget; lists, padding and kept rows are written by the kernel that selected
   // them); what is left is elementwise: the gains of protected tokens, per-head lambdas, position ids.
   const bool long_heads = lambda > 0.0f && kvr::pool_supported(l, b_max);
+  const bool long_topb = kvr::topb_supported(l, b_max, lambda) && l.dtype == KVR_BF16;
   const bool fused = (K_out == nullptr) == (V_out == nullptr) && (!K_out || K) &&
                      (kvr::pruned_supported(l, b_max, lambda, false) || kvr::dense_supported(l, b_max, 0, false) ||
-                      long_heads);
+                      long_heads || long_topb);
   if (fused) {
     hipError_t e;
-    if (long_heads) {
+    if (long_topb) {
+      e = kvr::launch_select_topb(K, V, s_work, l, b_max, idx_sorted, pick_order, pick_gain, K_out, V_out, st, b_h);
+    } else if (long_heads) {
       e = kvr::launch_select_pool(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
                                   V_out, st, b_h);
     } else if (kvr::pruned_supported(l, b_max, lambda, false)) {

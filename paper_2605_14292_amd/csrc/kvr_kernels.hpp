@@ -17,7 +17,7 @@ hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay,
 bool topb_supported(const Layout& lay, int b, float lambda);
 hipError_t launch_select_topb(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
-                              void* V_out, hipStream_t st);
+                              void* V_out, hipStream_t st, const int32_t* b_h = nullptr);
 // bf16 scores for up to 256 queries per head and any n: two passes over K on the matrix cores.
 bool score_wide_supported(const Layout& lay, int G);
 hipError_t launch_score_wide(const void* K, const void* Q, int G, const Layout& lay, float* s_out,

@@ -23,6 +23,7 @@ struct TopbArgs {
   char* K_out; char* V_out;
   long long stride_head, stride_tok;   // elements (bf16 when K_out / V_out are given)
   int n, b;
+  const int32_t* b_h;                  // per-head budgets <= b (output rows stay b apart), or null
 };
 
 template <int S>
@@ -36,10 +37,12 @@ __global__ __launch_bounds__(kTopbThreads) void select_topb_kernel(TopbArgs a) {
   int32_t* sel_tok = reinterpret_cast<int32_t*>(sel_key) + a.b;    // [b] = sort(S)
   int32_t* order_l = sel_tok + a.b;                                 // [b]
   float* gain_l = reinterpret_cast<float*>(order_l + a.b);          // [b]
+  const int bs = a.b;                                               // rows of the outputs per head
 
   const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n = a.n, b = a.b;
+  const int n = a.n;
+  const int b = a.b_h ? min(max(a.b_h[h], 0), bs) : bs;             // the head's own budget
   uint32_t key[S];
 #pragma unroll
   for (int k = 0; k < S; ++k) {
@@ -104,13 +107,13 @@ __global__ __launch_bounds__(kTopbThreads) void select_topb_kernel(TopbArgs a) {
   }
   lds_barrier();
   // ---- 4. outputs
-  const long long ob = static_cast<long long>(h) * b;
-  for (int u = tid; u < b; u += NT) {
-    a.idx_sorted[ob + u] = sel_tok[u];
-    if (a.pick_order) a.pick_order[ob + u] = order_l[u];
-    if (a.pick_gain) a.pick_gain[ob + u] = gain_l[u];
+  const long long ob = static_cast<long long>(h) * bs;
+  for (int u = tid; u < bs; u += NT) {                              // entries past the head's budget are padding
+    a.idx_sorted[ob + u] = u < b ? sel_tok[u] : -1;
+    if (a.pick_order) a.pick_order[ob + u] = u < b ? order_l[u] : -1;
+    if (a.pick_gain) a.pick_gain[ob + u] = u < b ? gain_l[u] : -INFINITY;
   }
-  if (a.K_out || a.V_out)
+  if ((a.K_out || a.V_out) && b > 0)
     compact_rows<4>(a.K, a.V, a.K_out, a.V_out, h * a.stride_head * 2, a.stride_tok, sel_tok, n, b, ob, tid, NT);
 }
 
@@ -120,8 +123,9 @@ bool topb_supported(const Layout& lay, int b, float lambda) {
 
 hipError_t launch_select_topb(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
-                              void* V_out, hipStream_t st) {
+                              void* V_out, hipStream_t st, const int32_t* b_h) {
   TopbArgs a;
+  a.b_h = b_h;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s_in = s;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);

@@ -546,7 +546,7 @@ def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
 
 
 @pytest.mark.parametrize("n,b_max,lam", [(192, 64, 0.5), (120, 48, 0.5), (256, 128, 0.3), (200, 32, 0.0),
-                                         (600, 64, 0.5), (1024, 128, 0.5), (3000, 40, 1.0)])
+                                         (600, 64, 0.5), (1024, 128, 0.5), (3000, 40, 1.0), (1000, 64, 0.0), (5000, 200, 0.0)])
 def test_budgeted_heads_match_the_unbudgeted_prefix(n, b_max, lam):
     """On bf16 heads of up to 4096 tokens the fused kernels take the per-head budgets themselves.  The picks for
     budget b_h must be the first b_h picks of the plain run for b_max (a greedy pick depends on the
