@@ -650,6 +650,15 @@ def test_strided_layouts_in_every_mode(n, dtype):
     c = B().kvr_retain_budgeted(Kc, Vc, b, 0.5, 1e-6, s=s, b_h=b_h, keep=keep)
     torch.cuda.synchronize()
     assert torch.equal(a.idx_sorted, c.idx_sorted) and torch.equal(a.K_out, c.K_out) and torch.equal(a.V_out, c.V_out)
+    # lambda = 0 (the top-b kernel on long heads), plain and with budgets
+    a, c = B().kvr_retain(K, V, b, 0.0, 1e-6, s=s), B().kvr_retain(Kc, Vc, b, 0.0, 1e-6, s=s)
+    torch.cuda.synchronize()
+    assert torch.equal(a.pick_order, c.pick_order) and torch.equal(a.K_out, c.K_out) and torch.equal(a.V_out, c.V_out)
+    _check_heads(W.WORKLOADS["c3"], {"K": Kc, "V": Vc, "s": s}, a, b, 0.0, 1e-6, range(h))
+    a = B().kvr_retain_budgeted(K, V, b, 0.0, 1e-6, s=s, b_h=b_h, keep=keep)
+    c = B().kvr_retain_budgeted(Kc, Vc, b, 0.0, 1e-6, s=s, b_h=b_h, keep=keep)
+    torch.cuda.synchronize()
+    assert torch.equal(a.idx_sorted, c.idx_sorted) and torch.equal(a.K_out, c.K_out) and torch.equal(a.V_out, c.V_out)
 
 
 @pytest.mark.parametrize("n,G", [(200, 12), (256, 32), (900, 28), (984, 32), (1500, 20)])
