@@ -183,6 +183,8 @@ def kernel_name(w, b, lam, has_q):
         return ("kvr::retain_pruned_kernel (the whole step; kvr::retain_dense_kernel follows for the heads "
                 "it marks, a few microseconds when there are none)")
     if w.dtype == "bf16" and w.n <= 256:
+        if w.n > 128 and w.heads <= 256:
+            return "kvr::retain_dense16_kernel (the whole step is this one launch; one head per CU, sixteen waves each)"
         return "kvr::retain_dense_kernel (the whole step is this one launch)"
     if w.dtype == "bf16" and w.n <= 4096 and b <= 256:
         tail = ["kvr::select_pool_kernel (selection + compaction)"]

@@ -39,6 +39,33 @@ int check_select(const kvr_layout* lay, int b, float lambda, float eps) {
   return KVR_OK;
 }
 
+// Compute units of the current device (256 on an MI355X), looked up once.
+int cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      cus = v;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+// The fused kernel for bf16 heads of up to 256 tokens: sixteen waves per head when every head gets
+// a CU to itself, four otherwise.
+hipError_t retain_dense_any(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                            const kvr::Layout& l, int b, float lambda, float eps, float* s_out,
+                            int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out, void* V_out,
+                            hipStream_t st, const int32_t* b_h = nullptr) {
+  if (kvr::dense16_supported(l, b, G, Q != nullptr, cu_count()))
+    return kvr::launch_retain_dense16(K, V, Q, G, s_in, l, b, lambda, eps, s_out, idx_sorted, pick_order,
+                                      pick_gain, K_out, V_out, st, b_h);
+  return kvr::launch_retain_dense(K, V, Q, G, s_in, l, b, lambda, eps, s_out, idx_sorted, pick_order, pick_gain,
+                                  K_out, V_out, st, false, b_h);
+}
+
 // Selection without compaction: the kernel is chosen by shape only.
 hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int b, float lambda, float eps,
                        int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, hipStream_t st) {
@@ -50,8 +77,8 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
                                     pick_order, pick_gain, nullptr, nullptr, st, true);
   }
   if (kvr::dense_supported(l, b, 0, false))
-    return kvr::launch_retain_dense(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
-                                    pick_order, pick_gain, nullptr, nullptr, st);
+    return retain_dense_any(nullptr, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted, pick_order,
+                            pick_gain, nullptr, nullptr, st);
   if (kvr::dense_f32_supported(l, b))
     return kvr::launch_select_dense_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
   if (kvr::topb_supported(l, b, lambda))
@@ -151,8 +178,8 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
   const kvr::Layout l = to_dev(lay);
   const float* s = s_in;
   if (Q && kvr::dense_supported(l, b, G, true)) {       // short heads, few queries: scoring is fused too
-    const hipError_t e = kvr::launch_retain_dense(K, V, Q, G, nullptr, l, b, lambda, eps, s_out, idx_sorted,
-                                                  pick_order, pick_gain, K_out, V_out, st);
+    const hipError_t e = retain_dense_any(K, V, Q, G, nullptr, l, b, lambda, eps, s_out, idx_sorted, pick_order,
+                                          pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (Q) {
@@ -169,8 +196,8 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (kvr::dense_supported(l, b, 0, false)) {
-    const hipError_t e = kvr::launch_retain_dense(K, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted,
-                                                  pick_order, pick_gain, K_out, V_out, st);
+    const hipError_t e = retain_dense_any(K, V, nullptr, 0, s, l, b, lambda, eps, nullptr, idx_sorted, pick_order,
+                                          pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (kvr::topb_supported(l, b, lambda) && l.dtype == KVR_BF16) {
@@ -242,8 +269,8 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
         e = kvr::launch_retain_dense(K, V, nullptr, 0, s_work, l, b_max, lambda, eps, nullptr, idx_sorted,
                                      pick_order, pick_gain, K_out, V_out, st, true, b_h);
     } else {
-      e = kvr::launch_retain_dense(K, V, nullptr, 0, s_work, l, b_max, lambda, eps, nullptr, idx_sorted, pick_order,
-                                   pick_gain, K_out, V_out, st, false, b_h);
+      e = retain_dense_any(K, V, nullptr, 0, s_work, l, b_max, lambda, eps, nullptr, idx_sorted, pick_order,
+                           pick_gain, K_out, V_out, st, b_h);
     }
     if (e != hipSuccess) return KVR_ERR_HIP;
     if (kvr::launch_budget_fixup(l, b_max, keep, lambda_h, lambda, pos_in, idx_sorted, pick_order, pick_gain,

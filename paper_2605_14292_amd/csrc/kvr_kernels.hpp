@@ -58,6 +58,14 @@ hipError_t launch_retain_dense(const void* K, const void* V, const void* Q, int 
                                void* K_out, void* V_out, hipStream_t st, bool only_marked = false,
                                const int32_t* b_h = nullptr);
 
+// The same event for calls with at most one head per CU (heads <= cus) and 128 < n <= 256: sixteen
+// waves per head for the parallel phases.
+bool dense16_supported(const Layout& lay, int b, int G, bool has_q, int cus);
+hipError_t launch_retain_dense16(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                                 const Layout& lay, int b, float lambda, float eps, float* s_out,
+                                 int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
+                                 void* V_out, hipStream_t st, const int32_t* b_h = nullptr);
+
 // Fused path for bf16 heads with 128 < n <= 256 and given scores: tokens that the score bound
 // s_j < s_(b) - lambda excludes from every pick are dropped first; heads left with at most 128
 // candidates are finished, the others get idx_sorted[h*b] = -1 and must be passed to
