@@ -164,6 +164,35 @@ def test_fp32_rows_with_score_bound_reduction(n, b, lam):
     _check_heads(W.WORKLOADS["c1"], {"K": K, "V": V, "s": s}, out, b, lam, 1e-6, range(h))
 
 
+@pytest.mark.parametrize("n,b,G,lam", [(256, 128, 7, 0.5), (200, 64, 4, 0.3), (192, 150, 0, 0.5), (250, 40, 0, 0.0)])
+def test_batched_and_single_event_kernels_agree_on_short_heads(n, b, G, lam):
+    """Heads of 128 < n <= 256 tokens go through the sixteen-wave kernel when the call has at most one
+    head per CU and through the four-wave kernel when it is batched: the same heads must give the
+    same picks either way, and both are checked against the oracle."""
+    h_big, h_small = 300, 40
+    K, V, s = _mk(h_big, n, 7300 + n + b)
+    V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
+    g = torch.Generator().manual_seed(n + G)
+    Q = torch.randn((h_big, G, 128), generator=g).to(torch.bfloat16).to(DEV) if G else None
+    s = None if G else torch.randn((h_big, n), generator=g).exp().to(DEV)
+    big = B().kvr_retain(K, V, b, lam, 1e-6, Q=Q, s=s)
+    small = B().kvr_retain(K[:h_small].contiguous(), V[:h_small].contiguous(), b, lam, 1e-6,
+                           Q=None if Q is None else Q[:h_small].contiguous(), s=None if s is None else s[:h_small].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(big.pick_order[:h_small], small.pick_order)
+    assert torch.equal(big.idx_sorted[:h_small], small.idx_sorted)
+    assert torch.equal(big.K_out[:h_small], small.K_out) and torch.equal(big.V_out[:h_small], small.V_out)
+    torch.testing.assert_close(big.pick_gain[:h_small], small.pick_gain, rtol=1e-5, atol=1e-7)
+    data = {"K": K, "V": V}
+    if G:
+        data["Q"] = Q
+    else:
+        data["s"] = s
+    _check_heads(W.WORKLOADS["c2"], data, big, b, lam, 1e-6, [0, 17, 150, 299])
+    data_s = {k: v[:h_small] for k, v in data.items()}
+    _check_heads(W.WORKLOADS["c2"], data_s, small, b, lam, 1e-6, [0, 17, 39])
+
+
 def test_exactly_representable_inputs_match_with_zero_near_ties():
     # signed basis rows (norm 1, eps 0) with duplicates, dyadic scores and
     # lambda: every quantity is exact in fp32, so the picks must be the
