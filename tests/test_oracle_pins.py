@@ -406,3 +406,83 @@ def test_score_pooling_matches_the_library_pooling_and_hand_values():
         np.testing.assert_array_equal(O.score_pool(x, k), F.max_pool1d(t, k, stride=1, padding=k // 2)[0, 0].numpy())
         np.testing.assert_allclose(O.score_pool(x, k, mean=True),
                                    F.avg_pool1d(t, k, stride=1, padding=k // 2)[0, 0].numpy(), rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------------------------------ randomized properties (hypothesis)
+def _problem(draw_n, draw_seed):
+    rng = np.random.default_rng(draw_seed)
+    n = draw_n
+    s = rng.normal(size=n).round(3)
+    V = rng.normal(size=(n, 6))
+    V[rng.integers(0, n)] = V[rng.integers(0, n)] * 2.0          # a pair of parallel rows now and then
+    return s, V
+
+
+def test_random_properties_of_algorithm1():
+    """Facts that hold for every input (Sec. 4.1, Eq. 2-3): a token permutation permutes the picks
+    (when no two gains tie), adding a constant to every score changes no pick and shifts every gain,
+    the first pick is the argmax of s, and a larger budget only appends picks."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None)
+    @given(n=st.integers(2, 24), seed=st.integers(0, 10**6), lam=st.sampled_from([0.0, 0.1, 0.5, 2.0]),
+           kfrac=st.floats(0.1, 1.0))
+    def run(n, seed, lam, kfrac):
+        s, V = _problem(n, seed)
+        k = max(1, int(round(kfrac * n)))
+        r = O.alpha_select(s, V, k, lam)
+        order, gain = r["order"], r["gain"]
+        assert order[0] == int(np.flatnonzero(s == s.max())[0])
+        assert len(set(order.tolist())) == k and np.all(np.diff(gain) <= 1e-12)
+        # a larger budget appends
+        if k < n:
+            r2 = O.alpha_select(s, V, k + 1, lam)
+            assert r2["order"][:k].tolist() == order.tolist()
+        # constant shift of the scores
+        r3 = O.alpha_select(s + 3.25, V, k, lam)
+        assert r3["order"].tolist() == order.tolist()
+        np.testing.assert_allclose(r3["gain"], gain + 3.25, rtol=0, atol=1e-9)
+        # permutation equivariance, checked only when the run has no (near-)ties
+        free = O.alpha_select(s, V, k, lam)
+        if "second" in free and np.all(free["gain"] - free["second"] > 1e-9):
+            perm = np.random.default_rng(seed + 1).permutation(n)
+            rp = O.alpha_select(s[perm], V[perm], k, lam)
+            assert perm[rp["order"]].tolist() == order.tolist()
+
+    run()
+
+
+def test_random_properties_of_the_budgeted_frame_and_the_epilogues():
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=40, deadline=None)
+    @given(n=st.integers(3, 20), seed=st.integers(0, 10**6), lam=st.sampled_from([0.1, 0.5, 2.0]))
+    def run(n, seed, lam):
+        s, V = _problem(n, seed)
+        rng = np.random.default_rng(seed + 7)
+        n_h = int(rng.integers(2, n + 1))
+        b_h = int(rng.integers(1, n_h + 1))
+        keep = np.zeros(n, dtype=bool)
+        keep[rng.choice(n_h, size=int(rng.integers(0, b_h + 1)), replace=False)] = True
+        r = O.select_budgeted(s, V, n_h, b_h, keep, lam)
+        chosen = r["sorted"].tolist()
+        assert len(chosen) == b_h and max(chosen) < n_h and set(np.flatnonzero(keep).tolist()) <= set(chosen)
+        # every non-protected pick is the argmax of Eq. 2 over the free candidates, given everything before it
+        Vh = O.signatures(V[:n_h], 1e-6)
+        S = r["protected"].tolist()
+        for i, g in zip(r["order"].tolist(), r["gain"].tolist()):
+            gains = O.marginal_gains(s[:n_h], Vh, S, lam)
+            gains[S] = -np.inf
+            assert i == int(np.flatnonzero(gains == gains.max())[0]) and abs(gains[i] - g) < 1e-12
+            S.append(i)
+        # pooling: max-pool dominates the scores, mean-pool preserves the sum up to the zero padding at the ends
+        k = int(rng.choice([1, 3, 5]))
+        assert np.all(O.score_pool(s, k) >= s)
+        inner = O.score_pool(np.pad(s, (k // 2, k // 2)), k, mean=True)
+        np.testing.assert_allclose(inner.sum(), s.sum(), rtol=0, atol=1e-9)
+        # the modular prior is bounded by |lambda_p| and vanishes with it
+        pr = O.score_mean_direction_prior(s, V, 0.7, 1e-6) - s
+        assert np.all(np.abs(pr) <= 0.7 + 1e-12)
+        np.testing.assert_array_equal(O.score_mean_direction_prior(s, V, 0.0, 1e-6), s)
+
+    run()
