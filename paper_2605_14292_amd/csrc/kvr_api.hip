@@ -69,7 +69,8 @@ hipError_t retain_dense_any(const void* K, const void* V, const void* Q, int G, 
 // Selection without compaction: the kernel is chosen by shape only.
 hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int b, float lambda, float eps,
                        int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, hipStream_t st) {
-  if (kvr::pruned_supported(l, b, lambda, false)) {
+  // (a call with at most one head per CU is a latency problem: the sixteen-wave kernel takes it)
+  if (kvr::pruned_supported(l, b, lambda, false) && !kvr::dense16_supported(l, b, 0, false, cu_count())) {
     const hipError_t e = kvr::launch_retain_pruned(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order,
                                                    pick_gain, nullptr, nullptr, st);
     if (e != hipSuccess) return e;
@@ -186,8 +187,9 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
     if (kvr::launch_score(K, Q, G, l, s_out, st) != hipSuccess) return KVR_ERR_HIP;
     s = s_out;
   }
-  // scores computed here are softmax means, far tighter than lambda: the score bound removes nothing
-  if (!Q && kvr::pruned_supported(l, b, lambda, false)) {
+  // scores computed here are softmax means, far tighter than lambda: the score bound removes nothing;
+  // and a call with at most one head per CU is a latency problem, which the sixteen-wave kernel takes
+  if (!Q && kvr::pruned_supported(l, b, lambda, false) && !kvr::dense16_supported(l, b, 0, false, cu_count())) {
     hipError_t e = kvr::launch_retain_pruned(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
                                              pick_gain, K_out, V_out, st);
     if (e == hipSuccess)
@@ -262,7 +264,8 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
     } else if (long_heads) {
       e = kvr::launch_select_pool(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
                                   V_out, st, b_h);
-    } else if (kvr::pruned_supported(l, b_max, lambda, false)) {
+    } else if (kvr::pruned_supported(l, b_max, lambda, false) &&
+               !kvr::dense16_supported(l, b_max, 0, false, cu_count())) {
       e = kvr::launch_retain_pruned(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
                                     V_out, st, b_h);
       if (e == hipSuccess)

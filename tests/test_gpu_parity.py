@@ -51,7 +51,7 @@ def _run(w, data, b=None, lam=None, eps=1e-6):
     return out, b, lam
 
 
-@pytest.mark.parametrize("name,heads", [("c1", 1), ("c2", 112), ("c3", 192), ("c5", 24), ("c4", 6)])
+@pytest.mark.parametrize("name,heads", [("c1", 1), ("c2", 112), ("c3", 192), ("c3", 320), ("c5", 24), ("c4", 6)])
 def test_config_small_slice_every_head(name, heads):
     w = W.WORKLOADS[name]
     data = W.generate(w, heads=heads, seed=0, device=DEV)
@@ -119,28 +119,31 @@ def test_ragged_sizes(n, b, dtype):
     assert rep["heads"] == 3
 
 
+@pytest.mark.parametrize("reps", [1, 23])
 @pytest.mark.parametrize("n,b,lam", [(129, 2, 0.05), (192, 64, 0.5), (192, 64, 0.02), (256, 128, 0.3),
                                      (256, 100, 1.0), (200, 128, 1e-4)])
-def test_score_bound_reduction_mixed_heads(n, b, lam):
+def test_score_bound_reduction_mixed_heads(n, b, lam, reps):
     # given scores whose spread differs per head: some heads keep few candidates under the bound
     # s_j >= s_(b) - lambda (finished by the reduced-footprint kernel), others keep nearly all
-    # (handed on to the full-size kernel); quantised scores put ties on the bound itself
-    h = 12
+    # (handed on to the full-size kernel); quantised scores put ties on the bound itself.
+    # reps = 23: 276 heads, more than one per CU, the batched kernels; reps = 1: a single small event
+    h = 12 * reps
     K, V, _ = _mk(h, n, 7000 + n + b)
     g = torch.Generator().manual_seed(n * 131 + b)
     s = torch.randn((h, n), generator=g).exp()
-    scale = torch.tensor([4.0, 1.0, 0.25, 0.05, 2.0, 1.0, 8.0, 0.5, 1.0, 3.0, 0.01, 1.5]).view(h, 1)
+    scale = torch.tensor([4.0, 1.0, 0.25, 0.05, 2.0, 1.0, 8.0, 0.5, 1.0, 3.0, 0.01, 1.5]).repeat(reps).view(h, 1)
     s = s * scale
-    s[5] = torch.floor(s[5] * 4) / 4
-    s[9] = torch.floor(s[9] * 2) / 2
+    s[5::12] = torch.floor(s[5::12] * 4) / 4
+    s[9::12] = torch.floor(s[9::12] * 2) / 2
     # near-duplicate value rows so that the penalty matters among the survivors
     V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
     s = s.to(DEV)
     data = {"K": K, "V": V, "s": s}
     out = B().kvr_retain(K, V, b, lam, 1e-6, s=s)
     torch.cuda.synchronize()
-    rep = _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, range(h))
-    assert rep["heads"] == h
+    heads = list(range(12)) + list(range(12, h, 11))
+    rep = _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, heads)
+    assert rep["heads"] == len(heads)
     sel = B().kvr_select_greedy(V, s, b, lam, 1e-6)
     torch.cuda.synchronize()
     assert torch.equal(sel[0], out.idx_sorted) and torch.equal(sel[1], out.pick_order)
@@ -376,12 +379,13 @@ def test_flat_signature_mode(seqs, group, n, b, lam, dtype):
     assert torch.equal(Ko, out.K_out) and torch.equal(Vo, out.V_out)
 
 
+@pytest.mark.parametrize("h", [6, 270])
 @pytest.mark.parametrize("n,b,dtype", [(192, 64, torch.bfloat16), (100, 40, torch.bfloat16), (256, 128, torch.bfloat16),
                                        (150, 50, torch.float32)])
-def test_non_finite_scores_still_give_distinct_indices_in_range(n, b, dtype):
+def test_non_finite_scores_still_give_distinct_indices_in_range(n, b, dtype, h):
     # unspecified picks, but never an index outside [0, n), never a duplicate, and finite heads
-    # of the same launch are untouched (short heads only: these kernels run a fixed number of steps)
-    h = 6
+    # of the same launch are untouched (short heads only: these kernels run a fixed number of steps);
+    # 6 heads: the single-event kernels, 270: the batched ones
     K, V, s = _mk(h, n, 4242 + n, dtype)
     s = s.clone()
     s[0, ::3] = float("nan")
@@ -399,7 +403,7 @@ def test_non_finite_scores_still_give_distinct_indices_in_range(n, b, dtype):
         assert len(set(idx[hh].tolist())) == b and np.all(np.diff(idx[hh]) > 0)
         assert sorted(order[hh].tolist()) == idx[hh].tolist()
     data = {"K": K, "V": V, "s": s}
-    _check_heads(W.WORKLOADS["c3"], data, out, b, 0.5, 1e-6, [4, 5])
+    _check_heads(W.WORKLOADS["c3"], data, out, b, 0.5, 1e-6, [4, 5, h - 1])
     assert order[2][0] == 5 and order[2][1] == 7          # +inf scores go first, lowest index first
 
 
