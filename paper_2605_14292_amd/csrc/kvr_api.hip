@@ -39,19 +39,7 @@ int check_select(const kvr_layout* lay, int b, float lambda, float eps) {
   return KVR_OK;
 }
 
-// Compute units of the current device (256 on an MI355X), looked up once.
-int cu_count() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      cus = v;
-    else
-      cus = 256;
-  }
-  return cus;
-}
+using kvr::cu_count;
 
 // The fused kernel for bf16 heads of up to 256 tokens: sixteen waves per head when every head gets
 // a CU to itself, four otherwise.

@@ -10,6 +10,20 @@ struct Layout {
   long long stride_head, stride_tok;
 };
 
+// Compute units of the current device (256 on an MI355X), looked up on first use.  The value only
+// sizes grids (persistent workgroups, one-head-per-CU dispatch), so the device of the first call
+// stands for every device of the process.
+inline int cu_count() {
+  static const int cus = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      return v;
+    return 256;
+  }();
+  return cus;
+}
+
 hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay,
                         float* s_out, hipStream_t st);
 // lambda = 0 for heads of more than 256 tokens: top-b of the scores (any dtype: V is not read), and

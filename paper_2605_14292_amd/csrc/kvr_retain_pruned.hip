@@ -457,13 +457,7 @@ hipError_t launch_retain_pruned(const void* K, const void* V, const float* s, co
   a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);
   a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
   a.n = lay.n; a.b = b; a.heads = lay.heads; a.lambda = lambda; a.eps = eps;
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-  }
+  const int cus = cu_count();
   constexpr int smem = pruned_smem_bytes();
   static_assert(4 * smem <= 160 * 1024, "four workgroups must share a CU's LDS");
   const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&retain_pruned_kernel),
