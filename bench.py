@@ -195,6 +195,8 @@ def kernel_name(w, b, lam, has_q):
     fits_lds = w.G <= 32 and w.G * w.n <= (24576 if w.G <= 8 else 31488)
     score = ("kvr::score_kernel" if w.dtype != "bf16" else
              "kvr::score_mfma_kernel" if fits_lds else "kvr::score_wide_kernel")
+    if w.dtype != "bf16" and w.n <= 256 and w.G <= 16:
+        return "kvr::select_dense_f32_kernel (scores, selection and kept rows: the whole step is this one launch)"
     parts = ([score] if has_q else []) + tail
     return " + ".join(parts) + " (whole step; the select kernel dominates)"
 

@@ -171,6 +171,11 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
                                           pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
+  if (kvr::dense_f32_supported(l, b) && (!Q || G <= kvr::kDenseF32MaxG)) {   // short fp32 heads: one launch
+    const hipError_t e = kvr::launch_retain_dense_f32(K, V, Q, G, s_in, l, b, lambda, eps, s_out, idx_sorted,
+                                                      pick_order, pick_gain, K_out, V_out, st);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+  }
   if (Q) {
     if (kvr::launch_score(K, Q, G, l, s_out, st) != hipSuccess) return KVR_ERR_HIP;
     s = s_out;

@@ -62,6 +62,12 @@ bool dense_f32_supported(const Layout& lay, int b);
 hipError_t launch_select_dense_f32(const void* V, const float* s, const Layout& lay, int b, float lambda,
                                    float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                                    hipStream_t st);
+// The same kernel with the base scores computed inside (Q given, G <= 16) and the kept rows written.
+constexpr int kDenseF32MaxG = 16;
+hipError_t launch_retain_dense_f32(const void* K, const void* V, const void* Q, int G, const float* s,
+                                   const Layout& lay, int b, float lambda, float eps, float* s_out,
+                                   int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
+                                   void* V_out, hipStream_t st);
 
 // Fused path for bf16 heads with n <= 256 (any of K/Q/K_out/V_out may be null
 // to skip scoring or compaction).

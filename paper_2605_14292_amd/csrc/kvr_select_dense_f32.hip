@@ -13,7 +13,8 @@
 //   cosines  packed fp32 triangle in the space the rows were staged in   (Algorithm 1, Sims)
 //   greedy   the single-wave pick loop of the bf16 kernels                (Eq. 2-3)
 //
-// Only the selection is done here; rows are compacted by compact_kernel.
+// With Q the kernel also computes the base scores (up to 16 queries), and with K_out / V_out it
+// copies the kept rows: a single fp32 head is then one launch instead of three.
 #include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 
@@ -39,6 +40,10 @@ struct F32Args {
   long long stride_head, stride_tok;   // elements
   int n, b;
   float lambda, eps;
+  // optional: the scores are computed here from K and Q (then `s` is unused and s_out receives them),
+  // and the kept rows are written here
+  const float* K; const float* Q; int G; float* s_out;
+  float* K_out; float* V_out;
 };
 
 template <int NT>
@@ -69,7 +74,59 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
   const long long q0 = __builtin_readcyclecounter();
   long long q1 = q0, q2 = q0, q3 = q0;
 #endif
-  if (tid < N32) s_l[tid] = tid < n ? a.s[static_cast<long long>(h) * n + tid] : -INFINITY;
+  if (a.Q) {
+    // Base scores (the stand-in for the paper's external scorer): s_i = (1/G) sum_g softmax_i(q_g . k_i / sqrt(d)).
+    // 32 threads per row (float4 each) take the dot products in fp32, one wave per query takes its softmax.
+    const float* Kh = a.K + h * a.stride_head;
+    float4 kr[NT];
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+      const int r = (tid >> 5) + 32 * k;
+      kr[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < n) kr[k] = *reinterpret_cast<const float4*>(Kh + r * a.stride_tok + (tid & 31) * 4);
+    }
+    float* zl = stage;                                 // [G][N32] logits, then probabilities (the stage is free until the rows arrive)
+    const float scale = 0.08838834764831845f;          // 1/sqrt(128)
+    for (int g = 0; g < a.G; ++g) {
+      const float4 qv = *reinterpret_cast<const float4*>(a.Q + (static_cast<long long>(h) * a.G + g) * kD + (tid & 31) * 4);
+#pragma unroll
+      for (int k = 0; k < NT; ++k) {
+        float p = fmaf(kr[k].x, qv.x, fmaf(kr[k].y, qv.y, fmaf(kr[k].z, qv.z, kr[k].w * qv.w)));
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) p += __shfl_xor(p, off, kWave);
+        const int r = (tid >> 5) + 32 * k;
+        if ((tid & 31) == 0) zl[g * N32 + r] = r < n ? p * scale : -INFINITY;
+      }
+    }
+    __syncthreads();
+    if (wave < a.G) {
+      float v[NQ];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) { v[q] = zl[wave * N32 + lane + 64 * q]; mx = fmaxf(mx, v[q]); }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+      float sum = 0.f;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) { v[q] = __expf(v[q] - mx); sum += v[q]; }   // exp(-inf) = 0 for padding
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+      const float inv = 1.0f / sum;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) zl[wave * N32 + lane + 64 * q] = v[q] * inv;
+    }
+    __syncthreads();
+    if (tid < N32) {
+      float p = 0.f;
+      for (int g = 0; g < a.G; ++g) p += zl[g * N32 + tid];
+      p /= static_cast<float>(a.G);
+      s_l[tid] = tid < n ? p : -INFINITY;                // padding never competes
+      if (tid < n && a.s_out) a.s_out[static_cast<long long>(h) * n + tid] = p;
+    }
+    __syncthreads();                                     // the stage is free again
+  } else {
+    if (tid < N32) s_l[tid] = tid < n ? a.s[static_cast<long long>(h) * n + tid] : -INFINITY;
+  }
   if (tid == 0) meta[0] = 0;
   typedef __attribute__((ext_vector_type(16))) float f32x16_t;
   f32x16_t acc[MAXT];
@@ -222,6 +279,29 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
     if (a.pick_order) a.pick_order[ob + t] = order_l[t];
     if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
   }
+  // kept rows: 32 threads per row, four rows per thread in flight
+  if (a.K_out || a.V_out) {
+    const int c4 = (tid & 31) * 4;
+    for (int t0 = 0; t0 < b; t0 += 128) {
+      float4 xk[4], xv[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int t = min(t0 + (tid >> 5) + 32 * k, b - 1);
+        const long long src = h * a.stride_head + min(max(idx_l[t], 0), n - 1) * a.stride_tok + c4;
+        xk[k] = xv[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (a.K_out) xk[k] = *reinterpret_cast<const float4*>(a.K + src);
+        if (a.V_out) xv[k] = *reinterpret_cast<const float4*>(a.V + src);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int t = t0 + (tid >> 5) + 32 * k;
+        if (t < b) {
+          if (a.K_out) *reinterpret_cast<float4*>(a.K_out + (ob + t) * kD + c4) = xk[k];
+          if (a.V_out) *reinterpret_cast<float4*>(a.V_out + (ob + t) * kD + c4) = xv[k];
+        }
+      }
+    }
+  }
 #ifdef KVR_STATS
   __syncthreads();
   if (tid == 0 && a.pick_gain && b >= 8) {
@@ -240,7 +320,17 @@ bool dense_f32_supported(const Layout& lay, int b) {
 hipError_t launch_select_dense_f32(const void* V, const float* s, const Layout& lay, int b, float lambda,
                                    float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                                    hipStream_t st) {
+  return launch_retain_dense_f32(nullptr, V, nullptr, 0, s, lay, b, lambda, eps, nullptr, idx_sorted, pick_order,
+                                 pick_gain, nullptr, nullptr, st);
+}
+
+hipError_t launch_retain_dense_f32(const void* K, const void* V, const void* Q, int G, const float* s,
+                                   const Layout& lay, int b, float lambda, float eps, float* s_out,
+                                   int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
+                                   void* V_out, hipStream_t st) {
   F32Args a;
+  a.K = static_cast<const float*>(K); a.Q = static_cast<const float*>(Q); a.G = G; a.s_out = s_out;
+  a.K_out = static_cast<float*>(K_out); a.V_out = static_cast<float*>(V_out);
   a.V = static_cast<const float*>(V); a.s = s;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
