@@ -121,6 +121,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   const float nlam = -a.lambda;
   int par = 0;
   int t = 0;
+  int kbits = kSelBits;          // leading key bits the pool choice looks at (uniform)
   bool starved = false;
 
   auto wg_argmax = [&](const float (&av)[S], float& gbest, int& ibest) {
@@ -176,11 +177,14 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       float g[S];
       uint32_t key[S];
 #pragma unroll
-      // Keys are cut to their leading kSelBits bits: the pool only has to be a good guess (the
+      // Keys are cut to their leading kbits bits: the pool only has to be a good guess (the
       // race against the exact outside bound keeps the picks exact), and the search is shorter.
-      for (int k = 0; k < S; ++k) { g[k] = fmaf(nlam, m[k], s[k]); key[k] = ordered_key(g[k]) >> (32 - kSelBits); }
+      // When the cut keys cannot tell a wave's best tokens apart the best one may be left outside
+      // and the epoch ends without a pick; it is then repeated on the full keys, where the best
+      // token of every wave is a member (equal values join in token order).
+      for (int k = 0; k < S; ++k) { g[k] = fmaf(nlam, m[k], s[k]); key[k] = ordered_key(g[k]) >> (32 - kbits); }
       uint32_t tau = 0;                              // largest key value with at least Q keys >= it
-      for (int bit = kSelBits - 1; bit >= 0; --bit) {
+      for (int bit = kbits - 1; bit >= 0; --bit) {
         const uint32_t cand = tau | (1u << bit);
         int c = 0;
 #pragma unroll
@@ -338,7 +342,14 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         ++t;
         break;
       }
-      if (np == 0) { starved = true; break; }        // cannot happen on finite input: the best token is in the pool
+      if (np == 0) {
+        if (kbits == 32) { starved = true; break; }  // cannot happen on finite input: the best token was in the pool
+        kbits = 32;                                  // the outside bound won on cut keys: full keys from here on
+#pragma unroll
+        for (int k = 0; k < S; ++k) pslot[k] = -1;
+        lds_barrier();                               // the pool tables are rewritten next
+        continue;
+      }
       lds_barrier();                               // everyone is done with the triangle (the stages alias it)
       // ================= 4. one pass over V: the epoch's picks against every outside token =================
       if (np > 0) {

@@ -928,3 +928,22 @@ def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
         except AssertionError as e:
             raise AssertionError(f"case {case}: n={n} b={b} lambda={lam} heads={h} {kind} {dtype}: {e}") from e
 
+
+
+@pytest.mark.parametrize("n,b", [(192, 64), (600, 48), (1024, 64), (3000, 40), (1024, 300), (5000, 24)])
+def test_gains_within_one_percent_of_each_other(n, b):
+    """Every gain of the event lies in [1.5014, 1.507): values that agree in their sign, exponent
+    and leading seven mantissa bits, so a candidate choice that looks at those bits only cannot
+    tell the tokens apart and has to fall back on the full values."""
+    heads = 3
+    g = torch.Generator(device="cpu").manual_seed(4200 + n)
+    K = torch.randn((heads, n, 128), generator=g).to(torch.bfloat16)
+    V = torch.randn((heads, n, 128), generator=g).to(torch.bfloat16)
+    s = (1.502 + 0.005 * torch.rand((heads, n), generator=g)).to(torch.float32)
+    lam = 0.002
+    data = {"K": K.to(DEV), "V": V.to(DEV), "s": s.to(DEV)}
+    out = B().kvr_retain(data["K"], data["V"], b, lam, 1e-6, s=data["s"])
+    torch.cuda.synchronize()
+    rep = _check_heads(W.WORKLOADS["c5"], data, out, b, lam, 1e-6, range(heads))
+    print(f"\n[crowded gains n={n}] {rep}")
+    assert rep["heads"] == heads
