@@ -947,3 +947,55 @@ def test_gains_within_one_percent_of_each_other(n, b):
     rep = _check_heads(W.WORKLOADS["c5"], data, out, b, lam, 1e-6, range(heads))
     print(f"\n[crowded gains n={n}] {rep}")
     assert rep["heads"] == heads
+
+
+def _adversarial_scores(kind, heads, n, g):
+    u = torch.rand((heads, n), generator=g)
+    if kind == "crowded":                      # one 16-bit key bucket
+        return 1.502 + 0.005 * u
+    if kind == "negative_crowded":
+        return -1.507 + 0.005 * u
+    if kind == "huge_range":                   # 60 decades
+        return torch.pow(10.0, 60.0 * u - 30.0)
+    if kind == "signed":
+        return torch.randn((heads, n), generator=g)
+    raise ValueError(kind)
+
+
+def _adversarial_rows(kind, heads, n, g):
+    V = torch.randn((heads, n, 128), generator=g)
+    if kind == "zero_rows":                    # v = 0/(0 + eps) = 0: cosine 0 to everything
+        V[:, ::5] = 0.0
+    elif kind == "norms_near_eps":             # ||V_i|| between 0.3 eps and 30 eps: the + eps of Eq. 1 decides the cosines
+        V = V * (1e-6 / 11.3) * torch.pow(10.0, 2.0 * torch.rand((heads, n, 1), generator=g) - 0.5)
+    elif kind == "duplicates":                 # every row occurs four times
+        V = V[:, : (n + 3) // 4].repeat(1, 4, 1)[:, :n]
+        V = V[:, torch.randperm(n, generator=g)]
+    elif kind == "scaled":                     # norms over six decades, directions in a few clusters
+        c = torch.randn((heads, 12, 128), generator=g)
+        V = c[:, torch.randint(0, 12, (n,), generator=g)] + 0.1 * V
+        V = V * torch.pow(10.0, 6.0 * torch.rand((heads, n, 1), generator=g) - 3.0)
+    else:
+        raise ValueError(kind)
+    return V
+
+
+@pytest.mark.parametrize("rows", ["zero_rows", "norms_near_eps", "duplicates", "scaled"])
+@pytest.mark.parametrize("scores", ["crowded", "negative_crowded", "huge_range", "signed"])
+@pytest.mark.parametrize("n,b,heads,dtype", [(100, 40, 300, torch.bfloat16), (192, 64, 300, torch.bfloat16),
+                                             (256, 128, 2, torch.bfloat16), (700, 64, 2, torch.bfloat16),
+                                             (2500, 48, 1, torch.bfloat16), (150, 50, 2, torch.float32)])
+def test_adversarial_scores_and_rows(n, b, heads, dtype, scores, rows):
+    """Score distributions and value rows chosen against the kernels' shortcuts (cut keys, score
+    bounds, norms): every kernel the dispatch picks for these shapes, a few heads checked each."""
+    g = torch.Generator(device="cpu").manual_seed(7000 + 13 * n + 101 * len(scores) + 1009 * len(rows))
+    K = torch.randn((heads, n, 128), generator=g).to(dtype)
+    V = _adversarial_rows(rows, heads, n, g).to(dtype)
+    s = _adversarial_scores(scores, heads, n, g).to(torch.float32)
+    lam = {"crowded": 0.002, "negative_crowded": 0.002, "huge_range": 0.5, "signed": 0.7}[scores]
+    data = {"K": K.to(DEV), "V": V.to(DEV), "s": s.to(DEV)}
+    out = B().kvr_retain(data["K"], data["V"], b, lam, 1e-6, s=data["s"])
+    torch.cuda.synchronize()
+    check = sorted(set([0, 1 % heads, heads // 2, heads - 1]))
+    rep = _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, check)
+    assert rep["heads"] == len(check)
