@@ -999,3 +999,79 @@ def test_adversarial_scores_and_rows(n, b, heads, dtype, scores, rows):
     check = sorted(set([0, 1 % heads, heads // 2, heads - 1]))
     rep = _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, check)
     assert rep["heads"] == len(check)
+
+
+def _check_budgeted_head(out, hh, K, V, s64, nh, bh, kp, lam, pos):
+    """One head of a budgeted call against the oracle: protected tokens first, then Eq. 2-3 on the
+    HIP path's own prefix, padding, kept rows and position ids."""
+    V64 = W.to_f64(V[hh])
+    ref = O.select_budgeted(s64, V64, nh, bh, kp, lam, 1e-6)
+    order = out.pick_order[hh].cpu().numpy(); gain = out.pick_gain[hh].cpu().numpy().astype(np.float64)
+    idx = out.idx_sorted[hh].cpu().numpy()
+    npz = len(ref["protected"])
+    assert np.all(order[bh:] == -1) and np.all(idx[bh:] == -1)
+    assert sorted(order[:npz].tolist()) == ref["protected"].tolist() and np.all(np.isinf(gain[:npz]))
+    assert sorted(order[:bh].tolist()) == idx[:bh].tolist()
+    if bh:
+        assert idx[:bh].max() < nh and len(set(idx[:bh].tolist())) == bh
+    Vh = O.signatures(V64[:nh], 1e-6); cos = Vh @ Vh.T
+    S = list(order[:npz])
+    for t in range(npz, bh):
+        red = np.maximum(0.0, cos[:, S].max(axis=1)) if S else np.zeros(nh)
+        gt = s64[:nh] - lam * red
+        gt[S] = -np.inf
+        i = int(order[t])
+        scale = np.abs(s64[i]) + lam * red[i]
+        assert gt.max() - gt[i] <= P.NEAR_TIE * max(scale, 1e-30), (hh, t)
+        assert abs(gain[t] - gt[i]) <= P.GAIN_RTOL * max(scale, 1e-30), (hh, t)
+        S.append(i)
+    assert len(ref["order"]) == bh - npz
+    np.testing.assert_array_equal(_bits(out.K_out[hh])[:bh], O.compact(_bits(K[hh]), idx[:bh]))
+    np.testing.assert_array_equal(_bits(out.V_out[hh])[:bh], O.compact(_bits(V[hh]), idx[:bh]))
+    if pos is not None:
+        np.testing.assert_array_equal(out.pos_out[hh].cpu().numpy()[:bh], pos[hh].numpy()[idx[:bh]])
+        assert np.all(out.pos_out[hh].cpu().numpy()[bh:] == -1)
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_seeded_sweep_of_the_budget_allocator_frame(seed):
+    # random head lengths, budgets, candidate counts, protected sets, per-head lambdas, dtypes and head
+    # counts (a few heads: the single-event kernels; hundreds: the batched ones)
+    rng = np.random.default_rng(seed)
+    for case in range(14):
+        dtype = torch.bfloat16 if rng.random() < 0.8 else torch.float32
+        n = int(rng.choice([rng.integers(8, 130), rng.integers(130, 257), rng.integers(257, 1500 if dtype == torch.bfloat16 else 400)]))
+        b_max = int(rng.integers(1, min(n, 200) + 1))
+        h = int(rng.choice([1, 3, 7, 280])) if n <= 256 else int(rng.choice([1, 3, 6]))
+        lam = float(rng.choice([0.0, 0.1, 0.5, 1.0]))
+        g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
+        K = torch.randn((h, n, 128), generator=g).to(dtype)
+        V = torch.randn((h, n, 128), generator=g).to(dtype)
+        if n > 4:
+            V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
+        s = torch.randn((h, n), generator=g).exp()
+        n_h = torch.from_numpy(rng.integers(1, n + 1, size=h).astype(np.int32))
+        if rng.random() < 0.3:
+            n_h[:] = n
+        b_h = torch.from_numpy(np.minimum(rng.integers(0, b_max + 1, size=h), n_h.numpy()).astype(np.int32))
+        keep = torch.zeros((h, n), dtype=torch.uint8)
+        for hh in range(h):
+            cnt = int(rng.integers(0, int(b_h[hh]) + 1)) if rng.random() < 0.6 else 0
+            if cnt:
+                keep[hh, torch.from_numpy(rng.choice(int(n_h[hh]), size=cnt, replace=False))] = 1
+        use_lam_h = lam > 0 and rng.random() < 0.4
+        lam_h = torch.from_numpy(rng.choice([0.1, 0.5, 2.0], size=h).astype(np.float32)) if use_lam_h else None
+        pos = torch.from_numpy(rng.integers(0, 1 << 20, size=(h, n)).astype(np.int32)) if rng.random() < 0.5 else None
+        out = B().kvr_retain_budgeted(K.to(DEV), V.to(DEV), b_max, lam, 1e-6, s=s.to(DEV), n_h=n_h.to(DEV),
+                                      b_h=b_h.to(DEV), keep=keep.to(DEV), pos=None if pos is None else pos.to(DEV),
+                                      lam_h=None if lam_h is None else lam_h.to(DEV))
+        torch.cuda.synchronize()
+        heads = range(h) if h <= 7 else sorted(rng.choice(h, size=6, replace=False).tolist())
+        for hh in heads:
+            lh = float(lam_h[hh]) if use_lam_h else lam
+            try:
+                _check_budgeted_head(out, hh, K, V, W.to_f64(s[hh]), int(n_h[hh]), int(b_h[hh]),
+                                     keep[hh].numpy().astype(bool), lh, pos)
+            except AssertionError as e:
+                raise AssertionError(f"case {case}: n={n} b_max={b_max} heads={h} head {hh} n_h={int(n_h[hh])} "
+                                     f"b_h={int(b_h[hh])} lambda={lh} {dtype}: {e}") from e
