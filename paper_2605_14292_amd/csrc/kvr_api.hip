@@ -354,8 +354,7 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
   kvr::Layout lu = l;                                   // the per-sequence problems: fp32 rows, dense
   lu.heads = l.heads / group; lu.dtype = KVR_F32;
   lu.stride_tok = l.d; lu.stride_head = static_cast<long long>(l.n) * l.d;
-  if (lambda != 0.0f && b > 1 &&
-      kvr::launch_signature_flat(V, l, group, u_out, st) != hipSuccess)
+  if (lambda != 0.0f && kvr::launch_signature_flat(V, l, group, u_out, st) != hipSuccess)
     return KVR_ERR_HIP;
   if (select_only(u_out, s, lu, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)
     return KVR_ERR_HIP;

@@ -349,7 +349,8 @@ def _flat_case(seqs, group, n, seed, dtype):
 @pytest.mark.parametrize("seqs,group,n,b,lam,dtype", [
     (3, 8, 192, 64, 0.5, torch.bfloat16), (2, 32, 77, 30, 0.3, torch.bfloat16),
     (2, 5, 256, 128, 1.0, torch.bfloat16), (2, 4, 300, 40, 0.5, torch.bfloat16),
-    (2, 6, 130, 20, 0.5, torch.float32), (2, 3, 64, 64, 0.0, torch.bfloat16)])
+    (2, 6, 130, 20, 0.5, torch.float32), (2, 3, 64, 64, 0.0, torch.bfloat16),
+    (1, 1, 4, 1, 0.2, torch.bfloat16), (4, 64, 10, 1, 0.2, torch.bfloat16), (2, 17, 500, 150, 0.5, torch.bfloat16)])
 def test_flat_signature_mode(seqs, group, n, b, lam, dtype):
     K, V, s = _flat_case(seqs, group, n, 9000 + n + group, dtype)
     out = B().kvr_retain_flat(K, V, s, group, b, lam, 1e-6)
