@@ -256,8 +256,9 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
  *   K_out, V_out  device, dense [heads, b_max, d] or NULL: rows t < b_h[h] are
  *         written, the others are left as they were
  * Exactly one of (Q, G) and s_in, as in kvr_retain.  The picks for budget b_h
- * are the first b_h picks of the run for b_max, so the work per head is that of
- * b_max.
+ * are the first b_h picks of a run for b_max (a pick depends on the earlier ones
+ * only); the fused kernels stop at the head's own budget, the general path runs
+ * b_max picks per head and keeps the first b_h.
  */
 int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, const float* s_in,
                         const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
