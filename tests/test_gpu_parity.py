@@ -893,7 +893,7 @@ def test_mean_direction_prior_scores(n, dtype, strided):
 
 @pytest.mark.parametrize("seed", [1, 2, 3, 4, 5])
 def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
-    # forty seeded cases per seed across every kernel the dispatch can choose: head lengths 1..4096,
+    # forty seeded cases per seed across every kernel the dispatch can choose (a few heads or hundreds): head lengths 1..4096,
     # budgets 1..n, lambda in {0, .05, .5, 1, 3}, bf16 and fp32 rows, given scores of wide and tight
     # spread (quantised now and then, so that ties occur), computed scores from 1..256 queries
     rng = np.random.default_rng(seed)
@@ -906,6 +906,8 @@ def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
             b = min(n, int(rng.choice([1, 2, 64, 128, n])))
         lam = float(rng.choice([0.0, 0.05, 0.5, 1.0, 3.0]))
         h = int(rng.integers(1, 4))
+        if n <= 256 and rng.random() < 0.25:
+            h = int(rng.integers(257, 500))            # more heads than CUs: the batched kernels
         kind = rng.choice(["given_wide", "given_tight", "computed"])
         g = torch.Generator().manual_seed(int(rng.integers(1 << 30)))
         K = torch.randn((h, n, 128), generator=g).to(dtype).to(DEV)
@@ -924,8 +926,9 @@ def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
             data["s"] = s.to(DEV)
         out = B().kvr_retain(K, V, b, lam, 1e-6, Q=data.get("Q"), s=data.get("s"))
         torch.cuda.synchronize()
+        check = range(h) if h <= 3 else sorted(set([0, h - 1] + rng.choice(h, size=2, replace=False).tolist()))
         try:
-            _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, range(h))
+            _check_heads(W.WORKLOADS["c3"], data, out, b, lam, 1e-6, check)
         except AssertionError as e:
             raise AssertionError(f"case {case}: n={n} b={b} lambda={lam} heads={h} {kind} {dtype}: {e}") from e
 
