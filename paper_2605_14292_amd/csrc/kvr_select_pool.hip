@@ -1,4 +1,4 @@
-// Greedy selection (paper Sec. 4.1, Algorithm 1) for heads with 256 < n <= 4096
+// Greedy selection (paper Sec. 4.1, Algorithm 1) for heads with 256 < n <= 8192
 // bf16 tokens and b <= 256, followed by the compaction of the kept rows.
 //
 // Exact greedy on a pool.  Streaming all of V for every pick (one cosine row per
@@ -24,7 +24,8 @@
 //
 // Layout: one workgroup per head, W wave64s, token j = 64*S*w + 64*k + lane in
 // wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
-// lane's registers for the whole event.
+// lane's registers for the whole event (slots 0-7; with sixteen slots per lane,
+// n > 4096, the state of slots 8-15 lives in LDS, one column per thread).
 #include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 
@@ -54,9 +55,14 @@ template <int W, int S> struct PoolCfg {
   static constexpr int kTriBytes = kPool * (kPool + 1) / 2 * 4;
   static constexpr int kUnion = (W * kWaveStage > kTriBytes ? W * kWaveStage : kTriBytes);
   // floats: slots 64 | shared 16 | wcount 16 | pool_tok,r,s,m,picked 5*128 | pend 32 | pend_r 32 |
-  //         order,gain,idxs 3*kPoolMaxB | rn 64*S*W ; then pool rows ; then the union area
-  static constexpr int kFixedFloats = 64 + 16 + 16 + 5 * kPool + 64 + 3 * kPoolMaxB + 64 * S * W;
-  static constexpr int kSmemBytes = kFixedFloats * 4 + kPool * kPoolPitch + kUnion;
+  //         order,gain,idxs 3*kPoolMaxB ; then pool rows ; then the union area (triangle, stages, and at
+  //         the end the pick flags of the read-out) ; then score, m, inverse norm and pool slot of the
+  //         token slots that do not live in registers
+  static constexpr int kFixedFloats = 64 + 16 + 16 + 5 * kPool + 64 + 3 * kPoolMaxB;
+  static constexpr int kRegSlots = S > 8 ? 8 : S;
+  static constexpr int kLdsState = (S - kRegSlots) * 64 * W * 16;
+  static_assert(64 * S * W * 4 <= kUnion, "the pick flags of the read-out fit the union area");
+  static constexpr int kSmemBytes = kFixedFloats * 4 + kPool * kPoolPitch + kUnion + kLdsState;
 };
 
 // BUD: per-head budgets are read from a.b_h (a variant of its own: the extra live value costs the
@@ -84,12 +90,17 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   int32_t* order_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64);
   float* gain_l = smem + 96 + 5 * kPool + 64 + kPoolMaxB;
   int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64 + 2 * kPoolMaxB);
-  float* rn = smem + Cfg::kFixedFloats - TPW * W;                // [n padded] pick flags for the final ascending read-out
-  int32_t* flag = reinterpret_cast<int32_t*>(rn);
   char* prow = reinterpret_cast<char*>(smem + Cfg::kFixedFloats);   // [P][272 B] pool rows
   char* uni = prow + kPool * kPoolPitch;
   float* tri = reinterpret_cast<float*>(uni);                    // packed P x P cosine triangle (race) ...
-  // ... or the per-wave row stages of the pass over V
+  // ... or the per-wave row stages of the pass over V ...
+  int32_t* flag = reinterpret_cast<int32_t*>(uni);               // ... or, at the end, [n padded] pick flags for the ascending read-out
+  constexpr int SR = Cfg::kRegSlots;                             // token slots whose state lives in registers
+  constexpr int SL = S - SR;                                     // ... and in LDS, [slot - SR][thread]
+  float* sX = reinterpret_cast<float*>(uni + Cfg::kUnion);
+  float* mX = sX + SL * NT;
+  float* rX = mX + SL * NT;
+  int32_t* pX = reinterpret_cast<int32_t*>(rX + SL * NT);
 
   const int h = blockIdx.x;
 #ifdef KVR_STATS
@@ -108,15 +119,26 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   float* scratch = reinterpret_cast<float*>(stage + CH * kPoolPitch);
   float* norm_x = scratch + 256;                                 // [64] squared norms of the wave's current 64 tokens
 
-  float s[S], m[S], r[S];
-  int tok[S], pslot[S];          // pslot: pool slot of this token in the current epoch, or -1
+  float s[SR], m[SR], r[SR];
+  int pslot[SR];                 // pool slot of this token in the current epoch, or -1
+  // slot k of this lane: a register for k < SR, this thread's LDS column otherwise (k is a constant
+  // wherever these are used: the loops over the slots are unrolled)
+  const int tidx = threadIdx.x;
+  auto get_s = [&](int k) -> float { return k < SR ? s[k < SR ? k : 0] : sX[(k - SR) * NT + tidx]; };
+  auto get_m = [&](int k) -> float { return k < SR ? m[k < SR ? k : 0] : mX[(k - SR) * NT + tidx]; };
+  auto get_r = [&](int k) -> float { return k < SR ? r[k < SR ? k : 0] : rX[(k - SR) * NT + tidx]; };
+  auto get_p = [&](int k) -> int { return k < SR ? pslot[k < SR ? k : 0] : pX[(k - SR) * NT + tidx]; };
+  auto set_s = [&](int k, float v) { if (k < SR) s[k < SR ? k : 0] = v; else sX[(k - SR) * NT + tidx] = v; };
+  auto set_m = [&](int k, float v) { if (k < SR) m[k < SR ? k : 0] = v; else mX[(k - SR) * NT + tidx] = v; };
+  auto set_r = [&](int k, float v) { if (k < SR) r[k < SR ? k : 0] = v; else rX[(k - SR) * NT + tidx] = v; };
+  auto set_p = [&](int k, int v) { if (k < SR) pslot[k < SR ? k : 0] = v; else pX[(k - SR) * NT + tidx] = v; };
+  auto tok_of = [&](int k) -> int { return base + 64 * k + lane; };
 #pragma unroll
   for (int k = 0; k < S; ++k) {
-    tok[k] = base + 64 * k + lane;
-    s[k] = tok[k] < n ? a.s_in[static_cast<long long>(h) * n + tok[k]] : -INFINITY;
-    m[k] = 0.f;
-    r[k] = 0.f;
-    pslot[k] = -1;
+    set_s(k, tok_of(k) < n ? a.s_in[static_cast<long long>(h) * n + tok_of(k)] : -INFINITY);
+    set_m(k, 0.f);
+    set_r(k, 0.f);
+    set_p(k, -1);
   }
   const float nlam = -a.lambda;
   int par = 0;
@@ -147,7 +169,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 
   if (b == 1) {
     float gmax; int i;
-    wg_argmax(s, gmax, i);
+    float sa[S];
+#pragma unroll
+    for (int k = 0; k < S; ++k) sa[k] = get_s(k);
+    wg_argmax(sa, gmax, i);
     if (!(gmax > -INFINITY)) starved = true;
     else { if (tid == 0) { order_l[0] = i; gain_l[0] = gmax; } t = 1; }
   } else {
@@ -182,7 +207,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       // When the cut keys cannot tell a wave's best tokens apart the best one may be left outside
       // and the epoch ends without a pick; it is then repeated on the full keys, where the best
       // token of every wave is a member (equal values join in token order).
-      for (int k = 0; k < S; ++k) { g[k] = fmaf(nlam, m[k], s[k]); key[k] = ordered_key(g[k]) >> (32 - kbits); }
+      for (int k = 0; k < S; ++k) { g[k] = fmaf(nlam, get_m(k), get_s(k)); key[k] = ordered_key(g[k]) >> (32 - kbits); }
       uint32_t tau = 0;                              // largest key value with at least Q keys >= it
       for (int bit = kbits - 1; bit >= 0; --bit) {
         const uint32_t cand = tau | (1u << bit);
@@ -205,12 +230,12 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         const bool in = above || (equal && eq_before < need_eq);
         const unsigned long long inm = __ballot(in);
         const int slot = w * Q + rank_base + __popcll(inm & ((1ull << lane) - 1ull));
-        pslot[k] = in ? slot : -1;
+        set_p(k, in ? slot : -1);
         if (in) {
-          pool_tok[slot] = tok[k] < n ? tok[k] : -1;
-          pool_r[slot] = r[k];
-          pool_s[slot] = s[k];
-          pool_m[slot] = m[k];
+          pool_tok[slot] = tok_of(k) < n ? tok_of(k) : -1;
+          pool_r[slot] = get_r(k);
+          pool_s[slot] = get_s(k);
+          pool_m[slot] = get_m(k);
           pool_picked[slot] = 0;
         }
         go[k] = in ? -INFINITY : g[k];
@@ -327,10 +352,11 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       // pool members: m from the race, picked members leave
 #pragma unroll
       for (int k = 0; k < S; ++k) {
-        if (pslot[k] >= 0) {
-          m[k] = pool_m[pslot[k]];
-          if (!have_r) r[k] = pool_r[pslot[k]];
-          if (pool_picked[pslot[k]]) s[k] = -INFINITY;
+        const int ps = get_p(k);
+        if (ps >= 0) {
+          set_m(k, pool_m[ps]);
+          if (!have_r) set_r(k, pool_r[ps]);
+          if (pool_picked[ps]) set_s(k, -INFINITY);
         }
       }
       if (t >= b) break;
@@ -338,7 +364,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       if (np == 0 && t + 1 == b) {                   // the outside token wins the last pick: no row needed
         if (tid == 0) { order_l[t] = jout; gain_l[t] = gout; }
 #pragma unroll
-        for (int k = 0; k < S; ++k) s[k] = tok[k] == jout ? -INFINITY : s[k];
+        for (int k = 0; k < S; ++k) { if (tok_of(k) == jout) set_s(k, -INFINITY); }
         ++t;
         break;
       }
@@ -346,7 +372,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         if (kbits == 32) { starved = true; break; }  // cannot happen on finite input: the best token was in the pool
         kbits = 32;                                  // the outside bound won on cut keys: full keys from here on
 #pragma unroll
-        for (int k = 0; k < S; ++k) pslot[k] = -1;
+        for (int k = 0; k < S; ++k) set_p(k, -1);
         lds_barrier();                               // the pool tables are rewritten next
         continue;
       }
@@ -439,13 +465,15 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           wave_lds_sync();
           const float* sp = scratch + kg * 64 + (lane & 15);
           const float mx = hw_max(hw_max(sp[0], sp[16]), hw_max(sp[32], sp[48]));
-          if (!have_r && pslot[k] < 0) r[k] = tok[k] < n ? 1.0f / (sqrtf(norm_x[lane]) + a.eps) : 0.f;
-          if (pslot[k] < 0) m[k] = hw_max(m[k], mx * r[k]);
+          const int ps = get_p(k);
+          float rk = get_r(k);
+          if (!have_r && ps < 0) { rk = tok_of(k) < n ? 1.0f / (sqrtf(norm_x[lane]) + a.eps) : 0.f; set_r(k, rk); }
+          if (ps < 0) set_m(k, hw_max(get_m(k), mx * rk));
         }
       }
       have_r = true;
 #pragma unroll
-      for (int k = 0; k < S; ++k) pslot[k] = -1;
+      for (int k = 0; k < S; ++k) set_p(k, -1);
       lds_barrier();                               // stages are dead: the next epoch reuses the area
 #ifdef KVR_STATS
       st[3] += __builtin_readcyclecounter() - c3;
@@ -481,7 +509,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     int cnt = 0;
 #pragma unroll
     for (int k = 0; k < S; ++k) {
-      sel[k] = __ballot(tok[k] < n && flag[tok[k]] != 0);
+      sel[k] = __ballot(tok_of(k) < n && flag[tok_of(k)] != 0);
       cnt += __popcll(sel[k]);
     }
     if (lane == 0) wcount[w] = cnt;
@@ -492,7 +520,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     for (int k = 0; k < S; ++k) {
       if ((sel[k] >> lane) & 1ull) {
         const int rank = off + __popcll(sel[k] & ((1ull << lane) - 1ull));
-        if (rank < b) idxs_l[rank] = tok[k];
+        if (rank < b) idxs_l[rank] = tok_of(k);
       }
       off += __popcll(sel[k]);
     }
@@ -521,7 +549,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 }
 
 bool pool_supported(const Layout& lay, int b) {
-  return lay.dtype == DT_BF16 && lay.n > 256 && lay.n <= 4096 && b <= kPoolMaxB;
+  return lay.dtype == DT_BF16 && lay.n > 256 && lay.n <= 8192 && b <= kPoolMaxB;
 }
 
 hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,
@@ -546,12 +574,14 @@ hipError_t launch_select_pool(const void* K, const void* V, const float* s, cons
     if (lay.n <= 512) return go(&select_pool_kernel<2, 4, true>, 128, PoolCfg<2, 4>::kSmemBytes);
     if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, true>, 256, PoolCfg<4, 4>::kSmemBytes);
     if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, true>, 512, PoolCfg<8, 4>::kSmemBytes);
-    return go(&select_pool_kernel<8, 8, true>, 512, PoolCfg<8, 8>::kSmemBytes);
+    if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, true>, 512, PoolCfg<8, 8>::kSmemBytes);
+    return go(&select_pool_kernel<8, 16, true>, 512, PoolCfg<8, 16>::kSmemBytes);
   }
   if (lay.n <= 512) return go(&select_pool_kernel<2, 4, false>, 128, PoolCfg<2, 4>::kSmemBytes);
   if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, false>, 256, PoolCfg<4, 4>::kSmemBytes);
   if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, false>, 512, PoolCfg<8, 4>::kSmemBytes);
-  return go(&select_pool_kernel<8, 8, false>, 512, PoolCfg<8, 8>::kSmemBytes);
+  if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, false>, 512, PoolCfg<8, 8>::kSmemBytes);
+  return go(&select_pool_kernel<8, 16, false>, 512, PoolCfg<8, 16>::kSmemBytes);
 }
 
 }  // namespace kvr

@@ -107,7 +107,7 @@ def _mk(h, n, seed, dtype=torch.bfloat16, d=128):
 
 
 @pytest.mark.parametrize("n,b", [(1, 1), (2, 2), (17, 5), (77, 77), (193, 64), (257, 1), (300, 299),
-                                 (1000, 33), (2049, 40)])
+                                 (1000, 33), (2049, 40), (4097, 70), (6000, 130), (8192, 256)])
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 def test_ragged_sizes(n, b, dtype):
     K, V, s = _mk(3, n, 1000 + n, dtype)
@@ -580,7 +580,8 @@ def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
 
 
 @pytest.mark.parametrize("n,b_max,lam", [(192, 64, 0.5), (120, 48, 0.5), (256, 128, 0.3), (200, 32, 0.0),
-                                         (600, 64, 0.5), (1024, 128, 0.5), (3000, 40, 1.0), (1000, 64, 0.0), (5000, 200, 0.0)])
+                                         (600, 64, 0.5), (1024, 128, 0.5), (3000, 40, 1.0), (1000, 64, 0.0), (5000, 200, 0.0),
+                                         (6000, 96, 0.5)])
 def test_budgeted_heads_match_the_unbudgeted_prefix(n, b_max, lam):
     """On bf16 heads of up to 4096 tokens the fused kernels take the per-head budgets themselves.  The picks for
     budget b_h must be the first b_h picks of the plain run for b_max (a greedy pick depends on the
@@ -934,7 +935,7 @@ def test_seeded_sweep_over_shapes_dtypes_and_score_kinds(seed):
 
 
 
-@pytest.mark.parametrize("n,b", [(192, 64), (600, 48), (1024, 64), (3000, 40), (1024, 300), (5000, 24)])
+@pytest.mark.parametrize("n,b", [(192, 64), (600, 48), (1024, 64), (3000, 40), (1024, 300), (5000, 24), (8000, 100)])
 def test_gains_within_one_percent_of_each_other(n, b):
     """Every gain of the event lies in [1.5014, 1.507): values that agree in their sign, exponent
     and leading seven mantissa bits, so a candidate choice that looks at those bits only cannot
