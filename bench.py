@@ -186,10 +186,8 @@ def kernel_name(w, b, lam, has_q):
         if w.n > 128 and w.heads <= 256:
             return "kvr::retain_dense16_kernel (the whole step is this one launch; one head per CU, sixteen waves each)"
         return "kvr::retain_dense_kernel (the whole step is this one launch)"
-    if w.dtype == "bf16" and w.n <= 4096 and b <= 256:
+    if w.dtype == "bf16" and w.n <= 8192 and b <= 1024:
         tail = ["kvr::select_pool_kernel (selection + compaction)"]
-    elif w.dtype == "bf16" and b <= 1024:
-        tail = ["kvr::select_blocked_kernel", "kvr::compact_kernel"]
     else:
         tail = ["kvr::select_generic_kernel", "kvr::compact_kernel"]
     fits_lds = w.G <= 32 and w.G * w.n <= (24576 if w.G <= 8 else 31488)

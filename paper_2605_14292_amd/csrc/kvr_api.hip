@@ -76,9 +76,6 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
   if (kvr::pool_supported(l, b))
     return kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                    nullptr, nullptr, st);
-  if (kvr::blocked_supported(l, b))
-    return kvr::launch_select_blocked(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
-                                      nullptr, nullptr, st);
   return kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
 }
 
@@ -203,11 +200,6 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
   if (kvr::pool_supported(l, b)) {
     const hipError_t e = kvr::launch_select_pool(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
                                                  pick_gain, K_out, V_out, st);
-    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
-  }
-  if (kvr::blocked_supported(l, b)) {
-    const hipError_t e = kvr::launch_select_blocked(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
-                                                    pick_gain, K_out, V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (select_only(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)

@@ -110,14 +110,7 @@ hipError_t launch_budget_finalize(const void* K, const void* V, const Layout& la
                                   float* pick_gain, void* K_out, void* V_out, int32_t* pos_out,
                                   hipStream_t st);
 
-// Speculative row-block path for bf16 heads with 256 < n <= 4096 (selection plus
-// optional compaction; scores come in through s).
-bool blocked_supported(const Layout& lay, int b);
-hipError_t launch_select_blocked(const void* K, const void* V, const float* s, const Layout& lay, int b,
-                                 float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
-                                 float* pick_gain, void* K_out, void* V_out, hipStream_t st);
-
-// Pool-based exact greedy for bf16 heads with 256 < n <= 4096 and b <= 256 (selection plus
+// Pool-based exact greedy for bf16 heads with 256 < n <= 8192 and b <= 1024 (selection plus
 // optional compaction; scores come in through s).
 bool pool_supported(const Layout& lay, int b);
 hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,

@@ -1,5 +1,5 @@
 // Greedy selection (paper Sec. 4.1, Algorithm 1) for heads with 256 < n <= 8192
-// bf16 tokens and b <= 256, followed by the compaction of the kept rows.
+// bf16 tokens and b <= 1024, followed by the compaction of the kept rows.
 //
 // Exact greedy on a pool.  Streaming all of V for every pick (one cosine row per
 // pick) is what Algorithm 1 asks for literally; it is also what makes large n
@@ -34,7 +34,7 @@ namespace kvr {
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kPool = 128;          // pool size
-constexpr int kPoolMaxB = 256;      // pick lists kept in LDS
+constexpr int kPoolMaxB = 1024;     // largest budget (the pick lists in LDS are sized for the call's b)
 constexpr int kPoolMaxPend = 32;    // picks per epoch (two 16-row MFMA operands)
 constexpr int kPoolPitch = 272;     // bytes per staged row (256 + 16)
 constexpr int kSelBits = 16;        // leading bits of a gain's ordered key used to choose the pool
@@ -55,14 +55,16 @@ template <int W, int S> struct PoolCfg {
   static constexpr int kTriBytes = kPool * (kPool + 1) / 2 * 4;
   static constexpr int kUnion = (W * kWaveStage > kTriBytes ? W * kWaveStage : kTriBytes);
   // floats: slots 64 | shared 16 | wcount 16 | pool_tok,r,s,m,picked 5*128 | pend 32 | pend_r 32 |
-  //         order,gain,idxs 3*kPoolMaxB ; then pool rows ; then the union area (triangle, stages, and at
+  //         order,gain,idxs 3*bcap (b rounded up to 64) ; then pool rows ; then the union area (triangle, stages, and at
   //         the end the pick flags of the read-out) ; then score, m, inverse norm and pool slot of the
   //         token slots that do not live in registers
-  static constexpr int kFixedFloats = 64 + 16 + 16 + 5 * kPool + 64 + 3 * kPoolMaxB;
+  static constexpr int kFixedFloats = 64 + 16 + 16 + 5 * kPool + 64;          // without the pick lists
   static constexpr int kRegSlots = S > 8 ? 8 : S;
   static constexpr int kLdsState = (S - kRegSlots) * 64 * W * 16;
   static_assert(64 * S * W * 4 <= kUnion, "the pick flags of the read-out fit the union area");
-  static constexpr int kSmemBytes = kFixedFloats * 4 + kPool * kPoolPitch + kUnion + kLdsState;
+  static constexpr int smem_bytes(int b) {
+    return (kFixedFloats + 3 * ((b + 63) & ~63)) * 4 + kPool * kPoolPitch + kUnion + kLdsState;
+  }
 };
 
 // BUD: per-head budgets are read from a.b_h (a variant of its own: the extra live value costs the
@@ -88,9 +90,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   int32_t* pend_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool);        // [32] pool slots picked this epoch
   float* pend_r = smem + 96 + 5 * kPool + 32;                                  // [32] their inverse norms
   int32_t* order_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64);
-  float* gain_l = smem + 96 + 5 * kPool + 64 + kPoolMaxB;
-  int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64 + 2 * kPoolMaxB);
-  char* prow = reinterpret_cast<char*>(smem + Cfg::kFixedFloats);   // [P][272 B] pool rows
+  const int bcap = (a.b + 63) & ~63;                             // rows of the pick lists
+  float* gain_l = smem + 96 + 5 * kPool + 64 + bcap;
+  int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * kPool + 64 + 2 * bcap);
+  char* prow = reinterpret_cast<char*>(smem + Cfg::kFixedFloats + 3 * bcap);   // [P][272 B] pool rows
   char* uni = prow + kPool * kPoolPitch;
   float* tri = reinterpret_cast<float*>(uni);                    // packed P x P cosine triangle (race) ...
   // ... or the per-wave row stages of the pass over V ...
@@ -571,17 +574,17 @@ hipError_t launch_select_pool(const void* K, const void* V, const float* s, cons
     return hipGetLastError();
   };
   if (b_h) {
-    if (lay.n <= 512) return go(&select_pool_kernel<2, 4, true>, 128, PoolCfg<2, 4>::kSmemBytes);
-    if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, true>, 256, PoolCfg<4, 4>::kSmemBytes);
-    if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, true>, 512, PoolCfg<8, 4>::kSmemBytes);
-    if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, true>, 512, PoolCfg<8, 8>::kSmemBytes);
-    return go(&select_pool_kernel<8, 16, true>, 512, PoolCfg<8, 16>::kSmemBytes);
+    if (lay.n <= 512) return go(&select_pool_kernel<2, 4, true>, 128, PoolCfg<2, 4>::smem_bytes(b));
+    if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, true>, 256, PoolCfg<4, 4>::smem_bytes(b));
+    if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, true>, 512, PoolCfg<8, 4>::smem_bytes(b));
+    if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, true>, 512, PoolCfg<8, 8>::smem_bytes(b));
+    return go(&select_pool_kernel<8, 16, true>, 512, PoolCfg<8, 16>::smem_bytes(b));
   }
-  if (lay.n <= 512) return go(&select_pool_kernel<2, 4, false>, 128, PoolCfg<2, 4>::kSmemBytes);
-  if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, false>, 256, PoolCfg<4, 4>::kSmemBytes);
-  if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, false>, 512, PoolCfg<8, 4>::kSmemBytes);
-  if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, false>, 512, PoolCfg<8, 8>::kSmemBytes);
-  return go(&select_pool_kernel<8, 16, false>, 512, PoolCfg<8, 16>::kSmemBytes);
+  if (lay.n <= 512) return go(&select_pool_kernel<2, 4, false>, 128, PoolCfg<2, 4>::smem_bytes(b));
+  if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, false>, 256, PoolCfg<4, 4>::smem_bytes(b));
+  if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, false>, 512, PoolCfg<8, 4>::smem_bytes(b));
+  if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, false>, 512, PoolCfg<8, 8>::smem_bytes(b));
+  return go(&select_pool_kernel<8, 16, false>, 512, PoolCfg<8, 16>::smem_bytes(b));
 }
 
 }  // namespace kvr

@@ -619,7 +619,7 @@ def test_budgeted_heads_match_the_unbudgeted_prefix(n, b_max, lam):
                                          (4096, 1024, torch.bfloat16, 0), (4096, 256, torch.bfloat16, 8),
                                          (256, 256, torch.bfloat16, 0), (192, 192, torch.float32, 0)])
 def test_maximum_sizes(n, b, dtype, G):
-    # the limits of the header (n = 8192, G = 256), of the pool (b = 256) and blocked (b = 1024)
+    # the limits of the header (n = 8192, G = 256) and of the pool kernel (b = 1024)
     # kernels, and budgets that keep every token
     K, V, s = _mk(1, n, 8800 + n + b, dtype)
     g = torch.Generator().manual_seed(n + b)
