@@ -75,7 +75,7 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
                                    nullptr, st);
   if (kvr::pool_supported(l, b))
     return kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
-                                   nullptr, nullptr, st);
+                                   nullptr, nullptr, st, nullptr, true);
   return kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
 }
 
@@ -199,7 +199,7 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
   }
   if (kvr::pool_supported(l, b)) {
     const hipError_t e = kvr::launch_select_pool(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
-                                                 pick_gain, K_out, V_out, st);
+                                                 pick_gain, K_out, V_out, st, nullptr, Q == nullptr);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (select_only(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)
@@ -248,7 +248,7 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
       e = kvr::launch_select_topb(K, V, s_work, l, b_max, idx_sorted, pick_order, pick_gain, K_out, V_out, st, b_h);
     } else if (long_heads) {
       e = kvr::launch_select_pool(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
-                                  V_out, st, b_h);
+                                  V_out, st, b_h, Q == nullptr);
     } else if (kvr::pruned_supported(l, b_max, lambda, false) &&
                !kvr::dense16_supported(l, b_max, 0, false, cu_count())) {
       e = kvr::launch_retain_pruned(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,

@@ -116,6 +116,9 @@ bool pool_supported(const Layout& lay, int b);
 hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
                               float* pick_gain, void* K_out, void* V_out, hipStream_t st,
-                              const int32_t* b_h = nullptr);
+                              const int32_t* b_h = nullptr, bool prune = false);
+// prune: take the variant that first drops the tokens the score bound rules out (s_j < s_(b) - lambda)
+// and skips their rows.  Worth it for scores the caller supplies; mean-of-softmax scores over hundreds
+// of tokens lie far below any lambda in use, nothing can be dropped, and the variant only costs.
 
 }  // namespace kvr

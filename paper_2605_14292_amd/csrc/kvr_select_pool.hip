@@ -28,6 +28,7 @@
 // n > 4096, the state of slots 8-15 lives in LDS, one column per thread).
 #include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
+#include <type_traits>
 
 namespace kvr {
 
@@ -69,7 +70,9 @@ template <int W, int S> struct PoolCfg {
 
 // BUD: per-head budgets are read from a.b_h (a variant of its own: the extra live value costs the
 // plain kernel a register it does not have).
-template <int W, int S, bool BUD>
+// PRUNE: the candidate reduction by the score bound (a variant of its own as well: where nothing
+// can be dropped, its row masks cost a head 3 us).
+template <int W, int S, bool BUD, bool PRUNE>
 __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(PoolArgs a) {
   using Cfg = PoolCfg<W, S>;
   constexpr int TPW = 64 * S;
@@ -184,6 +187,66 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
     // gets its norm in the first epoch's pass over V, which reads the row anyway.  Until then
     // r = 0 (it is only ever used for pool members and in that pass).
     bool have_r = false;
+    // Exact candidate reduction (as in the kernels for short heads): while fewer than b tokens are
+    // selected one of the b best-scored is free and gains at least s_(b) - lambda, and a token gains
+    // at most its score, so a token with s_j < s_(b) - lambda never wins Eq. 3.  Such tokens get the
+    // score -inf (they are never a pool member or a pick, so the picks are unchanged) and their rows
+    // are not read in the passes over V.  With scores that spread by more than lambda most of a long
+    // head goes; with scores far below lambda nothing does.
+    // Nothing can go when the finite scores spread by less than lambda (then s_(b) - lambda is below
+    // all of them); one workgroup-wide min/max settles that before the search for s_(b).
+    unsigned long long alive[PRUNE ? S : 1];         // per slot: which lanes' tokens still count (wave-uniform)
+    bool wide = false;
+    if constexpr (PRUNE) {
+    {
+      float hi = -INFINITY, lo = INFINITY;
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        const float sk = get_s(k);
+        if (sk > -INFINITY && sk < INFINITY) { hi = hw_max(hi, sk); lo = fminf(lo, sk); }
+      }
+      hi = wave_max_uniform(hi);
+      lo = -wave_max_uniform(-lo);
+      if (lane == 0) { slot_gain[par * 16 + w] = hi; slot_gain[32 + w] = lo; }   // (smem 32.. is slot_idx: free until the first argmax)
+      lds_barrier();
+      float ghi = -INFINITY, glo = INFINITY;
+#pragma unroll
+      for (int u = 0; u < W; ++u) { ghi = hw_max(ghi, slot_gain[par * 16 + u]); glo = fminf(glo, slot_gain[32 + u]); }
+      par ^= 1;
+      wide = __builtin_amdgcn_readfirstlane(ghi - glo > a.lambda ? 1 : 0) != 0;   // false also when no score is finite
+      lds_barrier();                                 // the min/max slots are rewritten below
+    }
+    if (!wide) {
+#pragma unroll
+      for (int k = 0; k < S; ++k) alive[k] = __ballot(!(get_s(k) == -INFINITY));
+    } else {
+      uint32_t key[S];
+#pragma unroll
+      for (int k = 0; k < S; ++k) key[k] = tok_of(k) < n ? ordered_key(get_s(k) + 0.0f) : 0u;
+      uint32_t T = 0;                                // s_(b) from the leading 16 bits: at most s_(b), the bound only loosens
+      for (int bit = 31; bit >= 16; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < S; ++k) c += __popcll(__ballot(key[k] >= cand));
+        if (lane == 0) slot_idx[par * 16 + w] = c;
+        lds_barrier();
+        int tot = 0;
+#pragma unroll
+        for (int u = 0; u < W; ++u) tot += slot_idx[par * 16 + u];
+        par ^= 1;
+        if (tot >= b) T = cand;
+      }
+      const float sb = key_to_float(T);
+      const float thr = sb - a.lambda * 1.00001f - 1e-5f * fabsf(sb);   // fp32 cosines may exceed 1 by a few ulp
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        const float sk = get_s(k);
+        if (sk < thr) set_s(k, -INFINITY);           // (a NaN threshold or score leaves the token in)
+        alive[k] = __ballot(!(sk < thr) && !(sk == -INFINITY));
+      }
+    }
+    }
     auto sum_sq = [](const uint4& x) -> float {
       const float e[8] = {bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y),
                           bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)};
@@ -412,11 +475,25 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         auto fetch = [&](int kk, int sub, int slot) {
           int row0 = base + (lane >> 4);
           asm volatile("" : "+v"(row0));             // keep the unrolled pass from hoarding addresses
+          if (PRUNE && wide) {                       // (uniform: heads without dropped tokens take the plain loads)
+            asm volatile("" ::: "memory");           // keeps this a branch: folded into selects it costs every head four VALU instructions a load
+            const uint32_t on16 = static_cast<uint32_t>(alive[PRUNE ? kk : 0] >> (sub * CH)) & 0xffffu;   // the sub-block's live rows
 #pragma unroll
-          for (int q = 0; q < LPC; ++q) {
-            const int row = min(row0 + (kk * 4 + sub) * CH + 4 * q, n - 1);
-            const uint4 x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
-            if (slot == 0) preA[sub][q] = x; else preB[sub][q] = x;
+            for (int q = 0; q < LPC; ++q) {
+              const int row = min(row0 + (kk * 4 + sub) * CH + 4 * q, n - 1);
+              // a row nobody can pick any more is not read: its lanes re-read the wave's first row (a cache
+              // hit; what they compute belongs to a token that never counts again)
+              const int rowc = ((on16 >> ((lane >> 4) + 4 * q)) & 1u) ? row : min(base, n - 1);
+              const uint4 x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(rowc) * a.stride_tok + (lane & 15) * 8) * 2);
+              if (slot == 0) preA[sub][q] = x; else preB[sub][q] = x;
+            }
+          } else {
+#pragma unroll
+            for (int q = 0; q < LPC; ++q) {
+              const int row = min(row0 + (kk * 4 + sub) * CH + 4 * q, n - 1);
+              const uint4 x = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(row) * a.stride_tok + (lane & 15) * 8) * 2);
+              if (slot == 0) preA[sub][q] = x; else preB[sub][q] = x;
+            }
           }
         };
 #pragma unroll
@@ -557,7 +634,8 @@ bool pool_supported(const Layout& lay, int b) {
 
 hipError_t launch_select_pool(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
-                              float* pick_gain, void* K_out, void* V_out, hipStream_t st, const int32_t* b_h) {
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st, const int32_t* b_h,
+                              bool prune) {
   PoolArgs a;
   a.b_h = b_h;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s_in = s;
@@ -573,18 +651,16 @@ hipError_t launch_select_pool(const void* K, const void* V, const float* s, cons
     hipLaunchKernelGGL(kern, grid, dim3(threads), smem, st, a);
     return hipGetLastError();
   };
-  if (b_h) {
-    if (lay.n <= 512) return go(&select_pool_kernel<2, 4, true>, 128, PoolCfg<2, 4>::smem_bytes(b));
-    if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, true>, 256, PoolCfg<4, 4>::smem_bytes(b));
-    if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, true>, 512, PoolCfg<8, 4>::smem_bytes(b));
-    if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, true>, 512, PoolCfg<8, 8>::smem_bytes(b));
-    return go(&select_pool_kernel<8, 16, true>, 512, PoolCfg<8, 16>::smem_bytes(b));
-  }
-  if (lay.n <= 512) return go(&select_pool_kernel<2, 4, false>, 128, PoolCfg<2, 4>::smem_bytes(b));
-  if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, false>, 256, PoolCfg<4, 4>::smem_bytes(b));
-  if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, false>, 512, PoolCfg<8, 4>::smem_bytes(b));
-  if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, false>, 512, PoolCfg<8, 8>::smem_bytes(b));
-  return go(&select_pool_kernel<8, 16, false>, 512, PoolCfg<8, 16>::smem_bytes(b));
+  auto by_shape = [&](auto bud, auto pr) -> hipError_t {
+    constexpr bool BUD = decltype(bud)::value, PR = decltype(pr)::value;
+    if (lay.n <= 512) return go(&select_pool_kernel<2, 4, BUD, PR>, 128, PoolCfg<2, 4>::smem_bytes(b));
+    if (lay.n <= 1024) return go(&select_pool_kernel<4, 4, BUD, PR>, 256, PoolCfg<4, 4>::smem_bytes(b));
+    if (lay.n <= 2048) return go(&select_pool_kernel<8, 4, BUD, PR>, 512, PoolCfg<8, 4>::smem_bytes(b));
+    if (lay.n <= 4096) return go(&select_pool_kernel<8, 8, BUD, PR>, 512, PoolCfg<8, 8>::smem_bytes(b));
+    return go(&select_pool_kernel<8, 16, BUD, PR>, 512, PoolCfg<8, 16>::smem_bytes(b));
+  };
+  if (b_h) return prune ? by_shape(std::true_type{}, std::true_type{}) : by_shape(std::true_type{}, std::false_type{});
+  return prune ? by_shape(std::false_type{}, std::true_type{}) : by_shape(std::false_type{}, std::false_type{});
 }
 
 }  // namespace kvr
