@@ -658,7 +658,7 @@ def test_budgeted_per_head_lambda(n, b_max):
     assert torch.equal(same.pick_order[0], out.pick_order[5]) and torch.equal(same.pick_gain[0], out.pick_gain[5])
 
 
-@pytest.mark.parametrize("n,dtype", [(200, torch.bfloat16), (150, torch.float32), (700, torch.bfloat16)])
+@pytest.mark.parametrize("n,dtype", [(200, torch.bfloat16), (150, torch.float32), (700, torch.bfloat16), (5000, torch.bfloat16)])
 def test_strided_layouts_in_every_mode(n, dtype):
     # K and V are views into larger buffers (token stride 136, extra tokens per head): the
     # strided calls must give what the same calls give on contiguous copies
