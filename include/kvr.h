@@ -216,7 +216,11 @@ int kvr_compact_inplace(void* K, void* V, const kvr_layout* lay, int group,
  * compaction of every head of the sequence with the shared index set.
  *   s           device, dense float32 [heads/group, n]: one score vector per sequence
  *   u_out       device, dense float32 [heads/group, n, d]: receives the signature
- *               rows (required unless lambda == 0, which reads no V)
+ *               rows (required unless lambda == 0, which reads no V).  Rows of
+ *               tokens that Algorithm 1 cannot select are not computed and read
+ *               zero: those with s_j < s_(b) - lambda, s_(b) the b-th largest score
+ *               of the sequence (one of the b best-scored tokens is always free
+ *               and gains at least s_(b) - lambda; a token gains at most s_j)
  *   idx_sorted, pick_order, pick_gain   [heads/group, b], as in kvr_select_greedy
  *   K_out, V_out  device, dense [heads, b, d], dtype of `lay`
  */

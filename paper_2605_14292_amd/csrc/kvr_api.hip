@@ -346,7 +346,9 @@ int kvr_retain_flat(const void* K, const void* V, const float* s, const kvr_layo
   kvr::Layout lu = l;                                   // the per-sequence problems: fp32 rows, dense
   lu.heads = l.heads / group; lu.dtype = KVR_F32;
   lu.stride_tok = l.d; lu.stride_head = static_cast<long long>(l.n) * l.d;
-  if (lambda != 0.0f && kvr::launch_signature_flat(V, l, group, u_out, st) != hipSuccess)
+  // (the per-sequence thresholds of the signature kernel park in idx_sorted[q * b], which the selection overwrites)
+  if (lambda != 0.0f && kvr::launch_signature_flat(V, l, group, u_out, st, s, b, lambda,
+                                                   reinterpret_cast<float*>(idx_sorted), b) != hipSuccess)
     return KVR_ERR_HIP;
   if (select_only(u_out, s, lu, b, lambda, eps, idx_sorted, pick_order, pick_gain, st) != hipSuccess)
     return KVR_ERR_HIP;

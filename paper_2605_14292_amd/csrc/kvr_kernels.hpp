@@ -55,7 +55,11 @@ hipError_t launch_score_prior(const void* V, const Layout& lay, const float* s_i
                               float* s_out, hipStream_t st);
 
 // Mean of V over each run of `group` consecutive heads: u_out is dense fp32 [heads/group, n, d].
-hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, float* u_out, hipStream_t st);
+hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, float* u_out, hipStream_t st,
+                                 const float* s = nullptr, int b = 0, float lambda = 0.f, float* thr = nullptr,
+                                 int thr_stride = 0);
+// With s (one score vector per sequence): the rows of tokens with s_j < s_(b) - lambda, which Algorithm 1 never
+// selects, are not computed (zero rows); thr[seq * thr_stride] receives the per-sequence threshold.
 
 // Selection for heads with fp32 rows and n <= 256 (no compaction).
 bool dense_f32_supported(const Layout& lay, int b);

@@ -8,6 +8,13 @@
 // each) x 8 slices of the group, every thread sums its slice in fp32 with sixteen loads in flight,
 // the slices meet in LDS.  Four tokens rather than eight per workgroup: 1536 workgroups fill the
 // resident slots of 256 CUs in whole rounds on the benchmark shape (66-68 us against 76 us).
+//
+// Inside the flat-mode event the rows of tokens that can never be selected are not computed:
+// while fewer than b tokens are selected one of the b best-scored is free and gains at least
+// s_(b) - lambda (Eq. 2, a cosine is at most 1), a token gains at most its score, so a token with
+// s_j < s_(b) - lambda never wins Eq. 3 and its signature row is never needed.  flat_bound_kernel
+// finds that threshold per sequence; the signature kernel then skips such tokens' loads and writes
+// zero rows for them (cosine 0 to everything: harmless wherever a later kernel still looks at them).
 #include "kvr_device.hpp"
 #include "kvr_kernels.hpp"
 
@@ -17,9 +24,38 @@ constexpr int kSigThreads = 512;
 constexpr int kSigTok = 4;                     // tokens per workgroup
 constexpr int kSigSlices = kSigThreads / (16 * kSigTok);   // slices of the group per token
 
+// thr[seq * thr_stride] = s_(b) - lambda (minus a margin for fp32 cosines a few ulp above 1), s_(b) from
+// the leading 16 bits of the ordered keys (at most s_(b): the bound only loosens).  One workgroup per sequence.
+__global__ __launch_bounds__(256) void flat_bound_kernel(const float* __restrict__ s, int n, int b, float lambda,
+                                                         float* __restrict__ thr, int thr_stride) {
+  __shared__ int cnt_l[2][4];
+  const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* sh = s + static_cast<long long>(seq) * n;
+  uint32_t T = 0;
+  int par = 0;
+  for (int bit = 31; bit >= 16; --bit) {
+    const uint32_t cand = T | (1u << bit);
+    int cnt = 0;
+    for (int j = tid; j < n; j += 256) cnt += ordered_key(sh[j] + 0.0f) >= cand ? 1 : 0;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+    if (lane == 0) cnt_l[par][wave] = cnt;
+    __syncthreads();
+    const int tot = cnt_l[par][0] + cnt_l[par][1] + cnt_l[par][2] + cnt_l[par][3];
+    par ^= 1;
+    if (tot >= b) T = cand;
+  }
+  if (tid == 0) {
+    const float sb = key_to_float(T);
+    thr[static_cast<long long>(seq) * thr_stride] = sb - lambda * 1.00001f - 1e-5f * fabsf(sb);
+  }
+}
+
 template <int DT>
 __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char* __restrict__ V, Layout lay,
-                                                                     int group, float* __restrict__ u_out) {
+                                                                     int group, float* __restrict__ u_out,
+                                                                     const float* __restrict__ s,
+                                                                     const float* __restrict__ thr, int thr_stride) {
   __shared__ float part[kSigSlices][kSigTok * 16][8];
   const int seq = blockIdx.y;
   const int tid = threadIdx.x;
@@ -27,7 +63,9 @@ __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char*
   const int tok = blockIdx.x * kSigTok + tk;
   constexpr int eb = DT == DT_BF16 ? 2 : 4;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (tok < lay.n) {
+  // (a token below its sequence's threshold keeps a zero row; a NaN score or threshold keeps the token)
+  const bool live = tok < lay.n && !(s && s[static_cast<long long>(seq) * lay.n + tok] < thr[static_cast<long long>(seq) * thr_stride]);
+  if (live) {
     const char* p = V + ((static_cast<long long>(seq) * group) * lay.stride_head +
                          static_cast<long long>(tok) * lay.stride_tok + chunk * 8) * eb;
     const long long hstep = lay.stride_head * eb;
@@ -80,15 +118,21 @@ __global__ __launch_bounds__(kSigThreads) void signature_flat_kernel(const char*
   }
 }
 
-hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, float* u_out, hipStream_t st) {
+hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, float* u_out, hipStream_t st,
+                                 const float* s, int b, float lambda, float* thr, int thr_stride) {
   const int seqs = lay.heads / group;
+  if (s) {                                         // the rows of tokens the score bound rules out stay zero
+    hipLaunchKernelGGL(flat_bound_kernel, dim3(seqs), dim3(256), 0, st, s, lay.n, b, lambda, thr, thr_stride);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   dim3 grid((lay.n + kSigTok - 1) / kSigTok, seqs);
   if (lay.dtype == DT_BF16)
     hipLaunchKernelGGL((signature_flat_kernel<DT_BF16>), grid, dim3(kSigThreads), 0, st,
-                       static_cast<const char*>(V), lay, group, u_out);
+                       static_cast<const char*>(V), lay, group, u_out, s, thr, thr_stride);
   else
     hipLaunchKernelGGL((signature_flat_kernel<DT_F32>), grid, dim3(kSigThreads), 0, st,
-                       static_cast<const char*>(V), lay, group, u_out);
+                       static_cast<const char*>(V), lay, group, u_out, s, thr, thr_stride);
   return hipGetLastError();
 }
 
