@@ -15,8 +15,8 @@ Diversity Penalty"):
 * marginal gain  s_i - lambda * max(0, max_{j in S} cos(v_i, v_j))  (Eq. 2).
 * greedy fill: first pick argmax s, then argmax of the marginal gain over
   the unselected tokens, k-1 times                                  (Eq. 3).
-* Algorithm 1: the same rule with the n x n cosine matrix computed once and
-  a running maximum m (initialised to zero, which is the max(0, .) floor);
+* Algorithm 1 is that rule with the inner maximum of Eq. 2 carried along as
+  a running vector (zero for the empty set, which is the max(0, .) floor);
   lambda == 0 returns top-k(s) through an explicit branch; the result is the
   sorted index set.
 * The cache after the event is the selected rows of K and V in ascending
@@ -32,13 +32,16 @@ lowest token index (this makes the greedy loop at lambda = 0 coincide with a
 stable top-k, as the text requires of the fast path); eps is added to the
 norm; all n tokens are candidates.
 
-Pins (tests/test_oracle_pins.py): a worked four-token case derived by hand,
-lambda = 0 against a stable sort, orthonormal / identical / antipodal value
-rows (closed forms), an exhaustive from-scratch evaluation of Eq. 2 on tiny
-inputs (`greedy_from_definition`, which keeps no running maximum and no cosine
-matrix), softmax rows summing to one and matching scipy, invariants (k unique
-indices, first pick = argmax s, non-increasing pick gains).  No function here
-is "parity unpinned".
+Pins (tests/test_oracle_pins.py): worked cases derived by hand (one of them
+with exactly tied gains), lambda = 0 against a stable sort, orthonormal /
+identical / antipodal value rows (closed forms), exactly tied gains at
+lambda > 0 against a sort by (score descending, index ascending) that does not
+go through this module's argmax, an exhaustive from-scratch evaluation of
+Eq. 2 on tiny inputs (`greedy_from_definition`, which keeps no running maximum
+and no cosine matrix), the runner-up gain against a brute-force second best,
+softmax rows summing to one and matching scipy, invariants (k unique indices,
+first pick = argmax s, non-increasing pick gains).  No function here is
+"parity unpinned".
 """
 from __future__ import annotations
 
@@ -131,18 +134,27 @@ def topk_order(s: np.ndarray, k: int) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# Algorithm 1
+# the selector (Eq. 2 and Eq. 3; the rule Algorithm 1 implements)
 # --------------------------------------------------------------------------
 def alpha_select(s, V, k: int, lam: float, eps: float = 1e-6):
-    """Algorithm 1, step by step, in fp64.
+    """The greedy fill of Eq. 3 under the marginal gain of Eq. 2, in fp64.
+
+    For the current set S every unselected token i is worth
+    s_i - lam * max(0, max_{j in S} <v_i, v_j>)  (Eq. 2); the best one joins S
+    (Eq. 3), k times, starting from the empty set, for which the inner term is
+    the floor 0 and the first member is therefore argmax s.  The inner maximum
+    is carried from one step to the next: when i joins S it gains exactly one
+    term, <v_., v_i>, which is the one row of cosines computed per member (the
+    n x n matrix of Algorithm 1 holds the same numbers; only k of its rows are
+    ever looked at).  lam == 0 takes the explicit branch the paper requires of
+    the selector: top-k of s, no value row is touched.
 
     Returns a dict with
-      order   [k]  picks in the order they were made,
-      gain    [k]  marginal gain of each pick when it was made (gain[0] is
-                   max s),
-      second  [k]  the best marginal gain among the other unselected tokens
+      order   [k]  members in the order they joined,
+      gain    [k]  Eq. 2 of each member when it joined (gain[0] is max s),
+      second  [k]  the largest Eq. 2 value among the other unselected tokens
                    at that step (-inf when none is left),
-      sorted  [k]  sort(S), the algorithm's return value.
+      sorted  [k]  sort(S), the selector's return value.
     """
     s = np.asarray(s, dtype=np.float64)
     n = s.shape[0]
@@ -150,39 +162,26 @@ def alpha_select(s, V, k: int, lam: float, eps: float = 1e-6):
         raise ValueError("need 1 <= k <= n")
     if not (lam >= 0.0):
         raise ValueError("need lambda >= 0")
-    if lam == 0.0:
-        order = topk_order(s, k)
-        gain = s[order].copy()
-        second = np.full(k, NEG_INF)
-        rest = np.sort(s)[::-1]
-        for t in range(k):
-            if t + 1 < n:
-                second[t] = rest[t + 1]
-        return dict(order=order, gain=gain, second=second,
-                    sorted=np.sort(order))
-    Vh = signatures(V, eps)
-    sims = Vh @ Vh.T                                # n x n cosine matrix
-    m = np.zeros(n)
-    selected = np.zeros(n, dtype=bool)
     order = np.empty(k, dtype=np.int64)
     gain = np.empty(k)
     second = np.full(k, NEG_INF)
-
-    def take(a, t):
-        i = _argmax_lowest(a)
-        order[t] = i
-        gain[t] = a[i]
-        b = a.copy()
-        b[i] = NEG_INF
-        second[t] = b.max() if n > 1 else NEG_INF
-        selected[i] = True
-        np.maximum(m, sims[i, :], out=m)
-
-    take(s.copy(), 0)                               # i_1 = argmax s
-    for t in range(1, k):
-        a = s - lam * m
-        a[selected] = NEG_INF
-        take(a, t)
+    if lam == 0.0:
+        order[:] = topk_order(s, k)
+        gain[:] = s[order]
+        by_value = np.sort(s)[::-1]
+        second[: min(k, n - 1)] = by_value[1: min(k, n - 1) + 1]
+        return dict(order=order, gain=gain, second=second, sorted=np.sort(order))
+    Vh = signatures(V, eps)
+    redundancy = np.zeros(n)            # Eq. 2's max(0, max_{j in S} <v_i, v_j>) for the current S
+    free = np.ones(n, dtype=bool)
+    for t in range(k):
+        value = np.where(free, s - lam * redundancy, NEG_INF)      # Eq. 2
+        i = _argmax_lowest(value)                                  # Eq. 3
+        order[t], gain[t] = i, value[i]
+        if n > 1:
+            second[t] = np.delete(value, i).max()
+        free[i] = False
+        np.maximum(redundancy, Vh @ Vh[i], out=redundancy)         # S now holds i
     return dict(order=order, gain=gain, second=second, sorted=np.sort(order))
 
 

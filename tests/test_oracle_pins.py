@@ -34,6 +34,136 @@ def test_hand_case_four_tokens_two_lambdas():
         np.testing.assert_allclose(r["gain"], c["gain"], atol=1e-12)
 
 
+def test_hand_case_with_exactly_tied_gains():
+    g = json.load(open(os.path.join(GOLD, "hand_case.json")))["tied_case"]
+    r = O.alpha_select(g["s"], np.array(g["V"]), g["k"], g["lambda"], g["eps"])
+    assert r["order"].tolist() == g["order"]
+    assert r["gain"].tolist() == g["gain"]
+    assert r["second"].tolist() == g["second"]
+    assert r["sorted"].tolist() == g["sorted"]
+    order, gains = O.greedy_from_definition(g["s"], np.array(g["V"]), g["k"], g["lambda"], g["eps"])
+    assert order.tolist() == g["order"] and gains.tolist() == g["gain"]
+
+
+# ------------------------------------------ the tie rule: lowest token index
+# Expected values below never go through the oracle's own argmax helper: they are
+# sorted(range(n), key=(-score, index)), written out.
+def _by_score_then_index(s, k):
+    return sorted(range(len(s)), key=lambda i: (-s[i], i))[:k]
+
+
+@pytest.mark.parametrize("lam", [0.25, 1.0])
+@pytest.mark.parametrize("seed", range(4))
+def test_tied_scores_on_orthonormal_rows_join_in_index_order(seed, lam):
+    # orthonormal rows: every cosine is exactly 0, so Eq. 2 is the score and the
+    # greedy loop must walk the tokens by (score descending, index ascending)
+    rng = _rng(300 + seed)
+    n, k = 24, 17
+    s = rng.integers(0, 4, n).astype(np.float64)        # four levels: many exact ties
+    V = np.eye(n)
+    expect = _by_score_then_index(s, k)
+    r = O.alpha_select(s, V, k, lam, 0.0)
+    assert r["order"].tolist() == expect
+    assert r["gain"].tolist() == [s[i] for i in expect]
+    order, _ = O.greedy_from_definition(s, V, k, lam, 0.0)
+    assert order.tolist() == expect
+    b = O.select_budgeted(s, V, n, k, None, lam, 0.0)
+    assert b["order"].tolist() == expect
+
+
+@pytest.mark.parametrize("lam", [0.25, 1.0])
+def test_tied_scores_on_identical_rows_join_in_index_order(lam):
+    # identical unit rows, eps = 0: after the first member every value is score - lam exactly
+    # (quarter-integer scores and these lambdas are exact in binary), so the order is again
+    # (score descending, index ascending), with ties at every level
+    rng = _rng(17)
+    n, k = 30, 21
+    s = rng.integers(0, 5, n) / 4.0
+    V = np.tile(np.array([[0.0, 1.0, 0.0]]), (n, 1))
+    expect = _by_score_then_index(s, k)
+    r = O.alpha_select(s, V, k, lam, 0.0)
+    assert r["order"].tolist() == expect
+    assert r["gain"].tolist() == [s[expect[0]]] + [s[i] - lam for i in expect[1:]]
+    order, _ = O.greedy_from_definition(s, V, k, lam, 0.0)
+    assert order.tolist() == expect
+
+
+def test_first_member_tie_goes_to_the_lowest_index():
+    s = np.array([1.0, 3.0, 3.0, 2.0, 3.0])
+    V = _rng(2).normal(size=(5, 3))
+    assert O.alpha_select(s, V, 1, 0.5)["order"].tolist() == [1]
+    assert O.alpha_select(s, V, 1, 0.0)["order"].tolist() == [1]
+    assert O.greedy_from_definition(s, V, 1, 0.5)[0].tolist() == [1]
+    assert O.select_budgeted(s, V, 5, 1)["order"].tolist() == [1]
+
+
+def test_greedy_loop_at_lambda_zero_is_the_stable_topk():
+    # the loop form of Eq. 3 with lam = 0 (no fast path) on heavily tied scores
+    rng = _rng(23)
+    n, k = 60, 33
+    s = rng.integers(0, 6, n).astype(np.float64)
+    V = rng.normal(size=(n, 5))
+    expect = _by_score_then_index(s, k)
+    assert O.greedy_from_definition(s, V, k, 0.0)[0].tolist() == expect
+    assert O.topk_order(s, k).tolist() == expect
+    assert O.select_budgeted(s, V, n, k, None, 0.0)["order"].tolist() == expect
+
+
+def test_budgeted_frame_breaks_ties_among_free_tokens_towards_the_lowest_index():
+    # token 0 protected (row e1); free tokens 1..4: rows e2,e2,e3,e3, equal scores.
+    # t0: values of 1..4 all 1.0 -> 1 joins; then 2 is penalised (1 - .5), 3 and 4 tie at 1.0 -> 3;
+    # then 2 and 4 tie at .5 -> 2.
+    E = np.eye(3)
+    V = np.stack([E[0], E[1], E[1], E[2], E[2]])
+    s = np.array([0.0, 1.0, 1.0, 1.0, 1.0])
+    keep = np.array([1, 0, 0, 0, 0], dtype=np.uint8)
+    r = O.select_budgeted(s, V, 5, 4, keep, 0.5, 0.0)
+    assert r["protected"].tolist() == [0]
+    assert r["order"].tolist() == [1, 3, 2]
+    assert r["gain"].tolist() == [1.0, 1.0, 0.5]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_runner_up_gain_is_the_brute_force_second_best(seed):
+    rng = _rng(500 + seed)
+    n = int(rng.integers(3, 11))
+    V = rng.normal(size=(n, 4))
+    s = rng.integers(0, 3, n) / 2.0 if seed % 2 else rng.uniform(0, 1, n)    # with and without ties
+    lam, eps, k = 0.5, 1e-6, n
+    r = O.alpha_select(s, V, k, lam, eps)
+    Vh = O.signatures(V, eps)
+    for t in range(k):
+        S = r["order"][:t].tolist()
+        vals = []
+        for i in range(n):
+            if i in S:
+                continue
+            red = max([0.0] + [float(Vh[i] @ Vh[j]) for j in S])
+            vals.append(s[i] - lam * red)
+        vals.sort(reverse=True)
+        assert abs(vals[0] - r["gain"][t]) < 1e-13
+        if len(vals) > 1:
+            assert abs(vals[1] - r["second"][t]) < 1e-13 and r["second"][t] <= r["gain"][t]
+        else:
+            assert r["second"][t] == -np.inf
+    z = O.alpha_select(s, V, k, 0.0)                 # the lambda = 0 branch reports the next score down
+    by_value = sorted(s.tolist(), reverse=True)
+    assert z["second"][: n - 1].tolist() == by_value[1:] and z["second"][n - 1] == -np.inf
+
+
+def test_tie_pins_fail_when_ties_go_to_the_highest_index(monkeypatch):
+    # the planted mistake: argmax returning the last maximum instead of the first
+    monkeypatch.setattr(O, "_argmax_lowest", lambda a: int(np.flatnonzero(a == a.max())[-1]))
+    for pin in (test_hand_case_with_exactly_tied_gains,
+                lambda: test_tied_scores_on_orthonormal_rows_join_in_index_order(0, 0.25),
+                lambda: test_tied_scores_on_identical_rows_join_in_index_order(1.0),
+                test_first_member_tie_goes_to_the_lowest_index,
+                test_greedy_loop_at_lambda_zero_is_the_stable_topk,
+                test_budgeted_frame_breaks_ties_among_free_tokens_towards_the_lowest_index):
+        with pytest.raises(AssertionError):
+            pin()
+
+
 # ------------------------------------------------- lambda = 0 is stable top-k
 @pytest.mark.parametrize("seed", range(5))
 def test_lambda_zero_is_stable_topk(seed):
