@@ -4,199 +4,369 @@ on one MI355X.  Prints one JSON line.
 
 A step is one kvr_retain call over all heads of the workload, with K, V and
 Q (or s) already resident in HBM.  value = heads / second.
+
+The headline is the largest configuration (c4, 4.4 GB of K and V per step).
+Every configuration, the headline and those under `other_configs`, carries its
+own `roofline` object (the step's kernels, their measured device time, the
+step's algorithmic bytes, the counter traffic of the committed profile), its own
+`cpu_baseline` (the fp64 oracle on the host cores, heads in parallel over a
+process pool) and, for the plain entry point, a `parity` object: after the timed
+loop a fixed sample of heads of the very buffers that were timed is compared
+with the oracle pick by pick, and the near-tie counts are reported.
+`worst_long_config` names the lowest roofline fraction among c3, c4 and c5.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
+import statistics
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
+EPS = 1e-6
 
 
-def cpu_baseline(w, data, b, lam, budget_s=12.0):
-    """The fp64 oracle, as it stands, on a bounded sample of the same heads."""
+# --------------------------------------------------------------------------- host side: the oracle legs
+def host_cores() -> int:
+    """Worker processes for the oracle legs: the CPUs this process may run on, at most 16 (the CPU
+    share of a one-GPU machine)."""
+    try:
+        return max(1, min(16, len(os.sched_getaffinity(0))))
+    except AttributeError:
+        return max(1, min(16, os.cpu_count() or 1))
+
+
+class OraclePool:
+    """A spawn-context process pool whose workers import numpy and the oracle only (never torch, never
+    the GPU) and run one BLAS thread each."""
+
+    def __init__(self):
+        import multiprocessing as mp
+        self.cores = host_cores()
+        saved = {k: os.environ.get(k) for k in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS")}
+        for k in saved:
+            os.environ[k] = "1"
+        self.pool = mp.get_context("spawn").Pool(self.cores)
+        self.pool.map(_warm, range(self.cores))          # imports done before anything is timed
+        for k, v in saved.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+    def close(self):
+        self.pool.close()
+        self.pool.join()
+
+
+def _warm(_):
+    import parity_util  # noqa: F401
+    return os.getpid()
+
+
+def _oracle_job(i):
+    import parity_util
+    return parity_util.oracle_event_job(i)
+
+
+def _check_job(i):
+    import parity_util
+    return parity_util.check_head_job(i)
+
+
+def _raw(t):
+    """A tensor in the form the pool jobs take: bf16 as its int16 bit patterns, anything else as is."""
+    import torch
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.int16).numpy() if t.dtype == torch.bfloat16 else t.numpy()
+
+
+def cpu_baseline(pool, case, budget_s):
+    """The fp64 oracle, as it stands, on a bounded sample of the same heads: one pilot head sizes the
+    sample so that the pool is busy for about `budget_s` seconds; the rate is sample / wall time of the
+    pool run (argument transfer to the workers included)."""
     import numpy as np
-    from oracle import alpha_oracle as O
-    from paper_2605_14292_amd import workloads as W
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
+    w, data = case["w"], case["data"]
     rng = np.random.default_rng(11)
-    heads = rng.permutation(w.heads)
-    done, t_used = 0, 0.0
-    for h in heads:
-        K64, V64 = W.to_f64(data["K"][h]), W.to_f64(data["V"][h])
-        Q64 = W.to_f64(data["Q"][h]) if "Q" in data else None
-        s64 = W.to_f64(data["s"][h]) if "s" in data else None
-        t0 = time.perf_counter()
-        r = O.retain(K64, V64, b, lam, 1e-6, Q=Q64, s=s64)
-        O.compact(K64, r["sorted"])
-        O.compact(V64, r["sorted"])
-        t_used += time.perf_counter() - t0
-        done += 1
-        if t_used >= budget_s:
-            break
-    return {"value": done / t_used, "unit": "head-events/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {w.heads} heads of {w.name} (fp64 numpy oracle, {t_used:.1f} s, "
-                      "rate extrapolates linearly over heads)"}
+    mode = case["mode"]
+    units = w.seqs if mode == "flat" else w.heads           # independent oracle problems
+    per_unit = case["group"] if mode == "flat" else 1       # heads per problem
+    order = rng.permutation(units).tolist()
+
+    def job(u):
+        j = {"b": case["b"], "lam": case["lam"], "eps": EPS, "mode": mode}
+        if mode == "flat":
+            sl = slice(u * case["group"], (u + 1) * case["group"])
+            j.update(K=_raw(data["K"][sl]), V=_raw(data["V"][sl]), s=_raw(case["s"][u]))
+            return j
+        j.update(K=_raw(data["K"][u]), V=_raw(data["V"][u]))
+        if case["Q"] is not None:
+            j["Q"] = _raw(case["Q"][u])
+        else:
+            j["s"] = _raw(case["s"][u])
+        if mode == "budgeted":
+            j.update(n_h=w.n, b=int(case["b_h_host"][u]), keep=case["keep_host"][u])
+        return j
+
+    import parity_util
+    first = job(order[0])
+    t_one = parity_util.oracle_event_job(first)              # pilot, in this process
+    want = int(min(units, max(pool.cores, pool.cores * budget_s / max(t_one, 1e-4))))
+    jobs = [first] + [job(u) for u in order[1:want]]
+    t0 = time.perf_counter()
+    secs = pool.pool.map(_oracle_job, jobs, chunksize=1)
+    wall = time.perf_counter() - t0
+    done = len(jobs) * per_unit
+    what = "sequences" if mode == "flat" else "heads"
+    return {"value": done / wall, "unit": "head-events/s", "cores": pool.cores, "kind": "oracle",
+            "sample": f"{len(jobs)} of {units} {what} of {w.name}"
+                      + (f" ({per_unit} heads each, flat-signature mode)" if mode == "flat" else "")
+                      + (", budget-allocator frame" if mode == "budgeted" else "")
+                      + f": fp64 numpy oracle, one process per core, {wall:.1f} s wall for the sample "
+                        f"({sum(secs):.1f} core-seconds inside the workers); the rate extrapolates linearly"}
 
 
-def cpu_baseline_flat(w, data, s, group, b, lam, budget_s=12.0):
-    """The fp64 oracle's flat-mode event on a bounded sample of sequences."""
-    from oracle import alpha_oracle as O
-    from paper_2605_14292_amd import workloads as W
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
-    done, t_used = 0, 0.0
-    for q in range(w.seqs):
-        sl = slice(q * group, (q + 1) * group)
-        K64, V64, s64 = W.to_f64(data["K"][sl]), W.to_f64(data["V"][sl]), W.to_f64(s[q])
-        t0 = time.perf_counter()
-        O.retain_flat(K64, V64, s64, b, lam, 1e-6)
-        t_used += time.perf_counter() - t0
-        done += 1
-        if t_used >= budget_s:
-            break
-    return {"value": done * group / t_used, "unit": "head-events/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {w.seqs} sequences ({group} heads each) of {w.name}, flat-signature mode "
-                      f"(fp64 numpy oracle, {t_used:.1f} s, rate extrapolates linearly over sequences)"}
-
-
-def cpu_baseline_budgeted(w, data, b_h, keep, lam, budget_s=12.0):
-    """The fp64 oracle's budgeted selection + compaction on a bounded sample of heads."""
+def verify(pool, case, out_timed, sample):
+    """After the timed loop: the step once more into buffers that also record the pick order and the
+    gains; its index sets must equal the timed buffers' on every head; a fixed sample of heads is then
+    compared with the oracle pick by pick (scores, picks, gains, kept rows)."""
     import numpy as np
-    from oracle import alpha_oracle as O
-    from paper_2605_14292_amd import workloads as W
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
-    rng = np.random.default_rng(11)
-    bh, kp = b_h.cpu().numpy(), keep.cpu().numpy().astype(bool)
-    done, t_used = 0, 0.0
-    for h in rng.permutation(w.heads):
-        K64, V64 = W.to_f64(data["K"][h]), W.to_f64(data["V"][h])
-        t0 = time.perf_counter()
-        s64 = O.score_softmax_mean(K64, W.to_f64(data["Q"][h])) if "Q" in data else W.to_f64(data["s"][h])
-        r = O.select_budgeted(s64, V64, w.n, int(bh[h]), kp[h], lam, 1e-6)
-        O.compact(K64, r["sorted"]); O.compact(V64, r["sorted"])
-        t_used += time.perf_counter() - t0
-        done += 1
-        if t_used >= budget_s:
-            break
-    return {"value": done / t_used, "unit": "head-events/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {w.heads} heads of {w.name}, budget-allocator frame (fp64 numpy oracle, "
-                      f"{t_used:.1f} s, rate extrapolates linearly over heads)"}
-
-
-def time_other(name, steps=5, warmup=2, seed=0, lam=None, flat=False, cold=False, budgeted=False):
-    """A short run of another benchmark configuration at its full size, for the
-    `other_configs` object: the default workload carries the headline figures, the others are
-    reported beside it from the same process.  `cold`: the small configurations (c1, c2) fit the
-    256 MiB memory-side cache, so a loop over one set of buffers times cache hits; with `cold` every
-    step takes the next of enough copies of the inputs to exceed that cache several times over, and
-    the hot figure (one set of buffers) is reported beside it."""
     import torch
     from paper_2605_14292_amd import binding as B
-    from paper_2605_14292_amd import workloads as W
-    w = W.WORKLOADS[name]
-    lam = w.lam if lam is None else lam
-    data = W.generate(w, seed=seed, device="cuda:0")
-    Q, s = data.get("Q"), data.get("s")
-    group = w.layers * w.kv_heads
-    if flat:
-        s = s.view(w.seqs, group, w.n)[:, 0].contiguous()
-        out = B.FlatBuffers(w.heads, group, w.n, w.b, w.d, w.torch_dtype, "cuda:0", want_trace=False)
-        step = lambda: B.kvr_retain_flat(data["K"], data["V"], s, group, w.b, lam, 1e-6, out=out)
-    elif budgeted:      # the frame of main()'s --budgeted: b_h in [b/2, b], 4 sinks + 16 recent protected, position ids
-        g = torch.Generator(device="cuda:0").manual_seed(seed + 17)
-        b_h = torch.randint(w.b // 2, w.b + 1, (w.heads,), generator=g, device="cuda:0", dtype=torch.int32)
-        keep = torch.zeros((w.heads, w.n), dtype=torch.uint8, device="cuda:0")
-        keep[:, :4] = 1
-        keep[:, w.n - 16:] = 1
-        pos = torch.arange(w.n, dtype=torch.int32, device="cuda:0").repeat(w.heads, 1).contiguous()
-        out = B.BudgetBuffers(w.heads, w.n, w.b, w.d, w.torch_dtype, "cuda:0", with_pos=True)
-        step = lambda: B.kvr_retain_budgeted(data["K"], data["V"], w.b, lam, 1e-6, Q=Q, s=s, b_h=b_h, keep=keep,
-                                             pos=pos, out=out)
-    else:
-        out = B.RetainBuffers(w.heads, w.n, w.b, w.d, w.torch_dtype, "cuda:0", "Q" in data, want_trace=False)
-        step = lambda: B.kvr_retain(data["K"], data["V"], w.b, lam, 1e-6, Q=Q, s=s, out=out)
-
-    def timed(fn, k):
-        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for i in range(k):
-            fn(i)
-        z.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(z) / k
-
-    for _ in range(warmup):
-        step()
+    w, data, b, lam = case["w"], case["data"], case["b"], case["lam"]
+    out = B.kvr_retain(data["K"], data["V"], b, lam, EPS, Q=case["Q"], s=case["s"])
     torch.cuda.synchronize()
-    ms = timed(lambda i: step(), steps)
-    cold_ms, copies = None, 0
-    if cold and not flat:
-        set_bytes = sum(v.numel() * v.element_size() for v in data.values())
-        copies = int(min(4096, max(16, -(-1_000_000_000 // set_bytes))))
-        sets = [data] + [{k: v.clone() for k, v in data.items()} for _ in range(copies - 1)]
-        cstep = lambda i: B.kvr_retain(sets[i % copies]["K"], sets[i % copies]["V"], w.b, lam, 1e-6,
-                                       Q=sets[i % copies].get("Q"), s=sets[i % copies].get("s"), out=out)
-        torch.cuda.synchronize()
-        cold_ms = timed(cstep, copies)          # every set once: none of it is in a cache
-        del sets
-    bytes_step = w.algorithmic_bytes_per_head(w.b, lam) * w.heads
-    if flat:
-        bytes_step -= (4 * w.n + 4 * w.b) * (w.heads - w.seqs)
-    if budgeted:
-        rows = (3 if w.scores == "given" else 2) * w.d * w.elem_bytes
-        bytes_step += int((float(b_h.float().mean().item()) - w.b) * rows * w.heads) + (w.n + 4 * w.n + 4 * w.b) * w.heads
-    del data, out
-    torch.cuda.empty_cache()
-    res = {"ms_per_step": ms, "head_events_per_s": w.heads / (ms * 1e-3), "steps": steps,
-           "algorithmic_GBps": bytes_step / (ms * 1e-3) / 1e9,
-           "frac_of_hbm_peak": bytes_step / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-           "heads": w.heads, "n": w.n, "b": w.b, "lambda": lam}
-    if cold_ms is not None:
-        res.update({"inputs": "hot: one set of buffers, served by the memory-side cache",
-                    "ms_per_step_cold": cold_ms, "cold_input_sets": copies,
-                    "head_events_per_s_cold": w.heads / (cold_ms * 1e-3)})
-    return res
+    if not torch.equal(out.idx_sorted, out_timed.idx_sorted):
+        raise AssertionError("the timed run and the verification run selected different tokens")
+    if not (torch.equal(out.K_out, out_timed.K_out) and torch.equal(out.V_out, out_timed.V_out)):
+        raise AssertionError("the timed run and the verification run kept different rows")
+    idx_all = out.idx_sorted.cpu().numpy()
+    assert idx_all.min() >= 0 and idx_all.max() < w.n and np.all(np.diff(idx_all, axis=1) > 0)
+    rng = np.random.default_rng(7)
+    heads = sorted(rng.choice(w.heads, size=min(sample, w.heads), replace=False).tolist())
+    jobs = []
+    for h in heads:
+        j = {"b": b, "lam": lam, "eps": EPS, "K": _raw(data["K"][h]), "V": _raw(data["V"][h]),
+             "order": out.pick_order[h].cpu().numpy(), "gain": out.pick_gain[h].cpu().numpy(),
+             "idx": idx_all[h], "K_out": _raw(out.K_out[h]), "V_out": _raw(out.V_out[h])}
+        if case["Q"] is not None:
+            j["Q"] = _raw(case["Q"][h])
+            j["s_hip"] = out.s_out[h].cpu().numpy()
+        else:
+            j["s"] = _raw(case["s"][h])
+        jobs.append(j)
+    reps = pool.pool.map(_check_job, jobs, chunksize=1)
+    return {"heads_checked": len(reps),
+            "identical_sets": sum(bool(r["identical_to_free_run"]) for r in reps),
+            "near_ties": sum(r["near_ties"] for r in reps),
+            "oracle_near_ties": sum(r["oracle_near_ties"] for r in reps),
+            "max_gain_err": max(r["max_gain_err"] for r in reps),
+            "max_score_err": max(r["score_err"] for r in reps),
+            "kept_rows": "bit-exact", "all_heads": "index sets ascending, in range, equal to the timed run's",
+            "near_tie": "oracle's best two gains within 1e-5 of the operand magnitude |s| + lambda*m"}
 
 
-def kernel_name(w, b, lam, has_q):
-    """The kernels one kvr_retain call launches for this shape (the roofline
-    object prices the whole step against the step's algorithmic bytes)."""
-    if w.dtype == "bf16" and 128 < w.n <= 256 and not has_q and 1 < b <= 128 and lam > 0:
-        return ("kvr::retain_pruned_kernel (the whole step; kvr::retain_dense_kernel follows for the heads "
-                "it marks, a few microseconds when there are none)")
+# --------------------------------------------------------------------------- device side
+def kernel_names(w, b, lam, has_q, mode):
+    """The kernels one call launches for this shape."""
+    if mode == "flat":
+        return ["kvr::flat_bound_kernel", "kvr::signature_flat_kernel", "kvr::select_dense_f32_kernel", "kvr::compact_kernel"]
+    if mode == "budgeted":
+        return ["kvr::budget_prepare_kernel"] + kernel_names(w, b, lam, has_q, "plain") + ["kvr::budget_fixup_kernel"]
+    if w.dtype == "bf16" and 128 < w.n <= 256 and not has_q and 1 < b <= 128 and lam > 0 and w.heads > 256:
+        return ["kvr::retain_pruned_kernel", "kvr::retain_dense_kernel (marked heads only)"]
     if w.dtype == "bf16" and w.n <= 256:
-        if w.n > 128 and w.heads <= 256:
-            return "kvr::retain_dense16_kernel (the whole step is this one launch; one head per CU, sixteen waves each)"
-        return "kvr::retain_dense_kernel (the whole step is this one launch)"
-    if w.dtype == "bf16" and w.n <= 8192 and b <= 1024:
-        tail = ["kvr::select_pool_kernel (selection + compaction)"]
-    else:
-        tail = ["kvr::select_generic_kernel", "kvr::compact_kernel"]
+        return ["kvr::retain_dense16_kernel" if (w.n > 128 and w.heads <= 256) else "kvr::retain_dense_kernel"]
+    if w.dtype != "bf16" and w.n <= 256 and w.G <= 16:
+        return ["kvr::select_dense_f32_kernel"]
     fits_lds = w.G <= 32 and w.G * w.n <= (24576 if w.G <= 8 else 31488)
     score = ("kvr::score_kernel" if w.dtype != "bf16" else
              "kvr::score_mfma_kernel" if fits_lds else "kvr::score_wide_kernel")
-    if w.dtype != "bf16" and w.n <= 256 and w.G <= 16:
-        return "kvr::select_dense_f32_kernel (scores, selection and kept rows: the whole step is this one launch)"
-    parts = ([score] if has_q else []) + tail
-    return " + ".join(parts) + " (whole step; the select kernel dominates)"
+    if w.dtype == "bf16" and w.n <= 8192 and b <= 1024:
+        tail = ["kvr::select_topb_kernel" if lam == 0.0 else "kvr::select_pool_kernel"]
+    else:
+        tail = ["kvr::select_generic_kernel", "kvr::compact_kernel"]
+    return ([score] if has_q else []) + tail
+
+
+def make_case(name, seed, b=None, lam=None, mode="plain", window=1, score_scale=1.0):
+    import torch
+    from paper_2605_14292_amd import binding as B
+    from paper_2605_14292_amd import workloads as W
+    dev = "cuda:0"
+    w = W.WORKLOADS[name]
+    if window != 1:
+        if w.scores != "computed" or window < 1 or w.G * window > 256:
+            sys.exit("bench.py: --window needs a workload with computed scores and G * WINDOW <= 256")
+        w = dataclasses.replace(w, G=w.G * window, what=w.what + f", observation window of {window} positions")
+    b = w.b if b is None else b
+    lam = w.lam if lam is None else lam
+    data = W.generate(w, seed=seed, device=dev)
+    Q, s = data.get("Q"), data.get("s")
+    if score_scale != 1.0:
+        if s is None:
+            sys.exit("bench.py: --score-scale needs a workload whose scores are given (c3)")
+        s = (s * score_scale).contiguous()
+    group = w.layers * w.kv_heads
+    case = {"w": w, "data": data, "b": b, "lam": lam, "mode": mode, "Q": Q, "s": s, "group": group,
+            "score_scale": score_scale}
+    bytes_step = w.algorithmic_bytes_per_head(b, lam) * w.heads
+    if mode == "flat":
+        if s is None:
+            sys.exit("bench.py: --flat needs a workload whose scores are given (c3)")
+        s = s.view(w.seqs, group, w.n)[:, 0].contiguous()     # one score vector per sequence
+        case["s"] = s
+        out = B.FlatBuffers(w.heads, group, w.n, b, w.d, w.torch_dtype, dev, want_trace=False)
+        step = lambda: B.kvr_retain_flat(data["K"], data["V"], s, group, b, lam, EPS, out=out)
+        bytes_step -= (4 * w.n + 4 * b) * (w.heads - w.seqs)  # scores and indices are per sequence
+    elif mode == "budgeted":
+        g = torch.Generator(device=dev).manual_seed(seed + 17)
+        b_h = torch.randint(b // 2, b + 1, (w.heads,), generator=g, device=dev, dtype=torch.int32)
+        keep = torch.zeros((w.heads, w.n), dtype=torch.uint8, device=dev)
+        keep[:, :4] = 1
+        keep[:, w.n - 16:] = 1
+        pos = torch.arange(w.n, dtype=torch.int32, device=dev).repeat(w.heads, 1).contiguous()
+        out = B.BudgetBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, with_pos=True)
+        step = lambda: B.kvr_retain_budgeted(data["K"], data["V"], b, lam, EPS, Q=Q, s=s, b_h=b_h, keep=keep,
+                                             pos=pos, out=out)
+        case.update(b_h_host=b_h.cpu().numpy(), keep_host=keep.cpu().numpy())
+        rows = (3 if w.scores == "given" else 2) * w.d * w.elem_bytes   # K in (given scores only), K out, V out
+        bytes_step += int((float(b_h.float().mean().item()) - b) * rows * w.heads) + (w.n + 4 * w.n + 4 * b) * w.heads
+    else:
+        out = B.RetainBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, Q is not None, want_trace=False)
+        step = lambda: B.kvr_retain(data["K"], data["V"], b, lam, EPS, Q=Q, s=s, out=out)
+    case.update(step=step, out=out, bytes_step=bytes_step, window=window)
+    return case
+
+
+def time_steps(step, steps, warmup):
+    """W untimed steps, then exactly K steps between two synchronisations.  HIP events on the stream the
+    kernels are launched on (torch's current stream) bracket every step: the median of the K per-step
+    durations and the mean over the whole region are both reported."""
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    return {"wall_ms": wall * 1e3 / steps, "dev_mean_ms": ev[0].elapsed_time(ev[steps]) / steps,
+            "dev_median_ms": statistics.median(per), "dev_min_ms": min(per), "dev_max_ms": max(per)}
+
+
+def time_cold(case, copies_bytes=1_000_000_000):
+    """c1 and c2 fit the 256 MiB memory-side cache: with `cold` every step takes the next of enough copies of
+    the inputs to exceed that cache several times over."""
+    import torch
+    from paper_2605_14292_amd import binding as B
+    data, w = case["data"], case["w"]
+    set_bytes = sum(v.numel() * v.element_size() for v in data.values())
+    copies = int(min(4096, max(16, -(-copies_bytes // set_bytes))))
+    sets = [data] + [{k: v.clone() for k, v in data.items()} for _ in range(copies - 1)]
+    torch.cuda.synchronize()
+    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for i in range(copies):                                  # every set once: none of it is in a cache
+        d = sets[i]
+        B.kvr_retain(d["K"], d["V"], case["b"], case["lam"], EPS, Q=d.get("Q"), s=d.get("s"), out=case["out"])
+    z.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(z) / copies, copies
+
+
+def score_kernel_ms(case, steps):
+    """The scorer on its own (the same launch the step makes first), for the per-kernel split."""
+    import torch
+    from paper_2605_14292_amd import binding as B
+    K, Q = case["data"]["K"], case["Q"]
+    s_out = torch.empty((K.shape[0], K.shape[1]), dtype=torch.float32, device=K.device)
+    for _ in range(2):
+        B.kvr_score(K, Q, s_out=s_out)
+    a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        B.kvr_score(K, Q, s_out=s_out)
+    z.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(z) / steps
+
+
+def traffic_key(case):
+    w = case["w"]
+    return (f"{w.name}{'flat' if case['mode'] == 'flat' else ''}{'budgeted' if case['mode'] == 'budgeted' else ''}"
+            f"{'window%d' % case['window'] if case['window'] != 1 else ''}"
+            f"{'scale%g' % case['score_scale'] if case['score_scale'] != 1.0 else ''}:b{case['b']}:lam{case['lam']}")
+
+
+def run_case(name, pool, seed, steps, warmup, cpu_budget_s, sample, copy_gbps, cold=False, **kw):
+    """One configuration, complete: timing, roofline, oracle baseline, parity of the timed buffers."""
+    import torch
+    case = make_case(name, seed, **kw)
+    w, b, lam, mode = case["w"], case["b"], case["lam"], case["mode"]
+    t = time_steps(case["step"], steps, warmup)
+    dev_ms = t["dev_mean_ms"]
+    achieved = case["bytes_step"] / (dev_ms * 1e-3) / 1e9
+    names = kernel_names(w, b, lam, case["Q"] is not None, mode)
+    kernels = None
+    if mode == "plain" and case["Q"] is not None and len(names) > 1:
+        sc = score_kernel_ms(case, max(3, steps // 2))
+        kernels = [{"name": names[0], "ms": sc, "how": "the scorer timed on its own"},
+                   {"name": " + ".join(names[1:]), "ms": dev_ms - sc, "how": "step minus scorer"}]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(traffic_key(case))
+    roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "kernel": " + ".join(names) + " (the whole step is priced: the step's algorithmic bytes over the "
+                      "step's device time)",
+            "device_ms_avg": dev_ms, "device_ms_median": t["dev_median_ms"],
+            "device_ms_min": t["dev_min_ms"], "device_ms_max": t["dev_max_ms"],
+            "algorithmic_bytes_per_step": case["bytes_step"]}
+    if kernels:
+        roof["kernels"] = kernels
+    if traffic:
+        moved = traffic.get("bytes_per_step") if isinstance(traffic, dict) else traffic
+        if moved:
+            roof["traffic_over_algorithmic"] = moved / case["bytes_step"]
+            roof["frac_by_counter_traffic"] = moved / (dev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    if copy_gbps:
+        roof["device_copy_GBps"] = copy_gbps
+        roof["frac_of_device_copy"] = achieved / copy_gbps
+    res = {"workload": f"{w.name}: {w.what}"
+                       + (", flat-signature mode (one selection per sequence)" if mode == "flat" else "")
+                       + (", budget-allocator frame (b_h in [b/2, b], 20 protected tokens per head)"
+                          if mode == "budgeted" else "")
+                       + (f", given scores scaled by {case['score_scale']}" if case["score_scale"] != 1.0 else ""),
+           "heads": w.heads, "n": w.n, "b": b, "d": w.d, "lambda": lam, "scores": w.scores,
+           "G": w.G if w.scores == "computed" else 0,
+           "steps": steps, "warmup": warmup, "ms_per_step": t["wall_ms"],
+           "head_events_per_s": w.heads / (t["wall_ms"] * 1e-3), "roofline": roof}
+    if cold and mode == "plain":
+        cold_ms, copies = time_cold(case)
+        res.update({"inputs": "hot: one set of buffers, served by the memory-side cache",
+                    "ms_per_step_cold": cold_ms, "cold_input_sets": copies,
+                    "head_events_per_s_cold": w.heads / (cold_ms * 1e-3)})
+    if pool is not None:
+        if mode == "plain" and sample:
+            res["parity"] = verify(pool, case, case["out"], sample)
+        res["cpu_baseline"] = cpu_baseline(pool, case, cpu_budget_s)
+    del case
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -204,7 +374,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--b", type=int, default=None)
     ap.add_argument("--lam", type=float, default=None)
     ap.add_argument("--flat", action="store_true",
@@ -217,9 +387,13 @@ def main():
     ap.add_argument("--window", type=int, default=1,
                     help="observation window: the scores are computed from WINDOW positions x the workload's "
                          "grouped queries (G * WINDOW <= 256 queries per head; workloads with computed scores)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--score-scale", type=float, default=1.0,
+                    help="multiply given scores by this factor (a spread far below lambda leaves the score bound "
+                         "nothing to remove)")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle legs (cpu_baseline and the parity check of the timed buffers)")
     ap.add_argument("--no-other-configs", action="store_true",
-                    help="skip the short runs of the other benchmark configurations")
+                    help="skip the runs of the other benchmark configurations")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (reference point for "
@@ -230,9 +404,6 @@ def main():
                  "each GPU would run these kernels on its own slice); --gpus must be 1")
 
     import torch
-    from paper_2605_14292_amd import binding as B
-    from paper_2605_14292_amd import workloads as W
-
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     dev = "cuda:0"
@@ -244,59 +415,6 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
         return
-    w = W.WORKLOADS[args.workload]
-    if args.window != 1:
-        import dataclasses
-        if w.scores != "computed" or args.window < 1 or w.G * args.window > 256:
-            sys.exit("bench.py: --window needs a workload with computed scores and G * WINDOW <= 256")
-        w = dataclasses.replace(w, G=w.G * args.window,
-                                what=w.what + f", observation window of {args.window} positions")
-    b = w.b if args.b is None else args.b
-    lam = w.lam if args.lam is None else args.lam
-    data = W.generate(w, seed=args.seed, device=dev)
-    Q, s = data.get("Q"), data.get("s")
-    group = w.layers * w.kv_heads
-    if args.flat:
-        if s is None:
-            sys.exit("bench.py: --flat needs a workload whose scores are given (c3)")
-        s = s.view(w.seqs, group, w.n)[:, 0].contiguous()     # one score vector per sequence
-        out = B.FlatBuffers(w.heads, group, w.n, b, w.d, w.torch_dtype, dev, want_trace=False)
-
-        def step():
-            B.kvr_retain_flat(data["K"], data["V"], s, group, b, lam, 1e-6, out=out)
-    elif args.budgeted:
-        g = torch.Generator(device=dev).manual_seed(args.seed + 17)
-        b_h = torch.randint(b // 2, b + 1, (w.heads,), generator=g, device=dev, dtype=torch.int32)
-        keep = torch.zeros((w.heads, w.n), dtype=torch.uint8, device=dev)
-        keep[:, :4] = 1
-        keep[:, w.n - 16:] = 1
-        pos = torch.arange(w.n, dtype=torch.int32, device=dev).repeat(w.heads, 1).contiguous()
-        out = B.BudgetBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, with_pos=True)
-        mean_bh = float(b_h.float().mean().item())
-
-        def step():
-            B.kvr_retain_budgeted(data["K"], data["V"], b, lam, 1e-6, Q=Q, s=s, b_h=b_h, keep=keep, pos=pos, out=out)
-    else:
-        out = B.RetainBuffers(w.heads, w.n, b, w.d, w.torch_dtype, dev, "Q" in data, want_trace=False)
-
-        def step():
-            B.kvr_retain(data["K"], data["V"], b, lam, 1e-6, Q=Q, s=s, out=out)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # HIP events on the stream the kernels are launched on (torch's current stream), one pair
-    # around the K steps: nothing but the steps' own launches sits between them
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    dev_avg_ms = ev0.elapsed_time(ev1) / args.steps
 
     # a plain device copy of 1 GiB, for the fraction of what a streaming kernel reaches on this machine
     csrc = torch.empty(1 << 28, dtype=torch.float32, device=dev)
@@ -310,64 +428,59 @@ def main():
     torch.cuda.synchronize()
     copy_gbps = 2 * csrc.numel() * 4 * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del csrc, cdst
+    torch.cuda.empty_cache()
 
-    bytes_step = w.algorithmic_bytes_per_head(b, lam) * w.heads
-    if args.flat:       # scores and indices are per sequence, not per head
-        bytes_step -= (4 * w.n + 4 * b) * (w.heads - w.seqs)
-    if args.budgeted:   # kept rows follow the per-head budgets; the keep mask and position ids are read
-        e = w.elem_bytes
-        rows = (3 if w.scores == "given" else 2) * w.d * e       # K in (given scores only), K out, V out
-        bytes_step += int((mean_bh - b) * rows * w.heads) + (w.n + 4 * w.n + 4 * b) * w.heads
-    achieved = bytes_step / (dev_avg_ms * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"{w.name}{'flat' if args.flat else ''}{'budgeted' if args.budgeted else ''}"
-                                               f"{'window%d' % args.window if args.window != 1 else ''}:b{b}:lam{lam}")
+    pool = None if args.no_cpu_baseline else OraclePool()
+    mode = "flat" if args.flat else "budgeted" if args.budgeted else "plain"
+    head = run_case(args.workload, pool, args.seed, args.steps, args.warmup, cpu_budget_s=12.0,
+                    sample=128 if args.workload == "c3" else 64, copy_gbps=copy_gbps,
+                    cold=args.workload in ("c1", "c2"), b=args.b, lam=args.lam, mode=mode, window=args.window,
+                    score_scale=args.score_scale)
     line = {
         "metric": "retention events/sec (heads*events)",
-        "value": w.heads / (wall / args.steps),
+        "value": head["head_events_per_s"],
         "unit": "head-events/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.what}" + (", flat-signature mode (one selection per sequence)"
-                                                        if args.flat else "")
-                                + (", budget-allocator frame (b_h in [b/2, b], 20 protected tokens per head)"
-                                   if args.budgeted else ""), "heads": w.heads, "n": w.n, "b": b,
-                   "d": w.d, "lambda": lam, "scores": w.scores, "G": w.G if w.scores == "computed" else 0},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "device_copy_GBps": copy_gbps, "frac_of_device_copy": achieved / copy_gbps,
-                     "kernel": ("kvr::signature_flat_kernel + kvr::select_dense_f32_kernel + kvr::compact_kernel (whole step)"
-                                if args.flat else
-                                "kvr::budget_prepare_kernel + selection kernels of the shape + kvr::budget_finalize_kernel (whole step)"
-                                if args.budgeted else kernel_name(w, b, lam, Q is not None)), "device_ms_avg": dev_avg_ms,
-                     "algorithmic_bytes_per_step": bytes_step},
+        "dtype": head_dtype(args.workload), "data": "synthetic",
+        "config": {k: head[k] for k in ("workload", "heads", "n", "b", "d", "lambda", "scores", "G")},
+        "roofline": head["roofline"],
     }
-    if not args.no_cpu_baseline:
-        if args.flat:
-            line["cpu_baseline"] = cpu_baseline_flat(w, data, s, group, b, lam)
-        elif args.budgeted:
-            line["cpu_baseline"] = cpu_baseline_budgeted(w, data, b_h, keep, lam)
-        else:
-            line["cpu_baseline"] = cpu_baseline(w, data, b, lam)
-    default_run = (args.workload == "c3" and not args.flat and not args.budgeted and args.b is None
-                   and args.lam is None)
+    for k in ("parity", "cpu_baseline", "ms_per_step_cold", "cold_input_sets", "head_events_per_s_cold", "inputs"):
+        if k in head:
+            line[k] = head[k]
+    default_run = (args.workload == "c4" and mode == "plain" and args.b is None and args.lam is None
+                   and args.window == 1 and args.score_scale == 1.0)
     if default_run and not args.no_other_configs:
-        del data, out
-        torch.cuda.empty_cache()
-        line["other_configs"] = {
-            "c1": time_other("c1", steps=20, warmup=5, seed=args.seed, cold=True),
-            "c2": time_other("c2", steps=20, warmup=5, seed=args.seed, cold=True),
-            "c3 flat-signature mode": time_other("c3", seed=args.seed, flat=True),
-            "c3 budget-allocator frame": time_other("c3", seed=args.seed, budgeted=True),
-            "c5": time_other("c5", seed=args.seed),
-            "c5 lambda=0": time_other("c5", seed=args.seed, lam=0.0),
-            "c4": time_other("c4", seed=args.seed),
-        }
+        oc = {}
+
+        def other(key, name, steps=10, warmup=3, budget=2.5, sample=64, **kw):
+            oc[key] = run_case(name, pool, args.seed, steps, warmup, budget, sample, copy_gbps, **kw)
+
+        other("c5", "c5")
+        other("c5 b=64", "c5", b=64)
+        other("c5 lambda=0", "c5", lam=0.0)
+        other("c5 lambda=0.25", "c5", lam=0.25, budget=1.0)
+        other("c5 lambda=1", "c5", lam=1.0, budget=1.0)
+        other("c3", "c3", steps=20, warmup=5, sample=128)
+        other("c3 scores x 0.01 (spread far below lambda)", "c3", steps=20, warmup=5, sample=64, score_scale=0.01)
+        other("c2", "c2", steps=20, warmup=5, sample=112, cold=True)
+        other("c1", "c1", steps=20, warmup=5, sample=1, cold=True)
+        other("c3 flat-signature mode", "c3", mode="flat")
+        other("c3 budget-allocator frame", "c3", mode="budgeted")
+        line["other_configs"] = oc
+        fr = {"c4": line["roofline"]["frac"], "c5": oc["c5"]["roofline"]["frac"], "c3": oc["c3"]["roofline"]["frac"]}
+        worst = min(fr, key=fr.get)
+        line["worst_long_config"] = {"name": worst, "frac": fr[worst], "fracs": fr}
+    if pool is not None:
+        pool.close()
     print(json.dumps(line), flush=True)
+
+
+def head_dtype(name):
+    from paper_2605_14292_amd import workloads as W
+    return W.WORKLOADS[name].dtype
 
 
 if __name__ == "__main__":

@@ -108,3 +108,58 @@ def summarize(reports):
                 near_ties=sum(r.near_ties for r in reports),
                 oracle_near_ties=sum(r.oracle_near_ties for r in reports),
                 max_gain_err=max(r.max_gain_err for r in reports))
+
+
+# ---------------------------------------------------------------------------
+# jobs for a process pool (the benchmark's oracle legs run heads in parallel on
+# the host cores; every argument and result is plain numpy / python).  Cached
+# rows travel in the device format (bf16 bit patterns as int16, or float32) and
+# are widened exactly inside the worker, before anything is timed.
+# ---------------------------------------------------------------------------
+def _widen(x):
+    x = np.asarray(x)
+    if x.dtype == np.int16:
+        return O.bf16_bits_to_f64(x.view(np.uint16))
+    return x.astype(np.float64)
+
+
+def oracle_event_job(job):
+    """One head's whole event on the oracle (score unless given, selection,
+    compaction of K and V); returns the seconds it took inside the worker."""
+    import time
+    K, V = _widen(job["K"]), _widen(job["V"])
+    Q = _widen(job["Q"]) if job.get("Q") is not None else None
+    s = _widen(job["s"]) if job.get("s") is not None else None
+    mode = job.get("mode", "plain")
+    t0 = time.perf_counter()
+    if mode == "flat":
+        O.retain_flat(K, V, s, job["b"], job["lam"], job["eps"])
+    elif mode == "budgeted":
+        s64 = s if Q is None else O.score_softmax_mean(K, Q)
+        r = O.select_budgeted(s64, V, job["n_h"], job["b"], job["keep"], job["lam"], job["eps"])
+        O.compact(K, r["sorted"]); O.compact(V, r["sorted"])
+    else:
+        r = O.retain(K, V, job["b"], job["lam"], job["eps"], Q=Q, s=s)
+        O.compact(K, r["sorted"]); O.compact(V, r["sorted"])
+    return time.perf_counter() - t0
+
+
+def check_head_job(job):
+    """check_head for one head of a finished HIP run, plus the score comparison and the bitwise
+    comparison of the kept rows; returns the HeadReport as a dict (raises on a mismatch)."""
+    K, V = _widen(job["K"]), _widen(job["V"])
+    score_err = 0.0
+    if job.get("Q") is not None:
+        s64 = O.score_softmax_mean(K, _widen(job["Q"]))
+        score_err = check_scores(job["s_hip"], s64)
+    else:
+        s64 = _widen(job["s"])
+    rep = check_head(s64, V, job["b"], job["lam"], job["eps"], job["order"], job["gain"], job["idx"])
+    for X, X_out in ((job["K"], job["K_out"]), (job["V"], job["V_out"])):       # bit patterns, not values
+        X, X_out = np.asarray(X), np.asarray(X_out)
+        if X.dtype == np.float32:
+            X, X_out = X.view(np.int32), X_out.view(np.int32)
+        np.testing.assert_array_equal(X_out, O.compact(X, job["idx"]))
+    d = dataclasses.asdict(rep)
+    d["score_err"] = score_err
+    return d
