@@ -26,17 +26,22 @@
  *     the default stream) and return without synchronising.
  *   - Inputs are read-only; outputs must not alias inputs or each other,
  *     except where a call says otherwise (kvr_compact_inplace, kvr_score_prior).
- *   - The library allocates no device memory and keeps no state between
- *     calls.  `workspace` is reserved for future kernels: every entry point
+ *   - The library allocates no device memory.  `workspace` is reserved for
+ *     future kernels: every entry point
  *     accepts NULL / 0 as long as kvr_workspace_bytes() reports 0 for the
  *     same arguments.
  *   - Return value: KVR_OK or a negative kvr_status.  Argument errors are
  *     detected on the host before anything is launched.  Non-finite scores or
  *     rows give unspecified picks (but never out-of-range indices).
- *   - Device pointers must be 16-byte aligned; d must be 128 (the head
- *     dimension of every benchmark configuration); strides are in elements,
+ *   - Device pointers must be 16-byte aligned; d must be 128: every kernel
+ *     maps the 256 bytes of a bf16 row (512 of an fp32 row) onto fixed lane
+ *     groups and MFMA k-steps, and 128 is the head dimension of every model
+ *     the paper evaluates and of every benchmark configuration; another d is
+ *     KVR_ERR_UNSUPPORTED, never a wrong result.  Strides are in elements,
  *     stride_tok >= d and a multiple of 8, stride_head >= n*stride_tok and a
  *     multiple of 8.
+ *   - The library keeps no state between calls apart from the device's
+ *     compute-unit count, read once.
  */
 #ifndef KVR_H_
 #define KVR_H_
@@ -106,8 +111,10 @@ int kvr_select_greedy(const void* V, const float* s, const kvr_layout* lay,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Cache update: K_out[h,t,:] = K[h, idx[h,t], :] and the same for V, copied
- * bit for bit.  Either of K / V (with its output) may be NULL to skip it.
+ * Cache update (Sec. 1: the cache keeps a budget-bounded subset of its tokens;
+ * Algorithm 1 returns sort(S), the rows kept, in token order):
+ * K_out[h,t,:] = K[h, idx[h,t], :] and the same for V, copied bit for bit.
+ * Either of K / V (with its output) may be NULL to skip it.
  *   idx           device, int32 [heads, b], every entry in [0, n)
  *   K_out, V_out  device, dense [heads, b, d], dtype of `lay`
  * An index outside [0, n) is clamped into range rather than read out of
@@ -117,7 +124,9 @@ int kvr_compact(const void* K, const void* V, const kvr_layout* lay,
                 const int32_t* idx, int b, void* K_out, void* V_out, void* stream);
 
 /*
- * The whole event in one call: score (when Q is given) -> select -> compact.
+ * The whole per-compression-event step of Sec. 4.1 in one call: base scores
+ * (when Q is given; the paper's scorer is external, the stand-in is kvr_score's)
+ * -> Algorithm 1 (Eq. 1-3) -> the cache update with sort(S).
  * Exactly one of (Q, G >= 1) and s_in must be provided:
  *   Q != NULL: scores are computed as in kvr_score; s_out (device, dense
  *              float32 [heads, n], required) receives them.

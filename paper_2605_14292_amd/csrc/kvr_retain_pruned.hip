@@ -137,7 +137,13 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         if (valid && key[q] < cut) out_best = fmaxf(out_best, sv[q]);
       }
       excl = wave_max_uniform(out_best);
-      if (ns >= bq && ns <= kPrN) break;
+      // The cut can only be verified if the last pick's gain stays above the best score left out.
+      // That gain is at most s_(b) and in practice a good part of lambda below it (the later picks
+      // of a head carry a penalty), so when the score left out is within a quarter of lambda of
+      // s_(b) the chain would be run in vain and then run again by the full-size kernel: such a
+      // head goes there at once.  (A guess about speed only: either way the picks are exact.)
+      const bool hopeless = !(excl < sb - 0.25f * a.lambda);
+      if (ns >= bq && ns <= kPrN && !hopeless) break;
       if (wave == 1 && lane == 0) a.idx_sorted[static_cast<long long>(hh) * b] = -1;
     }
     if (hh < a.heads) {
