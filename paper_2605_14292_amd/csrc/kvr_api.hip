@@ -73,6 +73,9 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
   if (kvr::topb_supported(l, b, lambda))
     return kvr::launch_select_topb(nullptr, nullptr, s, l, b, idx_sorted, pick_order, pick_gain, nullptr,
                                    nullptr, st);
+  if (kvr::lazy_supported(l, b, lambda))
+    return kvr::launch_select_lazy(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
+                                   nullptr, nullptr, st);
   if (kvr::pool_supported(l, b))
     return kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                    nullptr, nullptr, st, nullptr, true);
@@ -197,6 +200,11 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
                                                  V_out, st);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
+  if (kvr::lazy_supported(l, b, lambda)) {
+    const hipError_t e = kvr::launch_select_lazy(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
+                                                 pick_gain, K_out, V_out, st);
+    return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+  }
   if (kvr::pool_supported(l, b)) {
     const hipError_t e = kvr::launch_select_pool(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
                                                  pick_gain, K_out, V_out, st, nullptr, Q == nullptr);
@@ -246,6 +254,9 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
     hipError_t e;
     if (long_topb) {
       e = kvr::launch_select_topb(K, V, s_work, l, b_max, idx_sorted, pick_order, pick_gain, K_out, V_out, st, b_h);
+    } else if (long_heads && kvr::lazy_supported(l, b_max, lambda)) {
+      e = kvr::launch_select_lazy(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
+                                  V_out, st, b_h);
     } else if (long_heads) {
       e = kvr::launch_select_pool(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
                                   V_out, st, b_h, Q == nullptr);

@@ -125,4 +125,15 @@ hipError_t launch_select_pool(const void* K, const void* V, const float* s, cons
 // and skips their rows.  Worth it for scores the caller supplies; mean-of-softmax scores over hundreds
 // of tokens lie far below any lambda in use, nothing can be dropped, and the variant only costs.
 
+
+// The same selection with lazily refreshed penalties for bf16 heads with 256 < n <= 4096, b <= 128 and
+// lambda > 0: after the first epoch only the tokens whose gain bounds can matter soon are brought up to
+// date (against the rows of all picks, kept in LDS), so a head's rows are read about 2.7 times instead of
+// once per epoch.  Always applies the score bound first.
+bool lazy_supported(const Layout& lay, int b, float lambda);
+hipError_t launch_select_lazy(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                              float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st,
+                              const int32_t* b_h = nullptr);
+
 }  // namespace kvr

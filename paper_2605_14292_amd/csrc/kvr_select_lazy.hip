@@ -1,0 +1,777 @@
+// Greedy selection (paper Sec. 4.1, Algorithm 1) for heads with 256 < n <= 4096
+// bf16 tokens and b <= 128, followed by the compaction of the kept rows.
+//
+// Exact greedy with lazily refreshed penalties.  Algorithm 1 reads one cosine row per
+// pick, i.e. all of V once per pick.  The running maximum m_i of Eq. 2 only grows, so a
+// gain computed from an out-of-date m_i is an upper bound of the true one, and a token
+// whose upper bound is low needs no update until the bound matters.  Every token is either
+// "fresh" (its m covers all picks made so far) or "stale" (its m covers an earlier prefix of
+// them).  An epoch:
+//   1. the P = 128 best fresh unselected tokens form the pool (each wave contributes its
+//      best P/W, found by a bitwise threshold search on the gains); the best gain of any
+//      token outside the pool, fresh or stale, is the bound of the epoch;
+//   2. the pool's rows are gathered into LDS and their P x P cosine triangle is computed
+//      on bf16 MFMA (32x32x16, fp32 accumulate), then written over the rows;
+//   3. one wave runs Algorithm 1 inside the pool (DPP argmax, one LDS row read per pick)
+//      for as long as the pool's best (gain, lower index) beats the bound -- every outside
+//      gain is at most its bound, so such a pick is the exact argmax of Eq. 2 over all
+//      unselected tokens;
+//   4. the rows of the epoch's picks join the rows of all earlier picks in LDS, and every
+//      wave brings the quarter or so of its outside tokens with the highest bounds up to
+//      date against ALL picks so far (16-row MFMA operands, 16x16x32): these are fresh for
+//      the next epoch, the others keep their bound and go stale.  The first epoch's pass
+//      covers every token (it also takes the inverse norms of Eq. 1).
+// How many tokens step 4 refreshes is a matter of speed only: a stale token can only end an
+// epoch early (it then carries the bound and is among the refreshed ones), never change a
+// pick.  On the benchmark inputs an epoch serves 5-50 picks and a head reads its rows about
+// 2.7 times (once per epoch with a full pass).  Nothing is approximated.
+//
+// Layout: one workgroup per head, W wave64s, token j = 64*S*w + 64*k + lane in
+// wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
+// lane's registers for the whole event.
+#include "kvr_dense_common.hpp"
+#include "kvr_kernels.hpp"
+#include <type_traits>
+
+namespace kvr {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+#ifndef KVR_POOL_WIDE
+#define KVR_POOL_WIDE 128
+#endif
+constexpr int kLzPoolWide = KVR_POOL_WIDE;   // pool of the configurations with one workgroup per CU
+constexpr int kLzMaxB = 128;        // largest budget: the rows of all picks stay in LDS
+constexpr int kLzMaxPend = 64;      // picks per epoch (the chain logs pick u in lane u)
+constexpr int kLzPitch = 272;       // bytes per staged row (256 + 16)
+constexpr int kLzSelBits = 16;      // leading bits of a gain's ordered key used to choose the pool
+constexpr int kLzChunk = 16;        // rows staged per step and wave in the refresh pass
+
+struct LazyArgs {
+  const char* K; const char* V; const float* s_in;
+  int32_t* idx_sorted; int32_t* pick_order; float* pick_gain;
+  char* K_out; char* V_out;
+  long long stride_head, stride_tok;   // elements
+  int n, b;
+  float lambda, eps;
+  const int32_t* b_h;                  // per-head budgets <= b (output rows stay b apart), or null
+};
+
+// P: pool size, a multiple of 64.  192 was measured where a head has the CU to itself (n > 1024): an epoch less per head,
+// paid back by the larger triangle and the three-slot race, so every configuration runs 128.
+template <int W, int S, int P> struct LazyCfg {
+  static constexpr int TPW = 64 * S;
+  // per wave, during the pass: row stage | 256-float exchange | 64 squared norms | TPW inverse norms (first pass)
+  static constexpr int kWaveArea = kLzChunk * kLzPitch + 1024 + 256 + TPW * 4;
+  static constexpr int kTriBytes = P * (P + 1) / 2 * 4;
+  static constexpr int kRowBytes = P * kLzPitch;
+  static constexpr int kMax2 = kTriBytes > kRowBytes ? kTriBytes : kRowBytes;
+  static constexpr int kUnion = ((W * kWaveArea > kMax2 ? W * kWaveArea : kMax2) + 15) & ~15;
+  // floats: slots 64 | shared 16 | wcount 16 | pool_tok,r,s,m,picked 5*128 | pend 64 |
+  //         order,gain,idxs,pick_r 4*128 ; then per wave TPW list entries / results ;
+  //         then the rows of the picks ; then the union area (pool rows -> triangle -> pass areas ->
+  //         pick flags of the read-out)
+  static constexpr int kFixedFloats = 96 + 5 * P + 64 + 4 * kLzMaxB;
+  static constexpr int kListFloats = W * (TPW + 64);   // one group of padding past a full list
+  static constexpr int kPickBytes = (kLzMaxB + 1) * kLzPitch;    // one spare row past the last
+  static_assert(64 * S * W * 4 <= kUnion, "the pick flags of the read-out fit the union area");
+  static constexpr int smem_bytes() { return (kFixedFloats + kListFloats) * 4 + kPickBytes + kUnion; }
+};
+
+// BUD: per-head budgets are read from a.b_h.
+template <int W, int S, int P, bool BUD>
+__global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(LazyArgs a) {
+  using Cfg = LazyCfg<W, S, P>;
+  constexpr int TPW = 64 * S;
+  constexpr int NT = 64 * W;
+  constexpr int Q = P / W;                   // pool members contributed per wave
+  constexpr int CH = kLzChunk;
+  constexpr int LPC = CH / 4;
+  constexpr int KR = W <= 4 ? TPW / 2 : TPW / 4;   // tokens a wave aims to refresh per pass (measured: c5 / c4)
+  constexpr int NB = P / 32;                       // 32-token blocks of the pool
+  constexpr int NTRI = NB * (NB + 1) / 2;          // lower-triangular 32x32 tiles of its cosine matrix
+  constexpr int NTILE = (NTRI + W - 1) / W;        // ... per wave
+  constexpr int NQ = P / 64;                       // pool slots per lane in the race
+  static_assert(S <= 8 && Q <= 64, "token state lives in registers; a wave's pool share fits a ballot");
+  extern __shared__ __align__(16) float smem[];
+  float* slot_gain = smem;                                       // [2][16]
+  int32_t* slot_idx = reinterpret_cast<int32_t*>(smem + 32);     // [2][16]
+  int32_t* shared_i = reinterpret_cast<int32_t*>(smem + 64);     // [16] np, t, stop reason
+  int32_t* wcount = reinterpret_cast<int32_t*>(smem + 80);       // [16]
+  int32_t* pool_tok = reinterpret_cast<int32_t*>(smem + 96);     // [P] token of the member, -1 = none
+  float* pool_r = smem + 96 + P;
+  float* pool_s = smem + 96 + 2 * P;
+  float* pool_m = smem + 96 + 3 * P;
+  int32_t* pool_picked = reinterpret_cast<int32_t*>(smem + 96 + 4 * P);
+  int32_t* pend_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * P);        // [64] pool slots picked this epoch
+  int32_t* order_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * P + 64);
+  float* gain_l = smem + 96 + 5 * P + 64 + kLzMaxB;
+  int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * P + 64 + 2 * kLzMaxB);
+  float* pick_r = smem + 96 + 5 * P + 64 + 3 * kLzMaxB;                   // inverse norms of the picks, 0 past the last
+  float* lr_all = smem + Cfg::kFixedFloats;                                     // [W][TPW] refresh lists / results
+  char* pk = reinterpret_cast<char*>(smem + Cfg::kFixedFloats + Cfg::kListFloats);   // [128][272 B] rows of the picks
+  char* uni = pk + Cfg::kPickBytes;
+  char* prow = uni;                                              // [P][272 B] pool rows (gather, Gram) ...
+  float* tri = reinterpret_cast<float*>(uni);                    // ... then the packed P x P cosine triangle (race) ...
+  // ... then the per-wave areas of the pass ...
+  int32_t* flag = reinterpret_cast<int32_t*>(uni);               // ... and at the end [n padded] pick flags for the ascending read-out
+
+  const int h = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = a.n;
+  // the head's own budget: its picks are the first b picks of a run for a.b (the rows of the
+  // outputs per head), so the epochs stop there
+  const int b = BUD ? min(max(a.b_h[blockIdx.x], 0), a.b) : a.b;      // a scalar load: the index is uniform
+  const long long head_off = h * a.stride_head * 2;             // bytes
+  const char* Vh = a.V + head_off;
+  const uint32_t pitch_b = static_cast<uint32_t>(a.stride_tok) * 2u;   // bytes between tokens: a head spans less than 4 GiB (checked by the host)
+  const int base = w * TPW;
+  char* stage = uni + w * Cfg::kWaveArea;
+  float* scratch = reinterpret_cast<float*>(stage + CH * kLzPitch);
+  float* norm_x = scratch + 256;                                 // [64] squared norms of the wave's current 64 rows
+  float* lr2 = norm_x + 64;                                      // [TPW] inverse norms found in the first pass
+  float* lrw = lr_all + w * (TPW + 64);                                 // [TPW] list of tokens to refresh, then their raw maxima
+  int32_t* lrw_i = reinterpret_cast<int32_t*>(lrw);
+  const unsigned long long below = (1ull << lane) - 1ull;
+
+  float s[S], m[S], r[S];
+  int pslot[S];                  // >= 0: pool slot of this token in the current epoch; <= -2: position -2 - p in the wave's refresh list; -1: neither
+  uint32_t fresh = 0xffffffffu;  // bit k: m[k] covers every pick made so far
+  auto tok_of = [&](int k) -> int { return base + 64 * k + lane; };
+#pragma unroll
+  for (int k = 0; k < S; ++k) {
+    s[k] = tok_of(k) < n ? a.s_in[static_cast<long long>(h) * n + tok_of(k)] : -INFINITY;
+    m[k] = 0.f;
+    r[k] = 0.f;
+    pslot[k] = -1;
+  }
+  // rows of the picks: zero until written (a partly filled 16-row operand multiplies zeros)
+  for (int u = tid; u < kLzMaxB * kLzPitch / 16; u += NT) reinterpret_cast<uint4*>(pk)[u] = make_uint4(0u, 0u, 0u, 0u);
+  if (tid < kLzMaxB) pick_r[tid] = 0.f;
+  const float nlam = -a.lambda;
+  int par = 0;
+  int t = 0;
+  int kbits = kLzSelBits;        // leading key bits the pool choice looks at (uniform)
+  bool starved = false;
+  float delta = -1.f;            // refresh threshold: this far below the wave's best outside gain (< 0: not yet known)
+
+  // workgroup argmax over av (per slot); ibest carries bit 30 when the winner's slot has a stale m
+  auto wg_argmax = [&](const float (&av)[S], float& gbest, int& ibest, float& amax_w) {
+    float best = av[0];
+#pragma unroll
+    for (int k = 1; k < S; ++k) best = hw_max(best, av[k]);
+    amax_w = wave_max_uniform(best);
+    int i_w = -1;
+#pragma unroll
+    for (int k = S - 1; k >= 0; --k) {
+      const unsigned long long eq = __ballot(av[k] == amax_w);
+      if (eq) {
+        const int l0 = __ffsll(static_cast<long long>(eq)) - 1;
+        const int fr = (__builtin_amdgcn_readlane(static_cast<int>(fresh), l0) >> k) & 1;
+        i_w = (base + 64 * k + l0) | (fr ? 0 : (1 << 30));
+      }
+    }
+    if (lane == 0) { slot_gain[par * 16 + w] = amax_w; slot_idx[par * 16 + w] = i_w; }
+    lds_barrier();
+    const float g = lane < W ? slot_gain[par * 16 + lane] : -INFINITY;
+    const int ii = lane < W ? slot_idx[par * 16 + lane] : -1;
+    par ^= 1;
+    gbest = wave_max_uniform(g);
+    const unsigned long long eqw = __ballot(lane < W && g == gbest);
+    ibest = eqw ? __builtin_amdgcn_readlane(ii, __ffsll(static_cast<long long>(eqw)) - 1) : -1;
+  };
+
+  if (b == 1) {
+    float gmax, dummy; int i;
+    wg_argmax(s, gmax, i, dummy);
+    if (!(gmax > -INFINITY)) starved = true;
+    else { if (tid == 0) { order_l[0] = i & 0x3fffffff; gain_l[0] = gmax; } t = 1; }
+  } else {
+    bool have_r = false;
+    // Exact candidate reduction (as in the kernels for short heads): while fewer than b tokens are
+    // selected one of the b best-scored is free and gains at least s_(b) - lambda, and a token gains
+    // at most its score, so a token with s_j < s_(b) - lambda never wins Eq. 3.  Such tokens get the
+    // score -inf: they are never a pool member, a pick or in a refresh list, and their rows are never
+    // read.  Nothing can go when the finite scores spread by less than lambda (then s_(b) - lambda is
+    // below all of them); one workgroup-wide min/max settles that before the search for s_(b).
+    {
+      float hi = -INFINITY, lo = INFINITY;
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        if (s[k] > -INFINITY && s[k] < INFINITY) { hi = hw_max(hi, s[k]); lo = fminf(lo, s[k]); }
+      }
+      hi = wave_max_uniform(hi);
+      lo = -wave_max_uniform(-lo);
+      if (lane == 0) { slot_gain[par * 16 + w] = hi; slot_gain[32 + w] = lo; }   // (smem 32.. is slot_idx: free until the first argmax)
+      lds_barrier();
+      float ghi = -INFINITY, glo = INFINITY;
+#pragma unroll
+      for (int u = 0; u < W; ++u) { ghi = hw_max(ghi, slot_gain[par * 16 + u]); glo = fminf(glo, slot_gain[32 + u]); }
+      par ^= 1;
+      const bool wide = __builtin_amdgcn_readfirstlane(ghi - glo > a.lambda ? 1 : 0) != 0;   // false also when no score is finite
+      lds_barrier();                                 // the min/max slots are rewritten below
+      if (wide) {
+        uint32_t key[S];
+#pragma unroll
+        for (int k = 0; k < S; ++k) key[k] = tok_of(k) < n ? ordered_key(s[k] + 0.0f) : 0u;
+        uint32_t T = 0;                              // s_(b) from the leading 16 bits: at most s_(b), the bound only loosens
+        for (int bit = 31; bit >= 16; --bit) {
+          const uint32_t cand = T | (1u << bit);
+          int c = 0;
+#pragma unroll
+          for (int k = 0; k < S; ++k) c += __popcll(__ballot(key[k] >= cand));
+          if (lane == 0) slot_idx[par * 16 + w] = c;
+          lds_barrier();
+          int tot = 0;
+#pragma unroll
+          for (int u = 0; u < W; ++u) tot += slot_idx[par * 16 + u];
+          par ^= 1;
+          if (tot >= b) T = cand;
+        }
+        const float sb = key_to_float(T);
+        const float thr = sb - a.lambda * 1.00001f - 1e-5f * fabsf(sb);   // fp32 cosines may exceed 1 by a few ulp
+#pragma unroll
+        for (int k = 0; k < S; ++k)
+          if (s[k] < thr) s[k] = -INFINITY;          // (a NaN threshold or score leaves the token in)
+      }
+    }
+    auto sum_sq = [](const uint4& x) -> float {
+      const float e[8] = {bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y),
+                          bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)};
+      float ss = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) ss = fmaf(e[q], e[q], ss);
+      // the 16 lanes of a row hold its 16-byte chunks and form one DPP row: its last lane ends up with the total
+      KVR_DPP_ADD(ss, 0x111, 0xf) KVR_DPP_ADD(ss, 0x112, 0xf) KVR_DPP_ADD(ss, 0x114, 0xf) KVR_DPP_ADD(ss, 0x118, 0xf)
+      return ss;
+    };
+
+    int idle = 0;                                    // epochs in a row without a pick
+#ifdef KVR_STATS
+    long long st[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const long long st_begin = __builtin_readcyclecounter();
+#endif
+    while (t < b) {
+#ifdef KVR_STATS
+      const long long c0 = __builtin_readcyclecounter();
+#endif
+      // ================= 1. pool = the best Q fresh unselected tokens of every wave =================
+      float g[S];
+      uint32_t key[S];
+      // Keys are cut to their leading kbits bits: the pool only has to be a good guess (the
+      // race against the outside bound keeps the picks exact), and the search is shorter.
+      // When the cut keys cannot tell a wave's best tokens apart the best one may be left outside
+      // and the epoch ends without a pick; it is then repeated on the full keys, where the best
+      // fresh token of every wave is a member (equal values join in token order).
+      uint32_t ekey[S];                              // key + 1 of a fresh token, 0 of a stale one (never a member)
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        g[k] = fmaf(nlam, m[k], s[k]);
+        key[k] = ordered_key(g[k]) >> (32 - kbits);
+        const uint32_t k1 = key[k] + 1u;             // (wraps to 0 for an all-ones key, which only a NaN with full keys has)
+        ekey[k] = ((fresh >> k) & 1u) ? k1 : 0u;
+      }
+      uint32_t tau = 0;                              // largest value with at least Q fresh keys >= it
+      for (int bit = kbits; bit >= 0; --bit) {
+        if (bit == 32) continue;                     // keys + 1 of full-width keys are searched over 32 bits
+        const uint32_t cand = tau | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < S; ++k) c += __popcll(__ballot(ekey[k] >= cand));
+        if (c >= Q) tau = cand;
+      }
+      if (tau == 0) tau = 1;                         // fewer than Q fresh tokens: all of them join
+      int taken = 0;                                 // members with key > tau come first, ties in token order
+#pragma unroll
+      for (int k = 0; k < S; ++k) taken += __popcll(__ballot(ekey[k] > tau));
+      int need_eq = Q - taken;                       // how many of the key == tau tokens join
+      int rank_base = 0;
+      float go[S];                                   // gains (bounds) of the tokens left outside
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        const bool above = ekey[k] > tau, equal = ekey[k] == tau;
+        const unsigned long long eqm = __ballot(equal);
+        const int eq_before = __popcll(eqm & below);
+        const bool in = above || (equal && eq_before < need_eq);
+        const unsigned long long inm = __ballot(in);
+        const int slot = w * Q + rank_base + __popcll(inm & below);
+        pslot[k] = in ? slot : -1;
+        if (in) {
+          pool_tok[slot] = tok_of(k) < n ? tok_of(k) : -1;
+          pool_r[slot] = r[k];
+          pool_s[slot] = s[k];
+          pool_m[slot] = m[k];
+          pool_picked[slot] = 0;
+        }
+        go[k] = in ? -INFINITY : g[k];
+        rank_base += __popcll(inm);
+        const int eq_in = __popcll(eqm);
+        need_eq -= eq_in < need_eq ? eq_in : need_eq;
+      }
+      if (lane >= rank_base && lane < Q) {           // fewer fresh tokens than the wave's share: empty slots
+        const int slot = w * Q + lane;
+        pool_tok[slot] = -1; pool_r[slot] = 0.f; pool_s[slot] = -INFINITY; pool_m[slot] = 0.f; pool_picked[slot] = 0;
+      }
+      float gout, gmax_w; int jout_f;
+      wg_argmax(go, gout, jout_f, gmax_w);           // barrier inside: the pool tables are complete
+      const int jout = jout_f < 0 ? -1 : (jout_f & 0x3fffffff);
+      const bool jout_stale = jout_f >= 0 && (jout_f & (1 << 30));
+
+      // the pool's rows are requested now; the refresh list is built while they are on their way
+      // (all row loads of a thread are issued before the first one is stored: with the loads
+      // and stores interleaved, every load waits for the one before it)
+      constexpr int kGat = P * 16 / NT;          // rows per thread
+      uint4 x[kGat];
+#pragma unroll
+      for (int k = 0; k < kGat; ++k) {
+        const int tk = pool_tok[k * (NT / 16) + (tid >> 4)];
+        const int tkc = tk < 0 ? 0 : tk;                // an empty slot reads row 0 and stores zeros
+        x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(tkc) * pitch_b + (tid & 15) * 16u));
+      }
+#ifdef KVR_STATS
+      const long long c1 = __builtin_readcyclecounter();
+#endif
+      // ---- the wave's refresh list for this epoch's pass: outside tokens whose bound lies within
+      // delta of the wave's best one (all of them in the first pass).  delta is steered so that about
+      // KR tokens qualify: a few bisection steps around the previous epoch's value.
+      int cnt_r = 0;
+      {
+        auto count_ge = [&](float thr) -> int {
+          int c = 0;
+#pragma unroll
+          for (int k = 0; k < S; ++k) c += __popcll(__ballot(go[k] >= thr && go[k] > -INFINITY));
+          return c;
+        };
+        float thr_r = -INFINITY;                     // first pass: every outside token that can still be picked
+        if (have_r && gmax_w > -INFINITY) {
+          float lo_d, hi_d;
+          int steps;
+          if (delta < 0.f) {
+            float gmin = INFINITY;
+#pragma unroll
+            for (int k = 0; k < S; ++k) if (go[k] > -INFINITY) gmin = fminf(gmin, go[k]);
+            gmin = -wave_max_uniform(-gmin);
+            lo_d = 0.f; hi_d = gmax_w - gmin; steps = 8;
+          } else {
+            lo_d = 0.5f * delta; hi_d = 2.0f * delta; steps = 3;
+          }
+          int c_lo = 1;                              // tokens within lo_d of the best (not counted for the first guess)
+          for (int it = 0; it < steps; ++it) {       // count(delta) grows with delta
+            const float mid = 0.5f * (lo_d + hi_d);
+            const int c = count_ge(gmax_w - mid);
+            if (c > KR) hi_d = mid; else { lo_d = mid; c_lo = c; }
+          }
+          // the lower end of the bracket: at most KR tokens (whole 64-row groups are what the pass costs), always
+          // including the wave's best outside token, the one that can carry the epoch's bound
+          delta = lo_d;
+          thr_r = gmax_w - delta;
+          if (4 * c_lo < KR) delta = -1.f;           // the guess has collapsed or run away: a full search next time
+        }
+        int off = 0;
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+          const bool mem = go[k] >= thr_r && go[k] > -INFINITY;     // (go is -inf for pool members and dead tokens)
+          const unsigned long long mm = __ballot(mem);
+          if (mem) {
+            const int pos = off + __popcll(mm & below);
+            lrw_i[pos] = tok_of(k);
+            pslot[k] = -2 - pos;
+          }
+          off += __popcll(mm);
+        }
+        cnt_r = off;
+        // pad to a multiple of 64 with a valid row (its results are never read)
+        // (at least one group: the first group's rows are requested whether or not the list has entries)
+        const int padded = (cnt_r == 0 ? 64 : (cnt_r + 63) & ~63) + 64;     // ... and one group more: the pass requests a group ahead
+        for (int u = cnt_r + lane; u < padded; u += 64) lrw_i[u] = min(base, n - 1);
+      }
+      // The rows of the list's first 64 entries are requested here and travel while the pool's triangle is
+      // computed and raced; further groups follow inside the pass, one group ahead.
+      uint4 pre[4][LPC];
+      auto fetch = [&](int gi, int sub) {
+#pragma unroll
+        for (int q = 0; q < LPC; ++q) {
+          const int row = lrw_i[gi * 64 + sub * CH + (lane >> 4) + 4 * q];
+          pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(row) * pitch_b + (lane & 15) * 16u));
+        }
+      };
+      wave_lds_sync();                               // the list was written by other lanes of this wave
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub) fetch(0, sub);   // (no branch around them: the wait counts of what follows stay exact)
+
+#ifdef KVR_STATS
+      const long long c2 = __builtin_readcyclecounter();
+#endif
+      // ================= 2. pool rows -> LDS, cosine triangle on MFMA (written over the rows) =================
+      {
+#pragma unroll
+        for (int k = 0; k < kGat; ++k) {
+          const int slot = k * (NT / 16) + (tid >> 4);
+          if (pool_tok[slot] < 0) x[k] = make_uint4(0u, 0u, 0u, 0u);   // (only here: a select between the loads would make each wait for the one before)
+          *reinterpret_cast<uint4*>(prow + slot * kLzPitch + (tid & 15) * 16) = x[k];
+        }
+        if (!have_r) {
+#pragma unroll
+          for (int k = 0; k < kGat; ++k) {
+            const int slot = k * (NT / 16) + (tid >> 4);
+            const float ss = sum_sq(x[k]);
+            if ((tid & 15) == 15) pool_r[slot] = pool_tok[slot] < 0 ? 0.f : 1.0f / (sqrtf(ss) + a.eps);
+          }
+        }
+      }
+      lds_barrier();
+      {
+        const int hf = lane >> 5;
+        f32x16 acc[NTILE];
+#pragma unroll
+        for (int q = 0; q < NTILE; ++q) {
+          const int tile = w + q * W;                  // lower-triangular 32x32 tiles of the P x P matrix
+          acc[q] = f32x16{0};
+          if (tile < NTRI) {
+            int I = 0;
+            while ((I + 1) * (I + 2) / 2 <= tile) ++I;
+            const int J = tile - I * (I + 1) / 2;
+            const char* pa = prow + (I * 32 + (lane & 31)) * kLzPitch + hf * 16;
+            const char* pb = prow + (J * 32 + (lane & 31)) * kLzPitch + hf * 16;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+              acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pa + ks * 32),
+                                                               *reinterpret_cast<const bf16x8*>(pb + ks * 32), acc[q], 0, 0, 0);
+          }
+        }
+        lds_barrier();                                 // every wave has read its rows: the triangle takes their place
+#pragma unroll
+        for (int q = 0; q < NTILE; ++q) {
+          const int tile = w + q * W;
+          if (tile < NTRI) {
+            int I = 0;
+            while ((I + 1) * (I + 2) / 2 <= tile) ++I;
+            const int J = tile - I * (I + 1) / 2;
+            write_cos_tile(tri, pool_r, acc[q], I, J, lane);   // the diagonal holds +inf: the row of a pick retires it
+          }
+        }
+      }
+      lds_barrier();
+#ifdef KVR_STATS
+      const long long c3 = __builtin_readcyclecounter();
+#endif
+      // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
+      if (w == 0) {
+        // Pool slots NQ*lane .. NQ*lane+NQ-1 live in lane `lane` (slots are in token order, so the
+        // lowest slot is the lowest token).  A pick is parked in lane np of two registers; the
+        // pick lists and the pending-row tables are written once, after the loop.
+        typedef __attribute__((address_space(3))) const float* lds_fp;
+        const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
+            (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
+        float sq[NQ], mq[NQ];
+        int ja[NQ], tja[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          const int p = NQ * lane + q;
+          sq[q] = pool_s[p];
+          mq[q] = pool_m[p];
+          ja[q] = p * 4 + tri0;                        // column offset of the slot
+          tja[q] = p * (p + 1) * 2 + tri0;             // start of its row
+        }
+        const int jb = __builtin_amdgcn_readfirstlane(jout < 0 ? 0x7fffffff : jout);
+        const float gout_u = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(gout)));
+        const bool no_out = __builtin_amdgcn_readfirstlane(jout) < 0;
+        const int room = __builtin_amdgcn_readfirstlane(min(b - t, kLzMaxPend));
+        int np = 0, stop = 0;                        // stop: 1 = bound wins, 2 = nothing finite left
+        int rec_i = 0, rec_g = 0;
+        while (np < room) {
+          float av[NQ];
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) av[q] = fmaf(nlam, mq[q], sq[q]);
+          float best = av[0];
+#pragma unroll
+          for (int q = 1; q < NQ; ++q) best = hw_max(best, av[q]);
+          const float amax = wave_max_uniform(best);
+          unsigned long long e[NQ];
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) e[q] = __ballot(av[q] == amax);
+          const int i = first_of_slots<NQ>(e);       // negative when nothing compares equal (NaN)
+          if (!(amax > gout_u)) {                    // rare: the bound wins, a tie with it, or nothing finite
+            if (!(amax > -INFINITY)) { stop = no_out ? 2 : 1; break; }
+            const int ti = __builtin_amdgcn_readfirstlane(pool_tok[i < 0 ? 0 : i]);
+            if (!(amax == gout_u && ti < jb)) { stop = 1; break; }
+          }
+          write_lane2(rec_i, rec_g, i, __float_as_int(amax), np);
+          np = __builtin_amdgcn_readfirstlane(np + 1);   // keeps the loop control on the scalar unit
+          // element (i,j) of the triangle sits at max(T(i)+j, T(j)+i); the diagonal (+inf) retires i.
+          // For any i in [-NQ, 64*NQ) both addresses stay inside the triangle.
+          const int ti4 = i * (i + 1) * 2, i4 = i * 4;
+          float c[NQ];
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) {
+            const int x0 = ti4 + ja[q], x1 = tja[q] + i4;
+            c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(x0 > x1 ? x0 : x1)));
+          }
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) mq[q] = hw_max(mq[q], c[q]);
+        }
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) pool_m[NQ * lane + q] = mq[q];   // the pool's m is authoritative
+        if (lane < np) {
+          order_l[t + lane] = pool_tok[rec_i]; gain_l[t + lane] = __int_as_float(rec_g);
+          pend_l[lane] = rec_i; pick_r[t + lane] = pool_r[rec_i]; pool_picked[rec_i] = 1;
+        }
+        t += np;
+        if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
+      }
+      lds_barrier();
+#ifdef KVR_STATS
+      const long long c4 = __builtin_readcyclecounter();
+      st[0] += c1 - c0; st[1] += c2 - c1; st[2] += c3 - c2; st[3] += c4 - c3; st[6] += 1;
+#endif
+      const int np = shared_i[0];
+      t = shared_i[1];
+      const int stop = shared_i[2];
+      // pool members: m from the race (it covers every pick so far), picked members leave
+#pragma unroll
+      for (int k = 0; k < S; ++k) {
+        const int ps = pslot[k];
+        if (ps >= 0) {
+          m[k] = pool_m[ps];
+          if (!have_r) r[k] = pool_r[ps];
+          if (pool_picked[ps]) s[k] = -INFINITY;
+        }
+      }
+      if (t >= b) break;
+      if (stop == 2 || (np == 0 && !(gout > -INFINITY))) { starved = true; break; }
+      if (np == 0) {
+        // the bound won at once.  A stale token carried it: it is refreshed below.  A fresh one: the cut
+        // keys left it outside the pool, full keys from here on.  Either way the next epoch differs from
+        // this one; more than a few such epochs in a row only happen on non-finite input.
+        if (!jout_stale) kbits = 32;
+        if (++idle > 64) { starved = true; break; }
+      } else {
+        idle = 0;
+      }
+      lds_barrier();                               // everyone is done with the triangle and the pool tables
+      // ================= 4. picked rows -> LDS; the wave's refresh list against all picks so far =================
+      {
+        // the rows of this epoch's picks, read again from memory (the triangle has taken the place of
+        // the pool's rows): 16 threads per row
+        constexpr int RPI = NT / 16;                   // rows per round
+        constexpr int kRounds = (kLzMaxPend + RPI - 1) / RPI;
+        uint4 x[kRounds];
+#pragma unroll
+        for (int q = 0; q < kRounds; ++q) {
+          const int i = q * RPI + (tid >> 4);
+          const int tk = i < np ? order_l[t - np + i] : 0;
+          x[q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(min(max(tk, 0), n - 1)) * pitch_b + (tid & 15) * 16u));
+        }
+#pragma unroll
+        for (int q = 0; q < kRounds; ++q) {               // unconditional stores (rounds past np go to a spare row), so
+          const int i = q * RPI + (tid >> 4);             // that every load is issued before the first store waits
+          const int dst = i < np ? t - np + i : kLzMaxB;
+          *reinterpret_cast<uint4*>(pk + dst * kLzPitch + (tid & 15) * 16) = x[q];
+        }
+      }
+      lds_barrier();
+#ifdef KVR_STATS
+      const long long c5 = __builtin_readcyclecounter();
+#endif
+      const int groups = (cnt_r + 63) >> 6;
+      if (groups > 0) {
+        const int kg = lane >> 4;
+        const int tiles = (t + 15) >> 4;             // 16-row operands of picked rows (0 when nothing is picked yet)
+        // One 64-row group of the list is in flight (the first since before the race): the registers of a
+        // 16-row sub-block are refilled for the next group as soon as they have been written to the stage.
+        // The groups are unrolled as nested conditionals (group g + 1 inside group g), not a loop: the
+        // wait counts of straight-line code are exact, those at a loop head are not, and an inexact one
+        // waits for the group just requested.  The next group's rows are requested unconditionally (the
+        // list is padded by one group of valid rows).
+        auto run_group = [&](auto self, auto gi_c) -> void {
+          constexpr int gi = decltype(gi_c)::value;
+          float part[4];                             // per 16-row sub-block: max over my four picks of every operand
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub) {
+            wave_lds_sync();
+#pragma unroll
+            for (int q = 0; q < LPC; ++q) {
+              const uint4 x = pre[sub][q];
+              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kLzPitch + (lane & 15) * 16) = x;
+              if (!have_r) {                         // row (lane >> 4) + 4q of the sub-block is list entry 16*sub + row of the group
+                const float ss = sum_sq(x);
+                if ((lane & 15) == 15) norm_x[sub * 16 + (lane >> 4) + 4 * q] = ss;
+              }
+            }
+            fetch(gi + 1, sub);
+            wave_lds_sync();
+            const char* fp = stage + (lane & 15) * kLzPitch + kg * 16;
+            bf16x8 bfr[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bfr[ks] = *reinterpret_cast<const bf16x8*>(fp + ks * 64);
+            float pm = 0.f;                          // the floor of Eq. 2
+            for (int tl = 0; tl < tiles; tl += 2) {    // two operands at a time: their MFMA chains interleave
+              const char* ap = pk + (tl * 16 + (lane & 15)) * kLzPitch + kg * 16;
+              bf16x8 a0[4];
+#pragma unroll
+              for (int ks = 0; ks < 4; ++ks) a0[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 64);
+              const float4 p0 = *reinterpret_cast<const float4*>(pick_r + tl * 16 + 4 * kg);
+              f32x4 acc0 = {0.f, 0.f, 0.f, 0.f};
+              if (tl + 1 < tiles) {
+                bf16x8 a1[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) a1[ks] = *reinterpret_cast<const bf16x8*>(ap + 16 * kLzPitch + ks * 64);
+                const float4 p1 = *reinterpret_cast<const float4*>(pick_r + tl * 16 + 16 + 4 * kg);
+                f32x4 acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                  acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], bfr[ks], acc0, 0, 0, 0);
+                  acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[ks], bfr[ks], acc1, 0, 0, 0);
+                }
+                pm = hw_max(pm, hw_max(hw_max(acc1[0] * p1.x, acc1[1] * p1.y), hw_max(acc1[2] * p1.z, acc1[3] * p1.w)));
+              } else {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                  acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[ks], bfr[ks], acc0, 0, 0, 0);
+              }
+              pm = hw_max(pm, hw_max(hw_max(acc0[0] * p0.x, acc0[1] * p0.y), hw_max(acc0[2] * p0.z, acc0[3] * p0.w)));
+            }
+            part[sub] = pm;
+          }
+          // lane (col, kg) holds partial maxima of row col of sub-block 0..3; list entry 16*sub + col of the
+          // group is finished by lane (col, kg = sub).  Exchange through the wave's scratch: [sub][kg][col].
+          wave_lds_sync();
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub) scratch[sub * 64 + kg * 16 + (lane & 15)] = part[sub];
+          wave_lds_sync();
+          const float* sp = scratch + kg * 64 + (lane & 15);
+          const float mx = hw_max(hw_max(sp[0], sp[16]), hw_max(sp[32], sp[48]));
+          lrw[gi * 64 + lane] = mx;                  // (the list entries of this group have been consumed)
+          if (!have_r) lr2[gi * 64 + lane] = 1.0f / (sqrtf(norm_x[lane]) + a.eps);
+          if constexpr (gi + 1 < S) {
+            if (gi + 1 < groups) self(self, std::integral_constant<int, gi + 1>{});
+          }
+        };
+        run_group(run_group, std::integral_constant<int, 0>{});
+        wave_lds_sync();
+      }
+      // refreshed tokens take their new m; who is fresh for the next epoch
+      {
+        uint32_t now = 0;
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+          const int ps = pslot[k];
+          if (ps <= -2) {
+            const int pos = -2 - ps;
+            if (!have_r) r[k] = lr2[pos];
+            m[k] = hw_max(m[k], lrw[pos] * r[k]);
+          }
+          if (ps != -1) now |= 1u << k;              // pool members left the race up to date
+          pslot[k] = -1;
+        }
+        fresh = np > 0 ? now : (fresh | now);
+      }
+      have_r = true;
+      lds_barrier();                               // pass areas are dead: the next epoch reuses the union
+#ifdef KVR_STATS
+      const long long c6 = __builtin_readcyclecounter();
+      st[4] += c5 - c4; if (t <= np) st[7] += c6 - c5; else st[5] += c6 - c5;
+#endif
+    }
+#ifdef KVR_STATS
+    lds_barrier();
+    if (tid == 0 && b >= 16) {
+      for (int q = 0; q < 8; ++q) gain_l[b - 1 - q] = static_cast<float>(st[q]);
+      gain_l[b - 9] = static_cast<float>(__builtin_readcyclecounter() - st_begin);
+    }
+#endif
+  }
+
+  // ---- sort(S): flag the picked tokens, ascending indices by prefix counts
+  lds_barrier();
+#pragma unroll
+  for (int k = 0; k < S; ++k) flag[base + 64 * k + lane] = 0;
+  lds_barrier();
+  for (int u = tid; u < t; u += NT) flag[order_l[u]] = 1;
+  lds_barrier();
+  if (starved) {
+    if (tid == 0) {                                  // non-finite input only: lowest unpicked tokens fill up
+      int j = 0;
+      for (int u = t; u < b; ++u) {
+        while (j < n - 1 && flag[j]) ++j;
+        order_l[u] = j; gain_l[u] = -INFINITY; flag[j] = 1;
+      }
+    }
+    lds_barrier();
+  }
+  {
+    unsigned long long sel[S];
+    int cnt = 0;
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+      sel[k] = __ballot(tok_of(k) < n && flag[tok_of(k)] != 0);
+      cnt += __popcll(sel[k]);
+    }
+    if (lane == 0) wcount[w] = cnt;
+    lds_barrier();
+    int off = 0;
+    for (int u = 0; u < w; ++u) off += wcount[u];
+#pragma unroll
+    for (int k = 0; k < S; ++k) {
+      if ((sel[k] >> lane) & 1ull) {
+        const int rank = off + __popcll(sel[k] & below);
+        if (rank < b) idxs_l[rank] = tok_of(k);
+      }
+      off += __popcll(sel[k]);
+    }
+  }
+  lds_barrier();
+  const int bs = a.b;
+  const long long ob = static_cast<long long>(h) * bs;
+  for (int u = tid; u < b; u += NT) {
+    a.idx_sorted[ob + u] = idxs_l[u];
+    if (a.pick_order) a.pick_order[ob + u] = order_l[u];
+    if (a.pick_gain) a.pick_gain[ob + u] = gain_l[u];
+  }
+  if constexpr (BUD) {
+    for (int u = b + tid; u < bs; u += NT) {                   // entries past the head's budget are padding
+      a.idx_sorted[ob + u] = -1;
+      if (a.pick_order) a.pick_order[ob + u] = -1;
+      if (a.pick_gain) a.pick_gain[ob + u] = -INFINITY;
+    }
+  }
+  if ((a.K_out || a.V_out) && (!BUD || b > 0))
+    compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
+}
+
+bool lazy_supported(const Layout& lay, int b, float lambda) {
+  // (byte offsets inside a head are 32-bit in this kernel)
+  return lay.dtype == DT_BF16 && lay.n > 256 && lay.n <= 4096 && b <= kLzMaxB && lambda > 0.0f &&
+         static_cast<long long>(lay.n) * lay.stride_tok * 2 < (1ll << 31);
+}
+
+hipError_t launch_select_lazy(const void* K, const void* V, const float* s, const Layout& lay, int b,
+                              float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st, const int32_t* b_h) {
+  LazyArgs a;
+  a.b_h = b_h;
+  a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s_in = s;
+  a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
+  a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);
+  a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
+  a.n = lay.n; a.b = b; a.lambda = lambda; a.eps = eps;
+  dim3 grid(lay.heads);
+  auto go = [&](auto kern, int threads, int smem) -> hipError_t {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, dim3(threads), smem, st, a);
+    return hipGetLastError();
+  };
+  auto by_shape = [&](auto bud) -> hipError_t {
+    constexpr bool BUD = decltype(bud)::value;
+    if (lay.n <= 512) return go(&select_lazy_kernel<2, 4, 128, BUD>, 128, LazyCfg<2, 4, 128>::smem_bytes());
+    if (lay.n <= 1024) return go(&select_lazy_kernel<4, 4, 128, BUD>, 256, LazyCfg<4, 4, 128>::smem_bytes());
+    if (lay.n <= 2048) return go(&select_lazy_kernel<8, 4, kLzPoolWide, BUD>, 512, LazyCfg<8, 4, kLzPoolWide>::smem_bytes());
+    return go(&select_lazy_kernel<8, 8, kLzPoolWide, BUD>, 512, LazyCfg<8, 8, kLzPoolWide>::smem_bytes());
+  };
+  return b_h ? by_shape(std::true_type{}) : by_shape(std::false_type{});
+}
+
+}  // namespace kvr

@@ -325,11 +325,13 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           const int tk = pool_tok[k * (NT / 16) + (tid >> 4)];
           const int tkc = tk < 0 ? 0 : tk;              // an empty slot reads row 0 and stores zeros
           x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(tkc) * a.stride_tok + (tid & 15) * 8) * 2);
-          if (tk < 0) x[k] = make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
-        for (int k = 0; k < kGat; ++k)
-          *reinterpret_cast<uint4*>(prow + (k * (NT / 16) + (tid >> 4)) * kPoolPitch + (tid & 15) * 16) = x[k];
+        for (int k = 0; k < kGat; ++k) {
+          const int slot = k * (NT / 16) + (tid >> 4);
+          if (pool_tok[slot] < 0) x[k] = make_uint4(0u, 0u, 0u, 0u);   // (only here: a select between the loads would make each wait for the one before)
+          *reinterpret_cast<uint4*>(prow + slot * kPoolPitch + (tid & 15) * 16) = x[k];
+        }
         if (!have_r) {
 #pragma unroll
           for (int k = 0; k < kGat; ++k) {
