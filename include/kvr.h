@@ -26,7 +26,8 @@
  *     the default stream) and return without synchronising.
  *   - Inputs are read-only; outputs must not alias inputs or each other,
  *     except where a call says otherwise (kvr_compact_inplace, kvr_score_prior).
- *   - The library allocates no device memory.  `workspace` is reserved for
+ *   - The library allocates no device memory (kvr_retain_budgeted_static
+ *     brings a static device array along instead).  `workspace` is reserved for
  *     future kernels: every entry point
  *     accepts NULL / 0 as long as kvr_workspace_bytes() reports 0 for the
  *     same arguments.
@@ -278,6 +279,28 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
                         const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
                         float eps, float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                         void* K_out, void* V_out, int32_t* pos_out, void* stream);
+
+/*
+ * kvr_retain_budgeted for callers that cannot hand over (or allocate) the
+ * s_work buffer: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments without s_work, same results: the
+ * adjusted scores live in a static device array of the library,
+ * KVR_STATIC_SCRATCH_FLOATS floats (32 MiB) on every GPU the library runs on,
+ * held until the process ends.  The call allocates nothing.
+ *   - heads * n > KVR_STATIC_SCRATCH_FLOATS returns KVR_ERR_WORKSPACE before
+ *     anything is launched.
+ *   - Every call on a GPU uses that GPU's one array (each call rewrites the part
+ *     it reads, nothing has to be cleared): calls that overlap on one GPU, on
+ *     different streams or from different threads, race; calls on one stream
+ *     are ordered like any other work.
+ *   - The scores the selection ran on are not returned.
+ */
+#define KVR_STATIC_SCRATCH_FLOATS (8u << 20)
+int kvr_retain_budgeted_static(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                               const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
+                               const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
+                               float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                               void* K_out, void* V_out, int32_t* pos_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1
 EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
            "kvr_select_greedy", "kvr_compact", "kvr_retain",
            "kvr_signature_flat", "kvr_compact_shared", "kvr_compact_inplace", "kvr_score_prior", "kvr_score_pool", "kvr_retain_flat",
-           "kvr_retain_budgeted")
+           "kvr_retain_budgeted", "kvr_retain_budgeted_static")
 
 
 class kvr_layout(ctypes.Structure):
@@ -73,6 +73,9 @@ def _load() -> ctypes.CDLL:
     lib.kvr_retain_budgeted.restype = i32
     lib.kvr_retain_budgeted.argtypes = [vp, vp, vp, i32, vp, lp, vp, vp, i32, vp, vp, vp, f32, f32,
                                         vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.kvr_retain_budgeted_static.restype = i32
+    lib.kvr_retain_budgeted_static.argtypes = [vp, vp, vp, i32, vp, lp, vp, vp, i32, vp, vp, vp, f32, f32,
+                                               vp, vp, vp, vp, vp, vp, vp]
     return lib
 
 
@@ -331,3 +334,29 @@ def kvr_retain_budgeted(K, V, b_max, lam, eps=1e-6, Q=None, s=None, n_h=None, b_
            "kvr_retain_budgeted")
     return out
 
+
+STATIC_SCRATCH_FLOATS = 8 << 20
+
+
+def kvr_retain_budgeted_static(K, V, b_max, lam, eps=1e-6, Q=None, s=None, n_h=None, b_h=None, keep=None,
+                               pos=None, lam_h=None, out: BudgetBuffers | None = None, stream=None):
+    """kvr_retain_budgeted without the s_work argument: the adjusted scores live in the library's static
+    device array (heads * n <= STATIC_SCRATCH_FLOATS); the C call allocates nothing.  `out.s_work` is not
+    written."""
+    _need_cuda(K, V, Q, s, n_h, b_h, keep, pos, lam_h)
+    lay = layout_of(K)
+    if layout_of(V).stride_head != lay.stride_head or layout_of(V).stride_tok != lay.stride_tok:
+        raise ValueError("K and V must share one layout")
+    for t, dt in ((n_h, torch.int32), (b_h, torch.int32), (keep, torch.uint8), (pos, torch.int32),
+                  (lam_h, torch.float32)):
+        if t is not None and (t.dtype != dt or not t.is_contiguous()):
+            raise ValueError("n_h, b_h, pos must be contiguous int32 and keep contiguous uint8")
+    if out is None:
+        out = BudgetBuffers(lay.heads, lay.n, b_max, lay.d, K.dtype, K.device, pos is not None)
+    G = 0 if Q is None else Q.shape[1]
+    _check(_lib.kvr_retain_budgeted_static(_ptr(K), _ptr(V), _ptr(Q), G, _ptr(s), ctypes.byref(lay), _ptr(n_h),
+                                           _ptr(b_h), b_max, _ptr(keep), _ptr(pos), _ptr(lam_h), lam, eps,
+                                           _ptr(out.idx_sorted), _ptr(out.pick_order), _ptr(out.pick_gain),
+                                           _ptr(out.K_out), _ptr(out.V_out), _ptr(out.pos_out), _stream(stream)),
+           "kvr_retain_budgeted_static")
+    return out

@@ -3,6 +3,7 @@
 #include "../../include/kvr.h"
 
 #include <cmath>
+#include <mutex>
 
 #include "kvr_kernels.hpp"
 
@@ -80,6 +81,35 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
     return kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                    nullptr, nullptr, st, nullptr, true);
   return kvr::launch_select_generic(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
+}
+
+int retain_budgeted(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                    const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
+                    const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
+                    float eps, float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                    void* K_out, void* V_out, int32_t* pos_out, void* stream);
+
+// Scratch of kvr_retain_budgeted_static: the adjusted scores [heads, n] of a call, in device memory that
+// the library's code object brings along (every GPU the library runs on holds its own copy of the array at
+// its own address until the process ends).  In host code the array's name is only a handle: the device
+// address is asked for once per device, with that device current, and kept.
+static __device__ __align__(256) float scratch[KVR_STATIC_SCRATCH_FLOATS];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+float* scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVR_ERR_HIP;
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KVR_ERR_HIP;
+    scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = scratch_ptr[dev];
+  return KVR_OK;
 }
 
 }  // namespace
@@ -222,6 +252,35 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
                         const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
                         float eps, float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                         void* K_out, void* V_out, int32_t* pos_out, void* stream) {
+  return retain_budgeted(K, V, Q, G, s_in, lay, n_h, b_h, b_max, keep, pos_in, lambda_h, lambda, eps, s_work,
+                         idx_sorted, pick_order, pick_gain, K_out, V_out, pos_out, stream);
+}
+
+int kvr_retain_budgeted_static(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                               const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
+                               const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
+                               float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                               void* K_out, void* V_out, int32_t* pos_out, void* stream) {
+  const int rc = check_select(lay, b_max, lambda, eps);
+  if (rc) return rc;
+  if (static_cast<unsigned long long>(lay->heads) * static_cast<unsigned long long>(lay->n) > KVR_STATIC_SCRATCH_FLOATS)
+    return KVR_ERR_WORKSPACE;                 // the adjusted scores of this call do not fit the static array
+  float* s_work = nullptr;
+  const int rs = static_scratch(&s_work);
+  if (rs) return rs;
+  return retain_budgeted(K, V, Q, G, s_in, lay, n_h, b_h, b_max, keep, pos_in, lambda_h, lambda, eps, s_work,
+                         idx_sorted, pick_order, pick_gain, K_out, V_out, pos_out, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int retain_budgeted(const void* K, const void* V, const void* Q, int G, const float* s_in,
+                    const kvr_layout* lay, const int32_t* n_h, const int32_t* b_h, int b_max,
+                    const uint8_t* keep, const int32_t* pos_in, const float* lambda_h, float lambda,
+                    float eps, float* s_work, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
+                    void* K_out, void* V_out, int32_t* pos_out, void* stream) {
   const int rc = check_select(lay, b_max, lambda, eps);
   if (rc) return rc;
   if (!V || !s_work || !idx_sorted || !pick_order) return KVR_ERR_ARG;
@@ -284,6 +343,10 @@ int kvr_retain_budgeted(const void* K, const void* V, const void* Q, int G, cons
     return KVR_ERR_HIP;
   return KVR_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int kvr_signature_flat(const void* V, const kvr_layout* lay, int group, float* u_out, void* stream) {
   const int rc = check_layout(lay);
