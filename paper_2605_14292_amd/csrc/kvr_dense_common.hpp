@@ -78,37 +78,39 @@ __device__ __forceinline__ void write_lane2(int& ra, int& rb, int va, int vb, in
       : "s"(va), "s"(vb), "s"(ln)
       : "m0");
 }
-// Index of the winning token when tokens 2*lane and 2*lane+1 live in lane `lane`: e0 / e1 are
-// the lanes whose even / odd token equals the maximum.  The lowest such lane wins and its even
-// token goes first.  Returns -1 when both masks are empty.
-__device__ __forceinline__ int first_of_pairs(unsigned long long e0, unsigned long long e1) {
-  int i, L;
-  unsigned long long any;
-  asm("s_or_b64 %1, %3, %4\n\t"
-      "s_ff1_i32_b64 %2, %1\n\t"          // -1 for an empty mask
-      "s_lshl_b32 %0, %2, 1\n\t"
-      "s_bitcmp0_b64 %3, %2\n\t"          // scc = even token of that lane is not a winner
-      "s_addc_u32 %0, %0, 0"
-      : "=&s"(i), "=&s"(any), "=&s"(L)
-      : "s"(e0), "s"(e1)
-      : "scc");
-  return i;
-}
-// The same for NQ tokens per lane (token NQ*lane + q in slot q): lowest lane first, lowest slot
-// within the lane.  Negative (-NQ .. -1) when all masks are empty.
+// Index of the winning token when token lane + 64*q lives in slot q of lane `lane`: e[q] are the lanes
+// whose slot-q token equals the maximum.  The lowest token wins: the lowest non-empty slot, and the
+// lowest lane within it.  Negative or meaningless (but below 64*NQ) when all masks are empty.
+// (Why lane + 64*q and not NQ*lane + q: the race reads element (i, j) of the packed triangle for every j
+// at once, at T(i) + j for j < i and at T(j) + i for j > i, T(j) = j(j+1)/2.  With consecutive j across the
+// lanes the first is a stride-1 read and the second hits T(j) mod 64, and the triangular numbers of 64
+// consecutive j are a complete residue system mod 64: neither has a bank conflict.  With j = NQ*lane + q
+// the lanes read stride NQ and T(NQ*lane) mod 64, which collide.)
 template <int NQ>
 __device__ __forceinline__ int first_of_slots(const unsigned long long (&e)[NQ]) {
   if constexpr (NQ == 2) {
-    return first_of_pairs(e[0], e[1]);
+    // five scalar instructions, four of them in a chain (the race's time is its instruction count);
+    // with both masks empty (only a NaN maximum does that) the result is 63, which callers never use
+    int i, L;
+    unsigned long long m;
+    asm("s_cmp_lg_u64 %3, 0\n\t"
+        "s_cselect_b64 %1, %3, %4\n\t"
+        "s_cselect_b32 %0, 0, 64\n\t"
+        "s_ff1_i32_b64 %2, %1\n\t"
+        "s_add_i32 %0, %0, %2"
+        : "=&s"(i), "=&s"(m), "=&s"(L)
+        : "s"(e[0]), "s"(e[1])
+        : "scc");
+    return i;
   } else {
-    // slot q's first winner is token NQ*ff1(e[q]) + q; an empty mask gives -NQ + q, which is
-    // huge as an unsigned number, so the unsigned minimum over the slots is the answer
+    // slot q's first winner is token ff1(e[q]) | 64*q; an empty mask gives all ones, which is huge as an
+    // unsigned number, so the unsigned minimum over the slots is the answer (-1 when all are empty)
     unsigned best = 0xffffffffu;
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
       int L;
       asm("s_ff1_i32_b64 %0, %1" : "=s"(L) : "s"(e[q]));   // -1 for an empty mask
-      const unsigned cand = static_cast<unsigned>(L * NQ + q);
+      const unsigned cand = static_cast<unsigned>(L) | static_cast<unsigned>(64 * q);
       best = cand < best ? cand : best;
     }
     return static_cast<int>(best);
@@ -172,8 +174,8 @@ __device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, co
 // Algorithm 1's pick chain (Eq. 2-3) on one wave, for a head whose cosines sit in the packed
 // triangle `tri` (element (i,j), j <= i, at i(i+1)/2 + j, +inf on the diagonal) and whose scores
 // sit in s_l (-inf for padding).  A single wave issues one instruction every few cycles, so the
-// time of a pick is its instruction count: tokens NQ*lane .. NQ*lane+NQ-1 live in lane `lane`,
-// so that the lowest lane holding the maximum also holds the lowest tied index; pick u of a
+// time of a pick is its instruction count: tokens lane, lane + 64, .. live in lane `lane` (see
+// first_of_slots); pick u of a
 // 64-pick chunk is parked in lane u of two registers (v_writelane) and the chunk is written to
 // order_l / gain_l once; nothing is checked per pick.  Non-finite input is detected afterwards
 // from the logged gains: the picks before the first one without a finite gain are kept and the
@@ -189,7 +191,7 @@ __device__ __forceinline__ float pick_chain_impl(const float* s_l, const float* 
   int ja[NQ], tja[NQ];
 #pragma unroll
   for (int q = 0; q < NQ; ++q) {
-    const int j = NQ * lane + q;
+    const int j = lane + 64 * q;
     sreg[q] = s_l[j];
     mreg[q] = 0.f;
     ja[q] = j * 4 + tri0;                              // column offset of the token
@@ -216,7 +218,7 @@ __device__ __forceinline__ float pick_chain_impl(const float* s_l, const float* 
       write_lane2(rec_i, rec_g, i, __float_as_int(amax), u);
       if constexpr (DIVERSE) {
         // element (i,j) sits at max(T(i)+j, T(j)+i); the diagonal entry (+inf) retires the pick.
-        // For any i in [-NQ, 64*NQ) both addresses stay inside the triangle.
+        // For any i in [-1, 64*NQ) both addresses stay inside the triangle.
         const int ti4 = i * (i + 1) * 2, i4 = i * 4;
         float c[NQ];
 #pragma unroll
@@ -228,7 +230,7 @@ __device__ __forceinline__ float pick_chain_impl(const float* s_l, const float* 
         for (int q = 0; q < NQ; ++q) mreg[q] = hw_max(mreg[q], c[q]);
       } else {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) sreg[q] = (NQ * lane + q == i) ? -INFINITY : sreg[q];
+        for (int q = 0; q < NQ; ++q) sreg[q] = (lane + 64 * q == i) ? -INFINITY : sreg[q];
       }
     }
     const float g = __int_as_float(rec_g);

@@ -458,8 +458,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
 #endif
       // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
       if (w == 0) {
-        // Pool slots NQ*lane .. NQ*lane+NQ-1 live in lane `lane` (slots are in token order, so the
-        // lowest slot is the lowest token).  A pick is parked in lane np of two registers; the
+        // Pool slots lane, lane + 64, .. live in lane `lane` (slots are in token order, so the lowest
+        // slot is the lowest token; the mapping keeps the triangle reads free of bank conflicts).  A pick is parked in lane np of two registers; the
         // pick lists and the pending-row tables are written once, after the loop.
         typedef __attribute__((address_space(3))) const float* lds_fp;
         const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
@@ -468,7 +468,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         int ja[NQ], tja[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
-          const int p = NQ * lane + q;
+          const int p = lane + 64 * q;
           sq[q] = pool_s[p];
           mq[q] = pool_m[p];
           ja[q] = p * 4 + tri0;                        // column offset of the slot
@@ -500,7 +500,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
           write_lane2(rec_i, rec_g, i, __float_as_int(amax), np);
           np = __builtin_amdgcn_readfirstlane(np + 1);   // keeps the loop control on the scalar unit
           // element (i,j) of the triangle sits at max(T(i)+j, T(j)+i); the diagonal (+inf) retires i.
-          // For any i in [-NQ, 64*NQ) both addresses stay inside the triangle.
+          // For any i in [-1, 64*NQ) both addresses stay inside the triangle.
           const int ti4 = i * (i + 1) * 2, i4 = i * 4;
           float c[NQ];
 #pragma unroll
@@ -512,7 +512,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
           for (int q = 0; q < NQ; ++q) mq[q] = hw_max(mq[q], c[q]);
         }
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) pool_m[NQ * lane + q] = mq[q];   // the pool's m is authoritative
+        for (int q = 0; q < NQ; ++q) pool_m[lane + 64 * q] = mq[q];   // the pool's m is authoritative
         if (lane < np) {
           order_l[t + lane] = pool_tok[rec_i]; gain_l[t + lane] = __int_as_float(rec_g);
           pend_l[lane] = rec_i; pick_r[t + lane] = pool_r[rec_i]; pool_picked[rec_i] = 1;

@@ -364,17 +364,18 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #endif
       // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
       if (w == 0) {
-        // Pool slots 2*lane and 2*lane+1 live in lane `lane` (slots are in token order, so the
-        // lowest slot is the lowest token).  A pick is parked in lane np of two registers; the
-        // pick lists and the pending-row tables are written once, after the loop.
-        const int p0 = 2 * lane;
-        const float s0 = pool_s[p0], s1 = pool_s[p0 + 1];
-        float m0 = pool_m[p0], m1 = pool_m[p0 + 1];
+        // Pool slots lane and lane + 64 live in lane `lane` (slots are in token order, so the lowest
+        // slot is the lowest token; the mapping keeps the triangle reads free of bank conflicts).  A pick
+        // is parked in lane np of two registers; the pick lists and the pending-row tables are written
+        // once, after the loop.
+        const int p0 = lane, p1 = lane + 64;
+        const float s0 = pool_s[p0], s1 = pool_s[p1];
+        float m0 = pool_m[p0], m1 = pool_m[p1];
         typedef __attribute__((address_space(3))) const float* lds_fp;
         const int tri0 = static_cast<int>(reinterpret_cast<uintptr_t>(
             (__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tri)));
-        const int ja0 = p0 * 4 + tri0, ja1 = ja0 + 4;
-        const int tja0 = p0 * (p0 + 1) * 2 + tri0, tja1 = (p0 + 1) * (p0 + 2) * 2 + tri0;
+        const int ja0 = p0 * 4 + tri0, ja1 = p1 * 4 + tri0;
+        const int tja0 = p0 * (p0 + 1) * 2 + tri0, tja1 = p1 * (p1 + 1) * 2 + tri0;
         const int jb = __builtin_amdgcn_readfirstlane(jout < 0 ? 0x7fffffff : jout);
         const float gout_u = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(gout)));
         const bool no_out = __builtin_amdgcn_readfirstlane(jout) < 0;
@@ -385,7 +386,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           const float a0 = fmaf(nlam, m0, s0), a1 = fmaf(nlam, m1, s1);
           const float amax = wave_max_uniform(hw_max(a0, a1));
           const unsigned long long e0 = __ballot(a0 == amax), e1 = __ballot(a1 == amax);
-          const int i = first_of_pairs(e0, e1);
+          const unsigned long long e01[2] = {e0, e1};
+          const int i = first_of_slots<2>(e01);
           if (!(amax > gout_u)) {                    // rare: the bound wins, a tie with it, or nothing finite
             if (!(amax > -INFINITY)) { stop = no_out ? 2 : 1; break; }
             const int ti = __builtin_amdgcn_readfirstlane(pool_tok[i < 0 ? 0 : i]);
@@ -401,7 +403,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
           m0 = hw_max(m0, c0);
           m1 = hw_max(m1, c1);
         }
-        pool_m[p0] = m0; pool_m[p0 + 1] = m1;        // the pool's m is authoritative
+        pool_m[p0] = m0; pool_m[p1] = m1;            // the pool's m is authoritative
         if (lane < np) {
           order_l[t + lane] = pool_tok[rec_i]; gain_l[t + lane] = __int_as_float(rec_g);
           pend_l[lane] = rec_i; pend_r[lane] = pool_r[rec_i]; pool_picked[rec_i] = 1;
