@@ -556,18 +556,31 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         // the pool's rows): 16 threads per row
         constexpr int RPI = NT / 16;                   // rows per round
         constexpr int kRounds = (kLzMaxPend + RPI - 1) / RPI;
-        uint4 x[kRounds];
-#pragma unroll
-        for (int q = 0; q < kRounds; ++q) {
-          const int i = q * RPI + (tid >> 4);
-          const int tk = i < np ? order_l[t - np + i] : 0;
-          x[q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(min(max(tk, 0), n - 1)) * pitch_b + (tid & 15) * 16u));
-        }
-#pragma unroll
-        for (int q = 0; q < kRounds; ++q) {               // unconditional stores (rounds past np go to a spare row), so
+        // (named registers, not an array: the array form of this block ended up in scratch memory)
+        auto row_of = [&](int q) -> uint32_t {            // branch-free: rounds past np re-read the last pick's row
+          const int i = min(q * RPI + (tid >> 4), np - 1);
+          const int tk = order_l[max(t - np + i, 0)];
+          return static_cast<uint32_t>(min(max(tk, 0), n - 1)) * pitch_b + (tid & 15) * 16u;
+        };
+        auto put = [&](int q, const uint4& v) {           // unconditional stores (rounds past np go to a spare row), so
           const int i = q * RPI + (tid >> 4);             // that every load is issued before the first store waits
           const int dst = i < np ? t - np + i : kLzMaxB;
-          *reinterpret_cast<uint4*>(pk + dst * kLzPitch + (tid & 15) * 16) = x[q];
+          *reinterpret_cast<uint4*>(pk + dst * kLzPitch + (tid & 15) * 16) = v;
+        };
+        static_assert(kRounds == 2 || kRounds == 4 || kRounds == 8, "rounds of the pick-row copy");
+        for (int q0 = 0; q0 < kRounds; q0 += 4) {         // (one trip unless a workgroup has two waves)
+          const uint32_t o0 = row_of(q0), o1 = row_of(q0 + 1);
+          const uint32_t o2 = kRounds > 2 ? row_of(q0 + 2) : o0, o3 = kRounds > 2 ? row_of(q0 + 3) : o1;
+          const uint4 x0 = *reinterpret_cast<const uint4*>(Vh + o0);
+          const uint4 x1 = *reinterpret_cast<const uint4*>(Vh + o1);
+          uint4 x2 = x0, x3 = x1;
+          if constexpr (kRounds > 2) {
+            x2 = *reinterpret_cast<const uint4*>(Vh + o2);
+            x3 = *reinterpret_cast<const uint4*>(Vh + o3);
+          }
+          put(q0, x0);
+          put(q0 + 1, x1);
+          if constexpr (kRounds > 2) { put(q0 + 2, x2); put(q0 + 3, x3); }
         }
       }
       lds_barrier();
