@@ -75,7 +75,11 @@ template <int W, int S, int P> struct LazyCfg {
   static constexpr int kListFloats = W * (TPW + 64);   // one group of padding past a full list
   static constexpr int kPickBytes = (kLzMaxB + 1) * kLzPitch;    // one spare row past the last
   static_assert(64 * S * W * 4 <= kUnion, "the pick flags of the read-out fit the union area");
-  static constexpr int smem_bytes() { return (kFixedFloats + kListFloats) * 4 + kPickBytes + kUnion; }
+  // Where two workgroups share a CU (W <= 4) the triangle is written over the pool's rows and the rows of an epoch's
+  // picks are read from memory again; a workgroup that has the CU to itself keeps the rows and copies them inside LDS.
+  static constexpr bool kAlias = W <= 4;
+  static constexpr int kKeepBytes = kAlias ? 0 : kRowBytes;
+  static constexpr int smem_bytes() { return (kFixedFloats + kListFloats) * 4 + kPickBytes + kKeepBytes + kUnion; }
 };
 
 // BUD: per-head budgets are read from a.b_h.
@@ -110,8 +114,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
   float* pick_r = smem + 96 + 5 * P + 64 + 3 * kLzMaxB;                   // inverse norms of the picks, 0 past the last
   float* lr_all = smem + Cfg::kFixedFloats;                                     // [W][TPW] refresh lists / results
   char* pk = reinterpret_cast<char*>(smem + Cfg::kFixedFloats + Cfg::kListFloats);   // [128][272 B] rows of the picks
-  char* uni = pk + Cfg::kPickBytes;
-  char* prow = uni;                                              // [P][272 B] pool rows (gather, Gram) ...
+  char* uni = pk + Cfg::kPickBytes + Cfg::kKeepBytes;
+  char* prow = Cfg::kAlias ? uni : pk + Cfg::kPickBytes;        // [P][272 B] pool rows (gather, Gram) ...
   float* tri = reinterpret_cast<float*>(uni);                    // ... then the packed P x P cosine triangle (race) ...
   // ... then the per-wave areas of the pass ...
   int32_t* flag = reinterpret_cast<int32_t*>(uni);               // ... and at the end [n padded] pick flags for the ascending read-out
@@ -440,7 +444,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
                                                                *reinterpret_cast<const bf16x8*>(pb + ks * 32), acc[q], 0, 0, 0);
           }
         }
-        lds_barrier();                                 // every wave has read its rows: the triangle takes their place
+        if constexpr (Cfg::kAlias) lds_barrier();      // every wave has read its rows: the triangle takes their place
 #pragma unroll
         for (int q = 0; q < NTILE; ++q) {
           const int tile = w + q * W;
@@ -551,6 +555,12 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       }
       lds_barrier();                               // everyone is done with the triangle and the pool tables
       // ================= 4. picked rows -> LDS; the wave's refresh list against all picks so far =================
+      if constexpr (!Cfg::kAlias) {
+        // the rows of this epoch's picks, from the pool's rows to the rows of all picks: 16 threads per row
+        for (int i = tid >> 4; i < np; i += NT / 16)
+          *reinterpret_cast<uint4*>(pk + (t - np + i) * kLzPitch + (tid & 15) * 16) =
+              *reinterpret_cast<const uint4*>(prow + pend_l[i] * kLzPitch + (tid & 15) * 16);
+      } else
       {
         // the rows of this epoch's picks, read again from memory (the triangle has taken the place of
         // the pool's rows): 16 threads per row
