@@ -90,10 +90,6 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
   int h = next_head(blockIdx.x);
   if (h < a.heads) prefetch(h, tid0);
 
-#ifdef KVR_STATS
-  long long st_acc[4] = {0, 0, 0, 0};
-  long long st_x[2] = {0, 0};
-#endif
   while (h < a.heads) {
     const int h_next = next_head(h + gridDim.x);
     const long long head_off = h * a.stride_head * 2;  // bytes
@@ -102,10 +98,6 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     int tid = tid0;
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63, hf = lane >> 5;
-#ifdef KVR_STATS
-    const long long st0 = __builtin_readcyclecounter();
-    long long st_a = st0, st_b = st0;
-#endif
     // ---------------------------------------------------------------- scores
     if (a.Q) {
       {
@@ -201,9 +193,6 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     if (need_v) {
       store_rows<NT>(stage, tid, vpre);
       lds_barrier();
-#ifdef KVR_STATS
-      st_a = __builtin_readcyclecounter();
-#endif
       // Tile rows are paired so that every working wave owns NT+1 tiles: wave w takes row
       // NT-1-w (tiles J = 0..NT-1-w) and row w (tiles J = 0..w).  The row block's fragments stay
       // in registers while the column blocks stream out of LDS.
@@ -238,9 +227,6 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
         }
       }
       lds_barrier();                                // staged rows are dead from here on
-#ifdef KVR_STATS
-      st_b = __builtin_readcyclecounter();
-#endif
       for (int j = tid; j < N32; j += kDenseThreads) rinv[j] = 1.0f / (sqrtf(rinv[j]) + a.eps);
       lds_barrier();
       if (working) {
@@ -253,9 +239,6 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
       }
     }
     lds_barrier();
-#ifdef KVR_STATS
-    const long long st1 = __builtin_readcyclecounter();
-#endif
     // the next head of this workgroup starts its trip from HBM now
     if (h_next < a.heads) prefetch(h_next, tid);
 
@@ -269,9 +252,6 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     }
     lds_barrier();
 
-#ifdef KVR_STATS
-    const long long st2 = __builtin_readcyclecounter();
-#endif
     // ------------------------------------------------- outputs and compaction
     const long long ob = static_cast<long long>(h) * b;
     for (int t = tid; t < b; t += kDenseThreads) {              // entries past the head's budget are padding
@@ -282,20 +262,6 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 6 ? 2 : 1)) void retain_dense
     if ((a.K_out || a.V_out) && bh > 0)
       compact_rows<4>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idx_l, n, bh, ob, tid, kDenseThreads);
     lds_barrier();                                   // idx_l / s_l are reused by the next head
-#ifdef KVR_STATS
-    {
-      const long long st3 = __builtin_readcyclecounter();
-      st_acc[0] += st1 - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2; st_acc[3] += 1;
-      st_x[0] += st_a - st0; st_x[1] += st_b - st_a;
-      if (tid == 0 && a.pick_gain && b >= 4) {
-        a.pick_gain[ob + b - 1] = static_cast<float>(st_acc[0]) / st_acc[3];
-        a.pick_gain[ob + b - 2] = static_cast<float>(st_acc[1]) / st_acc[3];
-        a.pick_gain[ob + b - 3] = static_cast<float>(st_acc[2]) / st_acc[3];
-        a.pick_gain[ob + b - 4] = static_cast<float>(st_x[0]) / st_acc[3];
-        a.pick_gain[ob + b - 5] = static_cast<float>(st_x[1]) / st_acc[3];
-      }
-    }
-#endif
     h = h_next;
   }
 }

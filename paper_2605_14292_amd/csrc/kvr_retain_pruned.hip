@@ -267,11 +267,6 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     }
   };
 
-#ifdef KVR_STATS
-  long long st_acc[7] = {0, 0, 0, 0, 0, 0, 0};
-  const unsigned long long rt0 = __builtin_amdgcn_s_memrealtime();
-  long long lst[3] = {0, 0, 0};
-#endif
   int buf = 0;
   int hprev = -1;                                     // head whose results are still in LDS
   int bprev = b;                                      // and its budget
@@ -297,9 +292,6 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     int32_t* idx_l = idx_l2 + buf * kPrN;
     int32_t* order_l = order_l2 + buf * kPrN;
     float* gain_l = gain_l2 + buf * kPrN;
-#ifdef KVR_STATS
-    const long long st0 = __builtin_readcyclecounter();
-#endif
 
     if (wave != 0) {
       const int tl = tid - kWave, r0 = tl >> 4, chunk = tl & 15;
@@ -313,9 +305,6 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       }
     }
     lds_barrier();
-#ifdef KVR_STATS
-    const long long stA = __builtin_readcyclecounter();
-#endif
 
     // ------------------------------------------------ Gram -> packed cosines
     // Ten lower-triangular 32x32 tiles over four waves; tile rows that hold no survivor are
@@ -343,9 +332,6 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       }
     }
     lds_barrier();                                  // gathered rows are dead from here on
-#ifdef KVR_STATS
-    const long long stB = __builtin_readcyclecounter();
-#endif
 #pragma unroll
     for (int sl = 0; sl < 3; ++sl) {
       int I, J;
@@ -353,10 +339,6 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
     }
     lds_barrier();
 
-#ifdef KVR_STATS
-    const long long st1 = __builtin_readcyclecounter();
-    long long st2 = st1;
-#endif
     if (wave != 0) {
       // the previous head's kept rows start their trip first, the next head's survivor search
       // runs while they are in flight
@@ -369,9 +351,6 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       if (hprev >= 0) out_load(hprev, buf ^ 1, tl, kPrLoaders, 0, bprev);
       int ns_n;
       const int h_n = survivors(h + gridDim.x, buf ^ 1, tid, ns_n);
-#ifdef KVR_STATS
-      const long long lq0 = __builtin_readcyclecounter();
-#endif
       gather(h_n, buf ^ 1, ns_n, tid);   // in flight from here to the end of wave 0's chain
       if (hprev >= 0) {
         out_lists(hprev, buf ^ 1, tl, kPrLoaders, bprev);
@@ -381,13 +360,7 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
           out_store(hprev, tl, kPrLoaders, first, bprev);
         }
       }
-#ifdef KVR_STATS
-      const long long lq1 = __builtin_readcyclecounter();
-#endif
       norms();
-#ifdef KVR_STATS
-      lst[0] += lq0 - st1; lst[1] += lq1 - lq0; lst[2] += __builtin_readcyclecounter() - lq1;
-#endif
     } else {
       // ---------------------------------------------------------------- greedy
       __builtin_amdgcn_s_setprio(3);                   // the chain goes first when it shares a SIMD with loader waves
@@ -410,18 +383,8 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
         asm volatile("" : "=v"(vpre[k].x), "=v"(vpre[k].y), "=v"(vpre[k].z), "=v"(vpre[k].w), "=v"(rn[k]));
       }
     }
-#ifdef KVR_STATS
-    st2 = __builtin_readcyclecounter();
-#endif
     lds_barrier();
-#ifdef KVR_STATS
-    const long long st3 = __builtin_readcyclecounter();
-#endif
 
-#ifdef KVR_STATS
-    st_acc[0] += stA - st0; st_acc[1] += st2 - st1; st_acc[2] += st3 - st2; st_acc[3] += stB - stA; st_acc[6] += st1 - stB;
-    st_acc[4] += ns; st_acc[5] += 1;
-#endif
     hprev = h;
     bprev = bout;
     h = __builtin_amdgcn_readfirstlane(meta[buf ^ 1]);   // published before the barrier above
@@ -434,17 +397,6 @@ __global__ __launch_bounds__(kDenseThreads, 4) void retain_pruned_kernel(PrunedA
       out_load(hprev, buf ^ 1, tid0, kDenseThreads, first, bprev);
       out_store(hprev, tid0, kDenseThreads, first, bprev);
     }
-#ifdef KVR_STATS
-    lds_barrier();
-    if ((tid0 == 0 || tid0 == 64) && a.pick_gain && b >= 16) {
-      float* o = a.pick_gain + static_cast<long long>(hprev) * b + b - 1 - (tid0 == 64 ? 8 : 0);
-      for (int k = 0; k < 5; ++k) o[-k] = static_cast<float>(st_acc[k]) / st_acc[5];
-      o[-5] = static_cast<float>(st_acc[6]) / st_acc[5];
-      o[-6] = static_cast<float>(rt0 & 0xffffffull);
-      if (tid0 == 64) for (int k = 0; k < 3; ++k) o[-8 - k] = static_cast<float>(lst[k]) / st_acc[5];
-      o[-7] = static_cast<float>(__builtin_amdgcn_s_memrealtime() & 0xffffffull);
-    }
-#endif
   }
 }
 

@@ -70,10 +70,6 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
   const int n = a.n, b = a.b;
   const bool diverse = a.lambda != 0.0f && b > 1;
 
-#ifdef KVR_STATS
-  const long long q0 = __builtin_readcyclecounter();
-  long long q1 = q0, q2 = q0, q3 = q0;
-#endif
   if (a.Q) {
     // Base scores (the stand-in for the paper's external scorer): s_i = (1/G) sum_g softmax_i(q_g . k_i / sqrt(d)).
     // 32 threads per row (float4 each) take the dot products in fp32, one wave per query takes its softmax.
@@ -207,9 +203,6 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
       for (int r = ns + (tid >> 5); r < ((ns + 31) & ~31); r += kF32Threads / 32)
         *reinterpret_cast<float4*>(stage + r * kF32Pitch + (tid & 31) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
-#ifdef KVR_STATS
-    q1 = __builtin_readcyclecounter();
-#endif
     // tile t of the lower triangle: row block I, column block J <= I (only the blocks in use)
     const int nblk = ns ? (ns + 31) >> 5 : NT;
     const int ntiles = nblk * (nblk + 1) / 2;
@@ -242,9 +235,6 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
       }
     }
     __syncthreads();                                  // staged rows are dead from here on
-#ifdef KVR_STATS
-    q2 = __builtin_readcyclecounter();
-#endif
     if (tid < nblk * 32) rinv[tid] = 1.0f / (sqrtf(rinv[tid]) + a.eps);
     __syncthreads();
 #pragma unroll
@@ -259,9 +249,6 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
     }
   }
   __syncthreads();
-#ifdef KVR_STATS
-  q3 = __builtin_readcyclecounter();
-#endif
 
   if (wave == 0) {
     if (ns) {                                           // the reduced problem: indices go back through tok_c
@@ -302,15 +289,6 @@ __global__ __launch_bounds__(kF32Threads, 1) void select_dense_f32_kernel(F32Arg
       }
     }
   }
-#ifdef KVR_STATS
-  __syncthreads();
-  if (tid == 0 && a.pick_gain && b >= 8) {
-    const long long q4 = __builtin_readcyclecounter();
-    float* o = a.pick_gain + ob + b - 1;
-    o[0] = static_cast<float>(q1 - q0); o[-1] = static_cast<float>(q2 - q1); o[-2] = static_cast<float>(q3 - q2);
-    o[-3] = static_cast<float>(q4 - q3);
-  }
-#endif
 }
 
 bool dense_f32_supported(const Layout& lay, int b) {

@@ -252,14 +252,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
     };
 
     int idle = 0;                                    // epochs in a row without a pick
-#ifdef KVR_STATS
-    long long st[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const long long st_begin = __builtin_readcyclecounter();
-#endif
     while (t < b) {
-#ifdef KVR_STATS
-      const long long c0 = __builtin_readcyclecounter();
-#endif
       // ================= 1. pool = the best Q fresh unselected tokens of every wave =================
       float g[S];
       uint32_t key[S];
@@ -333,9 +326,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         const int tkc = tk < 0 ? 0 : tk;                // an empty slot reads row 0 and stores zeros
         x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(tkc) * pitch_b + (tid & 15) * 16u));
       }
-#ifdef KVR_STATS
-      const long long c1 = __builtin_readcyclecounter();
-#endif
       // ---- the wave's refresh list for this epoch's pass: outside tokens whose bound lies within
       // delta of the wave's best one (all of them in the first pass).  delta is steered so that about
       // KR tokens qualify: a few bisection steps around the previous epoch's value.
@@ -404,9 +394,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
 #pragma unroll
       for (int sub = 0; sub < 4; ++sub) fetch(0, sub);   // (no branch around them: the wait counts of what follows stay exact)
 
-#ifdef KVR_STATS
-      const long long c2 = __builtin_readcyclecounter();
-#endif
       // ================= 2. pool rows -> LDS, cosine triangle on MFMA (written over the rows) =================
       {
 #pragma unroll
@@ -457,9 +444,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         }
       }
       lds_barrier();
-#ifdef KVR_STATS
-      const long long c3 = __builtin_readcyclecounter();
-#endif
       // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
       if (w == 0) {
         // Pool slots lane, lane + 64, .. live in lane `lane` (slots are in token order, so the lowest
@@ -525,10 +509,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
       }
       lds_barrier();
-#ifdef KVR_STATS
-      const long long c4 = __builtin_readcyclecounter();
-      st[0] += c1 - c0; st[1] += c2 - c1; st[2] += c3 - c2; st[3] += c4 - c3; st[6] += 1;
-#endif
       const int np = shared_i[0];
       t = shared_i[1];
       const int stop = shared_i[2];
@@ -594,9 +574,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         }
       }
       lds_barrier();
-#ifdef KVR_STATS
-      const long long c5 = __builtin_readcyclecounter();
-#endif
       const int groups = (cnt_r + 63) >> 6;
       if (groups > 0) {
         const int kg = lane >> 4;
@@ -692,18 +669,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       }
       have_r = true;
       lds_barrier();                               // pass areas are dead: the next epoch reuses the union
-#ifdef KVR_STATS
-      const long long c6 = __builtin_readcyclecounter();
-      st[4] += c5 - c4; if (t <= np) st[7] += c6 - c5; else st[5] += c6 - c5;
-#endif
     }
-#ifdef KVR_STATS
-    lds_barrier();
-    if (tid == 0 && b >= 16) {
-      for (int q = 0; q < 8; ++q) gain_l[b - 1 - q] = static_cast<float>(st[q]);
-      gain_l[b - 9] = static_cast<float>(__builtin_readcyclecounter() - st_begin);
-    }
-#endif
   }
 
   // ---- sort(S): flag the picked tokens, ascending indices by prefix counts

@@ -109,9 +109,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   int32_t* pX = reinterpret_cast<int32_t*>(rX + SL * NT);
 
   const int h = blockIdx.x;
-#ifdef KVR_STATS
-  const long long st_begin = __builtin_readcyclecounter();
-#endif
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = a.n;
@@ -256,14 +253,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       return group16_sum(ss);                        // the 16 lanes of a row hold its 16-byte chunks
     };
 
-#ifdef KVR_STATS
-    long long st[6] = {0, 0, 0, 0, 0, 0};
-    st[5] = __builtin_readcyclecounter() - st_begin;   // prologue: scores
-#endif
     while (t < b) {
-#ifdef KVR_STATS
-      const long long c0 = __builtin_readcyclecounter();
-#endif
       // ================= 1. pool = the best Q unselected tokens of every wave =================
       float g[S];
       uint32_t key[S];
@@ -311,9 +301,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
       }
       float gout; int jout;
       wg_argmax(go, gout, jout);                     // barrier inside: the pool tables are complete
-#ifdef KVR_STATS
-      const long long c1 = __builtin_readcyclecounter();
-#endif
       // ================= 2. pool rows -> LDS, cosine triangle on MFMA =================
       {
         // all row loads of a thread are issued before the first one is stored: with the loads
@@ -359,9 +346,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         }
       }
       lds_barrier();
-#ifdef KVR_STATS
-      const long long c2 = __builtin_readcyclecounter();
-#endif
       // ================= 3. Algorithm 1 inside the pool, against the outside bound =================
       if (w == 0) {
         // Pool slots lane and lane + 64 live in lane `lane` (slots are in token order, so the lowest
@@ -412,10 +396,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
       }
       lds_barrier();
-#ifdef KVR_STATS
-      const long long c3 = __builtin_readcyclecounter();
-      st[0] += c1 - c0; st[1] += c2 - c1; st[2] += c3 - c2; st[4] += 1;
-#endif
       const int np = shared_i[0];
       t = shared_i[1];
       const int stop = shared_i[2];
@@ -559,16 +539,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #pragma unroll
       for (int k = 0; k < S; ++k) set_p(k, -1);
       lds_barrier();                               // stages are dead: the next epoch reuses the area
-#ifdef KVR_STATS
-      st[3] += __builtin_readcyclecounter() - c3;
-#endif
     }
-#ifdef KVR_STATS
-    lds_barrier();
-    if (tid == 0 && b >= 8) {
-      for (int q = 0; q < 6; ++q) gain_l[b - 1 - q] = static_cast<float>(st[q]);
-    }
-#endif
   }
 
   // ---- sort(S): flag the picked tokens, ascending indices by prefix counts
@@ -626,10 +597,6 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   }
   if ((a.K_out || a.V_out) && (!BUD || b > 0))
     compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
-#ifdef KVR_STATS
-  if (tid == 0 && a.pick_gain && b >= 8)
-    a.pick_gain[ob + b - 7] = static_cast<float>(__builtin_readcyclecounter() - st_begin);   // whole head
-#endif
 }
 
 bool pool_supported(const Layout& lay, int b) {
