@@ -139,11 +139,13 @@ __device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, co
   const float rc = rinv[j];
   int i = I * 32 + hf * 4;                            // first of this lane's rows in the tile
   int off = i * (i + 1) / 2 + j;
+  float4 rr4[4];                                      // the rows' inverse norms, all requested before the first use
+#pragma unroll
+  for (int R = 0; R < 4; ++R) rr4[R] = *reinterpret_cast<const float4*>(rinv + i + 8 * R);
   if (I != J) {                                       // two code paths: no per-element predicate off the diagonal
 #pragma unroll
     for (int R = 0; R < 4; ++R) {
-      const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
-      const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+      const float rrow[4] = {rr4[R].x, rr4[R].y, rr4[R].z, rr4[R].w};
       int o = off;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
@@ -156,8 +158,7 @@ __device__ __forceinline__ void write_cos_tile(float* tri, const float* rinv, co
   } else {
 #pragma unroll
     for (int R = 0; R < 4; ++R) {
-      const float4 rr = *reinterpret_cast<const float4*>(rinv + i);
-      const float rrow[4] = {rr.x, rr.y, rr.z, rr.w};
+      const float rrow[4] = {rr4[R].x, rr4[R].y, rr4[R].z, rr4[R].w};
       int o = off;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
