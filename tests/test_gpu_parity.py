@@ -228,18 +228,18 @@ def test_batched_and_single_event_kernels_agree_on_short_heads(n, b, G, lam):
     _check_heads(W.WORKLOADS["c2"], data_s, small, b, lam, 1e-6, [0, 17, 39])
 
 
-def test_exactly_representable_inputs_match_with_zero_near_ties():
+@pytest.mark.parametrize("h,n,b,lam", [(4, 160, 70, 0.5), (3, 900, 100, 0.5), (2, 3000, 128, 0.25), (2, 5000, 60, 0.5)])
+def test_exactly_representable_inputs_match_with_zero_near_ties(h, n, b, lam):
     # signed basis rows (norm 1, eps 0) with duplicates, dyadic scores and
     # lambda: every quantity is exact in fp32, so the picks must be the
-    # oracle's, pick by pick
+    # oracle's, pick by pick (short heads, and the two long-head kernels)
     rng = np.random.default_rng(5)
-    h, n, b, lam = 4, 160, 70, 0.5
     V = np.zeros((h, n, 128), dtype=np.float32)
     for hh in range(h):
         ax = rng.integers(0, 40, size=n)
         sg = rng.choice([-1.0, 1.0], size=n)
         V[hh, np.arange(n), ax] = sg
-    s = (rng.permutation(h * n).reshape(h, n) / 1024.0).astype(np.float32)
+    s = (rng.permutation(h * n).reshape(h, n) / 16384.0).astype(np.float32)
     Vt = torch.tensor(V).to(torch.bfloat16).to(DEV)
     Kt = torch.tensor(rng.normal(size=(h, n, 128)).astype(np.float32)).to(torch.bfloat16).to(DEV)
     st = torch.tensor(s).to(DEV)
@@ -252,8 +252,8 @@ def test_exactly_representable_inputs_match_with_zero_near_ties():
         np.testing.assert_array_equal(out.idx_sorted[hh].cpu().numpy(), r["sorted"])
 
 
-def test_identical_value_rows_and_score_ties():
-    h, n, b = 2, 130, 50
+@pytest.mark.parametrize("h,n,b", [(2, 130, 50), (2, 1000, 120), (1, 4000, 128), (1, 6000, 40)])
+def test_identical_value_rows_and_score_ties(h, n, b):
     K, V, s = _mk(h, n, 3)
     V[:] = V[:, :1, :]
     s = torch.floor(s * 8) / 8                    # many exact ties
