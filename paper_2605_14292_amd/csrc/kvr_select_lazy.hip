@@ -43,7 +43,17 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kLzPoolWide = KVR_POOL_WIDE;   // pool of the configurations with one workgroup per CU
 constexpr int kLzMaxB = 128;        // largest budget: the rows of all picks stay in LDS
 constexpr int kLzMaxPend = 64;      // picks per epoch (the chain logs pick u in lane u)
-constexpr int kLzPitch = 272;       // bytes per staged row (256 + 16)
+constexpr int kLzPitch = 272;       // bytes per pool row (256 + 16): conflict-free 32x32x16 operand reads
+// Rows read as 16x16x32 operands (the picks' rows, the staged rows of a pass) are kept as two planes of half rows:
+// 16-byte piece p of a row sits in plane p >> 3 at row * 144 + (p & 7) * 16, and the planes start a multiple of
+// 256 bytes apart.  Lane (row c, k-group kg) of an operand reads piece (kg >> 1) + 2 * ks + 8 * (kg & 1) in step
+// ks (both operands use the same order, so the sum over k is the row product).  Lanes l and l + 16 then hit the same
+// banks, which is what a 128-bit LDS read needs to run at full rate: measured 221 B/clk against 123 B/clk for
+// whole rows 272 bytes apart, where the four k-groups start four banks apart.  Row writes (16 lanes, one row)
+// run at the write rate of whole rows.
+constexpr int kLzHalf = 144;        // bytes between the half rows of a plane (128 + 16)
+constexpr int kLzStagePlane = 16 * kLzHalf;      // 2304 = 9 * 256
+constexpr int kLzPickPlane = 128 * kLzHalf;      // 18432 = 72 * 256
 constexpr int kLzSelBits = 16;      // leading bits of a gain's ordered key used to choose the pool
 constexpr int kLzChunk = 16;        // rows staged per step and wave in the refresh pass
 
@@ -62,18 +72,18 @@ struct LazyArgs {
 template <int W, int S, int P> struct LazyCfg {
   static constexpr int TPW = 64 * S;
   // per wave, during the pass: row stage | 256-float exchange | 64 squared norms | TPW inverse norms (first pass)
-  static constexpr int kWaveArea = kLzChunk * kLzPitch + 1024 + 256 + TPW * 4;
+  static constexpr int kWaveArea = 2 * kLzStagePlane + 1024 + 256 + TPW * 4;
   static constexpr int kTriBytes = P * (P + 1) / 2 * 4;
   static constexpr int kRowBytes = P * kLzPitch;
   static constexpr int kMax2 = kTriBytes > kRowBytes ? kTriBytes : kRowBytes;
   static constexpr int kUnion = ((W * kWaveArea > kMax2 ? W * kWaveArea : kMax2) + 15) & ~15;
   // floats: slots 64 | shared 16 | wcount 16 | pool_tok,r,s,m,picked 5*128 | pend 64 |
-  //         order,gain,idxs,pick_r 4*128 ; then per wave TPW list entries / results ;
-  //         then the rows of the picks ; then the union area (pool rows -> triangle -> pass areas ->
-  //         pick flags of the read-out)
-  static constexpr int kFixedFloats = 96 + 5 * P + 64 + 4 * kLzMaxB;
+  //         order,gain,pick_r 3*128 ; then per wave TPW list entries / results (at the end the sorted
+  //         indices) ; then the rows of the picks ; then the union area (pool rows -> triangle -> pass
+  //         areas -> pick flags of the read-out)
+  static constexpr int kFixedFloats = 96 + 5 * P + 64 + 3 * kLzMaxB;
   static constexpr int kListFloats = W * (TPW + 64);   // one group of padding past a full list
-  static constexpr int kPickBytes = (kLzMaxB + 1) * kLzPitch;    // one spare row past the last
+  static constexpr int kPickBytes = 2 * kLzPickPlane;
   static_assert(64 * S * W * 4 <= kUnion, "the pick flags of the read-out fit the union area");
   // Where two workgroups share a CU (W <= 4) the triangle is written over the pool's rows and the rows of an epoch's
   // picks are read from memory again; a workgroup that has the CU to itself keeps the rows and copies them inside LDS.
@@ -110,10 +120,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
   int32_t* pend_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * P);        // [64] pool slots picked this epoch
   int32_t* order_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * P + 64);
   float* gain_l = smem + 96 + 5 * P + 64 + kLzMaxB;
-  int32_t* idxs_l = reinterpret_cast<int32_t*>(smem + 96 + 5 * P + 64 + 2 * kLzMaxB);
-  float* pick_r = smem + 96 + 5 * P + 64 + 3 * kLzMaxB;                   // inverse norms of the picks, 0 past the last
+  float* pick_r = smem + 96 + 5 * P + 64 + 2 * kLzMaxB;                   // inverse norms of the picks, 0 past the last
   float* lr_all = smem + Cfg::kFixedFloats;                                     // [W][TPW] refresh lists / results
-  char* pk = reinterpret_cast<char*>(smem + Cfg::kFixedFloats + Cfg::kListFloats);   // [128][272 B] rows of the picks
+  int32_t* idxs_l = reinterpret_cast<int32_t*>(lr_all);                         // [128] sorted indices (the lists are dead by then)
+  char* pk = reinterpret_cast<char*>(smem + Cfg::kFixedFloats + Cfg::kListFloats);   // [2 planes][128][144 B] rows of the picks
   char* uni = pk + Cfg::kPickBytes + Cfg::kKeepBytes;
   char* prow = Cfg::kAlias ? uni : pk + Cfg::kPickBytes;        // [P][272 B] pool rows (gather, Gram) ...
   float* tri = reinterpret_cast<float*>(uni);                    // ... then the packed P x P cosine triangle (race) ...
@@ -132,7 +142,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
   const uint32_t pitch_b = static_cast<uint32_t>(a.stride_tok) * 2u;   // bytes between tokens: a head spans less than 4 GiB (checked by the host)
   const int base = w * TPW;
   char* stage = uni + w * Cfg::kWaveArea;
-  float* scratch = reinterpret_cast<float*>(stage + CH * kLzPitch);
+  float* scratch = reinterpret_cast<float*>(stage + 2 * kLzStagePlane);
   float* norm_x = scratch + 256;                                 // [64] squared norms of the wave's current 64 rows
   float* lr2 = norm_x + 64;                                      // [TPW] inverse norms found in the first pass
   float* lrw = lr_all + w * (TPW + 64);                                 // [TPW] list of tokens to refresh, then their raw maxima
@@ -151,7 +161,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
     pslot[k] = -1;
   }
   // rows of the picks: zero until written (a partly filled 16-row operand multiplies zeros)
-  for (int u = tid; u < kLzMaxB * kLzPitch / 16; u += NT) reinterpret_cast<uint4*>(pk)[u] = make_uint4(0u, 0u, 0u, 0u);
+  for (int u = tid; u < Cfg::kPickBytes / 16; u += NT) reinterpret_cast<uint4*>(pk)[u] = make_uint4(0u, 0u, 0u, 0u);
   if (tid < kLzMaxB) pick_r[tid] = 0.f;
   const float nlam = -a.lambda;
   int par = 0;
@@ -538,7 +548,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       if constexpr (!Cfg::kAlias) {
         // the rows of this epoch's picks, from the pool's rows to the rows of all picks: 16 threads per row
         for (int i = tid >> 4; i < np; i += NT / 16)
-          *reinterpret_cast<uint4*>(pk + (t - np + i) * kLzPitch + (tid & 15) * 16) =
+          *reinterpret_cast<uint4*>(pk + ((tid & 15) >> 3) * kLzPickPlane + (t - np + i) * kLzHalf + (tid & 7) * 16) =
               *reinterpret_cast<const uint4*>(prow + pend_l[i] * kLzPitch + (tid & 15) * 16);
       } else
       {
@@ -552,10 +562,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
           const int tk = order_l[max(t - np + i, 0)];
           return static_cast<uint32_t>(min(max(tk, 0), n - 1)) * pitch_b + (tid & 15) * 16u;
         };
-        auto put = [&](int q, const uint4& v) {           // unconditional stores (rounds past np go to a spare row), so
-          const int i = q * RPI + (tid >> 4);             // that every load is issued before the first store waits
-          const int dst = i < np ? t - np + i : kLzMaxB;
-          *reinterpret_cast<uint4*>(pk + dst * kLzPitch + (tid & 15) * 16) = v;
+        auto put = [&](int q, const uint4& v) {           // unconditional stores (rounds past np go to the union area, dead
+          const int i = q * RPI + (tid >> 4);             // here), so that every load is issued before the first store waits
+          char* dst = i < np ? pk + ((tid & 15) >> 3) * kLzPickPlane + (t - np + i) * kLzHalf + (tid & 7) * 16 : uni + tid * 16;
+          *reinterpret_cast<uint4*>(dst) = v;
         };
         static_assert(kRounds == 2 || kRounds == 4 || kRounds == 8, "rounds of the pick-row copy");
         for (int q0 = 0; q0 < kRounds; q0 += 4) {         // (one trip unless a workgroup has two waves)
@@ -593,7 +603,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
 #pragma unroll
             for (int q = 0; q < LPC; ++q) {
               const uint4 x = pre[sub][q];
-              *reinterpret_cast<uint4*>(stage + ((lane >> 4) + 4 * q) * kLzPitch + (lane & 15) * 16) = x;
+              *reinterpret_cast<uint4*>(stage + ((lane & 15) >> 3) * kLzStagePlane + ((lane >> 4) + 4 * q) * kLzHalf + (lane & 7) * 16) = x;
               if (!have_r) {                         // row (lane >> 4) + 4q of the sub-block is list entry 16*sub + row of the group
                 const float ss = sum_sq(x);
                 if ((lane & 15) == 15) norm_x[sub * 16 + (lane >> 4) + 4 * q] = ss;
@@ -601,22 +611,22 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
             }
             fetch(gi + 1, sub);
             wave_lds_sync();
-            const char* fp = stage + (lane & 15) * kLzPitch + kg * 16;
+            const char* fp = stage + (kg & 1) * kLzStagePlane + (lane & 15) * kLzHalf + (kg >> 1) * 16;
             bf16x8 bfr[4];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bfr[ks] = *reinterpret_cast<const bf16x8*>(fp + ks * 64);
+            for (int ks = 0; ks < 4; ++ks) bfr[ks] = *reinterpret_cast<const bf16x8*>(fp + ks * 32);
             float pm = 0.f;                          // the floor of Eq. 2
             for (int tl = 0; tl < tiles; tl += 2) {    // two operands at a time: their MFMA chains interleave
-              const char* ap = pk + (tl * 16 + (lane & 15)) * kLzPitch + kg * 16;
+              const char* ap = pk + (kg & 1) * kLzPickPlane + (tl * 16 + (lane & 15)) * kLzHalf + (kg >> 1) * 16;
               bf16x8 a0[4];
 #pragma unroll
-              for (int ks = 0; ks < 4; ++ks) a0[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 64);
+              for (int ks = 0; ks < 4; ++ks) a0[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 32);
               const float4 p0 = *reinterpret_cast<const float4*>(pick_r + tl * 16 + 4 * kg);
               f32x4 acc0 = {0.f, 0.f, 0.f, 0.f};
               if (tl + 1 < tiles) {
                 bf16x8 a1[4];
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) a1[ks] = *reinterpret_cast<const bf16x8*>(ap + 16 * kLzPitch + ks * 64);
+                for (int ks = 0; ks < 4; ++ks) a1[ks] = *reinterpret_cast<const bf16x8*>(ap + 16 * kLzHalf + ks * 32);
                 const float4 p1 = *reinterpret_cast<const float4*>(pick_r + tl * 16 + 16 + 4 * kg);
                 f32x4 acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll

@@ -264,7 +264,14 @@ def test_identical_value_rows_and_score_ties(h, n, b):
     sn = s.cpu().numpy()
     for hh in range(h):
         want = np.argsort(-sn[hh], kind="stable")[:b]
-        np.testing.assert_array_equal(out.pick_order[hh].cpu().numpy(), want)
+        got = out.pick_order[hh].cpu().numpy()
+        if n <= 256:
+            np.testing.assert_array_equal(got, want)
+        else:
+            # long heads take the cosines of pool members and of refreshed tokens from two MFMA shapes, whose
+            # fp32 sums may differ in the last bit: equal scores may swap (a near-tie for the oracle check
+            # above), the score levels, an eighth apart, may not
+            np.testing.assert_array_equal(sn[hh][got], sn[hh][want])
 
 
 def test_lambda_zero_reads_no_values_and_is_stable_topb():
