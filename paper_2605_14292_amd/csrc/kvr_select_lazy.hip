@@ -73,7 +73,7 @@ template <int W, int S, int P> struct LazyCfg {
   static constexpr int TPW = 64 * S;
   // per wave, during the pass: row stage | 256-float exchange | 64 squared norms | TPW inverse norms (first pass)
   static constexpr int kWaveArea = 2 * kLzStagePlane + 1024 + 256 + TPW * 4;
-  static constexpr int kTriBytes = P * (P + 1) / 2 * 4;
+  static constexpr int kTriBytes = 8 * (P / 4) * (P / 4 + 1) * 4;    // rows padded to multiples of four floats
   static constexpr int kRowBytes = P * kLzPitch;
   static constexpr int kMax2 = kTriBytes > kRowBytes ? kTriBytes : kRowBytes;
   static constexpr int kUnion = ((W * kWaveArea > kMax2 ? W * kWaveArea : kMax2) + 15) & ~15;
@@ -91,6 +91,44 @@ template <int W, int S, int P> struct LazyCfg {
   static constexpr int kKeepBytes = kAlias ? 0 : kRowBytes;
   static constexpr int smem_bytes() { return (kFixedFloats + kListFloats) * 4 + kPickBytes + kKeepBytes + kUnion; }
 };
+
+// The pool's cosine triangle keeps row i (columns 0..i) in (i + 4) & ~3 floats, so that four neighbouring columns of a
+// row are one aligned 16-byte store: row i = 4g + r starts at float 4 (g + 1)(2g + r).  Element (i, j), j <= i, sits
+// at start(i) + j; start(i) + j >= start(j) + i holds for i > j as in the packed triangle, so the race reads
+// max(start(i) + j, start(j) + i) without knowing which index is the larger.
+__device__ __forceinline__ int lz_row_start(int i) { return 4 * ((i >> 2) + 1) * (2 * (i >> 2) + (i & 3)); }
+
+// Writes one 32x32 tile of the pool's Gram matrix as cosines into the triangle.  acc comes from the MFMA with the
+// column block J as operand A and the row block I as operand B: lane (row = lane & 31, hf = lane >> 5) holds
+// columns 8R + 4hf .. + 3 of its row in acc[4R .. 4R+3].  The diagonal holds +inf (the row of a pick retires it);
+// what a store writes past the diagonal stays inside the row's padding and is never read.
+__device__ __forceinline__ void lz_write_cos_tile(float* tri, const float* rinv, const f32x16& acc, int I, int J, int lane) {
+  const int hf = lane >> 5;
+  const int row = I * 32 + (lane & 31);
+  const float rrow = rinv[row];
+  float4 rc[4];                                       // the columns' inverse norms, all requested before the first use
+#pragma unroll
+  for (int R = 0; R < 4; ++R) rc[R] = *reinterpret_cast<const float4*>(rinv + J * 32 + 8 * R + 4 * hf);
+  float* dst = tri + lz_row_start(row) + J * 32 + 4 * hf;
+  if (I != J) {                                       // two code paths: no per-element predicate off the diagonal
+#pragma unroll
+    for (int R = 0; R < 4; ++R)
+      *reinterpret_cast<float4*>(dst + 8 * R) = make_float4(acc[4 * R] * rrow * rc[R].x, acc[4 * R + 1] * rrow * rc[R].y,
+                                                            acc[4 * R + 2] * rrow * rc[R].z, acc[4 * R + 3] * rrow * rc[R].w);
+  } else {
+#pragma unroll
+    for (int R = 0; R < 4; ++R) {
+      const int col = J * 32 + 8 * R + 4 * hf;
+      float4 v = make_float4(acc[4 * R] * rrow * rc[R].x, acc[4 * R + 1] * rrow * rc[R].y,
+                             acc[4 * R + 2] * rrow * rc[R].z, acc[4 * R + 3] * rrow * rc[R].w);
+      if (col == row) v.x = INFINITY;
+      if (col + 1 == row) v.y = INFINITY;
+      if (col + 2 == row) v.z = INFINITY;
+      if (col + 3 == row) v.w = INFINITY;
+      if (col <= row) *reinterpret_cast<float4*>(dst + 8 * R) = v;
+    }
+  }
+}
 
 // BUD: per-head budgets are read from a.b_h.
 template <int W, int S, int P, bool BUD>
@@ -437,8 +475,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
             const char* pb = prow + (J * 32 + (lane & 31)) * kLzPitch + hf * 16;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
-              acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pa + ks * 32),
-                                                               *reinterpret_cast<const bf16x8*>(pb + ks * 32), acc[q], 0, 0, 0);
+              acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pb + ks * 32),
+                                                               *reinterpret_cast<const bf16x8*>(pa + ks * 32), acc[q], 0, 0, 0);
           }
         }
         if constexpr (Cfg::kAlias) lds_barrier();      // every wave has read its rows: the triangle takes their place
@@ -449,7 +487,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
             int I = 0;
             while ((I + 1) * (I + 2) / 2 <= tile) ++I;
             const int J = tile - I * (I + 1) / 2;
-            write_cos_tile(tri, pool_r, acc[q], I, J, lane);   // the diagonal holds +inf: the row of a pick retires it
+            lz_write_cos_tile(tri, pool_r, acc[q], I, J, lane);   // the diagonal holds +inf: the row of a pick retires it
           }
         }
       }
@@ -470,7 +508,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
           sq[q] = pool_s[p];
           mq[q] = pool_m[p];
           ja[q] = p * 4 + tri0;                        // column offset of the slot
-          tja[q] = p * (p + 1) * 2 + tri0;             // start of its row
+          tja[q] = lz_row_start(p) * 4 + tri0;         // start of its row
         }
         const int jb = __builtin_amdgcn_readfirstlane(jout < 0 ? 0x7fffffff : jout);
         const float gout_u = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(gout)));
@@ -497,9 +535,9 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
           }
           write_lane2(rec_i, rec_g, i, __float_as_int(amax), np);
           np = __builtin_amdgcn_readfirstlane(np + 1);   // keeps the loop control on the scalar unit
-          // element (i,j) of the triangle sits at max(T(i)+j, T(j)+i); the diagonal (+inf) retires i.
-          // For any i in [-1, 64*NQ) both addresses stay inside the triangle.
-          const int ti4 = i * (i + 1) * 2, i4 = i * 4;
+          // element (i,j) of the triangle sits at max(start(i)+j, start(j)+i); the diagonal (+inf) retires i.
+          // For any i in [-1, 64*NQ) the larger address stays inside the triangle.
+          const int ti4 = lz_row_start(i) * 4, i4 = i * 4;
           float c[NQ];
 #pragma unroll
           for (int q = 0; q < NQ; ++q) {
