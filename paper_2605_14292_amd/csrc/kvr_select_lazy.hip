@@ -205,6 +205,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
   int par = 0;
   int t = 0;
   int kbits = kLzSelBits;        // leading key bits the pool choice looks at (uniform)
+  uint32_t tau_prev = 0;         // the wave's pool threshold of the last epoch (0: none)
   bool starved = false;
   float delta = -1.f;            // refresh threshold: this far below the wave's best outside gain (< 0: not yet known)
 
@@ -318,14 +319,46 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         ekey[k] = ((fresh >> k) & 1u) ? k1 : 0u;
       }
       uint32_t tau = 0;                              // largest value with at least Q fresh keys >= it
-      for (int bit = kbits; bit >= 0; --bit) {
-        if (bit == 32) continue;                     // keys + 1 of full-width keys are searched over 32 bits
-        const uint32_t cand = tau | (1u << bit);
+      auto at_least_q = [&](uint32_t x) -> bool {
         int c = 0;
 #pragma unroll
-        for (int k = 0; k < S; ++k) c += __popcll(__ballot(ekey[k] >= cand));
-        if (c >= Q) tau = cand;
+        for (int k = 0; k < S; ++k) c += __popcll(__ballot(ekey[k] >= x));
+        return c >= Q;
+      };
+      if (kbits == kLzSelBits && tau_prev != 0) {
+        // the value moves little from one epoch to the next: bracket it from the last one with doubling
+        // steps, then bisect (a third of the counts of the bit-wise search on the benchmark inputs)
+        constexpr uint32_t kTop = (1u << kLzSelBits) + 1u;   // no key + 1 reaches this
+        uint32_t lo, hi;                             // at_least_q(lo), !at_least_q(hi)
+        if (at_least_q(tau_prev)) {
+          lo = tau_prev;
+          for (uint32_t d = 1;; d <<= 1) {
+            hi = lo + d;
+            if (hi >= kTop) { hi = kTop; break; }
+            if (!at_least_q(hi)) break;
+            lo = hi;
+          }
+        } else {
+          hi = tau_prev;
+          for (uint32_t d = 1;; d <<= 1) {
+            lo = hi > d ? hi - d : 0u;               // (every key is >= 0)
+            if (lo == 0u || at_least_q(lo)) break;
+            hi = lo;
+          }
+        }
+        while (hi - lo > 1u) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (at_least_q(mid)) lo = mid; else hi = mid;
+        }
+        tau = lo;
+      } else {
+        for (int bit = kbits; bit >= 0; --bit) {
+          if (bit == 32) continue;                   // keys + 1 of full-width keys are searched over 32 bits
+          const uint32_t cand = tau | (1u << bit);
+          if (at_least_q(cand)) tau = cand;
+        }
       }
+      tau_prev = tau;
       if (tau == 0) tau = 1;                         // fewer than Q fresh tokens: all of them join
       int taken = 0;                                 // members with key > tau come first, ties in token order
 #pragma unroll
