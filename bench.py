@@ -190,7 +190,8 @@ def kernel_names(w, b, lam, has_q, mode):
     score = ("kvr::score_kernel" if w.dtype != "bf16" else
              "kvr::score_mfma_kernel" if fits_lds else "kvr::score_wide_kernel")
     if w.dtype == "bf16" and w.n <= 8192 and b <= 1024:
-        tail = ["kvr::select_topb_kernel" if lam == 0.0 else "kvr::select_pool_kernel"]
+        lazy = w.n <= 4096 and b <= 128             # the library's dispatch: lazily refreshed penalties, else the pool kernel
+        tail = ["kvr::select_topb_kernel" if lam == 0.0 else "kvr::select_lazy_kernel" if lazy else "kvr::select_pool_kernel"]
     else:
         tail = ["kvr::select_generic_kernel", "kvr::compact_kernel"]
     return ([score] if has_q else []) + tail
