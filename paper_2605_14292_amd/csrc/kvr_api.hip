@@ -77,6 +77,8 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
   if (kvr::lazy_supported(l, b, lambda))
     return kvr::launch_select_lazy(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                    nullptr, nullptr, st);
+  if (kvr::lazy_f32_supported(l, b, lambda))
+    return kvr::launch_select_lazy_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
   if (kvr::pool_supported(l, b))
     return kvr::launch_select_pool(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
                                    nullptr, nullptr, st, nullptr, true);

@@ -26,6 +26,10 @@
 // pick.  On the benchmark inputs an epoch serves 5-50 picks and a head reads its rows about
 // 2.7 times (once per epoch with a full pass).  Nothing is approximated.
 //
+// F32 rows (the flat-signature mode's mean rows, fp32 caches) run the same epochs with the fp32 MFMAs (32x32x2 for
+// the pool's Gram, 16x16x4 for the passes); their 512-byte rows leave no room for a stage, so the rows of a pass are
+// loaded straight into the operand layout.
+//
 // Layout: one workgroup per head, W wave64s, token j = 64*S*w + 64*k + lane in
 // wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
 // lane's registers for the whole event.
@@ -54,6 +58,11 @@ constexpr int kLzPitch = 272;       // bytes per pool row (256 + 16): conflict-f
 constexpr int kLzHalf = 144;        // bytes between the half rows of a plane (128 + 16)
 constexpr int kLzStagePlane = 16 * kLzHalf;      // 2304 = 9 * 256
 constexpr int kLzPickPlane = 128 * kLzHalf;      // 18432 = 72 * 256
+// fp32 rows: 32 pieces, pool rows 528 bytes apart, half rows of 16 pieces 272 bytes apart; lane (c, kg) of a
+// 16x16x4 operand reads piece 4 j + kg (floats 16 j + 4 kg .. + 3) in step j, kept in plane kg & 1 at slot (kg >> 1) + 2 j
+constexpr int kLzPitchF = 528;
+constexpr int kLzHalfF = 272;
+constexpr int kLzPickPlaneF = 128 * kLzHalfF;    // 34816 = 136 * 256
 constexpr int kLzSelBits = 16;      // leading bits of a gain's ordered key used to choose the pool
 constexpr int kLzChunk = 16;        // rows staged per step and wave in the refresh pass
 
@@ -69,12 +78,16 @@ struct LazyArgs {
 
 // P: pool size, a multiple of 64.  192 was measured where a head has the CU to itself (n > 1024): an epoch less per head,
 // paid back by the larger triangle and the three-slot race, so every configuration runs 128.
-template <int W, int S, int P> struct LazyCfg {
+template <int W, int S, int P, bool F32 = false> struct LazyCfg {
   static constexpr int TPW = 64 * S;
+  // 16-row sub-blocks of the refresh list that a wave has in flight (one "group"): four, or two of fp32 rows
+  static constexpr int GSUB = F32 ? 2 : 4;
+  static constexpr int GR = 16 * GSUB;
   // per wave, during the pass: row stage | 256-float exchange | 64 squared norms | TPW inverse norms (first pass)
-  static constexpr int kWaveArea = 2 * kLzStagePlane + 1024 + 256 + TPW * 4;
+  // (fp32 rows: the inverse norms only)
+  static constexpr int kWaveArea = F32 ? TPW * 4 : 2 * kLzStagePlane + 1024 + 256 + TPW * 4;
   static constexpr int kTriBytes = 8 * (P / 4) * (P / 4 + 1) * 4;    // rows padded to multiples of four floats
-  static constexpr int kRowBytes = P * kLzPitch;
+  static constexpr int kRowBytes = P * (F32 ? kLzPitchF : kLzPitch);
   static constexpr int kMax2 = kTriBytes > kRowBytes ? kTriBytes : kRowBytes;
   static constexpr int kUnion = ((W * kWaveArea > kMax2 ? W * kWaveArea : kMax2) + 15) & ~15;
   // floats: slots 64 | shared 16 | wcount 16 | pool_tok,r,s,m,picked 5*128 | pend 64 |
@@ -83,11 +96,11 @@ template <int W, int S, int P> struct LazyCfg {
   //         areas -> pick flags of the read-out)
   static constexpr int kFixedFloats = 96 + 5 * P + 64 + 3 * kLzMaxB;
   static constexpr int kListFloats = W * (TPW + 64);   // one group of padding past a full list
-  static constexpr int kPickBytes = 2 * kLzPickPlane;
+  static constexpr int kPickBytes = 2 * (F32 ? kLzPickPlaneF : kLzPickPlane);
   static_assert(64 * S * W * 4 <= kUnion, "the pick flags of the read-out fit the union area");
   // Where two workgroups share a CU (W <= 4) the triangle is written over the pool's rows and the rows of an epoch's
   // picks are read from memory again; a workgroup that has the CU to itself keeps the rows and copies them inside LDS.
-  static constexpr bool kAlias = W <= 4;
+  static constexpr bool kAlias = W <= 4 || F32;
   static constexpr int kKeepBytes = kAlias ? 0 : kRowBytes;
   static constexpr int smem_bytes() { return (kFixedFloats + kListFloats) * 4 + kPickBytes + kKeepBytes + kUnion; }
 };
@@ -131,14 +144,20 @@ __device__ __forceinline__ void lz_write_cos_tile(float* tri, const float* rinv,
 }
 
 // BUD: per-head budgets are read from a.b_h.
-template <int W, int S, int P, bool BUD>
+template <int W, int S, int P, bool BUD, bool F32 = false>
 __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(LazyArgs a) {
-  using Cfg = LazyCfg<W, S, P>;
+  using Cfg = LazyCfg<W, S, P, F32>;
+  constexpr int GSUB = Cfg::GSUB;                  // sub-blocks per group of the pass
+  constexpr int GR = Cfg::GR;                      // rows per group
+  constexpr int LPR = F32 ? 32 : 16;               // 16-byte pieces (and lanes of a gather) per row
+  constexpr int kPitch = F32 ? kLzPitchF : kLzPitch;
+  constexpr int kHalf = F32 ? kLzHalfF : kLzHalf;
+  constexpr int kPickPlane = F32 ? kLzPickPlaneF : kLzPickPlane;
   constexpr int TPW = 64 * S;
   constexpr int NT = 64 * W;
   constexpr int Q = P / W;                   // pool members contributed per wave
   constexpr int CH = kLzChunk;
-  constexpr int LPC = CH / 4;
+  constexpr int LPC = F32 ? 8 : CH / 4;            // loads per lane and sub-block
   constexpr int KR = W <= 4 ? TPW / 2 : TPW / 4;   // tokens a wave aims to refresh per pass (measured: c5 / c4)
   constexpr int NB = P / 32;                       // 32-token blocks of the pool
   constexpr int NTRI = NB * (NB + 1) / 2;          // lower-triangular 32x32 tiles of its cosine matrix
@@ -175,18 +194,23 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
   // the head's own budget: its picks are the first b picks of a run for a.b (the rows of the
   // outputs per head), so the epochs stop there
   const int b = BUD ? min(max(a.b_h[blockIdx.x], 0), a.b) : a.b;      // a scalar load: the index is uniform
-  const long long head_off = h * a.stride_head * 2;             // bytes
+  const long long head_off = h * a.stride_head * (F32 ? 4 : 2);   // bytes
   const char* Vh = a.V + head_off;
-  const uint32_t pitch_b = static_cast<uint32_t>(a.stride_tok) * 2u;   // bytes between tokens: a head spans less than 4 GiB (checked by the host)
+  const uint32_t pitch_b = static_cast<uint32_t>(a.stride_tok) * (F32 ? 4u : 2u);   // bytes between tokens: a head spans less than 4 GiB (checked by the host)
   const int base = w * TPW;
   char* stage = uni + w * Cfg::kWaveArea;
   float* scratch = reinterpret_cast<float*>(stage + 2 * kLzStagePlane);
   float* norm_x = scratch + 256;                                 // [64] squared norms of the wave's current 64 rows
-  float* lr2 = norm_x + 64;                                      // [TPW] inverse norms found in the first pass
+  float* lr2 = F32 ? reinterpret_cast<float*>(stage) : norm_x + 64;   // [TPW] inverse norms found in the first pass
   float* lrw = lr_all + w * (TPW + 64);                                 // [TPW] list of tokens to refresh, then their raw maxima
   int32_t* lrw_i = reinterpret_cast<int32_t*>(lrw);
   const unsigned long long below = (1ull << lane) - 1ull;
 
+  // where 16-byte piece p of a pick's row goes in the rows of the picks (without the row's offset)
+  auto pick_piece = [](int p) -> int {
+    if constexpr (F32) return (p & 1) * kLzPickPlaneF + (((p >> 1) & 1) + 2 * (p >> 2)) * 16;
+    else return (p >> 3) * kLzPickPlane + (p & 7) * 16;
+  };
   float s[S], m[S], r[S];
   int pslot[S];                  // >= 0: pool slot of this token in the current epoch; <= -2: position -2 - p in the wave's refresh list; -1: neither
   uint32_t fresh = 0xffffffffu;  // bit k: m[k] covers every pick made so far
@@ -290,11 +314,17 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       }
     }
     auto sum_sq = [](const uint4& x) -> float {
-      const float e[8] = {bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y),
-                          bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)};
       float ss = 0.f;
+      if constexpr (F32) {
+        const float e[4] = {__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
 #pragma unroll
-      for (int q = 0; q < 8; ++q) ss = fmaf(e[q], e[q], ss);
+        for (int q = 0; q < 4; ++q) ss = fmaf(e[q], e[q], ss);
+      } else {
+        const float e[8] = {bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y),
+                            bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)};
+#pragma unroll
+        for (int q = 0; q < 8; ++q) ss = fmaf(e[q], e[q], ss);
+      }
       // the 16 lanes of a row hold its 16-byte chunks and form one DPP row: its last lane ends up with the total
       KVR_DPP_ADD(ss, 0x111, 0xf) KVR_DPP_ADD(ss, 0x112, 0xf) KVR_DPP_ADD(ss, 0x114, 0xf) KVR_DPP_ADD(ss, 0x118, 0xf)
       return ss;
@@ -399,13 +429,15 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       // the pool's rows are requested now; the refresh list is built while they are on their way
       // (all row loads of a thread are issued before the first one is stored: with the loads
       // and stores interleaved, every load waits for the one before it)
-      constexpr int kGat = P * 16 / NT;          // rows per thread
+      constexpr int kGat = P * LPR / NT;         // rows per thread
+      constexpr int kGatRows = NT / LPR;         // rows per round
+      const int gat_row = tid / LPR, gat_piece = tid % LPR;
       uint4 x[kGat];
 #pragma unroll
       for (int k = 0; k < kGat; ++k) {
-        const int tk = pool_tok[k * (NT / 16) + (tid >> 4)];
+        const int tk = pool_tok[k * kGatRows + gat_row];
         const int tkc = tk < 0 ? 0 : tk;                // an empty slot reads row 0 and stores zeros
-        x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(tkc) * pitch_b + (tid & 15) * 16u));
+        x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(tkc) * pitch_b + gat_piece * 16u));
       }
       // ---- the wave's refresh list for this epoch's pass: outside tokens whose bound lies within
       // delta of the wave's best one (all of them in the first pass).  delta is steered so that about
@@ -458,37 +490,46 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         cnt_r = off;
         // pad to a multiple of 64 with a valid row (its results are never read)
         // (at least one group: the first group's rows are requested whether or not the list has entries)
-        const int padded = (cnt_r == 0 ? 64 : (cnt_r + 63) & ~63) + 64;     // ... and one group more: the pass requests a group ahead
+        const int padded = (cnt_r == 0 ? GR : (cnt_r + GR - 1) & ~(GR - 1)) + GR;     // ... and one group more: the pass requests a group ahead
         for (int u = cnt_r + lane; u < padded; u += 64) lrw_i[u] = min(base, n - 1);
       }
       // The rows of the list's first 64 entries are requested here and travel while the pool's triangle is
       // computed and raced; further groups follow inside the pass, one group ahead.
-      uint4 pre[4][LPC];
+      uint4 pre[GSUB][LPC];
       auto fetch = [&](int gi, int sub) {
+        if constexpr (F32) {
+          // straight into the operand layout of the 16x16x4 MFMA: lane (c, kg) holds pieces kg, kg + 4, .. of row c
+          const int row = lrw_i[gi * GR + sub * CH + (lane & 15)];
+          const uint32_t o = static_cast<uint32_t>(row) * pitch_b + (lane >> 4) * 16u;
 #pragma unroll
-        for (int q = 0; q < LPC; ++q) {
-          const int row = lrw_i[gi * 64 + sub * CH + (lane >> 4) + 4 * q];
-          pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(row) * pitch_b + (lane & 15) * 16u));
+          for (int q = 0; q < LPC; ++q) pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (o + q * 64u));
+        } else {
+#pragma unroll
+          for (int q = 0; q < LPC; ++q) {
+            const int row = lrw_i[gi * GR + sub * CH + (lane >> 4) + 4 * q];
+            pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(row) * pitch_b + (lane & 15) * 16u));
+          }
         }
       };
       wave_lds_sync();                               // the list was written by other lanes of this wave
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub) fetch(0, sub);   // (no branch around them: the wait counts of what follows stay exact)
+      for (int sub = 0; sub < GSUB; ++sub) fetch(0, sub);   // (no branch around them: the wait counts of what follows stay exact)
 
       // ================= 2. pool rows -> LDS, cosine triangle on MFMA (written over the rows) =================
       {
 #pragma unroll
         for (int k = 0; k < kGat; ++k) {
-          const int slot = k * (NT / 16) + (tid >> 4);
+          const int slot = k * kGatRows + gat_row;
           if (pool_tok[slot] < 0) x[k] = make_uint4(0u, 0u, 0u, 0u);   // (only here: a select between the loads would make each wait for the one before)
-          *reinterpret_cast<uint4*>(prow + slot * kLzPitch + (tid & 15) * 16) = x[k];
+          *reinterpret_cast<uint4*>(prow + slot * kPitch + gat_piece * 16) = x[k];
         }
         if (!have_r) {
 #pragma unroll
           for (int k = 0; k < kGat; ++k) {
-            const int slot = k * (NT / 16) + (tid >> 4);
-            const float ss = sum_sq(x[k]);
-            if ((tid & 15) == 15) pool_r[slot] = pool_tok[slot] < 0 ? 0.f : 1.0f / (sqrtf(ss) + a.eps);
+            const int slot = k * kGatRows + gat_row;
+            float ss = sum_sq(x[k]);
+            if constexpr (F32) ss += __shfl_up(ss, 16);   // a row spans two 16-lane DPP rows
+            if (gat_piece == LPR - 1) pool_r[slot] = pool_tok[slot] < 0 ? 0.f : 1.0f / (sqrtf(ss) + a.eps);
           }
         }
       }
@@ -504,12 +545,25 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
             int I = 0;
             while ((I + 1) * (I + 2) / 2 <= tile) ++I;
             const int J = tile - I * (I + 1) / 2;
-            const char* pa = prow + (I * 32 + (lane & 31)) * kLzPitch + hf * 16;
-            const char* pb = prow + (J * 32 + (lane & 31)) * kLzPitch + hf * 16;
+            const char* pa = prow + (I * 32 + (lane & 31)) * kPitch + hf * 16;
+            const char* pb = prow + (J * 32 + (lane & 31)) * kPitch + hf * 16;
+            if constexpr (F32) {
+              // 32x32x2: the lane's two k per four MFMAs are floats 8 ks + 4 hf .. + 3 of its row (one LDS request)
+#pragma unroll 4
+              for (int ks = 0; ks < 16; ++ks) {
+                const float4 xa = *reinterpret_cast<const float4*>(pb + ks * 32);
+                const float4 xb = *reinterpret_cast<const float4*>(pa + ks * 32);
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.x, xb.x, acc[q], 0, 0, 0);
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.y, xb.y, acc[q], 0, 0, 0);
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.z, xb.z, acc[q], 0, 0, 0);
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa.w, xb.w, acc[q], 0, 0, 0);
+              }
+            } else {
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-              acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pb + ks * 32),
-                                                               *reinterpret_cast<const bf16x8*>(pa + ks * 32), acc[q], 0, 0, 0);
+              for (int ks = 0; ks < 8; ++ks)
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(pb + ks * 32),
+                                                                 *reinterpret_cast<const bf16x8*>(pa + ks * 32), acc[q], 0, 0, 0);
+            }
           }
         }
         if constexpr (Cfg::kAlias) lds_barrier();      // every wave has read its rows: the triangle takes their place
@@ -619,23 +673,23 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       if constexpr (!Cfg::kAlias) {
         // the rows of this epoch's picks, from the pool's rows to the rows of all picks: 16 threads per row
         for (int i = tid >> 4; i < np; i += NT / 16)
-          *reinterpret_cast<uint4*>(pk + ((tid & 15) >> 3) * kLzPickPlane + (t - np + i) * kLzHalf + (tid & 7) * 16) =
-              *reinterpret_cast<const uint4*>(prow + pend_l[i] * kLzPitch + (tid & 15) * 16);
+          *reinterpret_cast<uint4*>(pk + pick_piece(tid & 15) + (t - np + i) * kHalf) =
+              *reinterpret_cast<const uint4*>(prow + pend_l[i] * kPitch + (tid & 15) * 16);
       } else
       {
         // the rows of this epoch's picks, read again from memory (the triangle has taken the place of
         // the pool's rows): 16 threads per row
-        constexpr int RPI = NT / 16;                   // rows per round
+        constexpr int RPI = NT / LPR;                  // rows per round
         constexpr int kRounds = (kLzMaxPend + RPI - 1) / RPI;
         // (named registers, not an array: the array form of this block ended up in scratch memory)
         auto row_of = [&](int q) -> uint32_t {            // branch-free: rounds past np re-read the last pick's row
-          const int i = min(q * RPI + (tid >> 4), np - 1);
+          const int i = min(q * RPI + tid / LPR, np - 1);
           const int tk = order_l[max(t - np + i, 0)];
-          return static_cast<uint32_t>(min(max(tk, 0), n - 1)) * pitch_b + (tid & 15) * 16u;
+          return static_cast<uint32_t>(min(max(tk, 0), n - 1)) * pitch_b + (tid % LPR) * 16u;
         };
         auto put = [&](int q, const uint4& v) {           // unconditional stores (rounds past np go to the union area, dead
-          const int i = q * RPI + (tid >> 4);             // here), so that every load is issued before the first store waits
-          char* dst = i < np ? pk + ((tid & 15) >> 3) * kLzPickPlane + (t - np + i) * kLzHalf + (tid & 7) * 16 : uni + tid * 16;
+          const int i = q * RPI + tid / LPR;              // here), so that every load is issued before the first store waits
+          char* dst = i < np ? pk + pick_piece(tid % LPR) + (t - np + i) * kHalf : uni + tid * 16;
           *reinterpret_cast<uint4*>(dst) = v;
         };
         static_assert(kRounds == 2 || kRounds == 4 || kRounds == 8, "rounds of the pick-row copy");
@@ -655,7 +709,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         }
       }
       lds_barrier();
-      const int groups = (cnt_r + 63) >> 6;
+      const int groups = (cnt_r + GR - 1) / GR;
       if (groups > 0) {
         const int kg = lane >> 4;
         const int tiles = (t + 15) >> 4;             // 16-row operands of picked rows (0 when nothing is picked yet)
@@ -667,7 +721,58 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         // list is padded by one group of valid rows).
         auto run_group = [&](auto self, auto gi_c) -> void {
           constexpr int gi = decltype(gi_c)::value;
-          float part[4];                             // per 16-row sub-block: max over my four picks of every operand
+          float part[GSUB];                          // per 16-row sub-block: max over my four picks of every operand
+          if constexpr (F32) {
+            // fp32 rows: the registers of the sub-block are its B operand (lane (c, kg): floats 16 j + 4 kg .. + 3 of row
+            // c in pre[sub][j]); the rows of the picks give the A operand in the same order, 32 MFMAs of 16x16x4 per tile
+#pragma unroll
+            for (int sub = 0; sub < GSUB; ++sub) {
+              if (!have_r) {
+                float ss = 0.f;
+#pragma unroll
+                for (int q = 0; q < LPC; ++q) {
+                  const uint4 x = pre[sub][q];
+                  const float e[4] = {__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
+#pragma unroll
+                  for (int u = 0; u < 4; ++u) ss = fmaf(e[u], e[u], ss);
+                }
+                ss += __shfl_xor(ss, 16);            // the four k-groups hold the four quarters of row c
+                ss += __shfl_xor(ss, 32);
+                if (kg == 0) lr2[gi * GR + sub * 16 + (lane & 15)] = 1.0f / (sqrtf(ss) + a.eps);
+              }
+              float pm = 0.f;                        // the floor of Eq. 2
+              for (int tl = 0; tl < tiles; ++tl) {
+                const char* ap = pk + (kg & 1) * kLzPickPlaneF + (tl * 16 + (lane & 15)) * kLzHalfF + (kg >> 1) * 16;
+                float4 av[LPC];
+#pragma unroll
+                for (int q = 0; q < LPC; ++q) av[q] = *reinterpret_cast<const float4*>(ap + q * 32);
+                const float4 p0 = *reinterpret_cast<const float4*>(pick_r + tl * 16 + 4 * kg);
+                f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: even and odd pieces
+#pragma unroll
+                for (int q = 0; q < LPC; q += 2) {
+                  const uint4 x0 = pre[sub][q], x1 = pre[sub][q + 1];
+                  acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q].x, __uint_as_float(x0.x), acc0, 0, 0, 0);
+                  acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q + 1].x, __uint_as_float(x1.x), acc1, 0, 0, 0);
+                  acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q].y, __uint_as_float(x0.y), acc0, 0, 0, 0);
+                  acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q + 1].y, __uint_as_float(x1.y), acc1, 0, 0, 0);
+                  acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q].z, __uint_as_float(x0.z), acc0, 0, 0, 0);
+                  acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q + 1].z, __uint_as_float(x1.z), acc1, 0, 0, 0);
+                  acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q].w, __uint_as_float(x0.w), acc0, 0, 0, 0);
+                  acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[q + 1].w, __uint_as_float(x1.w), acc1, 0, 0, 0);
+                }
+                pm = hw_max(pm, hw_max(hw_max((acc0[0] + acc1[0]) * p0.x, (acc0[1] + acc1[1]) * p0.y),
+                                       hw_max((acc0[2] + acc1[2]) * p0.z, (acc0[3] + acc1[3]) * p0.w)));
+              }
+              fetch(gi + 1, sub);                    // the operand registers are free again
+              pm = hw_max(pm, __shfl_xor(pm, 16));   // the four k-groups hold the maxima over different picks
+              pm = hw_max(pm, __shfl_xor(pm, 32));
+              part[sub] = pm;
+            }
+            // (the list entries of this group have been consumed: entry 16 * sub + c takes its raw maximum)
+#pragma unroll
+            for (int sub = 0; sub < GSUB; ++sub)
+              if (kg == sub) lrw[gi * GR + sub * 16 + (lane & 15)] = part[sub];
+          } else {
 #pragma unroll
           for (int sub = 0; sub < 4; ++sub) {
             wave_lds_sync();
@@ -725,7 +830,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
           const float mx = hw_max(hw_max(sp[0], sp[16]), hw_max(sp[32], sp[48]));
           lrw[gi * 64 + lane] = mx;                  // (the list entries of this group have been consumed)
           if (!have_r) lr2[gi * 64 + lane] = 1.0f / (sqrtf(norm_x[lane]) + a.eps);
-          if constexpr (gi + 1 < S) {
+          }
+          if constexpr ((gi + 1) * GR < TPW) {
             if (gi + 1 < groups) self(self, std::integral_constant<int, gi + 1>{});
           }
         };
@@ -806,14 +912,42 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       if (a.pick_gain) a.pick_gain[ob + u] = -INFINITY;
     }
   }
-  if ((a.K_out || a.V_out) && (!BUD || b > 0))
-    compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
+  if constexpr (!F32) {                                          // (fp32 rows: the caller compacts)
+    if ((a.K_out || a.V_out) && (!BUD || b > 0))
+      compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
+  }
 }
 
 bool lazy_supported(const Layout& lay, int b, float lambda) {
   // (byte offsets inside a head are 32-bit in this kernel)
   return lay.dtype == DT_BF16 && lay.n > 256 && lay.n <= 4096 && b <= kLzMaxB && lambda > 0.0f &&
          static_cast<long long>(lay.n) * lay.stride_tok * 2 < (1ll << 31);
+}
+
+bool lazy_f32_supported(const Layout& lay, int b, float lambda) {
+  return lay.dtype == DT_F32 && lay.n > 256 && lay.n <= 4096 && b <= kLzMaxB && lambda > 0.0f &&
+         static_cast<long long>(lay.n) * lay.stride_tok * 4 < (1ll << 31);
+}
+
+// fp32 rows, selection only (the caller compacts): one workgroup of eight waves per head and CU
+hipError_t launch_select_lazy_f32(const void* V, const float* s, const Layout& lay, int b, float lambda, float eps,
+                                  int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, hipStream_t st) {
+  LazyArgs a;
+  a.b_h = nullptr;
+  a.K = nullptr; a.V = static_cast<const char*>(V); a.s_in = s;
+  a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
+  a.K_out = nullptr; a.V_out = nullptr;
+  a.stride_head = lay.stride_head; a.stride_tok = lay.stride_tok;
+  a.n = lay.n; a.b = b; a.lambda = lambda; a.eps = eps;
+  auto go = [&](auto kern, int smem) -> hipError_t {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(lay.heads), dim3(512), smem, st, a);
+    return hipGetLastError();
+  };
+  if (lay.n <= 2048) return go(&select_lazy_kernel<8, 4, 128, false, true>, LazyCfg<8, 4, 128, true>::smem_bytes());
+  return go(&select_lazy_kernel<8, 8, 128, false, true>, LazyCfg<8, 8, 128, true>::smem_bytes());
 }
 
 hipError_t launch_select_lazy(const void* K, const void* V, const float* s, const Layout& lay, int b,

@@ -181,6 +181,25 @@ def test_score_bound_reduction_mixed_heads(n, b, lam, reps):
     assert torch.equal(sel[0], out.idx_sorted) and torch.equal(sel[1], out.pick_order)
 
 
+@pytest.mark.parametrize("n,b,scale", [(300, 128, 1e-3), (1024, 128, 1e-3), (1024, 64, 1.0), (2048, 100, 1e-3),
+                                       (2049, 128, 1e-3), (4096, 128, 1e-3), (4096, 30, 1.0), (700, 128, 0.05)])
+def test_fp32_long_heads(n, b, scale):
+    # fp32 rows of 257-4096 tokens with b <= 128 take the selection with lazily refreshed penalties on the fp32
+    # MFMAs; scores far below lambda leave every token in play, near-duplicate rows make the penalty bite
+    h = 3
+    K, V, _ = _mk(h, n, 6100 + n + b, torch.float32)
+    g = torch.Generator().manual_seed(n * 7 + b)
+    s = (torch.randn((h, n), generator=g).exp() * scale).to(DEV)
+    V[:, n // 2:] = V[:, : n - n // 2] + 0.05 * V[:, n // 2:]
+    out = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s)
+    torch.cuda.synchronize()
+    rep = _check_heads(W.WORKLOADS["c1"], {"K": K, "V": V, "s": s}, out, b, 0.5, 1e-6, range(h))
+    assert rep["heads"] == h
+    sel = B().kvr_select_greedy(V, s, b, 0.5, 1e-6)
+    torch.cuda.synchronize()
+    assert torch.equal(sel[0], out.idx_sorted) and torch.equal(sel[1], out.pick_order)
+
+
 @pytest.mark.parametrize("n,b,lam", [(150, 16, 0.05), (192, 64, 0.5), (192, 64, 5.0), (256, 100, 0.3), (256, 128, 0.02),
                                      (129, 2, 0.5), (200, 128, 0.5)])
 def test_fp32_rows_with_score_bound_reduction(n, b, lam):
@@ -399,7 +418,8 @@ def _flat_case(seqs, group, n, seed, dtype):
     (3, 8, 192, 64, 0.5, torch.bfloat16), (2, 32, 77, 30, 0.3, torch.bfloat16),
     (2, 5, 256, 128, 1.0, torch.bfloat16), (2, 4, 300, 40, 0.5, torch.bfloat16),
     (2, 6, 130, 20, 0.5, torch.float32), (2, 3, 64, 64, 0.0, torch.bfloat16),
-    (1, 1, 4, 1, 0.2, torch.bfloat16), (4, 64, 10, 1, 0.2, torch.bfloat16), (2, 17, 500, 150, 0.5, torch.bfloat16)])
+    (1, 1, 4, 1, 0.2, torch.bfloat16), (4, 64, 10, 1, 0.2, torch.bfloat16), (2, 17, 500, 150, 0.5, torch.bfloat16),
+    (2, 4, 1024, 128, 0.5, torch.bfloat16), (1, 3, 4096, 100, 0.5, torch.bfloat16), (2, 2, 2100, 128, 2.0, torch.bfloat16)])
 def test_flat_signature_mode(seqs, group, n, b, lam, dtype):
     K, V, s = _flat_case(seqs, group, n, 9000 + n + group, dtype)
     out = B().kvr_retain_flat(K, V, s, group, b, lam, 1e-6)
