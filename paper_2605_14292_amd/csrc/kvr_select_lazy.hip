@@ -1,5 +1,6 @@
 // Greedy selection (paper Sec. 4.1, Algorithm 1) for heads with 256 < n <= 4096
-// bf16 tokens and b <= 128, followed by the compaction of the kept rows.
+// tokens and b <= 128: bf16 rows, followed by the compaction of the kept rows, or
+// fp32 rows (selection only).
 //
 // Exact greedy with lazily refreshed penalties.  Algorithm 1 reads one cosine row per
 // pick, i.e. all of V once per pick.  The running maximum m_i of Eq. 2 only grows, so a
