@@ -485,6 +485,33 @@ def test_non_finite_scores_still_give_distinct_indices_in_range(n, b, dtype, h):
     assert order[2][0] == 5 and order[2][1] == 7          # +inf scores go first, lowest index first
 
 
+@pytest.mark.parametrize("n,b,dtype", [(700, 64, torch.bfloat16), (1024, 128, torch.bfloat16), (3000, 100, torch.bfloat16),
+                                       (5000, 64, torch.bfloat16), (1024, 200, torch.bfloat16), (900, 100, torch.float32)])
+def test_non_finite_scores_on_long_heads_still_give_distinct_indices_in_range(n, b, dtype):
+    # the same promise on the kernels for long heads, whose epochs are data-dependent: every loop ends (an epoch either
+    # picks, or counts towards a limit after which the lowest unpicked tokens fill the list), the indices are distinct
+    # and in range, and the finite heads of the launch are the oracle's
+    h = 6
+    K, V, s = _mk(h, n, 4343 + n, dtype)
+    s = s.clone()
+    s[0, ::3] = float("nan")
+    s[1, :] = float("-inf")
+    s[2, 5] = float("inf"); s[2, 7] = float("inf")
+    s[3, : n - b // 2] = float("nan")            # fewer finite scores than the budget
+    V = V.clone()
+    V[4, 3] = 0                                  # a zero row: zero signature, never penalised
+    out = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s)
+    torch.cuda.synchronize()
+    idx = out.idx_sorted.cpu().numpy()
+    order = out.pick_order.cpu().numpy()
+    for hh in range(h):
+        assert idx[hh].min() >= 0 and idx[hh].max() < n
+        assert len(set(idx[hh].tolist())) == b and np.all(np.diff(idx[hh]) > 0)
+        assert sorted(order[hh].tolist()) == idx[hh].tolist()
+    _check_heads(W.WORKLOADS["c3"], {"K": K, "V": V, "s": s}, out, b, 0.5, 1e-6, [4, 5])
+    assert order[2][0] == 5 and order[2][1] == 7          # +inf scores go first, lowest index first
+
+
 def test_flat_mode_is_deterministic_and_group_one_is_the_per_head_selection():
     K, V, s = _flat_case(4, 1, 160, 77, torch.bfloat16)
     a = B().kvr_retain_flat(K, V, s, 1, 50, 0.5, 1e-6)
