@@ -472,6 +472,8 @@ def test_non_finite_scores_still_give_distinct_indices_in_range(n, b, dtype, h):
     s[3, : n - b // 2] = float("nan")            # fewer finite scores than the budget
     V = V.clone()
     V[4, 3] = 0                                  # a zero row: zero signature, never penalised
+    V[0, 10] = float("nan")                      # non-finite rows (in heads whose picks are unspecified anyway)
+    V[2, 11, 5] = float("inf")
     out = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s)
     torch.cuda.synchronize()
     idx = out.idx_sorted.cpu().numpy()
@@ -500,6 +502,8 @@ def test_non_finite_scores_on_long_heads_still_give_distinct_indices_in_range(n,
     s[3, : n - b // 2] = float("nan")            # fewer finite scores than the budget
     V = V.clone()
     V[4, 3] = 0                                  # a zero row: zero signature, never penalised
+    V[0, 10] = float("nan")                      # non-finite rows (in heads whose picks are unspecified anyway)
+    V[2, 11, 5] = float("inf")
     out = B().kvr_retain(K, V, b, 0.5, 1e-6, s=s)
     torch.cuda.synchronize()
     idx = out.idx_sorted.cpu().numpy()
