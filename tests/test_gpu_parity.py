@@ -421,7 +421,19 @@ def _flat_case(seqs, group, n, seed, dtype):
     (1, 1, 4, 1, 0.2, torch.bfloat16), (4, 64, 10, 1, 0.2, torch.bfloat16), (2, 17, 500, 150, 0.5, torch.bfloat16),
     (2, 4, 1024, 128, 0.5, torch.bfloat16), (1, 3, 4096, 100, 0.5, torch.bfloat16), (2, 2, 2100, 128, 2.0, torch.bfloat16)])
 def test_flat_signature_mode(seqs, group, n, b, lam, dtype):
+    _flat_signature_mode(seqs, group, n, b, lam, dtype, 1.0)
+
+
+@pytest.mark.parametrize("seqs,group,n,b", [(2, 4, 1024, 128), (1, 3, 4096, 128), (2, 2, 700, 64)])
+def test_flat_signature_mode_with_scores_far_below_lambda(seqs, group, n, b):
+    # long sequences whose scores the bound cannot thin out: every mean row is computed and every token stays in
+    # play for the fp32 instance of the long-head kernel
+    _flat_signature_mode(seqs, group, n, b, 0.5, torch.bfloat16, 1e-3)
+
+
+def _flat_signature_mode(seqs, group, n, b, lam, dtype, score_scale):
     K, V, s = _flat_case(seqs, group, n, 9000 + n + group, dtype)
+    s = (s * score_scale).contiguous()
     out = B().kvr_retain_flat(K, V, s, group, b, lam, 1e-6)
     torch.cuda.synchronize()
     V64 = W.to_f64(V).reshape(seqs, group, n, 128)
