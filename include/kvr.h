@@ -80,6 +80,28 @@ typedef struct {
 int kvr_version(void);
 const char* kvr_strerror(int status);
 
+/* Debug aid for the builds of this library, not part of the paper's method.
+ * The library can be built with bounds checks (-DKVR_BOUNDS, libkvr_bounds.so):
+ * the kernels for heads of more than 256 tokens then pass every index they
+ * compute from the data (pool slots, list positions, token indices read back
+ * from tables, triangle addresses, kept tokens) through a range check that
+ * records a failure and clamps the index instead of trapping.
+ *   worst_id (host pointer, required): receives the largest id of a check that
+ *     failed since the last call, 0 when none did.  The ids are listed in the
+ *     kernels' sources (file number * 100 + site).  The product build has no
+ *     checks and always stores 0.
+ * Synchronises the device and clears the record.  Returns KVR_OK, KVR_ERR_ARG
+ * for a NULL pointer, KVR_ERR_HIP when the record could not be read. */
+int kvr_debug_bounds_violation(uint32_t* worst_id);
+
+/* Shows that the record of kvr_debug_bounds_violation works: enqueues one
+ * thread that passes the index 5 with the limit 3 through the range check
+ * (id 199) without accessing memory through it, and stores the checked index
+ * in out[0] (device pointer to one int32, required): 2 in the build with
+ * bounds checks, whose next kvr_debug_bounds_violation then reports 199, and 5
+ * in the product build.  Returns KVR_OK, KVR_ERR_ARG, KVR_ERR_HIP. */
+int kvr_debug_bounds_selftest(int32_t* out, void* stream);
+
 /* Bytes of caller-provided device workspace the calls below need for these
  * arguments (currently always 0).  Host-only; returns a kvr_status. */
 int kvr_workspace_bytes(const kvr_layout* lay, int b, int G, size_t* bytes_out);

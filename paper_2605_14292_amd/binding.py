@@ -7,6 +7,7 @@ calling it without a GPU, raises.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 
@@ -21,7 +22,8 @@ KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1
 EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
            "kvr_select_greedy", "kvr_compact", "kvr_retain",
            "kvr_signature_flat", "kvr_compact_shared", "kvr_compact_inplace", "kvr_score_prior", "kvr_score_pool", "kvr_retain_flat",
-           "kvr_retain_budgeted", "kvr_retain_budgeted_static")
+           "kvr_retain_budgeted", "kvr_retain_budgeted_static", "kvr_debug_bounds_violation",
+           "kvr_debug_bounds_selftest")
 
 
 class kvr_layout(ctypes.Structure):
@@ -36,12 +38,12 @@ class KvrError(RuntimeError):
         super().__init__(f"{where}: {strerror(status)} ({status})")
 
 
-def _load() -> ctypes.CDLL:
-    if not os.path.exists(LIB_PATH):
+def _load(path: str = LIB_PATH) -> ctypes.CDLL:
+    if not os.path.exists(path):
         raise ImportError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2605_14292_amd.build` "
+            f"{path} is missing: build it with `python -m paper_2605_14292_amd.build` "
             "(there is no fallback path)")
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     vp, i32, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     lp = ctypes.POINTER(kvr_layout)
     lib.kvr_version.restype = i32
@@ -76,14 +78,47 @@ def _load() -> ctypes.CDLL:
     lib.kvr_retain_budgeted_static.restype = i32
     lib.kvr_retain_budgeted_static.argtypes = [vp, vp, vp, i32, vp, lp, vp, vp, i32, vp, vp, vp, f32, f32,
                                                vp, vp, vp, vp, vp, vp, vp]
+    lib.kvr_debug_bounds_violation.restype = i32
+    lib.kvr_debug_bounds_violation.argtypes = [ctypes.POINTER(ctypes.c_uint32)]
+    lib.kvr_debug_bounds_selftest.restype = i32
+    lib.kvr_debug_bounds_selftest.argtypes = [vp, vp]
     return lib
 
 
 _lib = _load()
+BOUNDS_LIB_PATH = os.path.join(os.path.dirname(LIB_PATH), "libkvr_bounds.so")
 
 
 def lib() -> ctypes.CDLL:
     return _lib
+
+
+@contextlib.contextmanager
+def bounds_checked_library():
+    """Routes every call of this module through the debug build with bounds checks (libkvr_bounds.so, built by
+    `python -m paper_2605_14292_amd.build`) for the duration of the block."""
+    global _lib
+    product, _lib = _lib, _load(BOUNDS_LIB_PATH)
+    try:
+        yield _lib
+    finally:
+        _lib = product
+
+
+def kvr_debug_bounds_selftest(stream=None) -> int:
+    """The index that the range check made of 5 with the limit 3: 2 with bounds checks, 5 without."""
+    import torch
+    out = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    _check(_lib.kvr_debug_bounds_selftest(_ptr(out), _stream(stream)), "kvr_debug_bounds_selftest")
+    torch.cuda.synchronize()
+    return int(out.item())
+
+
+def kvr_debug_bounds_violation() -> int:
+    """Largest id of a bounds check that failed since the last call (0: none; always 0 in the product build)."""
+    worst = ctypes.c_uint32(0xdeadbeef)
+    _check(_lib.kvr_debug_bounds_violation(ctypes.byref(worst)), "kvr_debug_bounds_violation")
+    return int(worst.value)
 
 
 def strerror(status: int) -> str:

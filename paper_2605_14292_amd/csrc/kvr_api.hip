@@ -120,6 +120,19 @@ extern "C" {
 
 int kvr_version(void) { return 1; }
 
+int kvr_debug_bounds_selftest(int32_t* out, void* stream) {
+  if (!out) return KVR_ERR_ARG;
+  return kvr::launch_bounds_selftest(out, static_cast<hipStream_t>(stream)) == hipSuccess ? KVR_OK : KVR_ERR_HIP;
+}
+
+int kvr_debug_bounds_violation(uint32_t* worst_id) {
+  if (!worst_id) return KVR_ERR_ARG;
+  const unsigned int a = kvr::bounds_bad_lazy(), b = kvr::bounds_bad_pool();
+  if (a == 0xffffffffu || b == 0xffffffffu) return KVR_ERR_HIP;
+  *worst_id = a > b ? a : b;
+  return KVR_OK;
+}
+
 const char* kvr_strerror(int status) {
   switch (status) {
     case KVR_OK: return "ok";

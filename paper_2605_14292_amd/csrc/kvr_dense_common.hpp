@@ -2,6 +2,10 @@
 // reductions, the padded LDS row stage and its MFMA fragment reads.
 #pragma once
 #include "kvr_device.hpp"
+#include "kvr_bounds.hpp"
+#ifndef KVR_BOUNDS_FILE
+#define KVR_BOUNDS_FILE 0   // (a source file that reports its bounds checks defines its number before this header)
+#endif
 
 namespace kvr {
 
@@ -310,7 +314,7 @@ __device__ __forceinline__ void compact_rows(const char* K, const char* V, char*
 #pragma unroll
       for (int k = 0; k < BATCH; ++k) {
         const int t = min(first + g + k * G, b - 1);
-        const long long src = base + min(max(il[t], 0), n - 1) * stride_tok * 2;
+        const long long src = base + min(max(kvr_ix(il[t], n, KVR_BOUNDS_FILE * 100 + 90), 0), n - 1) * stride_tok * 2;   // (x90: kept token)
         kr[k] = *reinterpret_cast<const uint4*>(K + src);
         vr[k] = *reinterpret_cast<const uint4*>(V + src);
       }
@@ -318,7 +322,7 @@ __device__ __forceinline__ void compact_rows(const char* K, const char* V, char*
 #pragma unroll
       for (int k = 0; k < BATCH; ++k) {
         const int t = min(first + g + k * G, b - 1);
-        const long long src = base + min(max(il[t], 0), n - 1) * stride_tok * 2;
+        const long long src = base + min(max(kvr_ix(il[t], n, KVR_BOUNDS_FILE * 100 + 90), 0), n - 1) * stride_tok * 2;   // (x90: kept token)
         kr[k] = vr[k] = make_uint4(0u, 0u, 0u, 0u);
         if (K_out) kr[k] = *reinterpret_cast<const uint4*>(K + src);
         if (V_out) vr[k] = *reinterpret_cast<const uint4*>(V + src);

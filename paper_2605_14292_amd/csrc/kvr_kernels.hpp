@@ -142,4 +142,12 @@ hipError_t launch_select_lazy_f32(const void* V, const float* s, const Layout& l
                                   float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                                   hipStream_t st);
 
+// Debug build only (-DKVR_BOUNDS): the largest id of a failed bounds check in the kernels of the source file since
+// the last call (0: none; the product build always returns 0).  Synchronises the device.
+unsigned int bounds_bad_lazy();
+unsigned int bounds_bad_pool();
+// One thread range-checks the index 5 against the limit 3 (id 199) and stores what the check returned (2 in the
+// debug build, 5 in the product build) in out[0]; no memory is accessed through the index.
+hipError_t launch_bounds_selftest(int32_t* out, hipStream_t st);
+
 }  // namespace kvr

@@ -34,6 +34,7 @@
 // Layout: one workgroup per head, W wave64s, token j = 64*S*w + 64*k + lane in
 // wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
 // lane's registers for the whole event.
+#define KVR_BOUNDS_FILE 1   // ids 1xx of the debug build's bounds checks (kvr_bounds.hpp)
 #include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 #include <type_traits>
@@ -404,7 +405,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         const int eq_before = __popcll(eqm & below);
         const bool in = above || (equal && eq_before < need_eq);
         const unsigned long long inm = __ballot(in);
-        const int slot = w * Q + rank_base + __popcll(inm & below);
+        const int slot = w * Q + kvr_ix_if(in, rank_base + __popcll(inm & below), Q, 101);   // 101: a member's place in the wave's share
         pslot[k] = in ? slot : -1;
         if (in) {
           pool_tok[slot] = tok_of(k) < n ? tok_of(k) : -1;
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
 #pragma unroll
       for (int k = 0; k < kGat; ++k) {
         const int tk = pool_tok[k * kGatRows + gat_row];
-        const int tkc = tk < 0 ? 0 : tk;                // an empty slot reads row 0 and stores zeros
+        const int tkc = kvr_ix(tk < 0 ? 0 : tk, n, 103);   // an empty slot reads row 0 and stores zeros (103: token of a pool member)
         x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(tkc) * pitch_b + gat_piece * 16u));
       }
       // ---- the wave's refresh list for this epoch's pass: outside tokens whose bound lies within
@@ -482,7 +483,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
           const bool mem = go[k] >= thr_r && go[k] > -INFINITY;     // (go is -inf for pool members and dead tokens)
           const unsigned long long mm = __ballot(mem);
           if (mem) {
-            const int pos = off + __popcll(mm & below);
+            const int pos = kvr_ix(off + __popcll(mm & below), TPW, 102);   // 102: position in the refresh list
             lrw_i[pos] = tok_of(k);
             pslot[k] = -2 - pos;
           }
@@ -500,14 +501,14 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       auto fetch = [&](int gi, int sub) {
         if constexpr (F32) {
           // straight into the operand layout of the 16x16x4 MFMA: lane (c, kg) holds pieces kg, kg + 4, .. of row c
-          const int row = lrw_i[gi * GR + sub * CH + (lane & 15)];
+          const int row = kvr_ix(lrw_i[gi * GR + sub * CH + (lane & 15)], n, 104);   // 104: token of a list entry
           const uint32_t o = static_cast<uint32_t>(row) * pitch_b + (lane >> 4) * 16u;
 #pragma unroll
           for (int q = 0; q < LPC; ++q) pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (o + q * 64u));
         } else {
 #pragma unroll
           for (int q = 0; q < LPC; ++q) {
-            const int row = lrw_i[gi * GR + sub * CH + (lane >> 4) + 4 * q];
+            const int row = kvr_ix(lrw_i[gi * GR + sub * CH + (lane >> 4) + 4 * q], n, 104);
             pre[sub][q] = *reinterpret_cast<const uint4*>(Vh + (static_cast<uint32_t>(row) * pitch_b + (lane & 15) * 16u));
           }
         }
@@ -630,7 +631,12 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
 #pragma unroll
           for (int q = 0; q < NQ; ++q) {
             const int x0 = ti4 + ja[q], x1 = tja[q] + i4;
-            c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(x0 > x1 ? x0 : x1)));
+#ifdef KVR_BOUNDS
+            const int xa = kvr_ix(((x0 > x1 ? x0 : x1) - tri0) >> 2, Cfg::kTriBytes / 4, 105) * 4 + tri0;   // 105: triangle element of the race
+#else
+            const int xa = x0 > x1 ? x0 : x1;
+#endif
+            c[q] = *reinterpret_cast<lds_fp>(static_cast<uintptr_t>(static_cast<unsigned>(xa)));
           }
 #pragma unroll
           for (int q = 0; q < NQ; ++q) mq[q] = hw_max(mq[q], c[q]);
@@ -638,8 +644,10 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
 #pragma unroll
         for (int q = 0; q < NQ; ++q) pool_m[lane + 64 * q] = mq[q];   // the pool's m is authoritative
         if (lane < np) {
-          order_l[t + lane] = pool_tok[rec_i]; gain_l[t + lane] = __int_as_float(rec_g);
-          pend_l[lane] = rec_i; pick_r[t + lane] = pool_r[rec_i]; pool_picked[rec_i] = 1;
+          const int ri = kvr_ix(rec_i, P, 106);          // 106: pool slot of a pick
+          const int tp = kvr_ix(t + lane, kLzMaxB, 107); // 107: number of a pick
+          order_l[tp] = pool_tok[ri]; gain_l[tp] = __int_as_float(rec_g);
+          pend_l[lane] = ri; pick_r[tp] = pool_r[ri]; pool_picked[ri] = 1;
         }
         t += np;
         if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
@@ -674,8 +682,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       if constexpr (!Cfg::kAlias) {
         // the rows of this epoch's picks, from the pool's rows to the rows of all picks: 16 threads per row
         for (int i = tid >> 4; i < np; i += NT / 16)
-          *reinterpret_cast<uint4*>(pk + pick_piece(tid & 15) + (t - np + i) * kHalf) =
-              *reinterpret_cast<const uint4*>(prow + pend_l[i] * kPitch + (tid & 15) * 16);
+          *reinterpret_cast<uint4*>(pk + pick_piece(tid & 15) + kvr_ix(t - np + i, kLzMaxB, 108) * kHalf) =   // 108: row of a pick
+              *reinterpret_cast<const uint4*>(prow + kvr_ix(pend_l[i], P, 109) * kPitch + (tid & 15) * 16);   // 109: its pool slot
       } else
       {
         // the rows of this epoch's picks, read again from memory (the triangle has taken the place of
@@ -690,7 +698,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         };
         auto put = [&](int q, const uint4& v) {           // unconditional stores (rounds past np go to the union area, dead
           const int i = q * RPI + tid / LPR;              // here), so that every load is issued before the first store waits
-          char* dst = i < np ? pk + pick_piece(tid % LPR) + (t - np + i) * kHalf : uni + tid * 16;
+          char* dst = i < np ? pk + pick_piece(tid % LPR) + kvr_ix(t - np + i, kLzMaxB, 108) * kHalf : uni + tid * 16;
           *reinterpret_cast<uint4*>(dst) = v;
         };
         static_assert(kRounds == 2 || kRounds == 4 || kRounds == 8, "rounds of the pick-row copy");
@@ -713,7 +721,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       const int groups = (cnt_r + GR - 1) / GR;
       if (groups > 0) {
         const int kg = lane >> 4;
-        const int tiles = (t + 15) >> 4;             // 16-row operands of picked rows (0 when nothing is picked yet)
+        const int tiles = kvr_ix((t + 15) >> 4, kLzMaxB / 16 + 1, 110);   // 16-row operands of picked rows (0 when nothing is picked yet; 110)
         // One 64-row group of the list is in flight (the first since before the race): the registers of a
         // 16-row sub-block are refilled for the next group as soon as they have been written to the stage.
         // The groups are unrolled as nested conditionals (group g + 1 inside group g), not a loop: the
@@ -846,7 +854,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
         for (int k = 0; k < S; ++k) {
           const int ps = pslot[k];
           if (ps <= -2) {
-            const int pos = -2 - ps;
+            const int pos = kvr_ix(-2 - ps, TPW, 111);   // 111: list position of a refreshed token
             if (!have_r) r[k] = lr2[pos];
             m[k] = hw_max(m[k], lrw[pos] * r[k]);
           }
@@ -865,7 +873,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
 #pragma unroll
   for (int k = 0; k < S; ++k) flag[base + 64 * k + lane] = 0;
   lds_barrier();
-  for (int u = tid; u < t; u += NT) flag[order_l[u]] = 1;
+  for (int u = tid; u < t; u += NT) flag[kvr_ix(order_l[u], 64 * S * W, 112)] = 1;   // 112: token of a pick
   lds_barrier();
   if (starved) {
     if (tid == 0) {                                  // non-finite input only: lowest unpicked tokens fill up
@@ -917,6 +925,20 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
     if ((a.K_out || a.V_out) && (!BUD || b > 0))
       compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
   }
+}
+
+KVR_BOUNDS_TU(lazy)
+
+// Debug aid: one thread passes the index 5 with the limit 3 through the range check (id 199); nothing is
+// accessed.  The bounds build then reports 199, the product build nothing.
+__global__ void bounds_selftest_kernel(int32_t* out) {
+  const int v = kvr_ix(5, 3, 199);
+  if (out) out[0] = v;
+}
+
+hipError_t launch_bounds_selftest(int32_t* out, hipStream_t st) {
+  hipLaunchKernelGGL(bounds_selftest_kernel, dim3(1), dim3(1), 0, st, out);
+  return hipGetLastError();
 }
 
 bool lazy_supported(const Layout& lay, int b, float lambda) {

@@ -26,6 +26,7 @@
 // wave w, lane `lane`, slot k; score, m and inverse norm of a token stay in its
 // lane's registers for the whole event (slots 0-7; with sixteen slots per lane,
 // n > 4096, the state of slots 8-15 lives in LDS, one column per thread).
+#define KVR_BOUNDS_FILE 2   // ids 2xx of the debug build's bounds checks (kvr_bounds.hpp)
 #include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 #include <type_traits>
@@ -285,7 +286,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         const int eq_before = __popcll(eqm & ((1ull << lane) - 1ull));
         const bool in = above || (equal && eq_before < need_eq);
         const unsigned long long inm = __ballot(in);
-        const int slot = w * Q + rank_base + __popcll(inm & ((1ull << lane) - 1ull));
+        const int slot = w * Q + kvr_ix_if(in, rank_base + __popcll(inm & ((1ull << lane) - 1ull)), Q, 201);   // 201: a member's place in the wave's share
         set_p(k, in ? slot : -1);
         if (in) {
           pool_tok[slot] = tok_of(k) < n ? tok_of(k) : -1;
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #pragma unroll
         for (int k = 0; k < kGat; ++k) {
           const int tk = pool_tok[k * (NT / 16) + (tid >> 4)];
-          const int tkc = tk < 0 ? 0 : tk;              // an empty slot reads row 0 and stores zeros
+          const int tkc = kvr_ix(tk < 0 ? 0 : tk, n, 203);   // an empty slot reads row 0 and stores zeros (203: token of a pool member)
           x[k] = *reinterpret_cast<const uint4*>(Vh + (static_cast<long long>(tkc) * a.stride_tok + (tid & 15) * 8) * 2);
         }
 #pragma unroll
@@ -389,8 +390,11 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
         }
         pool_m[p0] = m0; pool_m[p1] = m1;            // the pool's m is authoritative
         if (lane < np) {
-          order_l[t + lane] = pool_tok[rec_i]; gain_l[t + lane] = __int_as_float(rec_g);
-          pend_l[lane] = rec_i; pend_r[lane] = pool_r[rec_i]; pool_picked[rec_i] = 1;
+          const int ri = kvr_ix(rec_i, kPool, 206);      // 206: pool slot of a pick
+          const int tp = kvr_ix(t + lane, bcap, 207);    // 207: number of a pick
+          order_l[tp] = pool_tok[ri]; gain_l[tp] = __int_as_float(rec_g);
+          const int pl = kvr_ix(lane, kPoolMaxPend, 208);   // 208: picks of one epoch
+          pend_l[pl] = ri; pend_r[pl] = pool_r[ri]; pool_picked[ri] = 1;
         }
         t += np;
         if (lane == 0) { shared_i[0] = np; shared_i[1] = t; shared_i[2] = stop; }
@@ -436,7 +440,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #pragma unroll
         for (int at = 0; at < 2; ++at) {
           const int pi = at * 16 + (lane & 15);
-          const int ps = pi < np ? pend_l[pi] : -1;
+          const int ps = pi < np ? kvr_ix(pend_l[pi], kPool, 209) : -1;   // 209: pool slot of a pending row
 #pragma unroll
           for (int ks = 0; ks < 4; ++ks) {
             uint4 x = make_uint4(0u, 0u, 0u, 0u);
@@ -547,7 +551,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
 #pragma unroll
   for (int k = 0; k < S; ++k) flag[base + 64 * k + lane] = 0;
   lds_barrier();
-  for (int u = tid; u < t; u += NT) flag[order_l[u]] = 1;
+  for (int u = tid; u < t; u += NT) flag[kvr_ix(order_l[u], 64 * S * W, 212)] = 1;   // 212: token of a pick
   lds_barrier();
   if (starved) {
     if (tid == 0) {                                  // non-finite input only: lowest unpicked tokens fill up
@@ -598,6 +602,8 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_pool_kernel(P
   if ((a.K_out || a.V_out) && (!BUD || b > 0))
     compact_rows<(NT >= 512 ? 2 : 4)>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idxs_l, n, b, ob, tid, NT);
 }
+
+KVR_BOUNDS_TU(pool)
 
 bool pool_supported(const Layout& lay, int b) {
   return lay.dtype == DT_BF16 && lay.n > 256 && lay.n <= 8192 && b <= kPoolMaxB;

@@ -29,6 +29,21 @@ def test_version_and_strerror():
         assert isinstance(B.strerror(code), str) and B.strerror(code)
 
 
+def test_debug_entry_points_of_the_product_build():
+    # the product build has no bounds checks: its record is always empty (no GPU call is made)
+    L = B.lib()
+    worst = ctypes.c_uint32(77)
+    assert L.kvr_debug_bounds_violation(ctypes.byref(worst)) == 0 and worst.value == 0
+    assert L.kvr_debug_bounds_violation(None) == B.KVR_ERR_ARG
+    assert L.kvr_debug_bounds_selftest(None, None) == B.KVR_ERR_ARG
+
+
+def test_the_build_with_bounds_checks_exports_the_same_symbols():
+    lib = ctypes.CDLL(B.BOUNDS_LIB_PATH)
+    for nm in _declared():
+        assert hasattr(lib, nm), nm
+
+
 def _lay(heads=2, n=64, d=128, dtype=B.KVR_BF16, sh=None, st=None):
     st = d if st is None else st
     sh = n * st if sh is None else sh
