@@ -59,7 +59,8 @@ typedef enum {
   KVR_ERR_ARG = -1,        /* NULL pointer, bad size, b<1, b>n, lambda<0/NaN, G<1, misaligned */
   KVR_ERR_UNSUPPORTED = -2,/* d != 128, unknown dtype, n or G above the limits below */
   KVR_ERR_WORKSPACE = -3,  /* workspace smaller than kvr_workspace_bytes() */
-  KVR_ERR_HIP = -4         /* a HIP launch or runtime call failed */
+  KVR_ERR_HIP = -4,        /* a HIP launch or runtime call failed */
+  KVR_ERR_NONFINITE = -5   /* kvr_debug_validate_finite found a NaN or an infinity */
 } kvr_status;
 
 typedef enum { KVR_F32 = 0, KVR_BF16 = 1 } kvr_dtype;
@@ -101,6 +102,18 @@ int kvr_debug_bounds_violation(uint32_t* worst_id);
  * bounds checks, whose next kvr_debug_bounds_violation then reports 199, and 5
  * in the product build.  Returns KVR_OK, KVR_ERR_ARG, KVR_ERR_HIP. */
 int kvr_debug_bounds_selftest(int32_t* out, void* stream);
+
+/* Optional validator of an event's inputs, for debugging: Algorithm 1 (Sec. 4.1)
+ * is stated for finite scores and rows, and the selection calls promise only
+ * distinct, in-range indices for anything else.  Scans K and V ([heads, n, d] in
+ * `lay`; either may be NULL), Q ([heads, G, d] dense, of lay's dtype; NULL with
+ * G = 0: none) and s ([heads, n] fp32; NULL: none) for NaN and +-inf.
+ * Unlike every other call it synchronises `stream` (and reads one flag back).
+ * Returns KVR_OK when every value is finite, KVR_ERR_NONFINITE otherwise;
+ * KVR_ERR_ARG / KVR_ERR_UNSUPPORTED for a bad layout, misaligned pointers, all
+ * four pointers NULL, or Q with G outside [1, KVR_MAX_G]; KVR_ERR_HIP. */
+int kvr_debug_validate_finite(const void* K, const void* V, const void* Q, int G, const float* s,
+                              const kvr_layout* lay, void* stream);
 
 /* Bytes of caller-provided device workspace the calls below need for these
  * arguments (currently always 0).  Host-only; returns a kvr_status. */

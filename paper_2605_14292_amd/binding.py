@@ -17,13 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libkvr.so")
 
 KVR_F32, KVR_BF16 = 0, 1
-KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP = 0, -1, -2, -3, -4
+KVR_OK, KVR_ERR_ARG, KVR_ERR_UNSUPPORTED, KVR_ERR_WORKSPACE, KVR_ERR_HIP, KVR_ERR_NONFINITE = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("kvr_version", "kvr_strerror", "kvr_workspace_bytes", "kvr_score",
            "kvr_select_greedy", "kvr_compact", "kvr_retain",
            "kvr_signature_flat", "kvr_compact_shared", "kvr_compact_inplace", "kvr_score_prior", "kvr_score_pool", "kvr_retain_flat",
            "kvr_retain_budgeted", "kvr_retain_budgeted_static", "kvr_debug_bounds_violation",
-           "kvr_debug_bounds_selftest")
+           "kvr_debug_bounds_selftest", "kvr_debug_validate_finite")
 
 
 class kvr_layout(ctypes.Structure):
@@ -82,6 +82,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.kvr_debug_bounds_violation.argtypes = [ctypes.POINTER(ctypes.c_uint32)]
     lib.kvr_debug_bounds_selftest.restype = i32
     lib.kvr_debug_bounds_selftest.argtypes = [vp, vp]
+    lib.kvr_debug_validate_finite.restype = i32
+    lib.kvr_debug_validate_finite.argtypes = [vp, vp, vp, i32, vp, lp, vp]
     return lib
 
 
@@ -103,6 +105,26 @@ def bounds_checked_library():
         yield _lib
     finally:
         _lib = product
+
+
+def kvr_debug_validate_finite(K=None, V=None, Q=None, s=None, lay=None, stream=None) -> bool:
+    """True when K, V, Q and s (those given) hold only finite values.  Synchronises the stream."""
+    rows = K if K is not None else V
+    _need_cuda(K, V, Q, s)
+    lay = layout_of(rows) if lay is None else lay
+    for t in (K, V):
+        if t is not None and (t.shape[0], t.shape[1], t.stride(0), t.stride(1)) != (lay.heads, lay.n, lay.stride_head, lay.stride_tok):
+            raise ValueError("K and V must share the layout")
+    if s is not None and (tuple(s.shape) != (lay.heads, lay.n) or not s.is_contiguous() or s.dtype != torch.float32):
+        raise ValueError("s must be a dense fp32 [heads, n] tensor")
+    if Q is not None and (Q.shape[0] != lay.heads or not Q.is_contiguous()):
+        raise ValueError("Q must be a dense [heads, G, d] tensor")
+    G = 0 if Q is None else int(Q.shape[1])
+    rc = _lib.kvr_debug_validate_finite(_ptr(K), _ptr(V), _ptr(Q), G, _ptr(s), ctypes.byref(lay), _stream(stream))
+    if rc == KVR_ERR_NONFINITE:
+        return False
+    _check(rc, "kvr_debug_validate_finite")
+    return True
 
 
 def kvr_debug_bounds_selftest(stream=None) -> int:

@@ -120,6 +120,20 @@ extern "C" {
 
 int kvr_version(void) { return 1; }
 
+int kvr_debug_validate_finite(const void* K, const void* V, const void* Q, int G, const float* s,
+                              const kvr_layout* lay, void* stream) {
+  const int rc = check_layout(lay);
+  if (rc) return rc;
+  if (!K && !V && !Q && !s) return KVR_ERR_ARG;
+  if (Q && G < 1) return KVR_ERR_ARG;
+  if (Q && G > KVR_MAX_G) return KVR_ERR_UNSUPPORTED;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(Q) || !aligned16(s)) return KVR_ERR_ARG;
+  int found = 0;
+  if (kvr::validate_finite(K, V, Q, G, s, to_dev(lay), static_cast<hipStream_t>(stream), &found) != hipSuccess)
+    return KVR_ERR_HIP;
+  return found ? KVR_ERR_NONFINITE : KVR_OK;
+}
+
 int kvr_debug_bounds_selftest(int32_t* out, void* stream) {
   if (!out) return KVR_ERR_ARG;
   return kvr::launch_bounds_selftest(out, static_cast<hipStream_t>(stream)) == hipSuccess ? KVR_OK : KVR_ERR_HIP;
@@ -140,6 +154,7 @@ const char* kvr_strerror(int status) {
     case KVR_ERR_UNSUPPORTED: return "unsupported shape or dtype";
     case KVR_ERR_WORKSPACE: return "workspace too small";
     case KVR_ERR_HIP: return "HIP launch failed";
+    case KVR_ERR_NONFINITE: return "non-finite value in the inputs";
     default: return "unknown kvr status";
   }
 }

@@ -142,6 +142,11 @@ hipError_t launch_select_lazy_f32(const void* V, const float* s, const Layout& l
                                   float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain,
                                   hipStream_t st);
 
+// Debug validator: found = 1 when K, V ([heads, n, d] in lay; either may be null), Q ([heads, G, d] dense, may
+// be null) or s ([heads, n], may be null) hold a NaN or an infinity.  Synchronises the stream.
+hipError_t validate_finite(const void* K, const void* V, const void* Q, int G, const float* s, const Layout& lay,
+                           hipStream_t st, int* found);
+
 // Debug build only (-DKVR_BOUNDS): the largest id of a failed bounds check in the kernels of the source file since
 // the last call (0: none; the product build always returns 0).  Synchronises the device.
 unsigned int bounds_bad_lazy();

@@ -36,6 +36,17 @@ def test_debug_entry_points_of_the_product_build():
     assert L.kvr_debug_bounds_violation(ctypes.byref(worst)) == 0 and worst.value == 0
     assert L.kvr_debug_bounds_violation(None) == B.KVR_ERR_ARG
     assert L.kvr_debug_bounds_selftest(None, None) == B.KVR_ERR_ARG
+    lay = _lay()
+    fake = ctypes.c_void_p(0x1000)
+    val = L.kvr_debug_validate_finite
+    assert val(None, None, None, 0, None, ctypes.byref(lay), None) == B.KVR_ERR_ARG
+    assert val(fake, None, None, 0, None, None, None) == B.KVR_ERR_ARG
+    assert val(fake, None, fake, 0, None, ctypes.byref(lay), None) == B.KVR_ERR_ARG
+    assert val(fake, None, fake, 257, None, ctypes.byref(lay), None) == B.KVR_ERR_UNSUPPORTED
+    assert val(ctypes.c_void_p(0x1004), None, None, 0, None, ctypes.byref(lay), None) == B.KVR_ERR_ARG
+    bad_d = _lay(d=64)
+    assert val(fake, None, None, 0, None, ctypes.byref(bad_d), None) == B.KVR_ERR_UNSUPPORTED
+    assert "finite" in B.strerror(B.KVR_ERR_NONFINITE)
 
 
 def test_the_build_with_bounds_checks_exports_the_same_symbols():

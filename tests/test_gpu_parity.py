@@ -528,6 +528,33 @@ def test_non_finite_scores_on_long_heads_still_give_distinct_indices_in_range(n,
     assert order[2][0] == 5 and order[2][1] == 7          # +inf scores go first, lowest index first
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_debug_validator_finds_non_finite_inputs(dtype):
+    h, n, G = 5, 300, 3
+    K, V, s = _mk(h, n, 515, dtype)
+    Q = torch.randn((h, G, 128)).to(dtype).to(DEV)
+    v = B().kvr_debug_validate_finite
+    assert v(K=K, V=V, Q=Q, s=s)
+    assert v(K=K) and v(V=V) and v(s=s, lay=B().layout_of(K)) and v(K=K, Q=Q)
+    for which, plant in (("K", (4, 299, 127, float("nan"))), ("V", (0, 0, 0, float("inf"))),
+                         ("V", (2, 150, 64, float("-inf"))), ("Q", (3, 2, 5, float("nan")))):
+        t = {"K": K, "V": V, "Q": Q}[which].clone()
+        t[plant[0], plant[1], plant[2]] = plant[3]
+        args = {"K": K, "V": V, "Q": Q, "s": s}
+        args[which] = t
+        assert not v(**args), which
+    for val in (float("nan"), float("inf"), float("-inf")):
+        s2 = s.clone(); s2[h - 1, n - 1] = val
+        assert not v(K=K, V=V, s=s2)
+    # rows of a strided view: only the view's elements count
+    big = torch.randn((h, n, 256)).to(dtype).to(DEV)
+    big[:, :, 128:] = float("nan")
+    assert v(K=big[:, :, :128])
+    with pytest.raises(ValueError):
+        v(K=big[:, :, :128], V=V)                        # one layout describes both: the strides must agree
+    assert v(K=K, V=V, Q=Q, s=s)                         # the record is cleared by every call
+
+
 def test_flat_mode_is_deterministic_and_group_one_is_the_per_head_selection():
     K, V, s = _flat_case(4, 1, 160, 77, torch.bfloat16)
     a = B().kvr_retain_flat(K, V, s, 1, 50, 0.5, 1e-6)
