@@ -23,7 +23,8 @@
  *
  * Common rules
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL =
- *     the default stream) and return without synchronising.
+ *     the default stream) and return without synchronising (the kvr_debug_*
+ *     calls say where they differ).
  *   - Inputs are read-only; outputs must not alias inputs or each other,
  *     except where a call says otherwise (kvr_compact_inplace, kvr_score_prior).
  *   - The library allocates no device memory (kvr_retain_budgeted_static
