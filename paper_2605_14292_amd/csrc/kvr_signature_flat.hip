@@ -25,46 +25,34 @@ constexpr int kSigTok = 4;                     // tokens per workgroup
 constexpr int kSigSlices = kSigThreads / (16 * kSigTok);   // slices of the group per token
 
 // thr[seq * thr_stride] = s_(b) - lambda (minus a margin for fp32 cosines a few ulp above 1), s_(b) from
-// the leading 16 bits of the ordered keys (at most s_(b): the bound only loosens).  One workgroup per sequence.
-__global__ __launch_bounds__(256) void flat_bound_kernel(const float* __restrict__ s, int n, int b, float lambda,
-                                                         float* __restrict__ thr, int thr_stride) {
-  extern __shared__ uint32_t keys[];                 // [n] ordered keys of the sequence's scores
-  __shared__ int cnt_l[2][4];
-  const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nt = blockDim.x;                         // 64 (short sequences: no barrier in the search) or 256
+// the leading 16 bits of the ordered keys (at most s_(b): the bound only loosens).  One workgroup of WV waves
+// per sequence: the keys of up to 64 * NQ * WV tokens sit in registers, a wave's count is NQ ballots, and with
+// more than one wave the counts meet in LDS once per bit.
+template <int NQ, int WV>
+__global__ __launch_bounds__(64 * WV) void flat_bound_kernel(const float* __restrict__ s, int n, int b, float lambda,
+                                                             float* __restrict__ thr, int thr_stride) {
+  __shared__ int cnt_l[2][WV];
+  const int seq = blockIdx.x, tid = threadIdx.x, wave = tid >> 6;
   const float* sh = s + static_cast<long long>(seq) * n;
-  for (int j = tid; j < n; j += nt) keys[j] = ordered_key(sh[j] + 0.0f);
-  __syncthreads();
-  uint32_t T = 0;
-  if (nt == 64 && n <= 512) {                        // one wave, keys in registers, counts by ballot
-    uint32_t k[8];
+  uint32_t k[NQ];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) k[q] = lane + 64 * q < n ? keys[lane + 64 * q] : 0u;
-    for (int bit = 31; bit >= 16; --bit) {
-      const uint32_t cand = T | (1u << bit);
-      int tot = 0;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) tot += __popcll(__ballot(k[q] >= cand));
-      if (tot >= b) T = cand;
-    }
-    if (tid == 0) {
-      const float sb = key_to_float(T);
-      thr[static_cast<long long>(seq) * thr_stride] = sb - lambda * 1.00001f - 1e-5f * fabsf(sb);
-    }
-    return;
+  for (int q = 0; q < NQ; ++q) {
+    const int j = tid + 64 * WV * q;
+    k[q] = j < n ? ordered_key(sh[j] + 0.0f) : 0u;
   }
+  uint32_t T = 0;
   int par = 0;
   for (int bit = 31; bit >= 16; --bit) {
     const uint32_t cand = T | (1u << bit);
-    int cnt = 0;
-    for (int j = tid; j < n; j += nt) cnt += keys[j] >= cand ? 1 : 0;
+    int tot = 0;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
-    int tot = cnt;
-    if (nt > 64) {
-      if (lane == 0) cnt_l[par][wave] = cnt;
+    for (int q = 0; q < NQ; ++q) tot += __popcll(__ballot(k[q] >= cand));
+    if constexpr (WV > 1) {
+      if ((tid & 63) == 0) cnt_l[par][wave] = tot;
       __syncthreads();
-      tot = cnt_l[par][0] + cnt_l[par][1] + cnt_l[par][2] + cnt_l[par][3];
+      tot = 0;
+#pragma unroll
+      for (int u = 0; u < WV; ++u) tot += cnt_l[par][u];
       par ^= 1;
     }
     if (tot >= b) T = cand;
@@ -146,8 +134,12 @@ hipError_t launch_signature_flat(const void* V, const Layout& lay, int group, fl
                                  const float* s, int b, float lambda, float* thr, int thr_stride) {
   const int seqs = lay.heads / group;
   if (s) {                                         // the rows of tokens the score bound rules out stay zero
-    hipLaunchKernelGGL(flat_bound_kernel, dim3(seqs), dim3(lay.n <= 1024 ? 64 : 256), static_cast<size_t>(lay.n) * 4, st, s,
-                       lay.n, b, lambda, thr, thr_stride);
+    auto go = [&](auto kern, int threads) {
+      hipLaunchKernelGGL(kern, dim3(seqs), dim3(threads), 0, st, s, lay.n, b, lambda, thr, thr_stride);
+    };
+    if (lay.n <= 512) go(&flat_bound_kernel<8, 1>, 64);
+    else if (lay.n <= 2048) go(&flat_bound_kernel<8, 4>, 256);
+    else go(&flat_bound_kernel<32, 4>, 256);         // (n <= 8192 is checked by the entry points)
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
