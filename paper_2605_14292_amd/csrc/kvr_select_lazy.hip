@@ -466,16 +466,25 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
             lo_d = 0.5f * delta; hi_d = 2.0f * delta; steps = 3;
           }
           int c_lo = 1;                              // tokens within lo_d of the best (not counted for the first guess)
+          bool above = false;                        // some count exceeded KR: more than KR tokens lie within hi_d
           for (int it = 0; it < steps; ++it) {       // count(delta) grows with delta
             const float mid = 0.5f * (lo_d + hi_d);
             const int c = count_ge(gmax_w - mid);
-            if (c > KR) hi_d = mid; else { lo_d = mid; c_lo = c; }
+            if (c > KR) { hi_d = mid; above = true; } else { lo_d = mid; c_lo = c; }
           }
           // the lower end of the bracket: at most KR tokens (whole 64-row groups are what the pass costs), always
           // including the wave's best outside token, the one that can carry the epoch's bound
           delta = lo_d;
           thr_r = gmax_w - delta;
-          if (4 * c_lo < KR) delta = -1.f;           // the guess has collapsed or run away: a full search next time
+          if (4 * c_lo < KR) {
+            // The guess has collapsed or run away: a full search next time.  When the bracket could not split a
+            // crowd of bounds (scores within a hair of each other, not yet penalised: a handful of tokens inside
+            // lo_d, more than KR inside hi_d) and the last epoch ended without a pick, the whole crowd is
+            // refreshed, or the epochs would crawl through it a few tokens at a time (the list holds every token
+            // of the wave).  While the epochs do pick, the short list is the cheaper one.
+            if (above && idle > 0) thr_r = gmax_w - hi_d;
+            delta = -1.f;
+          }
         }
         int off = 0;
 #pragma unroll
@@ -669,11 +678,16 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
       if (t >= b) break;
       if (stop == 2 || (np == 0 && !(gout > -INFINITY))) { starved = true; break; }
       if (np == 0) {
-        // the bound won at once.  A stale token carried it: it is refreshed below.  A fresh one: the cut
-        // keys left it outside the pool, full keys from here on.  Either way the next epoch differs from
-        // this one; more than a few such epochs in a row only happen on non-finite input.
-        if (!jout_stale) kbits = 32;
-        if (++idle > 64) { starved = true; break; }
+        // The bound won at once.  A stale token carried it: it is refreshed below and fresh from then on, so the
+        // fresh set grows with every such epoch (at most n of them in a row).  A fresh one: the cut keys left it
+        // outside the pool, full keys from here on; under full keys every wave's best fresh tokens are members
+        // (equal gains join in token order), so a fresh token can only block on non-finite gains, and then
+        // nothing would ever change.
+        if (!jout_stale) {
+          if (kbits == 32) { starved = true; break; }
+          kbits = 32;
+        }
+        if (++idle > n + 8) { starved = true; break; }   // (never reached on finite input, by the count above)
       } else {
         idle = 0;
       }

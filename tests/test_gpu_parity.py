@@ -1136,6 +1136,30 @@ def _adversarial_rows(kind, heads, n, g):
     return V
 
 
+@pytest.mark.parametrize("rows", ["scaled", "duplicates", "zero_rows"])
+@pytest.mark.parametrize("scores", ["crowded", "negative_crowded"])
+@pytest.mark.parametrize("n,b,lam,dtype", [(1069, 128, 3.0, torch.bfloat16), (527, 128, 1.0, torch.float32),
+                                           (3000, 128, 1.0, torch.bfloat16), (4096, 100, 3.0, torch.float32),
+                                           (700, 64, 0.5, torch.bfloat16), (6000, 128, 3.0, torch.bfloat16),
+                                           (1024, 200, 1.0, torch.bfloat16)])
+def test_crowded_scores_under_a_large_lambda(n, b, lam, dtype, scores, rows):
+    """Scores within a hair of each other and a penalty that dwarfs their spread: after the first picks most
+    tokens carry the same out-of-date bound, far above every up-to-date gain.  The selection with lazily
+    refreshed penalties has to bring that whole crowd up to date before it can go on (it once refreshed it
+    a token at a time and gave up); the kernels that pass over all of V per epoch are run on the same inputs."""
+    heads = 2
+    g = torch.Generator(device="cpu").manual_seed(9100 + 7 * n + 31 * len(scores) + 101 * len(rows))
+    K = torch.randn((heads, n, 128), generator=g).to(dtype)
+    V = _adversarial_rows(rows, heads, n, g).to(dtype)
+    s = _adversarial_scores(scores, heads, n, g).to(torch.float32)
+    data = {"K": K.to(DEV), "V": V.to(DEV), "s": s.to(DEV)}
+    out = B().kvr_retain(data["K"], data["V"], b, lam, 1e-6, s=data["s"])
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.pick_gain).all()                 # (a head that gives up logs -inf gains)
+    rep = _check_heads(W.WORKLOADS["c3" if dtype == torch.bfloat16 else "c1"], data, out, b, lam, 1e-6, range(heads))
+    assert rep["heads"] == heads
+
+
 @pytest.mark.parametrize("rows", ["zero_rows", "norms_near_eps", "duplicates", "scaled"])
 @pytest.mark.parametrize("scores", ["crowded", "negative_crowded", "huge_range", "signed"])
 @pytest.mark.parametrize("n,b,heads,dtype", [(100, 40, 300, torch.bfloat16), (192, 64, 300, torch.bfloat16),
