@@ -177,15 +177,15 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const void* __rest
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-template <int GQ>
-__global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* __restrict__ K,
+template <int GQ, int NW>
+__global__ __launch_bounds__(64 * NW) void score_mfma_kernel(const char* __restrict__ K,
                                                                    const char* __restrict__ Q, int G,
                                                                    Layout lay,
                                                                    float* __restrict__ s_out) {
   extern __shared__ __align__(16) char smem_raw[];
   float* zbuf = reinterpret_cast<float*>(smem_raw);                         // [G][n]
   const int n = lay.n;
-  float* red = zbuf + G * n;                                                // [2][4][GQ]
+  float* red = zbuf + G * n;                                                // [2][NW][GQ]
   const int h = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
       qf[ks] = *reinterpret_cast<bf16x8*>(&w);
     }
   }
-  // Wave w takes the 32-token tiles w, w+4, ...: the rows go straight into the registers in the
+  // Wave w takes the 32-token tiles w, w+NW, ...: the rows go straight into the registers in the
   // MFMA operand layout (lane l: token l % 32, eight consecutive k at 8 * (l / 32) per step; the
   // two halves of a row are 32 contiguous bytes per request), the next tile is in flight while
   // the current one is multiplied, and no wave waits for another until the softmax.
@@ -218,8 +218,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
   };
   const float scale = 0.08838834764831845f;
   if (wave < ntiles) fetch(wave, kf);
-  for (int t = wave; t < ntiles; t += 4) {
-    if (t + 4 < ntiles) fetch(t + 4, kn);
+  for (int t = wave; t < ntiles; t += NW) {
+    if (t + NW < ntiles) fetch(t + NW, kn);
     f32x16 acc = {0};
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
         if (g < G) zbuf[g * n + j] = acc[r] * scale;
       }
     }
-    if (t + 4 < ntiles) {
+    if (t + NW < ntiles) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) kf[ks] = kn[ks];
     }
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
   float zmax[GQ], zsum[GQ];
 #pragma unroll
   for (int g = 0; g < GQ; ++g) { zmax[g] = -INFINITY; zsum[g] = 0.f; }
-  for (int j = tid; j < n; j += kScoreThreads)
+  for (int j = tid; j < n; j += 64 * NW)
 #pragma unroll
     for (int g = 0; g < GQ; ++g)
       if (g < G) zmax[g] = fmaxf(zmax[g], zbuf[g * n + j]);
@@ -256,8 +256,13 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
   }
   __syncthreads();
 #pragma unroll
-  for (int g = 0; g < GQ; ++g) zmax[g] = fmaxf(fmaxf(red[g], red[GQ + g]), fmaxf(red[2 * GQ + g], red[3 * GQ + g]));
-  for (int j = tid; j < n; j += kScoreThreads)
+  for (int g = 0; g < GQ; ++g) {
+    float v = red[g];
+#pragma unroll
+    for (int u = 1; u < NW; ++u) v = fmaxf(v, red[u * GQ + g]);
+    zmax[g] = v;
+  }
+  for (int j = tid; j < n; j += 64 * NW)
 #pragma unroll
     for (int g = 0; g < GQ; ++g)
       if (g < G) {
@@ -270,15 +275,20 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(const char* _
     float v = zsum[g];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-    if (lane == 0) red[4 * GQ + wave * GQ + g] = v;
+    if (lane == 0) red[(NW + wave) * GQ + g] = v;
   }
   __syncthreads();
   const float invG = 1.0f / static_cast<float>(G);
   float wgt[GQ];
 #pragma unroll
-  for (int g = 0; g < GQ; ++g) wgt[g] = invG / (red[4 * GQ + g] + red[5 * GQ + g] + red[6 * GQ + g] + red[7 * GQ + g]);
+  for (int g = 0; g < GQ; ++g) {
+    float v = red[NW * GQ + g];
+#pragma unroll
+    for (int u = 1; u < NW; ++u) v += red[(NW + u) * GQ + g];
+    wgt[g] = invG / v;
+  }
   float* so = s_out + static_cast<long long>(h) * n;
-  for (int j = tid; j < n; j += kScoreThreads) {
+  for (int j = tid; j < n; j += 64 * NW) {
     float p = 0.f;
 #pragma unroll
     for (int g = 0; g < GQ; ++g)
@@ -292,16 +302,22 @@ hipError_t launch_score(const void* K, const void* Q, int G, const Layout& lay, 
   // the logits of a head (G x n floats) wait in LDS
   if (lay.dtype == DT_BF16 && G <= 32 && static_cast<long long>(G) * lay.n <= (G <= 8 ? 24576 : 31488)) {
     const int gq = G <= 8 ? 8 : 32;
-    const int smem_m = (G * lay.n + 8 * gq) * 4;
+    // The logit buffer sets how many workgroups share a CU; when it leaves room for two or fewer, eight waves per
+    // workgroup keep as many rows in flight as four waves do with a small buffer.
+    const int smem_one = (G * lay.n + 8 * gq) * 4;
+    const bool big = 3 * smem_one > 160 * 1024;
+    const int nw = big ? 8 : 4;
+    const int smem_m = (G * lay.n + 2 * nw * gq) * 4;
     auto go_m = [&](auto kern) -> hipError_t {
       const hipError_t em = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem_m);
       if (em != hipSuccess) return em;
-      hipLaunchKernelGGL(kern, dim3(lay.heads), dim3(kScoreThreads), smem_m, st,
+      hipLaunchKernelGGL(kern, dim3(lay.heads), dim3(64 * nw), smem_m, st,
                          static_cast<const char*>(K), static_cast<const char*>(Q), G, lay, s_out);
       return hipGetLastError();
     };
-    return gq == 8 ? go_m(&score_mfma_kernel<8>) : go_m(&score_mfma_kernel<32>);
+    if (big) return gq == 8 ? go_m(&score_mfma_kernel<8, 8>) : go_m(&score_mfma_kernel<32, 8>);
+    return gq == 8 ? go_m(&score_mfma_kernel<8, 4>) : go_m(&score_mfma_kernel<32, 4>);
   }
   if (score_wide_supported(lay, G)) return launch_score_wide(K, Q, G, lay, s_out, st);
   const bool zfits = static_cast<long long>(G) * lay.n <= kZMaxFloats;
