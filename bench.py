@@ -199,12 +199,17 @@ def kernel_names(w, b, lam, has_q, mode):
     return ([score] if has_q else []) + tail
 
 
-def make_case(name, seed, b=None, lam=None, mode="plain", window=1, score_scale=1.0):
+def make_case(name, seed, b=None, lam=None, mode="plain", window=1, score_scale=1.0, scores=None):
     import torch
     from paper_2605_14292_amd import binding as B
     from paper_2605_14292_amd import workloads as W
     dev = "cuda:0"
     w = W.WORKLOADS[name]
+    if scores is not None and scores != w.scores:
+        # the configuration's other reading: the same K and V (they are drawn first), the scores handed in
+        # (log-normal(0, 1), as in c3) instead of computed from Q, or the other way round
+        w = dataclasses.replace(w, scores=scores, G=w.G if scores == "computed" else 1,
+                                what=w.what + (", scores given (log-normal)" if scores == "given" else ", scores computed"))
     if window != 1:
         if w.scores != "computed" or window < 1 or w.G * window > 256:
             sys.exit("bench.py: --window needs a workload with computed scores and G * WINDOW <= 256")
@@ -219,7 +224,7 @@ def make_case(name, seed, b=None, lam=None, mode="plain", window=1, score_scale=
         s = (s * score_scale).contiguous()
     group = w.layers * w.kv_heads
     case = {"w": w, "data": data, "b": b, "lam": lam, "mode": mode, "Q": Q, "s": s, "group": group,
-            "score_scale": score_scale}
+            "score_scale": score_scale, "scores_variant": scores is not None and scores != W.WORKLOADS[name].scores}
     bytes_step = w.algorithmic_bytes_per_head(b, lam) * w.heads
     if mode == "flat":
         if s is None:
@@ -317,7 +322,8 @@ def traffic_key(case):
     w = case["w"]
     return (f"{w.name}{'flat' if case['mode'] == 'flat' else ''}{'budgeted' if case['mode'] == 'budgeted' else ''}"
             f"{'window%d' % case['window'] if case['window'] != 1 else ''}"
-            f"{'scale%g' % case['score_scale'] if case['score_scale'] != 1.0 else ''}:b{case['b']}:lam{case['lam']}")
+            f"{'scale%g' % case['score_scale'] if case['score_scale'] != 1.0 else ''}"
+            f"{case['w'].scores if case['scores_variant'] else ''}:b{case['b']}:lam{case['lam']}")
 
 
 def run_case(name, pool, seed, steps, warmup, cpu_budget_s, sample, copy_gbps, cold=False, baseline=True, **kw):
@@ -404,6 +410,9 @@ def main():
     ap.add_argument("--score-scale", type=float, default=1.0,
                     help="multiply given scores by this factor (a spread far below lambda leaves the score bound "
                          "nothing to remove)")
+    ap.add_argument("--scores", choices=["computed", "given"], default=None,
+                    help="the other reading of a configuration that does not say where its scores come from: "
+                         "c4 / c5 with log-normal scores handed in (default: the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle legs (cpu_baseline and the parity check of the timed buffers)")
     ap.add_argument("--no-other-configs", action="store_true",
@@ -449,7 +458,7 @@ def main():
     head = run_case(args.workload, pool, args.seed, args.steps, args.warmup, cpu_budget_s=12.0,
                     sample=128 if args.workload == "c3" else 64, copy_gbps=copy_gbps,
                     cold=args.workload in ("c1", "c2"), b=args.b, lam=args.lam, mode=mode, window=args.window,
-                    score_scale=args.score_scale)
+                    score_scale=args.score_scale, scores=args.scores)
     line = {
         "metric": "retention events/sec (heads*events)",
         "value": head["head_events_per_s"],
@@ -465,7 +474,7 @@ def main():
         if k in head:
             line[k] = head[k]
     default_run = (args.workload == "c4" and mode == "plain" and args.b is None and args.lam is None
-                   and args.window == 1 and args.score_scale == 1.0)
+                   and args.window == 1 and args.score_scale == 1.0 and args.scores is None)
     if default_run and not args.no_other_configs:
         oc = {}
 
@@ -477,6 +486,9 @@ def main():
         other("c5 lambda=0", "c5", lam=0.0)
         other("c5 lambda=0.25", "c5", lam=0.25, budget=1.0)
         other("c5 lambda=1", "c5", lam=1.0, budget=1.0)
+        # c4 and c5 do not say where their scores come from: the other reading, scores handed in as in c3
+        other("c4 scores given (log-normal)", "c4", scores="given")
+        other("c5 scores given (log-normal)", "c5", scores="given")
         other("c3", "c3", steps=20, warmup=5, sample=128)
         other("c3 scores x 0.01 (spread far below lambda)", "c3", steps=20, warmup=5, sample=64, score_scale=0.01)
         other("c2", "c2", steps=20, warmup=5, sample=112, cold=True)

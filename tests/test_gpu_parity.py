@@ -1,5 +1,7 @@
 """Parity of the HIP path (through the C-ABI) with the fp64 oracle on the five
 benchmark configurations and on edge cases.  Needs an MI355X."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -89,13 +91,17 @@ MAX_NEAR_TIE_FLIPS = 8
 def test_config_full_size_sampled_heads(name, sample, b, lam):
     """The launch configuration the benchmark times: all heads resident in HBM,
     a fixed random sample of heads checked element by element."""
-    w = W.WORKLOADS[name]
+    _full_size_sampled(W.WORKLOADS[name], sample, b, lam)
+
+
+def _full_size_sampled(w, sample, b, lam):
+    name = w.name
     data = W.generate(w, seed=0, device=DEV)
     out, b, lam = _run(w, data, b=b, lam=lam)
     rng = np.random.default_rng(7)
     heads = sorted(rng.choice(w.heads, size=min(sample, w.heads), replace=False).tolist())
     rep = _check_heads(w, data, out, b, lam, 1e-6, heads)
-    print(f"\n[{name} full, {w.heads} heads, b={b}, lambda={lam}] {rep}")
+    print(f"\n[{name} full, {w.heads} heads, b={b}, lambda={lam}, scores {w.scores}] {rep}")
     assert rep["near_ties"] <= MAX_NEAR_TIE_FLIPS
     if lam == 0.0:                               # exactly the stable top-b of the scores the HIP path itself produced
         s = out.s_out.cpu().numpy()
@@ -109,6 +115,14 @@ def test_config_full_size_sampled_heads(name, sample, b, lam):
     np.testing.assert_array_equal(po, idx)
     g = out.pick_gain.cpu().numpy()
     assert np.all(np.diff(g, axis=1) <= 0)
+
+
+@pytest.mark.parametrize("name,b,lam", [("c4", 128, 0.5), ("c5", 128, 0.5), ("c5", 64, 1.0), ("c5", 128, 0.25)])
+def test_long_configs_with_scores_handed_in_full_size(name, b, lam):
+    """The other reading of c4 and c5 (the configurations do not say where the scores come from): log-normal scores
+    handed in, as in c3.  Their spread exceeds lambda, so the score bound removes most of a head before any row is read."""
+    w = W.WORKLOADS[name]
+    _full_size_sampled(dataclasses.replace(w, scores="given", G=1), 64, b, lam)
 
 
 @pytest.mark.parametrize("scale", [0.01, 0.2])
@@ -863,7 +877,9 @@ def test_scores_from_a_wide_query_window(n, G):
 @pytest.mark.parametrize("n,G,sharp,strided", [
     (1, 40, 1.0, False), (33, 200, 1.0, False), (1000, 33, 1.0, False), (1500, 20, 4.0, False),
     (4096, 8, 1.0, False), (777, 100, 2.0, True), (4096, 256, 1.0, False), (8192, 64, 1.0, False),
-    (2050, 255, 6.0, False)])
+    (2050, 255, 6.0, False),
+    # the LDS-resident scorer with eight waves per workgroup (large logit buffers), ragged last tiles
+    (3001, 8, 1.0, False), (899, 32, 2.0, False), (2047, 5, 1.0, True)])
 def test_scores_from_an_observation_window_of_up_to_256_queries(n, G, sharp, strided):
     """W recent positions x grouped heads as one wide Q: the two-pass matrix-core scorer (any n, G <= 256).
     `sharp` scales the queries: peaked softmaxes, logits tens of units apart."""
