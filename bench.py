@@ -194,6 +194,8 @@ def kernel_names(w, b, lam, has_q, mode):
     if w.dtype == "bf16" and w.n <= 8192 and b <= 1024:
         lazy = w.n <= 4096 and b <= 128             # the library's dispatch: lazily refreshed penalties, else the pool kernel
         tail = ["kvr::select_topb_kernel" if lam == 0.0 else "kvr::select_lazy_kernel" if lazy else "kvr::select_pool_kernel"]
+        if lazy and lam > 0.0 and not has_q and b >= 2:   # scores handed in: the heads the score bound shrinks to a short head first
+            tail = ["kvr::retain_sparse_kernel", "kvr::select_lazy_kernel (the heads it hands on)"]
     else:
         tail = ["kvr::select_generic_kernel", "kvr::compact_kernel"]
     return ([score] if has_q else []) + tail

@@ -21,7 +21,7 @@ LIB_BOUNDS = os.path.join(HERE, "libkvr_bounds.so")
 SOURCES = ["kvr_api.hip", "kvr_score.hip", "kvr_score_wide.hip", "kvr_select_generic.hip", "kvr_compact.hip",
            "kvr_retain_dense.hip", "kvr_retain_dense16.hip", "kvr_select_dense_f32.hip", "kvr_signature_flat.hip",
            "kvr_score_prior.hip", "kvr_score_pool.hip", "kvr_budget.hip", "kvr_retain_pruned.hip",
-           "kvr_select_pool.hip", "kvr_select_lazy.hip", "kvr_select_topb.hip", "kvr_validate.hip"]
+           "kvr_select_pool.hip", "kvr_select_lazy.hip", "kvr_retain_sparse.hip", "kvr_select_topb.hip", "kvr_validate.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -74,9 +74,16 @@ hipError_t select_only(const void* V, const float* s, const kvr::Layout& l, int 
   if (kvr::topb_supported(l, b, lambda))
     return kvr::launch_select_topb(nullptr, nullptr, s, l, b, idx_sorted, pick_order, pick_gain, nullptr,
                                    nullptr, st);
-  if (kvr::lazy_supported(l, b, lambda))
+  if (kvr::lazy_supported(l, b, lambda)) {
+    const bool sparse = kvr::sparse_supported(l, b, lambda);   // heads that the score bound shrinks to a short head first
+    if (sparse) {
+      const hipError_t e = kvr::launch_retain_sparse(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order,
+                                                     pick_gain, nullptr, nullptr, st);
+      if (e != hipSuccess) return e;
+    }
     return kvr::launch_select_lazy(nullptr, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain,
-                                   nullptr, nullptr, st);
+                                   nullptr, nullptr, st, nullptr, sparse);
+  }
   if (kvr::lazy_f32_supported(l, b, lambda))
     return kvr::launch_select_lazy_f32(V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, st);
   if (kvr::pool_supported(l, b))
@@ -261,8 +268,15 @@ int kvr_retain(const void* K, const void* V, const void* Q, int G, const float* 
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (kvr::lazy_supported(l, b, lambda)) {
-    const hipError_t e = kvr::launch_select_lazy(K, V, s, l, b, lambda, eps, idx_sorted, pick_order,
-                                                 pick_gain, K_out, V_out, st);
+    // scores handed in may spread by more than lambda: the heads that the score bound shrinks to a short head are
+    // finished first (scores computed here are softmax means, far tighter than lambda: nothing to drop)
+    const bool sparse = !Q && kvr::sparse_supported(l, b, lambda);
+    hipError_t e = hipSuccess;
+    if (sparse)
+      e = kvr::launch_retain_sparse(K, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, K_out, V_out, st);
+    if (e == hipSuccess)
+      e = kvr::launch_select_lazy(K, V, s, l, b, lambda, eps, idx_sorted, pick_order, pick_gain, K_out, V_out, st,
+                                  nullptr, sparse);
     return e == hipSuccess ? KVR_OK : KVR_ERR_HIP;
   }
   if (kvr::pool_supported(l, b)) {

@@ -134,7 +134,17 @@ bool lazy_supported(const Layout& lay, int b, float lambda);
 hipError_t launch_select_lazy(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
                               float* pick_gain, void* K_out, void* V_out, hipStream_t st,
-                              const int32_t* b_h = nullptr);
+                              const int32_t* b_h = nullptr, bool only_marked = false);
+// only_marked: only the heads whose idx_sorted[h*b] is -1 are processed (launch_retain_sparse has finished the others).
+
+// Fused path for the same heads (b >= 2) when their scores are handed in: the tokens that the score bound
+// s_j < s_(b) - lambda excludes from every pick are dropped first; heads left with at most 128 (b <= 64) or 192
+// candidates are finished as short heads are (rows gathered into LDS, cosine triangle, pick chain, kept rows),
+// the others get idx_sorted[h*b] = -1 and must be passed to launch_select_lazy(..., only_marked = true) afterwards.
+bool sparse_supported(const Layout& lay, int b, float lambda);
+hipError_t launch_retain_sparse(const void* K, const void* V, const float* s, const Layout& lay, int b, float lambda,
+                                float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
+                                void* V_out, hipStream_t st);
 // The same for fp32 rows (the mean rows of the flat-signature mode, fp32 caches), selection only: the
 // Gram and the passes run on the fp32 MFMAs, the rows of a pass are loaded straight into operand layout.
 bool lazy_f32_supported(const Layout& lay, int b, float lambda);

@@ -76,6 +76,7 @@ struct LazyArgs {
   int n, b;
   float lambda, eps;
   const int32_t* b_h;                  // per-head budgets <= b (output rows stay b apart), or null
+  int only_marked;                     // process only heads whose idx_sorted[h*b] is -1 (an earlier kernel has finished the others)
 };
 
 // P: pool size, a multiple of 64.  192 was measured where a head has the CU to itself (n > 1024): an epoch less per head,
@@ -190,6 +191,7 @@ __global__ __launch_bounds__(64 * W, (W <= 4 ? 2 : 1)) void select_lazy_kernel(L
   int32_t* flag = reinterpret_cast<int32_t*>(uni);               // ... and at the end [n padded] pick flags for the ascending read-out
 
   const int h = blockIdx.x;
+  if (a.only_marked && a.idx_sorted[static_cast<long long>(h) * a.b] != -1) return;   // (uniform: a scalar load)
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = a.n;
@@ -970,7 +972,7 @@ bool lazy_f32_supported(const Layout& lay, int b, float lambda) {
 hipError_t launch_select_lazy_f32(const void* V, const float* s, const Layout& lay, int b, float lambda, float eps,
                                   int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, hipStream_t st) {
   LazyArgs a;
-  a.b_h = nullptr;
+  a.b_h = nullptr; a.only_marked = 0;
   a.K = nullptr; a.V = static_cast<const char*>(V); a.s_in = s;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.K_out = nullptr; a.V_out = nullptr;
@@ -989,9 +991,10 @@ hipError_t launch_select_lazy_f32(const void* V, const float* s, const Layout& l
 
 hipError_t launch_select_lazy(const void* K, const void* V, const float* s, const Layout& lay, int b,
                               float lambda, float eps, int32_t* idx_sorted, int32_t* pick_order,
-                              float* pick_gain, void* K_out, void* V_out, hipStream_t st, const int32_t* b_h) {
+                              float* pick_gain, void* K_out, void* V_out, hipStream_t st, const int32_t* b_h,
+                              bool only_marked) {
   LazyArgs a;
-  a.b_h = b_h;
+  a.b_h = b_h; a.only_marked = only_marked ? 1 : 0;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s_in = s;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);

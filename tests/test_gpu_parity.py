@@ -125,6 +125,40 @@ def test_long_configs_with_scores_handed_in_full_size(name, b, lam):
     _full_size_sampled(dataclasses.replace(w, scores="given", G=1), 64, b, lam)
 
 
+@pytest.mark.parametrize("n,b,lam", [(257, 2, 0.5), (300, 64, 0.5), (700, 65, 0.25), (1024, 128, 0.5), (1025, 17, 1.0),
+                                     (2047, 128, 0.5), (2049, 40, 0.3), (3001, 100, 0.5), (4096, 128, 0.5), (4096, 64, 2.0)])
+def test_long_heads_with_wide_scores_shrink_to_their_candidates(n, b, lam):
+    """Scores handed in that spread by more than lambda: the score bound leaves a short head, which one kernel
+    finishes; heads that stay too large (scores tighter than lambda, a bound that removes too little) and heads
+    with fewer than b candidates left (most scores -inf) are handed on in the same launch.  Every head is compared
+    with the oracle pick by pick; the selection-only entry point must agree with the fused one."""
+    h = 9
+    g = torch.Generator().manual_seed(77 * n + b)
+    K = torch.randn((h, n, 128), generator=g).to(torch.bfloat16)
+    V = torch.randn((h, n, 128), generator=g)
+    V[:, n // 3: n // 3 + n // 4] = V[:, : n // 4] + 0.05 * V[:, n // 3: n // 3 + n // 4]      # near-duplicates of earlier tokens
+    V = V.to(torch.bfloat16)
+    s = torch.randn((h, n), generator=g).exp()                      # log-normal(0, 1)
+    s[1] = 0.3 + 0.01 * torch.rand((n,), generator=g)               # spread far below lambda: nothing can go
+    s[2] = s[2] * 0.2                                               # a bound that removes too little
+    s[3] = torch.floor(s[3] * 2) / 2                                # ties, also at the threshold
+    s[4, : n - max(b // 2, 1)] = float("-inf")                      # fewer candidates than the budget
+    s[5] = -s[5]                                                    # negative scores
+    s[6] = s[6] * 100                                               # the bound leaves little more than the b best
+    s = s.to(torch.float32)
+    K, V, s = K.to(DEV), V.to(DEV), s.to(DEV)
+    out = B().kvr_retain(K, V, b, lam, 1e-6, s=s)
+    sel_idx, sel_order, sel_gain = B().kvr_select_greedy(V, s, b, lam, 1e-6)
+    torch.cuda.synchronize()
+    heads = [hh for hh in range(h) if hh != 4]
+    _check_heads(W.WORKLOADS["c3"], {"K": K, "V": V, "s": s}, out, b, lam, 1e-6, heads)
+    idx = out.idx_sorted.cpu().numpy()
+    assert idx.min() >= 0 and idx.max() < n and np.all(np.diff(idx, axis=1) > 0)     # head 4 too: distinct, in range
+    np.testing.assert_array_equal(sel_idx.cpu().numpy()[heads], idx[heads])
+    np.testing.assert_array_equal(sel_order.cpu().numpy()[heads], out.pick_order.cpu().numpy()[heads])
+    np.testing.assert_array_equal(_bits(sel_gain)[heads], _bits(out.pick_gain)[heads])
+
+
 @pytest.mark.parametrize("scale", [0.01, 0.2])
 def test_c3_shape_with_scores_far_below_lambda(scale):
     """c3's launch with its given scores scaled down: the score bound removes nothing (0.01) or too little
