@@ -11,9 +11,12 @@
 // chain, and the kept rows of K and V are copied out.  Survivors keep their token order, so every tie
 // still goes to the lowest token index.
 //
-// A head with more survivors than the kernel's capacity (128 or 192 tokens), or with fewer than b of them
-// (non-finite scores), gets idx_sorted[h*b] = -1 and is left to the kernel for long heads, which is
-// launched afterwards on the marked heads only.
+// A head with more survivors than the kernel's capacity (128 or 192 tokens) keeps the best-scored of them and
+// remembers the best score left out; the run is valid iff that score stays below the gain of the last pick
+// (gains never increase, and a token gains at most its score), which is checked when the chain is done.  A head
+// that fails the check, or whose cut could not be verified anyway, or with fewer than b candidates (non-finite
+// scores), gets idx_sorted[h*b] = -1 and is left to the kernel for long heads, which is launched afterwards on
+// the marked heads only.
 //
 // Layout: persistent workgroups of four wave64s, one head at a time; token j = 256*k + thread in slot k of
 // its thread while the scores are searched (coalesced score loads), compacted to positions 0..ns-1 for
@@ -105,36 +108,70 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
     }
     int ns = 0;
     unsigned long long km[S];
+    float excl = -INFINITY;                          // best score among the candidates left out (none: -inf)
     if (!marked) {
       uint32_t key[S];
 #pragma unroll
       for (int k = 0; k < S; ++k) key[k] = k * 256 + tid < n ? ordered_key(sv[k] + 0.0f) : 0u;
-      // s_(b) from the leading 16 bits of the ordered keys: at most s_(b), so the bound only loosens
-      uint32_t T = 0;
-      for (int bit = 31; bit >= 16; --bit) {
-        const uint32_t cand = T | (1u << bit);
+      // largest value of the leading 16 key bits that at least `want` keys reach (0 when fewer keys exist)
+      auto kth_key16 = [&](int want) -> uint32_t {
+        uint32_t T = 0;
+        for (int bit = 31; bit >= 16; --bit) {
+          const uint32_t cand = T | (1u << bit);
+          int c = 0;
+#pragma unroll
+          for (int k = 0; k < S; ++k) c += __popcll(__ballot(key[k] >= cand));
+          if (lane == 0) redi[par * 4 + wave] = c;
+          lds_barrier();
+          const int tot = redi[par * 4] + redi[par * 4 + 1] + redi[par * 4 + 2] + redi[par * 4 + 3];
+          par ^= 1;
+          if (tot >= want) T = cand;
+        }
+        return T;
+      };
+      // survivors per slot and wave into cnt[], their number over the workgroup returned
+      auto count_kept = [&]() -> int {
         int c = 0;
 #pragma unroll
-        for (int k = 0; k < S; ++k) c += __popcll(__ballot(key[k] >= cand));
+        for (int k = 0; k < S; ++k) {
+          c += __popcll(km[k]);
+          if (lane == 0) cnt[k * 4 + wave] = __popcll(km[k]);
+        }
         if (lane == 0) redi[par * 4 + wave] = c;
         lds_barrier();
         const int tot = redi[par * 4] + redi[par * 4 + 1] + redi[par * 4 + 2] + redi[par * 4 + 3];
         par ^= 1;
-        if (tot >= b) T = cand;
-      }
-      const float sb = key_to_float(T);
+        return tot;
+      };
+      // s_(b) from the leading 16 bits of the ordered keys: at most s_(b), so the bound only loosens
+      const float sb = key_to_float(kth_key16(b));
       const float thr = sb - a.lambda * 1.00001f - 1e-5f * fabsf(sb);   // fp32 cosines may exceed 1 by a few ulp
-      int c = 0;
 #pragma unroll
-      for (int k = 0; k < S; ++k) {
-        km[k] = __ballot(k * 256 + tid < n && !(sv[k] < thr));          // (a NaN threshold or score keeps the token)
-        c += __popcll(km[k]);
-        if (lane == 0) cnt[k * 4 + wave] = __popcll(km[k]);
+      for (int k = 0; k < S; ++k) km[k] = __ballot(k * 256 + tid < n && !(sv[k] < thr));   // (a NaN threshold or score keeps the token)
+      ns = count_kept();
+      if (ns > N32) {
+        // More candidates than fit: the best-scored are kept, cut where the leading 16 key bits change (at most N32
+        // of them), and the best score left out is remembered.  Pick gains never increase and a token gains at most
+        // its score, so the run is valid iff that score stays below the last pick's gain, which is checked when the
+        // chain is done.  That gain is at most s_(b) and in practice a good part of lambda below it: when the score
+        // left out lies within a quarter of lambda of s_(b) the chain would be run in vain, and the head is handed
+        // on at once (a guess about speed only: either way the picks are exact).
+        const uint32_t T2 = kth_key16(N32 + 1);       // > 0: more than N32 keys exist
+        const uint32_t cut = T2 + 0x10000u;            // (wraps to 0 only for all-ones keys, NaNs: every token then passes and the head is handed on)
+        float ob = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < S; ++k) {
+          const bool in = k * 256 + tid < n && key[k] >= cut;
+          if (k * 256 + tid < n && !in) ob = hw_max(ob, sv[k]);
+          km[k] = __ballot(in);
+        }
+        ob = wave_max_uniform(ob);
+        if (lane == 0) redf[par * 4 + wave] = ob;      // (exchanged by the barrier inside count_kept, read right after it)
+        const int pf = par;
+        ns = count_kept();
+        excl = hw_max(hw_max(redf[pf * 4], redf[pf * 4 + 1]), hw_max(redf[pf * 4 + 2], redf[pf * 4 + 3]));
+        if (!(excl < sb - 0.25f * a.lambda)) ns = N32 + 1;              // hopeless: handed on
       }
-      if (lane == 0) redi[par * 4 + wave] = c;
-      lds_barrier();
-      ns = redi[par * 4] + redi[par * 4 + 1] + redi[par * 4 + 2] + redi[par * 4 + 3];
-      par ^= 1;
       marked = ns > N32 || ns < b;
     }
     if (marked) {                                    // uniform: every wave takes the same branch
@@ -195,10 +232,12 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
           int I = 0;
           while ((I + 1) * (I + 2) / 2 <= tile) ++I;
           const int J = tile - I * (I + 1) / 2;
+          __builtin_amdgcn_sched_barrier(0);          // keep one tile's fragment loads in flight, not all of them
 #pragma unroll
           for (int ks = 0; ks < 8; ++ks)
             acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_at(stage, I, ks, lane), frag_at(stage, J, ks, lane),
                                                              acc[q], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
           if (I == J) {                               // squared norms sit on the diagonal
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -227,19 +266,23 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
 
     // ------------------------------------------------ greedy on the survivors, then back to token numbers
     if (wave == 0) {
-      pick_chain<NQ>(s_l, tri, order_l, gain_l, ns, b, a.lambda, true, lane);
+      const float last_g = pick_chain<NQ>(s_l, tri, order_l, gain_l, ns, b, a.lambda, true, lane);
       sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, tok_c);   // rinv is dead by now
+      // the cut, if there was one, holds when every token left out scores below the last pick's gain
+      const bool ok = excl == -INFINITY || excl < last_g - 1e-5f * (fabsf(last_g) + a.lambda);
+      if (lane == 0) redi[8] = ok ? 0 : 1;
     }
     lds_barrier();
+    const bool redo = redi[8] != 0;                  // the head is left to the kernel for long heads
 
     // ------------------------------------------------ outputs and compaction
     const long long ob = static_cast<long long>(h) * b;
     for (int t = tid; t < b; t += kDenseThreads) {
-      a.idx_sorted[ob + t] = idx_l[t];
+      a.idx_sorted[ob + t] = (redo && t == 0) ? -1 : idx_l[t];
       if (a.pick_order) a.pick_order[ob + t] = order_l[t];
       if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
     }
-    if (a.K_out || a.V_out)
+    if ((a.K_out || a.V_out) && !redo)
       compact_rows<4>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idx_l, n, b, ob, tid, kDenseThreads);
     lds_barrier();                                   // the lists and tables are reused by the next head
   }

@@ -852,7 +852,9 @@ def test_budgeted_per_head_lambda(n, b_max):
     # heads 2 and 5 share lambda = the launch lambda: their scores went through unscaled
     same = B().kvr_retain(K[5:6].contiguous(), V[5:6].contiguous(), b_max, 0.5, 1e-6, s=s[5:6].contiguous())
     torch.cuda.synchronize()
-    assert torch.equal(same.pick_order[0], out.pick_order[5]) and torch.equal(same.pick_gain[0], out.pick_gain[5])
+    # (another kernel may serve the plain call: the same picks, gains to fp32 rounding of a different summation order)
+    assert torch.equal(same.pick_order[0], out.pick_order[5])
+    torch.testing.assert_close(same.pick_gain[0], out.pick_gain[5], rtol=1e-5, atol=1e-6)
 
 
 @pytest.mark.parametrize("n,dtype", [(200, torch.bfloat16), (150, torch.float32), (700, torch.bfloat16), (5000, torch.bfloat16)])
