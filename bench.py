@@ -504,7 +504,11 @@ def main():
         line["other_configs"] = oc
         fr = {"c4": line["roofline"]["frac"], "c5": oc["c5"]["roofline"]["frac"], "c3": oc["c3"]["roofline"]["frac"]}
         worst = min(fr, key=fr.get)
-        line["worst_long_config"] = {"name": worst, "frac": fr[worst], "fracs": fr}
+        line["worst_long_config"] = {"name": worst, "frac": fr[worst], "fracs": fr,
+                                     # the other reading of c4 / c5 (scores handed in); by algorithmic bytes, which price
+                                     # all of V although the score bound rules most of it out before it is read
+                                     "fracs_scores_given": {"c4": oc["c4 scores given (log-normal)"]["roofline"]["frac"],
+                                                            "c5": oc["c5 scores given (log-normal)"]["roofline"]["frac"]}}
     if pool is not None:
         pool.close()
     print(json.dumps(line), flush=True)
