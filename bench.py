@@ -53,8 +53,18 @@ class OraclePool:
         saved = {k: os.environ.get(k) for k in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS")}
         for k in saved:
             os.environ[k] = "1"
-        self.pool = mp.get_context("spawn").Pool(self.cores)
-        self.pool.map(_warm, range(self.cores))          # imports done before anything is timed
+        ctx = mp.get_context("spawn")
+        ready = ctx.Barrier(self.cores + 1)
+        self.pool = ctx.Pool(self.cores, initializer=_worker_init, initargs=(ready,))
+        # Every worker imports numpy and the oracle in its initializer and then meets this process at the barrier:
+        # no import is still running (and competing with the launching thread for the host's cores) when the
+        # first configuration is timed.  (A map of warm-up jobs does not do that: the workers that are up first
+        # take all of them.)
+        try:
+            ready.wait(timeout=120)
+        except Exception:                                # (a worker that could not start: the oracle legs will say so)
+            pass
+        time.sleep(0.2)
         for k, v in saved.items():
             if v is None:
                 os.environ.pop(k, None)
@@ -66,9 +76,12 @@ class OraclePool:
         self.pool.join()
 
 
-def _warm(_):
+def _worker_init(ready):
     import parity_util  # noqa: F401
-    return os.getpid()
+    try:
+        ready.wait(timeout=120)
+    except Exception:
+        pass
 
 
 def _oracle_job(i):
@@ -394,8 +407,8 @@ def run_case(name, pool, seed, steps, warmup, cpu_budget_s, sample, copy_gbps, c
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--b", type=int, default=None)
     ap.add_argument("--lam", type=float, default=None)
