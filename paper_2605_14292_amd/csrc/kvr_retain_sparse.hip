@@ -266,7 +266,9 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
 
     // ------------------------------------------------ greedy on the survivors, then back to token numbers
     if (wave == 0) {
+      __builtin_amdgcn_s_setprio(3);                 // the chain goes first when it shares a SIMD with other workgroups' waves
       const float last_g = pick_chain<NQ>(s_l, tri, order_l, gain_l, ns, b, a.lambda, true, lane);
+      __builtin_amdgcn_s_setprio(0);
       sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, tok_c);   // rinv is dead by now
       // the cut, if there was one, holds when every token left out scores below the last pick's gain
       const bool ok = excl == -INFINITY || excl < last_g - 1e-5f * (fabsf(last_g) + a.lambda);
