@@ -148,9 +148,9 @@ int kvr_debug_bounds_selftest(int32_t* out, void* stream) {
 
 int kvr_debug_bounds_violation(uint32_t* worst_id) {
   if (!worst_id) return KVR_ERR_ARG;
-  const unsigned int a = kvr::bounds_bad_lazy(), b = kvr::bounds_bad_pool();
-  if (a == 0xffffffffu || b == 0xffffffffu) return KVR_ERR_HIP;
-  *worst_id = a > b ? a : b;
+  const unsigned int a = kvr::bounds_bad_lazy(), b = kvr::bounds_bad_pool(), c = kvr::bounds_bad_sparse();
+  if (a == 0xffffffffu || b == 0xffffffffu || c == 0xffffffffu) return KVR_ERR_HIP;
+  *worst_id = a > b ? (a > c ? a : c) : (b > c ? b : c);
   return KVR_OK;
 }
 

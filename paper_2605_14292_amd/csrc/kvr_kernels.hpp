@@ -161,6 +161,7 @@ hipError_t validate_finite(const void* K, const void* V, const void* Q, int G, c
 // the last call (0: none; the product build always returns 0).  Synchronises the device.
 unsigned int bounds_bad_lazy();
 unsigned int bounds_bad_pool();
+unsigned int bounds_bad_sparse();
 // One thread range-checks the index 5 against the limit 3 (id 199) and stores what the check returned (2 in the
 // debug build, 5 in the product build) in out[0]; no memory is accessed through the index.
 hipError_t launch_bounds_selftest(int32_t* out, hipStream_t st);

@@ -21,6 +21,7 @@
 // Layout: persistent workgroups of four wave64s, one head at a time; token j = 256*k + thread in slot k of
 // its thread while the scores are searched (coalesced score loads), compacted to positions 0..ns-1 for
 // everything after.  The scores of the workgroup's next head travel during the pick chain.
+#define KVR_BOUNDS_FILE 3   // ids 3xx of the debug build's bounds checks (kvr_bounds.hpp)
 #include "kvr_dense_common.hpp"
 #include "kvr_kernels.hpp"
 
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
 #pragma unroll
     for (int k = 0; k < S; ++k) {
       if ((km[k] >> lane) & 1ull) {
-        const int pos = min(off[k * 4 + wave] + __popcll(km[k] & below), N32 - 1);
+        const int pos = min(kvr_ix(off[k * 4 + wave] + __popcll(km[k] & below), N32, 301), N32 - 1);   // 301: a survivor's position
         tok_c[pos] = k * 256 + tid;
         s_l[pos] = sv[k];
       }
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
       const char* vb = a.V + head_off + chunk * 16;
       int trow[kIters];
 #pragma unroll
-      for (int k = 0; k < kIters; ++k) trow[k] = min(max(tok_c[r0 + 16 * k], 0), n - 1);
+      for (int k = 0; k < kIters; ++k) trow[k] = min(max(kvr_ix(tok_c[r0 + 16 * k], n, 302), 0), n - 1);   // 302: token of a survivor
 #pragma unroll
       for (int k = 0; k < kIters; ++k) {
         vreg[k] = make_uint4(0u, 0u, 0u, 0u);        // rows past the survivors read as zero: zero Gram entries
@@ -289,6 +290,8 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
     lds_barrier();                                   // the lists and tables are reused by the next head
   }
 }
+
+KVR_BOUNDS_TU(sparse)
 
 bool sparse_supported(const Layout& lay, int b, float lambda) {
   // (the heads this kernel marks go to the kernel for long heads: its shapes bound this one's)

@@ -84,3 +84,16 @@ def test_tied_and_crowded_scores_under_bounds_checks():
         s2 = (1.502 + 0.005 * torch.rand((2, n), generator=torch.Generator().manual_seed(n))).to(DEV)
         ref, dbg, worst = _both(lambda: B.kvr_retain(K, V, b, 0.5, 1e-6, s=s2))
         assert worst == 0 and torch.equal(ref.pick_order, dbg.pick_order)
+
+
+@pytest.mark.parametrize("n,b", [(1024, 128), (4096, 64), (2500, 100)])
+def test_long_heads_with_wide_scores_under_bounds_checks(n, b):
+    # log-normal scores handed in: the kernel that shrinks a long head to the tokens the score bound leaves
+    # (survivor positions and tokens are range-checked), the lazy kernel on the heads it hands on
+    K, V, s = _mk(5, n, 99 + n + b, torch.bfloat16, 1.0)
+    s = torch.randn(s.shape, generator=torch.Generator().manual_seed(n + b)).exp().to(DEV)
+    s[1] = s[1] * 0.05                                   # too tight for the bound: handed on
+    ref, dbg, worst = _both(lambda: B.kvr_retain(K, V, b, 0.5, 1e-6, s=s))
+    assert worst == 0
+    for f in ("idx_sorted", "pick_order", "pick_gain", "K_out", "V_out"):
+        assert torch.equal(getattr(ref, f), getattr(dbg, f)), f
