@@ -194,9 +194,7 @@ def kernel_names(w, b, lam, has_q, mode):
                "kvr::select_lazy_kernel (fp32 rows)" if w.n <= 4096 and b <= 128 and lam > 0 else "kvr::select_generic_kernel")
         return ["kvr::flat_bound_kernel", "kvr::signature_flat_kernel", sel, "kvr::compact_kernel"]
     if mode == "budgeted":
-        inner = [k for k in kernel_names(w, b, lam, has_q, "plain") if "retain_sparse" not in k]   # (not in this frame)
-        inner = ["kvr::select_lazy_kernel" if "select_lazy_kernel" in k else k for k in inner]
-        return ["kvr::budget_prepare_kernel"] + inner + ["kvr::budget_fixup_kernel"]
+        return ["kvr::budget_prepare_kernel"] + kernel_names(w, b, lam, has_q, "plain") + ["kvr::budget_fixup_kernel"]
     if w.dtype == "bf16" and 128 < w.n <= 256 and not has_q and 1 < b <= 128 and lam > 0 and w.heads > 256:
         return ["kvr::retain_pruned_kernel", "kvr::retain_dense_kernel (marked heads only)"]
     if w.dtype == "bf16" and w.n <= 256:

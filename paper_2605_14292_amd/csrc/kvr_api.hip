@@ -358,8 +358,17 @@ int retain_budgeted(const void* K, const void* V, const void* Q, int G, const fl
     if (long_topb) {
       e = kvr::launch_select_topb(K, V, s_work, l, b_max, idx_sorted, pick_order, pick_gain, K_out, V_out, st, b_h);
     } else if (long_heads && kvr::lazy_supported(l, b_max, lambda)) {
-      e = kvr::launch_select_lazy(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
-                                  V_out, st, b_h);
+      // scores handed in may spread by more than lambda: the heads that the score bound shrinks to a short head are
+      // finished first (computed scores are tighter than lambda, and the offsets of protected tokens would only
+      // make the kernel search every head in vain)
+      const bool sparse = !Q && kvr::sparse_supported(l, b_max, lambda);
+      e = hipSuccess;
+      if (sparse)
+        e = kvr::launch_retain_sparse(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
+                                      V_out, st, b_h);
+      if (e == hipSuccess)
+        e = kvr::launch_select_lazy(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
+                                    V_out, st, b_h, sparse);
     } else if (long_heads) {
       e = kvr::launch_select_pool(K, V, s_work, l, b_max, lambda, eps, idx_sorted, pick_order, pick_gain, K_out,
                                   V_out, st, b_h, Q == nullptr);

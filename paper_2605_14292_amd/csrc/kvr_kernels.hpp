@@ -144,7 +144,7 @@ hipError_t launch_select_lazy(const void* K, const void* V, const float* s, cons
 bool sparse_supported(const Layout& lay, int b, float lambda);
 hipError_t launch_retain_sparse(const void* K, const void* V, const float* s, const Layout& lay, int b, float lambda,
                                 float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
-                                void* V_out, hipStream_t st);
+                                void* V_out, hipStream_t st, const int32_t* b_h = nullptr);
 // The same for fp32 rows (the mean rows of the flat-signature mode, fp32 caches), selection only: the
 // Gram and the passes run on the fp32 MFMAs, the rows of a pass are loaded straight into operand layout.
 bool lazy_f32_supported(const Layout& lay, int b, float lambda);

@@ -34,6 +34,7 @@ struct SparseArgs {
   long long stride_head, stride_tok;   // elements
   int n, b, heads;
   float lambda, eps;
+  const int32_t* b_h;                  // per-head budgets <= b (output rows stay b apart), or null
 };
 
 constexpr int kSpMaxB = 128;
@@ -88,6 +89,10 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
     float sv[S];
 #pragma unroll
     for (int k = 0; k < S; ++k) sv[k] = spre[k];
+    // the head's own budget: its picks are the first bt picks of a run for b (the rows of the outputs per head); a head
+    // with budget 0 still runs one pick, nothing of which is written
+    const int bt = a.b_h ? __builtin_amdgcn_readfirstlane(min(max(a.b_h[h], 0), b)) : b;
+    const int bq = bt < 1 ? 1 : bt;
 
     // ------------------------------------------------ the tokens that can ever be picked
     // Nothing can go when the finite scores spread by at most lambda: one min/max settles that.
@@ -145,11 +150,23 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
         return tot;
       };
       // s_(b) from the leading 16 bits of the ordered keys: at most s_(b), so the bound only loosens
-      const float sb = key_to_float(kth_key16(b));
+      const float sb = key_to_float(kth_key16(bq));
       const float thr = sb - a.lambda * 1.00001f - 1e-5f * fabsf(sb);   // fp32 cosines may exceed 1 by a few ulp
 #pragma unroll
       for (int k = 0; k < S; ++k) km[k] = __ballot(k * 256 + tid < n && !(sv[k] < thr));   // (a NaN threshold or score keeps the token)
       ns = count_kept();
+      if (ns > N32) {
+        // (first the cheap half of the test below: when more than N32 tokens score within a quarter of lambda of
+        // s_(b), the best one left out does too, and the second search is not worth running)
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < S; ++k) c += __popcll(__ballot(k * 256 + tid < n && !(sv[k] < sb - 0.25f * a.lambda)));
+        if (lane == 0) redi[par * 4 + wave] = c;
+        lds_barrier();
+        const int near = redi[par * 4] + redi[par * 4 + 1] + redi[par * 4 + 2] + redi[par * 4 + 3];
+        par ^= 1;
+        if (near > N32) ns = -1;                       // handed on
+      }
       if (ns > N32) {
         // More candidates than fit: the best-scored are kept, cut where the leading 16 key bits change (at most N32
         // of them), and the best score left out is remembered.  Pick gains never increase and a token gains at most
@@ -173,7 +190,7 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
         excl = hw_max(hw_max(redf[pf * 4], redf[pf * 4 + 1]), hw_max(redf[pf * 4 + 2], redf[pf * 4 + 3]));
         if (!(excl < sb - 0.25f * a.lambda)) ns = N32 + 1;              // hopeless: handed on
       }
-      marked = ns > N32 || ns < b;
+      marked = ns > N32 || ns < bq;
     }
     if (marked) {                                    // uniform: every wave takes the same branch
       if (tid == 0) a.idx_sorted[static_cast<long long>(h) * b] = -1;
@@ -268,9 +285,9 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
     // ------------------------------------------------ greedy on the survivors, then back to token numbers
     if (wave == 0) {
       __builtin_amdgcn_s_setprio(3);                 // the chain goes first when it shares a SIMD with other workgroups' waves
-      const float last_g = pick_chain<NQ>(s_l, tri, order_l, gain_l, ns, b, a.lambda, true, lane);
+      const float last_g = pick_chain<NQ>(s_l, tri, order_l, gain_l, ns, bq, a.lambda, true, lane);
       __builtin_amdgcn_s_setprio(0);
-      sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), b, lane, tok_c);   // rinv is dead by now
+      sort_picks<NQ>(order_l, idx_l, reinterpret_cast<int32_t*>(rinv), bq, lane, tok_c);   // rinv is dead by now
       // the cut, if there was one, holds when every token left out scores below the last pick's gain
       const bool ok = excl == -INFINITY || excl < last_g - 1e-5f * (fabsf(last_g) + a.lambda);
       if (lane == 0) redi[8] = ok ? 0 : 1;
@@ -280,13 +297,13 @@ __global__ __launch_bounds__(kDenseThreads, (NT <= 4 ? 4 : 2)) void retain_spars
 
     // ------------------------------------------------ outputs and compaction
     const long long ob = static_cast<long long>(h) * b;
-    for (int t = tid; t < b; t += kDenseThreads) {
-      a.idx_sorted[ob + t] = (redo && t == 0) ? -1 : idx_l[t];
-      if (a.pick_order) a.pick_order[ob + t] = order_l[t];
-      if (a.pick_gain) a.pick_gain[ob + t] = gain_l[t];
+    for (int t = tid; t < b; t += kDenseThreads) {             // entries past the head's budget are padding
+      a.idx_sorted[ob + t] = ((redo && t == 0) || t >= bt) ? -1 : idx_l[t];
+      if (a.pick_order) a.pick_order[ob + t] = t < bt ? order_l[t] : -1;
+      if (a.pick_gain) a.pick_gain[ob + t] = t < bt ? gain_l[t] : -INFINITY;
     }
-    if ((a.K_out || a.V_out) && !redo)
-      compact_rows<4>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idx_l, n, b, ob, tid, kDenseThreads);
+    if ((a.K_out || a.V_out) && !redo && bt > 0)
+      compact_rows<4>(a.K, a.V, a.K_out, a.V_out, head_off, a.stride_tok, idx_l, n, bt, ob, tid, kDenseThreads);
     lds_barrier();                                   // the lists and tables are reused by the next head
   }
 }
@@ -300,8 +317,9 @@ bool sparse_supported(const Layout& lay, int b, float lambda) {
 
 hipError_t launch_retain_sparse(const void* K, const void* V, const float* s, const Layout& lay, int b, float lambda,
                                 float eps, int32_t* idx_sorted, int32_t* pick_order, float* pick_gain, void* K_out,
-                                void* V_out, hipStream_t st) {
+                                void* V_out, hipStream_t st, const int32_t* b_h) {
   SparseArgs a;
+  a.b_h = b_h;
   a.K = static_cast<const char*>(K); a.V = static_cast<const char*>(V); a.s_in = s;
   a.idx_sorted = idx_sorted; a.pick_order = pick_order; a.pick_gain = pick_gain;
   a.K_out = static_cast<char*>(K_out); a.V_out = static_cast<char*>(V_out);

@@ -721,7 +721,10 @@ def test_observation_window_scores_full_size_sampled_heads():
 # ---------------------------------------------------------------- budgets and protected tokens
 @pytest.mark.parametrize("n,b_max,lam,dtype,computed", [
     (192, 64, 0.5, torch.bfloat16, False), (256, 100, 0.3, torch.bfloat16, True), (120, 48, 0.7, torch.bfloat16, False),
-    (600, 64, 0.5, torch.bfloat16, False), (150, 40, 0.5, torch.float32, False)])
+    (600, 64, 0.5, torch.bfloat16, False), (150, 40, 0.5, torch.float32, False),
+    # long heads with scores handed in: the kernel that shrinks them to their candidates takes the budgets too
+    (1024, 128, 0.5, torch.bfloat16, False), (3000, 64, 0.5, torch.bfloat16, False), (2048, 100, 1.0, torch.bfloat16, False),
+    (1024, 128, 0.5, torch.bfloat16, True)])
 def test_budgeted_heads_and_protected_tokens(n, b_max, lam, dtype, computed):
     h = 8
     K, V, s = _mk(h, n, 5100 + n, dtype)
